@@ -1,0 +1,491 @@
+/*
+ * CPU oracle for the modified L-BFGS-B method (box-constrained quasi-Newton without the
+ * Cauchy-point search).  TEST INFRASTRUCTURE ONLY: plain, single-threaded, fp64, slow.
+ * It shares no code with the HIP library and must never be called from the product path.
+ *
+ * What it follows, in the paper's notation:
+ *   - Algorithm 1 (main loop)                               -> orc_step / orc_solve
+ *   - Eq. (ws), the working set S^k of free variables       -> orc_free_mask
+ *   - Algorithm 3 (modified two-loop recursion, appendix)   -> orc_two_loop
+ *   - Algorithm 2 (projectDirection)                        -> orc_project_direction
+ *   - backtracking Armijo line search (Section "Algorithm") -> line_search
+ *   - objectives: the NNLS section's least-squares objective (scaled by 1/2), its
+ *     L1-regularised variant split into x = p - q, and the regularised empirical
+ *     logistic risk of the fairness section restricted to a box       -> orc_fg
+ *
+ * Nothing here is blocked, fused or reordered: every objective value and gradient is
+ * evaluated from scratch at every trial point, the two-loop recursion is the literal
+ * sequence of dot products and axpys.  All sums are Neumaier-compensated so that the
+ * oracle's own rounding is negligible next to that of the code it checks.
+ *
+ * Readings taken where the paper gives no value or is ambiguous (each one is also an
+ * option or a comment at the place it is used):
+ *   - one epsilon for Eq. (ws), Algorithm 2 and the curvature gate of Algorithm 3;
+ *     convergence uses a separate tolerance on ||grad f(x^k)[S^k]||_2;
+ *   - ||y^i||^2 in Algorithm 3 is the full-vector norm, as printed (no [S^k]);
+ *   - the gate is the strict '>' of the algorithm listing;
+ *   - d[S] = -q for the q Algorithm 3 returns;
+ *   - with fewer than m pairs only the stored ones are visited; with none d = -g[S];
+ *   - every pair is stored; the gate alone decides whether it is used;
+ *   - step-length bound: 1 in the projection branch, the largest feasible step in the
+ *     other branch; the first trial step is min(1, bound);
+ *   - Armijo constant 1e-4 and halving are defaults of the options struct;
+ *   - the Armijo inequality f(x + alpha p) <= f(x) + c1 alpha <grad f, p> is tested as
+ *     [f(x_t) - f(x)] <= c1 alpha <grad f, p>, where the bracket is summed row by row from
+ *     the identity  loss_r(x_t) - loss_r(x)  written in terms of (A (x_t - x))_r, and
+ *     A (x_t - x) is a from-scratch product with the difference of the two points
+ *     (orc_delta_f).  It is the same inequality, evaluated without cancellation:
+ *     differencing two rounded objective values stalls the iteration at
+ *     ||g|| ~ sqrt(ulp(f) * L), above the 1e-8 that the small NNLS case asks for.  f(x_t)
+ *     itself is still evaluated from scratch at every trial (reported, finiteness check);
+ *   - x + alpha p is clamped to the box (an exact no-op in exact arithmetic);
+ *   - when backtracking is exhausted the pair memory is cleared and the iteration is
+ *     redone once from the steepest-descent direction; if that fails too the solver
+ *     stops with ORC_LINESEARCH_FAILED.
+ *
+ * Parity pins (tests/test_oracle_*.py): KKT at the returned point, numpy lstsq when no
+ * bound is active, brute-force active-set enumeration, scipy nnls / lsq_linear /
+ * L-BFGS-B minimisers, dense BFGS-matrix construction for Algorithm 3, truth tables for
+ * Eq. (ws) and Algorithm 2, finite differences for the gradients.  The individual
+ * trajectory (iterates, step lengths) is parity unpinned: the paper prints no worked
+ * example and none of the constants above.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_LSQ = 0, ORC_LSQ_L1SPLIT = 1, ORC_LOGISTIC_L2 = 2 };
+enum { ORC_F64 = 0, ORC_F32 = 1 };
+enum { ORC_RUNNING = 0, ORC_CONVERGED = 1, ORC_MAX_ITER = 2, ORC_LINESEARCH_FAILED = 3 };
+
+typedef struct {
+    int kind, dtype;
+    int64_t rows, cols, ld;
+    const void* A;     /* row-major rows x cols, leading dimension ld */
+    const double* b;   /* targets (least squares) or labels in {-1,+1} (logistic) */
+    double lambda, mu;
+} orc_objective;
+
+typedef struct {
+    double eps;
+    double armijo_c1;
+    double backtrack;
+    int max_backtracks;
+    double tol;
+    int tol_relative;
+    int max_iter;
+    int always_branch2;   /* skip the projection branch of Algorithm 2 (remark after the corollary) */
+} orc_options;
+
+typedef struct {
+    int status;
+    int64_t iters, fevals;
+    double f, pg2, pginf;
+    int64_t n_fixed;
+    /* diagnostics of the last completed iteration */
+    int branch;            /* 1 = projection branch, 2 = masked quasi-Newton direction */
+    int backtracks;
+    int pairs_used;
+    int memory_resets;
+    double alpha, alpha_ub, gp;
+} orc_info;
+
+/* ---- compensated summation ------------------------------------------------------------- */
+
+typedef struct { double s, c; } nsum;
+
+static inline void ns_add(nsum* a, double v) {
+    double t = a->s + v;
+    if (fabs(a->s) >= fabs(v)) a->c += (a->s - t) + v;
+    else a->c += (v - t) + a->s;
+    a->s = t;
+}
+static inline double ns_val(const nsum* a) { return a->s + a->c; }
+
+/* adds the exact product a*b (rounded product plus its fma-recovered error) */
+static inline void ns_add_prod(nsum* acc, double a, double b) {
+    double p = a * b;
+    double e = fma(a, b, -p);
+    ns_add(acc, p);
+    acc->c += e;
+}
+
+static double dot_masked(int64_t n, const double* a, const double* b, const uint8_t* mask) {
+    nsum acc = {0.0, 0.0};
+    for (int64_t i = 0; i < n; ++i)
+        if (!mask || mask[i]) ns_add_prod(&acc, a[i], b[i]);
+    return ns_val(&acc);
+}
+
+static inline double a_at(const orc_objective* o, int64_t r, int64_t c) {
+    return o->dtype == ORC_F64 ? ((const double*)o->A)[r * o->ld + c]
+                               : (double)((const float*)o->A)[r * o->ld + c];
+}
+
+static inline double softplus(double t) { return (t > 0.0 ? t : 0.0) + log1p(exp(-fabs(t))); }
+static inline double sigmoid(double t) {
+    if (t >= 0.0) return 1.0 / (1.0 + exp(-t));
+    double e = exp(t);
+    return e / (1.0 + e);
+}
+
+/* ---- objectives -------------------------------------------------------------------------- */
+
+int64_t orc_num_vars(const orc_objective* o) {
+    return o->kind == ORC_LSQ_L1SPLIT ? 2 * o->cols : o->cols;
+}
+
+/* f(x); if g != NULL also grad f(x); if rowvec != NULL it receives the residual A v - b
+ * (least squares) or the margins X w (logistic), one entry per row. */
+double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec) {
+    const int64_t rows = o->rows, cols = o->cols;
+    double* v = (double*)malloc(sizeof(double) * (size_t)cols);   /* the vector A multiplies */
+    double* psi = (double*)malloc(sizeof(double) * (size_t)(rows > 0 ? rows : 1));
+    for (int64_t c = 0; c < cols; ++c)
+        v[c] = o->kind == ORC_LSQ_L1SPLIT ? x[c] - x[cols + c] : x[c];
+
+    nsum fsum = {0.0, 0.0};
+    for (int64_t r = 0; r < rows; ++r) {
+        nsum acc = {0.0, 0.0};
+        for (int64_t c = 0; c < cols; ++c) ns_add_prod(&acc, a_at(o, r, c), v[c]);
+        double z = ns_val(&acc);
+        if (o->kind == ORC_LOGISTIC_L2) {
+            double yr = o->b[r];
+            ns_add(&fsum, softplus(-yr * z));
+            psi[r] = -yr * sigmoid(-yr * z);
+            if (rowvec) rowvec[r] = z;
+        } else {
+            double res = z - o->b[r];
+            ns_add(&fsum, 0.5 * res * res);
+            psi[r] = res;
+            if (rowvec) rowvec[r] = res;
+        }
+    }
+    double f = ns_val(&fsum);
+    if (o->kind == ORC_LOGISTIC_L2) {
+        f /= (double)rows;
+        f += 0.5 * o->mu * dot_masked(cols, x, x, NULL);
+    } else if (o->kind == ORC_LSQ_L1SPLIT) {
+        nsum l1 = {0.0, 0.0};
+        for (int64_t i = 0; i < 2 * cols; ++i) ns_add(&l1, x[i]);
+        f += o->lambda * ns_val(&l1);
+    }
+
+    if (g) {
+        /* w = A^T psi, column by column as the definition says */
+        nsum* acc = (nsum*)calloc((size_t)cols, sizeof(nsum));
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&acc[c], a_at(o, r, c), psi[r]);
+        for (int64_t c = 0; c < cols; ++c) {
+            double w = ns_val(&acc[c]);
+            if (o->kind == ORC_LSQ) g[c] = w;
+            else if (o->kind == ORC_LSQ_L1SPLIT) { g[c] = w + o->lambda; g[cols + c] = -w + o->lambda; }
+            else g[c] = w / (double)rows + o->mu * x[c];
+        }
+        free(acc);
+    }
+    free(v);
+    free(psi);
+    return f;
+}
+
+/* f(xt) - f(x) without cancellation.  row = residuals (least squares) or margins
+ * (logistic) at x, as orc_fg produced them.  With dz = A (vt - v) computed from scratch:
+ *   least squares:  0.5*(res+dz)^2 - 0.5*res^2 = dz*(res + 0.5*dz)
+ *   logistic:       softplus(a+da) - softplus(a) = log1p(sigmoid(a)*expm1(da)),
+ *                   a = -y*z, da = -y*dz
+ * plus the difference of the separable terms (lambda*sum x, mu/2*||x||^2). */
+double orc_delta_f(const orc_objective* o, const double* x, const double* xt, const double* row) {
+    const int64_t rows = o->rows, cols = o->cols, n = orc_num_vars(o);
+    double* dv = (double*)malloc(sizeof(double) * (size_t)cols);
+    for (int64_t c = 0; c < cols; ++c)
+        dv[c] = o->kind == ORC_LSQ_L1SPLIT ? (xt[c] - x[c]) - (xt[cols + c] - x[cols + c])
+                                           : xt[c] - x[c];
+    nsum acc = {0.0, 0.0};
+    for (int64_t r = 0; r < rows; ++r) {
+        nsum dacc = {0.0, 0.0};
+        for (int64_t c = 0; c < cols; ++c) ns_add_prod(&dacc, a_at(o, r, c), dv[c]);
+        double dz = ns_val(&dacc);
+        if (o->kind == ORC_LOGISTIC_L2) {
+            double a = -o->b[r] * row[r], da = -o->b[r] * dz;
+            if (fabs(da) < 30.0) ns_add(&acc, log1p(sigmoid(a) * expm1(da)));
+            else ns_add(&acc, softplus(a + da) - softplus(a));
+        } else {
+            ns_add_prod(&acc, dz, row[r] + 0.5 * dz);
+        }
+    }
+    free(dv);
+    double df = ns_val(&acc);
+    if (o->kind == ORC_LOGISTIC_L2) {
+        nsum reg = {0.0, 0.0};
+        for (int64_t i = 0; i < n; ++i) ns_add_prod(&reg, xt[i] - x[i], xt[i] + x[i]);
+        df = df / (double)rows + 0.5 * o->mu * ns_val(&reg);
+    } else if (o->kind == ORC_LSQ_L1SPLIT) {
+        nsum l1 = {0.0, 0.0};
+        for (int64_t i = 0; i < n; ++i) ns_add(&l1, xt[i] - x[i]);
+        df += o->lambda * ns_val(&l1);
+    }
+    return df;
+}
+
+/* ---- Eq. (ws): mask[i] = 1 for free variables, 0 for fixed ones -------------------------- */
+
+void orc_free_mask(int64_t n, const double* x, const double* g, const double* l, const double* u,
+                   double eps, uint8_t* mask) {
+    for (int64_t i = 0; i < n; ++i) {
+        int at_lower = (x[i] <= l[i] + eps) && (g[i] >= 0.0);
+        int at_upper = (x[i] >= u[i] - eps) && (g[i] <= 0.0);
+        mask[i] = (at_lower || at_upper) ? 0 : 1;
+    }
+}
+
+/* ---- Algorithm 3: modified two-loop recursion -------------------------------------------
+ * S, Y: npairs x n, oldest pair first, newest last.  ynorm2[i] = ||y^i||^2 over the full
+ * vector.  Returns d with d[S^k] = -q, d elsewhere = 0; *pairs_used counts pairs that
+ * passed the curvature gate. */
+void orc_two_loop(int64_t n, int npairs, const double* S, const double* Y, const double* ynorm2,
+                  const double* g, const uint8_t* mask, double eps, double* d, int* pairs_used) {
+    double* q = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    double* rho = (double*)malloc(sizeof(double) * (size_t)(npairs > 0 ? npairs : 1));
+    double* alpha = (double*)malloc(sizeof(double) * (size_t)(npairs > 0 ? npairs : 1));
+    int* pass = (int*)malloc(sizeof(int) * (size_t)(npairs > 0 ? npairs : 1));
+    int used = 0;
+
+    for (int64_t e = 0; e < n; ++e) q[e] = mask[e] ? g[e] : 0.0;
+
+    for (int i = npairs - 1; i >= 0; --i) {
+        const double* s = S + (size_t)i * n;
+        const double* y = Y + (size_t)i * n;
+        rho[i] = dot_masked(n, s, y, mask);
+        pass[i] = rho[i] > eps * ynorm2[i];
+        if (pass[i]) {
+            ++used;
+            alpha[i] = dot_masked(n, s, q, mask) / rho[i];
+            for (int64_t e = 0; e < n; ++e)
+                if (mask[e]) q[e] -= alpha[i] * y[e];
+        }
+    }
+    if (npairs > 0 && pass[npairs - 1]) {
+        double scale = rho[npairs - 1] / ynorm2[npairs - 1];
+        for (int64_t e = 0; e < n; ++e) q[e] *= scale;
+    }
+    for (int i = 0; i < npairs; ++i) {
+        if (!pass[i]) continue;
+        const double* s = S + (size_t)i * n;
+        const double* y = Y + (size_t)i * n;
+        double beta = dot_masked(n, y, q, mask) / rho[i];
+        for (int64_t e = 0; e < n; ++e)
+            if (mask[e]) q[e] += (alpha[i] - beta) * s[e];
+    }
+    for (int64_t e = 0; e < n; ++e) d[e] = mask[e] ? -q[e] : 0.0;
+    if (pairs_used) *pairs_used = used;
+    free(q); free(rho); free(alpha); free(pass);
+}
+
+/* ---- Algorithm 2: projectDirection ------------------------------------------------------
+ * Returns the branch taken (1 or 2), writes p and the step-length bound. */
+static inline double clampd(double v, double lo, double hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+int orc_project_direction(int64_t n, const double* x, const double* g, const double* d,
+                          const double* l, const double* u, double eps, int always_branch2,
+                          double* p, double* alpha_ub) {
+    nsum pg = {0.0, 0.0}, pp = {0.0, 0.0};
+    for (int64_t i = 0; i < n; ++i) {
+        double z = clampd(x[i] + d[i], l[i], u[i]);
+        p[i] = z - x[i];
+        ns_add(&pg, p[i] * g[i]);
+        ns_add(&pp, p[i] * p[i]);
+    }
+    double pgv = ns_val(&pg), ppv = ns_val(&pp);
+    if (!always_branch2 && pgv <= -eps * ppv && ppv >= eps) {
+        *alpha_ub = 1.0;
+        return 1;
+    }
+    double ub = INFINITY;
+    for (int64_t i = 0; i < n; ++i) {
+        double pi = d[i];
+        if (d[i] < 0.0 && x[i] <= l[i] + eps) pi = 0.0;
+        if (d[i] > 0.0 && x[i] >= u[i] - eps) pi = 0.0;
+        p[i] = pi;
+        if (pi > 0.0) { double a = (u[i] - x[i]) / pi; if (a < ub) ub = a; }
+        else if (pi < 0.0) { double a = (l[i] - x[i]) / pi; if (a < ub) ub = a; }
+    }
+    *alpha_ub = ub;
+    return 2;
+}
+
+/* ---- solver state (Algorithm 1) ---------------------------------------------------------- */
+
+typedef struct {
+    int64_t n;
+    int m;
+    orc_objective obj;
+    orc_options opt;
+    double *l, *u, *x, *g, *d, *p, *xt, *gt;
+    double *row;              /* residuals (margins) at x */
+    uint8_t* mask;
+    double *S, *Y, *ynorm2;   /* oldest first */
+    int npairs;
+    double f;
+    double tol_abs;           /* resolved at the first iteration when tol_relative is set */
+    int tol_resolved;
+    orc_info info;
+} orc_solver;
+
+void orc_default_options(orc_options* o) {
+    o->eps = 1e-10;
+    o->armijo_c1 = 1e-4;
+    o->backtrack = 0.5;
+    o->max_backtracks = 60;
+    o->tol = 1e-8;
+    o->tol_relative = 0;
+    o->max_iter = 1000;
+    o->always_branch2 = 0;
+}
+
+void orc_destroy(orc_solver* s) {
+    if (!s) return;
+    free(s->l); free(s->u); free(s->x); free(s->g); free(s->d); free(s->p); free(s->xt); free(s->gt);
+    free(s->row);
+    free(s->mask); free(s->S); free(s->Y); free(s->ynorm2);
+    free(s);
+}
+
+/* Returns NULL when the arguments are invalid, bounds cross, or x0 is infeasible
+ * (Algorithm 1 requires l <= x^0 <= u). */
+orc_solver* orc_create(int64_t n, int m, const double* l, const double* u, const double* x0,
+                       const orc_objective* obj, const orc_options* opt) {
+    if (n <= 0 || m <= 0 || !l || !u || !x0 || !obj || orc_num_vars(obj) != n) return NULL;
+    for (int64_t i = 0; i < n; ++i)
+        if (!(l[i] <= u[i]) || !(x0[i] >= l[i]) || !(x0[i] <= u[i])) return NULL;
+    orc_solver* s = (orc_solver*)calloc(1, sizeof(orc_solver));
+    s->n = n; s->m = m; s->obj = *obj;
+    if (opt) s->opt = *opt; else orc_default_options(&s->opt);
+    size_t nb = sizeof(double) * (size_t)n;
+    s->l = (double*)malloc(nb); s->u = (double*)malloc(nb); s->x = (double*)malloc(nb);
+    s->g = (double*)malloc(nb); s->d = (double*)malloc(nb); s->p = (double*)malloc(nb);
+    s->xt = (double*)malloc(nb); s->gt = (double*)malloc(nb);
+    s->mask = (uint8_t*)malloc((size_t)n);
+    s->row = (double*)malloc(sizeof(double) * (size_t)(obj->rows > 0 ? obj->rows : 1));
+    s->S = (double*)malloc(nb * (size_t)m); s->Y = (double*)malloc(nb * (size_t)m);
+    s->ynorm2 = (double*)malloc(sizeof(double) * (size_t)m);
+    memcpy(s->l, l, nb); memcpy(s->u, u, nb); memcpy(s->x, x0, nb);
+    s->npairs = 0;
+    s->f = orc_fg(&s->obj, s->x, s->g, s->row);
+    s->info.status = ORC_RUNNING;
+    s->info.fevals = 1;
+    s->info.f = s->f;
+    return s;
+}
+
+static void kkt_measures(orc_solver* s) {
+    /* ||g[S^k]||_2 (the stopping quantity) and ||x - P(x - g)||_inf (epsilon-free KKT residual) */
+    int64_t fixed = 0;
+    double pginf = 0.0;
+    for (int64_t i = 0; i < s->n; ++i) {
+        if (!s->mask[i]) ++fixed;
+        double r = fabs(s->x[i] - clampd(s->x[i] - s->g[i], s->l[i], s->u[i]));
+        if (r > pginf) pginf = r;
+    }
+    s->info.pg2 = sqrt(dot_masked(s->n, s->g, s->g, s->mask));
+    s->info.pginf = pginf;
+    s->info.n_fixed = fixed;
+    s->info.f = s->f;
+}
+
+/* backtracking Armijo search along p from x; on success xt holds the accepted point and
+ * *f_new its objective value.  Every trial evaluates f from scratch. */
+static int line_search(orc_solver* s, double gp, double alpha_ub, double* alpha_out, double* f_new,
+                       int* backtracks) {
+    double alpha = alpha_ub < 1.0 ? alpha_ub : 1.0;
+    for (int t = 0; t <= s->opt.max_backtracks; ++t) {
+        for (int64_t i = 0; i < s->n; ++i)
+            s->xt[i] = clampd(s->x[i] + alpha * s->p[i], s->l[i], s->u[i]);
+        double ft = orc_fg(&s->obj, s->xt, NULL, NULL);
+        s->info.fevals++;
+        double df = orc_delta_f(&s->obj, s->x, s->xt, s->row);
+        if (isfinite(ft) && isfinite(df) && df <= s->opt.armijo_c1 * alpha * gp) {
+            *alpha_out = alpha; *f_new = ft; *backtracks = t;
+            return 1;
+        }
+        alpha *= s->opt.backtrack;
+    }
+    return 0;
+}
+
+/* One iteration of Algorithm 1.  Returns the status after it. */
+int orc_step(orc_solver* s) {
+    if (s->info.status != ORC_RUNNING) return s->info.status;
+    const int64_t n = s->n;
+
+    orc_free_mask(n, s->x, s->g, s->l, s->u, s->opt.eps, s->mask);
+    kkt_measures(s);
+    if (!s->tol_resolved) {
+        s->tol_abs = s->opt.tol_relative ? s->opt.tol * fmax(1.0, s->info.pg2) : s->opt.tol;
+        s->tol_resolved = 1;
+    }
+    if (s->info.pg2 <= s->tol_abs) return s->info.status = ORC_CONVERGED;
+    if (s->info.iters >= s->opt.max_iter) return s->info.status = ORC_MAX_ITER;
+
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        int used = 0;
+        orc_two_loop(n, s->npairs, s->S, s->Y, s->ynorm2, s->g, s->mask, s->opt.eps, s->d, &used);
+        double alpha_ub;
+        int branch = orc_project_direction(n, s->x, s->g, s->d, s->l, s->u, s->opt.eps,
+                                           s->opt.always_branch2, s->p, &alpha_ub);
+        double gp = dot_masked(n, s->g, s->p, NULL);
+        double alpha, f_new;
+        int bt;
+        if (line_search(s, gp, alpha_ub, &alpha, &f_new, &bt)) {
+            orc_fg(&s->obj, s->xt, s->gt, s->row);      /* gradient at the new point, from scratch */
+            s->info.fevals++;
+            if (s->npairs == s->m) {                    /* evict the oldest pair */
+                memmove(s->S, s->S + n, sizeof(double) * (size_t)n * (size_t)(s->m - 1));
+                memmove(s->Y, s->Y + n, sizeof(double) * (size_t)n * (size_t)(s->m - 1));
+                memmove(s->ynorm2, s->ynorm2 + 1, sizeof(double) * (size_t)(s->m - 1));
+                s->npairs--;
+            }
+            double* sn = s->S + (size_t)s->npairs * n;
+            double* yn = s->Y + (size_t)s->npairs * n;
+            for (int64_t i = 0; i < n; ++i) { sn[i] = s->xt[i] - s->x[i]; yn[i] = s->gt[i] - s->g[i]; }
+            s->ynorm2[s->npairs] = dot_masked(n, yn, yn, NULL);
+            s->npairs++;
+            memcpy(s->x, s->xt, sizeof(double) * (size_t)n);
+            memcpy(s->g, s->gt, sizeof(double) * (size_t)n);
+            s->f = f_new;
+            s->info.f = f_new;
+            s->info.iters++;
+            s->info.branch = branch; s->info.backtracks = bt; s->info.pairs_used = used;
+            s->info.alpha = alpha; s->info.alpha_ub = alpha_ub; s->info.gp = gp;
+            return ORC_RUNNING;
+        }
+        if (s->npairs == 0) break;
+        s->npairs = 0;                                  /* clear the memory, retry once */
+        s->info.memory_resets++;
+    }
+    return s->info.status = ORC_LINESEARCH_FAILED;
+}
+
+int orc_solve(orc_solver* s) {
+    while (orc_step(s) == ORC_RUNNING) {}
+    return s->info.status;
+}
+
+/* Re-evaluates the mask and the KKT measures at the current point without stepping
+ * (used after the last iteration so that info describes the returned x). */
+void orc_refresh_info(orc_solver* s) {
+    orc_free_mask(s->n, s->x, s->g, s->l, s->u, s->opt.eps, s->mask);
+    kkt_measures(s);
+}
+
+void orc_get_info(const orc_solver* s, orc_info* out) { *out = s->info; }
+const double* orc_x(const orc_solver* s) { return s->x; }
+const double* orc_g(const orc_solver* s) { return s->g; }
+const double* orc_d(const orc_solver* s) { return s->d; }
+const double* orc_p(const orc_solver* s) { return s->p; }
+const uint8_t* orc_mask(const orc_solver* s) { return s->mask; }
+const double* orc_S(const orc_solver* s) { return s->S; }
+const double* orc_Y(const orc_solver* s) { return s->Y; }
+const double* orc_ynorm2(const orc_solver* s) { return s->ynorm2; }
+int orc_npairs(const orc_solver* s) { return s->npairs; }

@@ -1,0 +1,219 @@
+"""Seeded synthetic inputs for the box-constrained solver: the five benchmark
+configurations and scaled-down relatives of them.
+
+This module is shared by the CPU oracle's tests and by the HIP path's tests and
+benchmark.  It only draws random numbers and assembles arrays; it contains none of
+the solver's arithmetic beyond what is needed to *define* the data (b = A x* + noise,
+labels = sign(X w* + noise), lambda = 0.1 * ||A^T b||_inf).
+
+Draw order, fixed for reproducibility: matrix, support of the ground truth, its
+non-zero values, noise.  The matrix is drawn row-chunk by row-chunk directly in its
+storage dtype so that the 8 GB configuration never needs an fp64 temporary.
+
+The NNLS family follows the paper's experiment (ii) of its non-negative least squares
+section (tall Gaussian design, sparse non-negative ground truth, small Gaussian
+noise); `paper_nnls_i` / `paper_nnls_ii` reproduce the two recipes of that section
+with their printed scalings.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+OBJ_LSQ = 0          # 0.5*||A x - b||^2,                                   n = cols
+OBJ_LSQ_L1SPLIT = 1  # 0.5*||A(p-q) - b||^2 + lam*sum(p+q), x = [p; q],     n = 2*cols
+OBJ_LOGISTIC_L2 = 2  # (1/rows)*sum softplus(-y_i * X_i.w) + mu/2*||w||^2,  n = cols
+
+
+@dataclass
+class Problem:
+    name: str
+    kind: int
+    A: np.ndarray            # rows x cols, C-contiguous, float64 or float32
+    b: np.ndarray            # rows, float64 (targets, or labels in {-1,+1})
+    l: np.ndarray            # n, float64 (may hold -inf)
+    u: np.ndarray            # n, float64 (may hold +inf)
+    x0: np.ndarray           # n, float64, feasible
+    m: int                   # number of stored curvature pairs
+    lam: float = 0.0
+    mu: float = 0.0
+    tol: float = 1e-8
+    tol_relative: bool = False
+    x_true: Optional[np.ndarray] = None
+    meta: dict = field(default_factory=dict)
+
+    @property
+    def rows(self) -> int:
+        return self.A.shape[0]
+
+    @property
+    def cols(self) -> int:
+        return self.A.shape[1]
+
+    @property
+    def n(self) -> int:
+        return 2 * self.cols if self.kind == OBJ_LSQ_L1SPLIT else self.cols
+
+
+def _normal_matrix(rng: np.random.Generator, rows: int, cols: int, dtype, scale: float = 1.0,
+                   out: Optional[np.ndarray] = None) -> np.ndarray:
+    """rows x cols iid N(0, scale^2) in `dtype`, drawn in row chunks of <= 64 MiB."""
+    A = out if out is not None else np.empty((rows, cols), dtype=dtype)
+    chunk = max(1, (64 << 20) // (cols * A.itemsize))
+    for r0 in range(0, rows, chunk):
+        r1 = min(rows, r0 + chunk)
+        blk = rng.standard_normal((r1 - r0, cols), dtype=A.dtype)
+        if scale != 1.0:
+            blk *= A.dtype.type(scale)
+        A[r0:r1] = blk
+    return A
+
+
+def _matvec(A: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """A @ x accumulated in float64, in row chunks (data definition, not solver code)."""
+    rows, cols = A.shape
+    out = np.empty(rows, dtype=np.float64)
+    chunk = max(1, (256 << 20) // (cols * 8))
+    nz = np.flatnonzero(x)
+    xs = x[nz]
+    for r0 in range(0, rows, chunk):
+        r1 = min(rows, r0 + chunk)
+        out[r0:r1] = A[r0:r1][:, nz].astype(np.float64) @ xs
+    return out
+
+
+def _rmatvec(A: np.ndarray, v: np.ndarray) -> np.ndarray:
+    rows, cols = A.shape
+    out = np.zeros(cols, dtype=np.float64)
+    chunk = max(1, (256 << 20) // (cols * 8))
+    for r0 in range(0, rows, chunk):
+        r1 = min(rows, r0 + chunk)
+        out += v[r0:r1] @ A[r0:r1].astype(np.float64)
+    return out
+
+
+def nnls(rows: int, cols: int, *, seed: int, dtype=np.float64, zero_frac: float, nonzero: str,
+         noise: float = 0.01, upper: float = math.inf, m: int = 10, name: str = "nnls",
+         tol: float = 1e-8, tol_relative: bool = False, a_out: Optional[np.ndarray] = None) -> Problem:
+    """min 0.5*||A x - b||^2  s.t. 0 <= x <= upper.  A iid N(0,1); x* has round(zero_frac*cols)
+    zeros on a uniformly random support complement; non-zeros |N(0,1)| ("absnormal") or
+    U(0,1) ("uniform"); b = A x* + noise*N(0,1)."""
+    rng = np.random.default_rng(seed)
+    A = _normal_matrix(rng, rows, cols, np.dtype(dtype), out=a_out)
+    n_zero = int(round(zero_frac * cols))
+    perm = rng.permutation(cols)
+    support = np.sort(perm[n_zero:])
+    x_true = np.zeros(cols)
+    if nonzero == "absnormal":
+        x_true[support] = np.abs(rng.standard_normal(support.size))
+    elif nonzero == "uniform":
+        x_true[support] = rng.random(support.size)
+    else:
+        raise ValueError(nonzero)
+    b = _matvec(A, x_true) + noise * rng.standard_normal(rows)
+    return Problem(name=name, kind=OBJ_LSQ, A=A, b=b, l=np.zeros(cols), u=np.full(cols, upper),
+                   x0=np.zeros(cols), m=m, tol=tol, tol_relative=tol_relative, x_true=x_true,
+                   meta=dict(seed=seed, zero_frac=zero_frac, nonzero=nonzero, noise=noise))
+
+
+def l1_split(rows: int, cols: int, *, seed: int, nnz_frac: float = 0.01, noise: float = 0.01,
+             lam_frac: float = 0.1, m: int = 10, name: str = "l1split", tol: float = 1e-8,
+             tol_relative: bool = False) -> Problem:
+    """L1-regularised least squares written as a box problem through x = p - q, p, q >= 0:
+    min 0.5*||A(p-q) - b||^2 + lam*sum(p+q).  A iid N(0,1)/sqrt(rows); x* has
+    round(nnz_frac*cols) N(0,1) non-zeros; b = A x* + noise*N(0,1);
+    lam = lam_frac*||A^T b||_inf."""
+    rng = np.random.default_rng(seed)
+    A = _normal_matrix(rng, rows, cols, np.dtype(np.float64), scale=1.0 / math.sqrt(rows))
+    nnz = int(round(nnz_frac * cols))
+    support = np.sort(rng.permutation(cols)[:nnz])
+    x_true = np.zeros(cols)
+    x_true[support] = rng.standard_normal(nnz)
+    b = _matvec(A, x_true) + noise * rng.standard_normal(rows)
+    lam = lam_frac * float(np.max(np.abs(_rmatvec(A, b))))
+    n = 2 * cols
+    return Problem(name=name, kind=OBJ_LSQ_L1SPLIT, A=A, b=b, l=np.zeros(n), u=np.full(n, math.inf),
+                   x0=np.zeros(n), m=m, lam=lam, tol=tol, tol_relative=tol_relative, x_true=x_true,
+                   meta=dict(seed=seed, nnz_frac=nnz_frac, noise=noise, lam_frac=lam_frac))
+
+
+def logistic(rows: int, cols: int, *, seed: int, dtype=np.float32, label_noise: float = 0.5,
+             mu: float = 1e-3, bound: float = 0.5, m: int = 10, name: str = "logistic",
+             tol: float = 1e-8, tol_relative: bool = False) -> Problem:
+    """Box-constrained L2-regularised logistic regression:
+    min (1/rows)*sum_i softplus(-y_i * X_i.w) + mu/2*||w||^2  s.t. -bound <= w <= bound.
+    X iid N(0,1); w* N(0,1); y = sign(X w* + label_noise*N(0,1)) in {-1,+1}."""
+    rng = np.random.default_rng(seed)
+    X = _normal_matrix(rng, rows, cols, np.dtype(dtype))
+    w_true = rng.standard_normal(cols)
+    score = _matvec(X, w_true) + label_noise * rng.standard_normal(rows)
+    y = np.where(score >= 0.0, 1.0, -1.0)
+    return Problem(name=name, kind=OBJ_LOGISTIC_L2, A=X, b=y, l=np.full(cols, -bound),
+                   u=np.full(cols, bound), x0=np.zeros(cols), m=m, mu=mu, tol=tol,
+                   tol_relative=tol_relative, x_true=w_true,
+                   meta=dict(seed=seed, label_noise=label_noise, bound=bound))
+
+
+def paper_nnls_i(t: float, *, seed: int, m: int = 10) -> Problem:
+    """The paper's NNLS experiment (i): A in R^{2000t x 6000t} with U(0,1) entries, x with
+    N(0,1) non-zeros at sparsity 0.01, y = sqrt(0.003)*A x + 0.003*z."""
+    rows, cols = int(round(2000 * t)), int(round(6000 * t))
+    rng = np.random.default_rng(seed)
+    A = rng.random((rows, cols))
+    nnz = max(1, int(round(0.01 * cols)))
+    support = np.sort(rng.permutation(cols)[:nnz])
+    x_true = np.zeros(cols)
+    x_true[support] = rng.standard_normal(nnz)
+    b = math.sqrt(0.003) * _matvec(A, x_true) + 0.003 * rng.standard_normal(rows)
+    return Problem(name=f"paper_nnls_i_t{t}", kind=OBJ_LSQ, A=A, b=b, l=np.zeros(cols),
+                   u=np.full(cols, math.inf), x0=np.zeros(cols), m=m, tol=1e-6, tol_relative=True,
+                   x_true=x_true, meta=dict(seed=seed, t=t))
+
+
+def paper_nnls_ii(t: float, *, seed: int, m: int = 10) -> Problem:
+    """The paper's NNLS experiment (ii): A in R^{6000t x 3000t} Gaussian, x at sparsity 0.1
+    (taken as 10 % non-zeros, |N(0,1)|), y = sqrt(1/6000)*A x + 0.003*z."""
+    rows, cols = int(round(6000 * t)), int(round(3000 * t))
+    rng = np.random.default_rng(seed)
+    A = _normal_matrix(rng, rows, cols, np.dtype(np.float64))
+    nnz = max(1, int(round(0.1 * cols)))
+    support = np.sort(rng.permutation(cols)[:nnz])
+    x_true = np.zeros(cols)
+    x_true[support] = np.abs(rng.standard_normal(nnz))
+    b = math.sqrt(1.0 / 6000.0) * _matvec(A, x_true) + 0.003 * rng.standard_normal(rows)
+    return Problem(name=f"paper_nnls_ii_t{t}", kind=OBJ_LSQ, A=A, b=b, l=np.zeros(cols),
+                   u=np.full(cols, math.inf), x0=np.zeros(cols), m=m, tol=1e-6, tol_relative=True,
+                   x_true=x_true, meta=dict(seed=seed, t=t))
+
+
+# ---- the five benchmark configurations -------------------------------------------------------
+
+CONFIG_SEEDS = {"C1": 1001, "C2": 1002, "C3": 1003, "C4": 1004, "C5": 1005}
+
+
+def config(name: str, *, scale: float = 1.0, a_out: Optional[np.ndarray] = None) -> Problem:
+    """C1..C5 at full size (scale=1) or with both matrix dimensions multiplied by `scale`
+    (same seed, same recipe) for parity cases the CPU oracle finishes in seconds."""
+    def dim(v: int) -> int:
+        return max(4, int(round(v * scale)))
+    seed = CONFIG_SEEDS[name]
+    if name == "C1":
+        return nnls(dim(200), dim(100), seed=seed, zero_frac=0.5, nonzero="absnormal", m=5,
+                    name="C1", tol=1e-8, tol_relative=False)
+    if name == "C2":
+        return nnls(dim(20000), dim(5000), seed=seed, zero_frac=0.8, nonzero="uniform", m=10,
+                    name="C2", tol=1e-6, tol_relative=True, a_out=a_out)
+    if name == "C3":
+        return l1_split(dim(10000), dim(20000), seed=seed, nnz_frac=0.01, m=10, name="C3",
+                        tol=1e-6, tol_relative=True)
+    if name == "C4":
+        return logistic(dim(200000), dim(2000), seed=seed, dtype=np.float32, m=10, name="C4",
+                        tol=1e-6, tol_relative=True)
+    if name == "C5":
+        return nnls(dim(100000), dim(20000), seed=seed, dtype=np.float32, zero_frac=0.9,
+                    nonzero="uniform", upper=1.0, m=20, name="C5", tol=1e-6, tol_relative=True,
+                    a_out=a_out)
+    raise KeyError(name)
