@@ -1,0 +1,200 @@
+/*
+ * liblbfgsb -- box-constrained limited-memory quasi-Newton solver for one MI355X (gfx950).
+ *
+ * Problem (the paper's section "Algorithm"):  minimise f(x) subject to l <= x <= u, with
+ * l, u in (R u {-inf,+inf})^n and a FEASIBLE initial iterate.  One call of lbfgsb_step is one
+ * pass of the body of Algorithm 1:
+ *     gradient + free set S^k (Eq. (ws)) -> modified two-loop recursion on S^k (Algorithm 3,
+ *     appendix) -> d[complement of S^k] = 0 -> projectDirection (Algorithm 2) -> backtracking
+ *     Armijo line search with the step bounded so that the iterate stays in the box -> new
+ *     curvature pair (s, y) stored in a FIFO of m pairs.
+ * There is no Cauchy-point search: the free set is computed directly, which is what lets every
+ * part of an iteration run data-parallel on the GPU.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name ends in _host or the comment says host.
+ *   - All vectors (x, g, l, u, b, ...) are fp64.  Only the matrix A may be stored in fp32
+ *     (dtype), and then every product is still accumulated in fp64.
+ *   - A is row-major, rows x cols, leading dimension ld >= cols (in elements).
+ *   - Infinite bounds are IEEE infinities.
+ *   - The library allocates no device memory: the caller passes a workspace of
+ *     lbfgsb_workspace_bytes() bytes (256-byte aligned) that the solver owns until
+ *     lbfgsb_destroy.  A, b are BORROWED for the solver's lifetime and must not change;
+ *     l, u, x0 are copied into the workspace.
+ *   - All work is enqueued on the HIP stream given at creation (NULL = the default stream).
+ *   - Every function returns LBFGSB_OK (0) or a negative error code; none throws, aborts or
+ *     prints.  lbfgsb_last_error() gives a human-readable message for the calling thread.
+ *     The reason a solve stopped is not an error; it is reported in lbfgsb_info.status.
+ */
+#ifndef LBFGSB_H
+#define LBFGSB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LBFGSB_MAX_M 31   /* at most 31 stored pairs (2m+1 <= 64 vectors in the batched two-loop) */
+
+typedef struct lbfgsb_solver lbfgsb_solver;   /* opaque, host object */
+
+/* storage type of the matrix only */
+enum { LBFGSB_F64 = 0, LBFGSB_F32 = 1 };
+
+/* objective kinds.  LSQ is the least-squares objective of the paper's NNLS section scaled by
+ * 1/2; L1SPLIT is its L1-regularised form written over x = [p; q], x_orig = p - q, p, q >= 0;
+ * LOGISTIC_L2 is the regularised empirical logistic risk (the loss of the paper's fairness
+ * section) over a box. */
+enum {
+    LBFGSB_OBJ_LSQ = 0,          /* f = 0.5*||A x - b||^2,                               n = cols   */
+    LBFGSB_OBJ_LSQ_L1SPLIT = 1,  /* f = 0.5*||A(p-q) - b||^2 + lambda*sum(p+q), x=[p;q], n = 2*cols */
+    LBFGSB_OBJ_LOGISTIC_L2 = 2   /* f = (1/rows)*sum_i softplus(-b_i*(A x)_i) + mu/2*||x||^2, b_i in {-1,+1}, n = cols */
+};
+
+typedef struct {
+    int kind;            /* LBFGSB_OBJ_* */
+    int dtype;           /* LBFGSB_F64 / LBFGSB_F32: element type of A */
+    int64_t rows, cols, ld;
+    const void* A;       /* device, row-major, borrowed */
+    const double* b;     /* device, rows entries: targets (least squares) or labels (logistic), borrowed */
+    double lambda;       /* L1SPLIT only */
+    double mu;           /* LOGISTIC_L2 only */
+} lbfgsb_objective;
+
+/* how the products with A are organised (results agree to rounding) */
+enum {
+    LBFGSB_APASS_AUTO = 0,     /* fused single read of A when the shape allows it, else two passes */
+    LBFGSB_APASS_TWO_PASS = 1, /* t = A v, then w = A^T psi: A is read twice per evaluation */
+    LBFGSB_APASS_FUSED = 2     /* force the fused kernel; lbfgsb_create fails if the shape does not fit */
+};
+
+typedef struct {
+    double eps;            /* the paper's epsilon: Eq. (ws), Algorithm 2 and the curvature gate of Algorithm 3. default 1e-10 */
+    double armijo_c1;      /* Armijo constant, default 1e-4 */
+    double backtrack;      /* step reduction factor in (0,1), default 0.5 */
+    int max_backtracks;    /* default 60 */
+    double tol;            /* stop when ||grad f(x^k)[S^k]||_2 <= tol (absolute) or <= tol*max(1, its value at x^0) */
+    int tol_relative;      /* 0 absolute (default), 1 relative */
+    int max_iter;          /* default 1000 */
+    int refresh_every;     /* least-squares kinds carry residual and gradient by recurrence; every this many
+                              iterations they are recomputed from x (default 32, 0 = never) */
+    int poll_every;        /* lbfgsb_solve reads the device status flag every this many iterations (default 8) */
+    int a_pass;            /* LBFGSB_APASS_* */
+} lbfgsb_options;
+
+/* termination state */
+enum { LBFGSB_RUNNING = 0, LBFGSB_CONVERGED = 1, LBFGSB_MAX_ITER = 2, LBFGSB_LINESEARCH_FAILED = 3 };
+
+typedef struct {          /* HOST struct */
+    int status;           /* LBFGSB_RUNNING ... */
+    int64_t iters;        /* accepted iterations so far */
+    int64_t fevals;       /* objective evaluations (line-search trials + refreshes) */
+    double f;             /* objective at the current iterate */
+    double pg2;           /* ||grad f(x)[S]||_2 at the last free-set evaluation (the stopping quantity) */
+    double pginf;         /* ||x - P(x - grad f(x))||_inf at the same point (epsilon-free KKT residual) */
+    int64_t n_fixed;      /* variables outside the free set at that point */
+    int branch;           /* last iteration: 1 = projected direction returned by Algorithm 2, 2 = masked quasi-Newton direction */
+    int backtracks;       /* last iteration: rejected trial steps */
+    int pairs_used;       /* last iteration: pairs that passed the curvature gate */
+    int memory_resets;    /* times the pair memory was cleared after an exhausted line search */
+    double alpha;         /* last accepted step length */
+    double alpha_ub;      /* its upper bound */
+    double gp;            /* <grad f, p> of the last iteration */
+} lbfgsb_info;
+
+/* error codes */
+enum {
+    LBFGSB_OK = 0,
+    LBFGSB_E_INVALID_ARG = -1,   /* null pointer, n <= 0, m <= 0 or > LBFGSB_MAX_M, ld < cols, n inconsistent with the objective,
+                                    workspace too small or misaligned, bad option value */
+    LBFGSB_E_BOUNDS = -2,        /* some l_i > u_i, or a NaN bound */
+    LBFGSB_E_INFEASIBLE_X0 = -3, /* x0 outside [l, u] or NaN (Algorithm 1 requires a feasible start; it is not projected silently) */
+    LBFGSB_E_NONFINITE = -4,     /* f or grad f not finite at x0 */
+    LBFGSB_E_HIP = -5,           /* a HIP runtime call failed */
+    LBFGSB_E_UNSUPPORTED = -6    /* LBFGSB_APASS_FUSED requested for a shape the fused kernel cannot hold */
+};
+
+/* Message for the last error on the calling thread (host string owned by the library). */
+const char* lbfgsb_last_error(void);
+
+/* Fills *opt (host) with the defaults listed above. */
+void lbfgsb_default_options(lbfgsb_options* opt);
+
+/* Bytes of device workspace lbfgsb_create needs for n variables, m pairs and this objective
+ * (only kind, dtype, rows, cols are read).  Returns 0 on invalid arguments. */
+size_t lbfgsb_workspace_bytes(int64_t n, int m, const lbfgsb_objective* obj_host, const lbfgsb_options* opt_host);
+
+/* Creates a solver.  l, u: device, n entries each, copied.  obj_host/opt_host: host structs,
+ * copied (opt_host may be NULL = defaults).  workspace: device, borrowed until destroy.
+ * hip_stream: a hipStream_t (or NULL).  Synchronises the stream (bounds are validated on the
+ * host).  The iterate is undefined until lbfgsb_set_x. */
+int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const double* u,
+                  const lbfgsb_objective* obj_host, const lbfgsb_options* opt_host,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Sets the iterate to x0 (device, n entries, copied), clears the pair memory and the
+ * iteration counter, and evaluates f and grad f there.  Fails with LBFGSB_E_INFEASIBLE_X0 /
+ * LBFGSB_E_NONFINITE.  Synchronises the stream. */
+int lbfgsb_set_x(lbfgsb_solver* s, const double* x0);
+
+/* One iteration of Algorithm 1 (a no-op once the status is not RUNNING).  With
+ * info_host == NULL the call only enqueues kernels and returns without synchronising; with a
+ * non-NULL info_host it synchronises and fills it. */
+int lbfgsb_step(lbfgsb_solver* s, lbfgsb_info* info_host);
+
+/* Iterates until the tolerance, max_iter or a line-search failure.  The device decides all
+ * data-dependent branches; the host only polls the status flag every poll_every iterations.
+ * A least-squares solve is declared converged only with residual and gradient freshly
+ * recomputed from x.  info_host may be NULL. */
+int lbfgsb_solve(lbfgsb_solver* s, lbfgsb_info* info_host);
+
+/* Synchronises and reports the current state. */
+int lbfgsb_get_info(lbfgsb_solver* s, lbfgsb_info* info_host);
+
+/* Device-to-device copies of the current iterate / gradient (n entries), enqueued on the
+ * solver's stream. */
+int lbfgsb_get_x(lbfgsb_solver* s, double* x_out);
+int lbfgsb_get_g(lbfgsb_solver* s, double* g_out);
+
+/* Frees the host object (the workspace stays the caller's).  NULL is a no-op. */
+void lbfgsb_destroy(lbfgsb_solver* s);
+
+/* ---- timing of the products with A (the kernels that dominate an iteration) ------------------
+ * When enabled, every lbfgsb_step brackets its A-pass kernel launches with HIP events on the
+ * solver's stream (at most 4096 pairs are kept).  lbfgsb_apass_timing synchronises and returns
+ * how many passes were timed, their total duration in milliseconds and the bytes of A one pass
+ * requests from memory (rows*cols*sizeof(element) times the number of reads of A in it). */
+int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable);
+int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count_host, double* total_ms_host, double* bytes_per_pass_host);
+/* Name of the A-pass organisation in use: "fused" or "two_pass" (host string). */
+const char* lbfgsb_apass_name(const lbfgsb_solver* s);
+
+/* ---- primitive-level hooks --------------------------------------------------------------------
+ * Each runs ONE step of the path, with the same kernels lbfgsb_step uses, on inputs the caller
+ * supplies, so that it can be compared with a reference implementation on identical data.  They
+ * overwrite the solver's iterate and pair memory: call lbfgsb_set_x before stepping again.  All
+ * synchronise. */
+
+/* f(x) -> *f_host, grad f(x) -> g (n entries); rowvec (rows entries, may be NULL) receives
+ * A v - b (least squares) or the margins A x (logistic). */
+int lbfgsb_dbg_fg(lbfgsb_solver* s, const double* x, double* f_host, double* g, double* rowvec);
+
+/* Eq. (ws): mask[i] = 1 if i is free at (x, g), else 0. */
+int lbfgsb_dbg_free_mask(lbfgsb_solver* s, const double* x, const double* g, uint8_t* mask);
+
+/* Algorithm 3 on npairs <= m pairs (S, Y: npairs x n, oldest first), gradient g and free mask
+ * (1 = free); ynorm2: npairs full-vector values ||y^i||^2.  d receives -q on the free set and 0
+ * elsewhere; *pairs_used_host the number of pairs that passed the gate. */
+int lbfgsb_dbg_two_loop(lbfgsb_solver* s, const double* S, const double* Y, const double* ynorm2, int npairs,
+                        const double* g, const uint8_t* mask, double* d, int* pairs_used_host);
+
+/* Algorithm 2 at (x, g, d): p, the branch taken (1 or 2) and the step-length bound. */
+int lbfgsb_dbg_project_direction(lbfgsb_solver* s, const double* x, const double* g, const double* d,
+                                 double* p, int* branch_host, double* alpha_ub_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LBFGSB_H */

@@ -1,0 +1,295 @@
+"""Thin Python binding of liblbfgsb (include/lbfgsb.h): argument marshalling only.
+
+Every step of the solver runs in the HIP library; PyTorch is used for device memory and
+streams.  There is no CPU fallback: importing the binding's functions without the built
+library raises.  Build with `python -m paper_2203_16340_amd.build` (or __graft_entry__.build()).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblbfgsb.so")
+
+F64, F32 = 0, 1
+OBJ_LSQ, OBJ_LSQ_L1SPLIT, OBJ_LOGISTIC_L2 = 0, 1, 2
+APASS_AUTO, APASS_TWO_PASS, APASS_FUSED = 0, 1, 2
+RUNNING, CONVERGED, MAX_ITER, LINESEARCH_FAILED = 0, 1, 2, 3
+OK, E_INVALID_ARG, E_BOUNDS, E_INFEASIBLE_X0, E_NONFINITE, E_HIP, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+MAX_M = 31
+
+EXPORTS = [
+    "lbfgsb_last_error", "lbfgsb_default_options", "lbfgsb_workspace_bytes", "lbfgsb_create", "lbfgsb_set_x",
+    "lbfgsb_step", "lbfgsb_solve", "lbfgsb_get_info", "lbfgsb_get_x", "lbfgsb_get_g", "lbfgsb_destroy",
+    "lbfgsb_enable_apass_timing", "lbfgsb_apass_timing", "lbfgsb_apass_name", "lbfgsb_dbg_fg",
+    "lbfgsb_dbg_free_mask", "lbfgsb_dbg_two_loop", "lbfgsb_dbg_project_direction",
+]
+
+
+class Objective(C.Structure):
+    _fields_ = [("kind", C.c_int), ("dtype", C.c_int), ("rows", C.c_int64), ("cols", C.c_int64),
+                ("ld", C.c_int64), ("A", C.c_void_p), ("b", C.c_void_p), ("lam", C.c_double),
+                ("mu", C.c_double)]
+
+
+class Options(C.Structure):
+    _fields_ = [("eps", C.c_double), ("armijo_c1", C.c_double), ("backtrack", C.c_double),
+                ("max_backtracks", C.c_int), ("tol", C.c_double), ("tol_relative", C.c_int),
+                ("max_iter", C.c_int), ("refresh_every", C.c_int), ("poll_every", C.c_int),
+                ("a_pass", C.c_int)]
+
+
+class Info(C.Structure):
+    _fields_ = [("status", C.c_int), ("iters", C.c_int64), ("fevals", C.c_int64), ("f", C.c_double),
+                ("pg2", C.c_double), ("pginf", C.c_double), ("n_fixed", C.c_int64), ("branch", C.c_int),
+                ("backtracks", C.c_int), ("pairs_used", C.c_int), ("memory_resets", C.c_int),
+                ("alpha", C.c_double), ("alpha_ub", C.c_double), ("gp", C.c_double)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+class LbfgsbError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"liblbfgsb error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2203_16340_amd.build`; "
+                               "there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, dbl = C.c_void_p, C.c_int64, C.c_double
+        L.lbfgsb_last_error.restype = C.c_char_p
+        L.lbfgsb_last_error.argtypes = []
+        L.lbfgsb_default_options.restype = None
+        L.lbfgsb_default_options.argtypes = [C.POINTER(Options)]
+        L.lbfgsb_workspace_bytes.restype = C.c_size_t
+        L.lbfgsb_workspace_bytes.argtypes = [i64, C.c_int, C.POINTER(Objective), C.POINTER(Options)]
+        L.lbfgsb_create.restype = C.c_int
+        L.lbfgsb_create.argtypes = [C.POINTER(vp), i64, C.c_int, vp, vp, C.POINTER(Objective), C.POINTER(Options),
+                                    vp, C.c_size_t, vp]
+        L.lbfgsb_set_x.restype = C.c_int
+        L.lbfgsb_set_x.argtypes = [vp, vp]
+        L.lbfgsb_step.restype = C.c_int
+        L.lbfgsb_step.argtypes = [vp, C.POINTER(Info)]
+        L.lbfgsb_solve.restype = C.c_int
+        L.lbfgsb_solve.argtypes = [vp, C.POINTER(Info)]
+        L.lbfgsb_get_info.restype = C.c_int
+        L.lbfgsb_get_info.argtypes = [vp, C.POINTER(Info)]
+        L.lbfgsb_get_x.restype = C.c_int
+        L.lbfgsb_get_x.argtypes = [vp, vp]
+        L.lbfgsb_get_g.restype = C.c_int
+        L.lbfgsb_get_g.argtypes = [vp, vp]
+        L.lbfgsb_destroy.restype = None
+        L.lbfgsb_destroy.argtypes = [vp]
+        L.lbfgsb_enable_apass_timing.restype = C.c_int
+        L.lbfgsb_enable_apass_timing.argtypes = [vp, C.c_int]
+        L.lbfgsb_apass_timing.restype = C.c_int
+        L.lbfgsb_apass_timing.argtypes = [vp, C.POINTER(i64), C.POINTER(dbl), C.POINTER(dbl)]
+        L.lbfgsb_apass_name.restype = C.c_char_p
+        L.lbfgsb_apass_name.argtypes = [vp]
+        L.lbfgsb_dbg_fg.restype = C.c_int
+        L.lbfgsb_dbg_fg.argtypes = [vp, vp, C.POINTER(dbl), vp, vp]
+        L.lbfgsb_dbg_free_mask.restype = C.c_int
+        L.lbfgsb_dbg_free_mask.argtypes = [vp, vp, vp, vp]
+        L.lbfgsb_dbg_two_loop.restype = C.c_int
+        L.lbfgsb_dbg_two_loop.argtypes = [vp, vp, vp, vp, C.c_int, vp, vp, vp, C.POINTER(C.c_int)]
+        L.lbfgsb_dbg_project_direction.restype = C.c_int
+        L.lbfgsb_dbg_project_direction.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_int), C.POINTER(dbl)]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise LbfgsbError(rc, lib().lbfgsb_last_error().decode())
+
+
+def default_options(**overrides) -> Options:
+    o = Options()
+    lib().lbfgsb_default_options(C.byref(o))
+    for k, v in overrides.items():
+        if not hasattr(o, k):
+            raise AttributeError(k)
+        setattr(o, k, v)
+    return o
+
+
+def _dev_f64(t, name: str, numel: Optional[int] = None):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float64 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous float64 tensor on the GPU")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{name} must have {numel} entries, got {t.numel()}")
+    return t
+
+
+class Solver:
+    """lbfgsb_create / lbfgsb_set_x / lbfgsb_step / lbfgsb_solve / lbfgsb_destroy on torch tensors.
+
+    A: (rows, cols) float64 or float32 CUDA tensor with unit column stride; b, l, u: float64 CUDA
+    tensors.  The solver keeps references to A and b (the library borrows them) and owns its
+    workspace tensor.  All work runs on torch's current stream at construction time.
+    """
+
+    def __init__(self, kind: int, A, b, l, u, m: int, *, lam: float = 0.0, mu: float = 0.0,
+                 options: Optional[Options] = None):
+        import torch
+        if not (isinstance(A, torch.Tensor) and A.is_cuda and A.dim() == 2 and A.stride(1) == 1
+                and A.dtype in (torch.float64, torch.float32)):
+            raise TypeError("A must be a 2-d float64/float32 CUDA tensor with unit column stride")
+        rows, cols = A.shape
+        self.n = 2 * cols if kind == OBJ_LSQ_L1SPLIT else cols
+        self.rows, self.cols, self.m, self.kind = rows, cols, m, kind
+        self._A, self._b = A, _dev_f64(b, "b", rows)
+        _dev_f64(l, "l", self.n)
+        _dev_f64(u, "u", self.n)
+        self.device = A.device
+        self.options = options if options is not None else default_options()
+        self._obj = Objective(kind, F64 if A.dtype == torch.float64 else F32, rows, cols,
+                              A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), float(lam), float(mu))
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            nbytes = lib().lbfgsb_workspace_bytes(self.n, m, C.byref(self._obj), C.byref(self.options))
+            if nbytes == 0:
+                raise LbfgsbError(E_INVALID_ARG, lib().lbfgsb_last_error().decode())
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self._stream = torch.cuda.current_stream(self.device)
+            _check(lib().lbfgsb_create(C.byref(self._h), self.n, m, l.data_ptr(), u.data_ptr(), C.byref(self._obj),
+                                       C.byref(self.options), self.workspace.data_ptr(), nbytes,
+                                       C.c_void_p(self._stream.cuda_stream)))
+
+    # -- lifetime
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h:
+            lib().lbfgsb_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    # -- the path
+    def set_x(self, x0) -> None:
+        _check(lib().lbfgsb_set_x(self._h, _dev_f64(x0, "x0", self.n).data_ptr()))
+
+    def step(self, want_info: bool = True) -> Optional[Info]:
+        if want_info:
+            info = Info()
+            _check(lib().lbfgsb_step(self._h, C.byref(info)))
+            return info
+        _check(lib().lbfgsb_step(self._h, None))
+        return None
+
+    def solve(self) -> Info:
+        info = Info()
+        _check(lib().lbfgsb_solve(self._h, C.byref(info)))
+        return info
+
+    def info(self) -> Info:
+        info = Info()
+        _check(lib().lbfgsb_get_info(self._h, C.byref(info)))
+        return info
+
+    def x(self):
+        import torch
+        out = torch.empty(self.n, dtype=torch.float64, device=self.device)
+        _check(lib().lbfgsb_get_x(self._h, out.data_ptr()))
+        return out
+
+    def g(self):
+        import torch
+        out = torch.empty(self.n, dtype=torch.float64, device=self.device)
+        _check(lib().lbfgsb_get_g(self._h, out.data_ptr()))
+        return out
+
+    # -- timing of the A pass
+    def enable_apass_timing(self, enable: bool = True) -> None:
+        _check(lib().lbfgsb_enable_apass_timing(self._h, int(enable)))
+
+    def apass_timing(self):
+        """(launches timed, total milliseconds, bytes of A one launch reads)"""
+        cnt, ms, by = C.c_int64(0), C.c_double(0.0), C.c_double(0.0)
+        _check(lib().lbfgsb_apass_timing(self._h, C.byref(cnt), C.byref(ms), C.byref(by)))
+        return cnt.value, ms.value, by.value
+
+    @property
+    def apass_name(self) -> str:
+        return lib().lbfgsb_apass_name(self._h).decode()
+
+    # -- primitive-level hooks
+    def dbg_fg(self, x, want_rowvec: bool = False):
+        import torch
+        g = torch.empty(self.n, dtype=torch.float64, device=self.device)
+        row = torch.empty(self.rows, dtype=torch.float64, device=self.device) if want_rowvec else None
+        f = C.c_double(0.0)
+        _check(lib().lbfgsb_dbg_fg(self._h, _dev_f64(x, "x", self.n).data_ptr(), C.byref(f), g.data_ptr(),
+                                   row.data_ptr() if row is not None else None))
+        return (f.value, g, row) if want_rowvec else (f.value, g)
+
+    def dbg_free_mask(self, x, g):
+        import torch
+        mask = torch.empty(self.n, dtype=torch.uint8, device=self.device)
+        _check(lib().lbfgsb_dbg_free_mask(self._h, _dev_f64(x, "x", self.n).data_ptr(),
+                                          _dev_f64(g, "g", self.n).data_ptr(), mask.data_ptr()))
+        return mask
+
+    def dbg_two_loop(self, S, Y, ynorm2, g, mask):
+        import torch
+        npairs = 0 if S is None else S.shape[0]
+        d = torch.empty(self.n, dtype=torch.float64, device=self.device)
+        used = C.c_int(0)
+        if not (mask.is_cuda and mask.dtype == torch.uint8 and mask.is_contiguous() and mask.numel() == self.n):
+            raise TypeError("mask must be a contiguous uint8 CUDA tensor with n entries")
+        sp = _dev_f64(S, "S", npairs * self.n).data_ptr() if npairs else None
+        yp = _dev_f64(Y, "Y", npairs * self.n).data_ptr() if npairs else None
+        np_ = _dev_f64(ynorm2, "ynorm2", npairs).data_ptr() if npairs else None
+        _check(lib().lbfgsb_dbg_two_loop(self._h, sp, yp, np_, npairs, _dev_f64(g, "g", self.n).data_ptr(),
+                                         mask.data_ptr(), d.data_ptr(), C.byref(used)))
+        return d, used.value
+
+    def dbg_project_direction(self, x, g, d):
+        import torch
+        p = torch.empty(self.n, dtype=torch.float64, device=self.device)
+        br, ub = C.c_int(0), C.c_double(0.0)
+        _check(lib().lbfgsb_dbg_project_direction(self._h, _dev_f64(x, "x", self.n).data_ptr(),
+                                                  _dev_f64(g, "g", self.n).data_ptr(),
+                                                  _dev_f64(d, "d", self.n).data_ptr(), p.data_ptr(), C.byref(br),
+                                                  C.byref(ub)))
+        return p, br.value, ub.value
+
+
+def solver_for_problem(prob, device="cuda:0", **option_overrides) -> Solver:
+    """Uploads a workloads.Problem and creates a solver positioned at its x0."""
+    import torch
+    dev = torch.device(device)
+    A = torch.from_numpy(prob.A).to(dev)
+    b = torch.from_numpy(prob.b).to(dev)
+    l = torch.from_numpy(prob.l).to(dev)
+    u = torch.from_numpy(prob.u).to(dev)
+    opts = default_options(tol=prob.tol, tol_relative=int(prob.tol_relative))
+    for k, v in option_overrides.items():
+        if not hasattr(opts, k):
+            raise AttributeError(k)
+        setattr(opts, k, v)
+    s = Solver(prob.kind, A, b, l, u, prob.m, lam=prob.lam, mu=prob.mu, options=opts)
+    s.set_x(torch.from_numpy(prob.x0).to(dev))
+    return s

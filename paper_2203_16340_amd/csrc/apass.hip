@@ -1,0 +1,194 @@
+// Products with the data matrix A (row-major, rows x cols): the only O(rows*cols) work of an
+// iteration, and HBM-bandwidth bound (2 flops per element read).
+//
+// Two organisations:
+//   two-pass : k_gemv  (u = A v, one wave per group of rows, lanes stride over the columns with
+//              16-byte loads, fp64 accumulation) applies the per-row operation of the objective
+//              and leaves per-row weights psi; k_gemvt (w = A^T psi, threads own columns, row
+//              blocks produce partial columns) reads A a second time.
+//   fused    : see fused.hip -- a workgroup owns whole rows, keeps them in registers between the
+//              row dot product and the transposed accumulation, so A is read once.
+//
+// The per-row operations (RowMode) are what "compute f and grad f" of Algorithm 1 means for the
+// three objectives, and the t = A p needed by the closed-form line search of the quadratic ones.
+#include "common.h"
+
+namespace lb {
+
+template <typename T, int VEC>
+struct Loader;
+template <>
+struct Loader<float, 4> {
+    static __device__ __forceinline__ void load(const float* p, double (&o)[4]) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+};
+template <>
+struct Loader<double, 2> {
+    static __device__ __forceinline__ void load(const double* p, double (&o)[2]) {
+        const double2 v = *reinterpret_cast<const double2*>(p);
+        o[0] = v.x; o[1] = v.y;
+    }
+};
+template <typename T>
+struct Loader<T, 1> {
+    static __device__ __forceinline__ void load(const T* p, double (&o)[1]) { o[0] = (double)*p; }
+};
+
+// Resolves the vector A multiplies: either fixed pointers, or the direction Algorithm 2 selected.
+__device__ __forceinline__ void resolve_v(const APassArgs& a, const Scal* scal, int64_t cols, const double*& va,
+                                          const double*& vb) {
+    va = a.va;
+    vb = a.vb;
+    if (a.select_p) {
+        va = scal->branch == 1 ? a.p1 : a.p2;
+        vb = a.split ? va + cols : nullptr;
+    }
+}
+
+// The objective's per-row operation on u = a_r . v.  Returns the row's loss contribution.
+__device__ __forceinline__ double row_op(int mode, double u, int64_t r, int64_t rows, const double* __restrict__ b,
+                                         double* __restrict__ row, double* __restrict__ t,
+                                         double* __restrict__ psi) {
+    switch (mode) {
+        case kRowLsqEval: {
+            const double res = u - b[r];
+            row[r] = res;
+            psi[r] = res;
+            return 0.5 * res * res;
+        }
+        case kRowDir:
+            t[r] = u;
+            return u * u;
+        case kRowLogiEval: {
+            const double y = b[r];
+            const double a = -y * u;
+            row[r] = u;
+            psi[r] = -y * sigmoid_d(a) / (double)rows;
+            return softplus_d(a) / (double)rows;
+        }
+        default:  // kRowLogiDir
+            t[r] = u;
+            return 0.0;
+    }
+}
+
+template <typename T, int VEC, int R>
+__global__ __launch_bounds__(kBlock) void k_gemv(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t cols,
+                                                 APassArgs a, const Scal* __restrict__ scal,
+                                                 double* __restrict__ row, double* __restrict__ t,
+                                                 double* __restrict__ psi, double* __restrict__ losspart) {
+    __shared__ double lds[kWaves];
+    if (a.check_status && scal->status != LBFGSB_RUNNING) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const double *va, *vb;
+    resolve_v(a, scal, cols, va, vb);
+    const int64_t nwaves = (int64_t)gridDim.x * kWaves;
+    double loss = 0.0;
+    for (int64_t r0 = ((int64_t)blockIdx.x * kWaves + wave) * R; r0 < rows; r0 += nwaves * R) {
+        double acc[R];
+        const T* rp[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            acc[k] = 0.0;
+            const int64_t rr = r0 + k < rows ? r0 + k : rows - 1;
+            rp[k] = A + rr * ld;
+        }
+#pragma unroll 2
+        for (int64_t c = (int64_t)lane * VEC; c < cols; c += 64 * VEC) {
+            double v[VEC];
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) v[j] = va[c + j];
+            if (vb) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) v[j] -= vb[c + j];
+            }
+#pragma unroll
+            for (int k = 0; k < R; ++k) {
+                double e[VEC];
+                Loader<T, VEC>::load(rp[k] + c, e);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[k] = fma(e[j], v[j], acc[k]);
+            }
+        }
+        double mine = 0.0;   // lane k applies the row operation of row r0 + k
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const double tot = wave_sum(acc[k]);
+            if (lane == k) mine = tot;
+        }
+        if (lane < R && r0 + lane < rows) loss += row_op(a.mode, mine, r0 + lane, rows, a.b, row, t, psi);
+    }
+    double lv[1] = {loss};
+    block_sum<1, kWaves>(lv, lds);
+    if (threadIdx.x == 0) losspart[blockIdx.x] = lv[0];
+}
+
+// w = A^T psi: threads own VEC adjacent columns, a workgroup covers kBlock*VEC columns and a
+// block of rows; partial columns go to wpart[row_block][c] and are summed (in row-block order)
+// by the kernel that consumes w.
+template <typename T, int VEC>
+__global__ __launch_bounds__(kBlock) void k_gemvt(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t cols,
+                                                  const double* __restrict__ psi, double* __restrict__ wpart,
+                                                  int64_t rows_per_block, const Scal* __restrict__ scal,
+                                                  int check_status) {
+    if (check_status && scal->status != LBFGSB_RUNNING) return;
+    const int64_t c = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+    if (c >= cols) return;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    const int64_t r1 = r0 + rows_per_block < rows ? r0 + rows_per_block : rows;
+    double acc[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = 0.0;
+    const T* p = A + r0 * ld + c;
+#pragma unroll 8
+    for (int64_t r = r0; r < r1; ++r, p += ld) {
+        double e[VEC];
+        Loader<T, VEC>::load(p, e);
+        const double w = psi[r];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = fma(e[j], w, acc[j]);
+    }
+    double* out = wpart + (int64_t)blockIdx.y * cols + c;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) out[j] = acc[j];
+}
+
+template <typename T, int VEC>
+static void gemv_dispatch(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL((k_gemv<T, VEC, 4>), dim3(ge.gemv_blocks), dim3(kBlock), 0, st, (const T*)a.A, dm.ld, dm.rows,
+                       dm.cols, a, bf.scal, bf.row, bf.t, bf.psi, bf.losspart);
+}
+
+void launch_gemv(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st) {
+    if (dm.dtype == LBFGSB_F32) {
+        if (ge.vec > 1) gemv_dispatch<float, 4>(dm, ge, bf, a, st);
+        else gemv_dispatch<float, 1>(dm, ge, bf, a, st);
+    } else {
+        if (ge.vec > 1) gemv_dispatch<double, 2>(dm, ge, bf, a, st);
+        else gemv_dispatch<double, 1>(dm, ge, bf, a, st);
+    }
+}
+
+template <typename T, int VEC>
+static void gemvt_dispatch(const Dims& dm, const Geometry& ge, const Buffers& bf, const void* A, const double* psi,
+                           int check_status, hipStream_t st) {
+    hipLaunchKernelGGL((k_gemvt<T, VEC>), dim3(ge.gemvt_col_tiles, ge.gemvt_row_blocks), dim3(kBlock), 0, st,
+                       (const T*)A, dm.ld, dm.rows, dm.cols, psi, bf.wpart, ge.gemvt_rows_per_block, bf.scal,
+                       check_status);
+}
+
+// psi_src: the per-row weights (bf.psi after an evaluation, bf.t after a direction pass).
+void launch_gemvt_from(const Dims& dm, const Geometry& ge, const Buffers& bf, const void* A, const double* psi_src,
+                       int check_status, hipStream_t st) {
+    if (dm.dtype == LBFGSB_F32) {
+        if (ge.vec > 1) gemvt_dispatch<float, 4>(dm, ge, bf, A, psi_src, check_status, st);
+        else gemvt_dispatch<float, 1>(dm, ge, bf, A, psi_src, check_status, st);
+    } else {
+        if (ge.vec > 1) gemvt_dispatch<double, 2>(dm, ge, bf, A, psi_src, check_status, st);
+        else gemvt_dispatch<double, 1>(dm, ge, bf, A, psi_src, check_status, st);
+    }
+}
+
+}  // namespace lb

@@ -1,0 +1,555 @@
+// C-ABI layer of liblbfgsb: argument checks, workspace layout, the fixed kernel sequence of one
+// iteration of Algorithm 1, the polling loop of lbfgsb_solve and the primitive-level hooks.
+// No solver arithmetic happens on the host.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+using namespace lb;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                           \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess) return fail(LBFGSB_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr int kMaxTimed = 4096;
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace
+
+struct lbfgsb_solver {
+    Dims dm;
+    Opts op;
+    lbfgsb_options options;
+    lbfgsb_objective obj;
+    Geometry ge;
+    Buffers bf;
+    hipStream_t stream;
+    Scal* h_scal;            // pinned host copy
+    int use_fused;
+    int steps_since_refresh;
+    bool x_set;
+    // timing
+    bool timing;
+    std::vector<hipEvent_t> ev0, ev1;
+    int timed;
+};
+
+namespace {
+
+bool is_quadratic(int kind) { return kind != LBFGSB_OBJ_LOGISTIC_L2; }
+
+int check_objective(int64_t n, int m, const lbfgsb_objective* o) {
+    if (!o) return fail(LBFGSB_E_INVALID_ARG, "objective is NULL");
+    if (n <= 0) return fail(LBFGSB_E_INVALID_ARG, "n must be positive (got %lld)", (long long)n);
+    if (m <= 0 || m > LBFGSB_MAX_M) return fail(LBFGSB_E_INVALID_ARG, "m must be in 1..%d (got %d)", LBFGSB_MAX_M, m);
+    if (o->kind < LBFGSB_OBJ_LSQ || o->kind > LBFGSB_OBJ_LOGISTIC_L2)
+        return fail(LBFGSB_E_INVALID_ARG, "unknown objective kind %d", o->kind);
+    if (o->dtype != LBFGSB_F64 && o->dtype != LBFGSB_F32) return fail(LBFGSB_E_INVALID_ARG, "unknown dtype %d", o->dtype);
+    if (o->rows <= 0 || o->cols <= 0) return fail(LBFGSB_E_INVALID_ARG, "rows and cols must be positive");
+    if (o->rows > (1ll << 31) - 1 || o->cols > (1ll << 31) - 1) return fail(LBFGSB_E_INVALID_ARG, "rows/cols exceed 2^31-1");
+    if (o->ld < o->cols) return fail(LBFGSB_E_INVALID_ARG, "ld (%lld) < cols (%lld)", (long long)o->ld, (long long)o->cols);
+    const int64_t expect = o->kind == LBFGSB_OBJ_LSQ_L1SPLIT ? 2 * o->cols : o->cols;
+    if (n != expect) return fail(LBFGSB_E_INVALID_ARG, "n = %lld does not match the objective (%lld variables)", (long long)n, (long long)expect);
+    return LBFGSB_OK;
+}
+
+int check_options(const lbfgsb_options* o) {
+    if (!(o->eps >= 0.0) || !(o->armijo_c1 > 0.0 && o->armijo_c1 < 1.0) || !(o->backtrack > 0.0 && o->backtrack < 1.0) ||
+        o->max_backtracks < 0 || !(o->tol >= 0.0) || o->max_iter < 0 || o->refresh_every < 0 || o->poll_every < 1 ||
+        o->a_pass < LBFGSB_APASS_AUTO || o->a_pass > LBFGSB_APASS_FUSED)
+        return fail(LBFGSB_E_INVALID_ARG, "bad option value");
+    return LBFGSB_OK;
+}
+
+Geometry make_geometry(const Dims& dm, const void* A) {
+    Geometry ge{};
+    const int per16 = dm.dtype == LBFGSB_F32 ? 4 : 2;
+    const bool aligned = ((uintptr_t)A % 16 == 0) && (dm.cols % per16 == 0) && (dm.ld % per16 == 0);
+    ge.vec = aligned ? per16 : 1;
+    int64_t gb = (dm.rows + kWaves * 4 - 1) / (kWaves * 4);
+    ge.gemv_blocks = (int)(gb > 2048 ? 2048 : gb);
+    const int64_t cols_per_tile = (int64_t)kBlock * ge.vec;
+    ge.gemvt_col_tiles = (int)((dm.cols + cols_per_tile - 1) / cols_per_tile);
+    int64_t rb = 2048 / ge.gemvt_col_tiles;
+    const int64_t rb_max = (dm.rows + 31) / 32;
+    if (rb > rb_max) rb = rb_max;
+    if (rb > 512) rb = 512;
+    if (rb < 1) rb = 1;
+    ge.gemvt_rows_per_block = (dm.rows + rb - 1) / rb;
+    ge.gemvt_row_blocks = (int)((dm.rows + ge.gemvt_rows_per_block - 1) / ge.gemvt_rows_per_block);
+    ge.fused_ok = fused_shape_ok(dm, A, &ge.fused_variant, &ge.fused_blocks) ? 1 : 0;
+    ge.gram_blocks = gram_blocks_for(dm.n);
+    int64_t db = (dm.n + kBlock - 1) / kBlock;
+    ge.dir_blocks = (int)(db > 256 ? 256 : db);
+    int64_t ub = (dm.cols + 31) / 32;
+    ge.upd_blocks = ge.fin_blocks = (int)(ub > 1024 ? 1024 : ub);
+    int64_t lb_ = (dm.rows + kBlock - 1) / kBlock;
+    ge.ls_blocks = (int)(lb_ > 512 ? 512 : lb_);
+    return ge;
+}
+
+struct Layout {
+    size_t scal, x, g, l, u, d, p1, p2, mask, S, Y, row, t, psi, wpart, losspart, grampart, redpart, lspart, total;
+};
+
+Layout make_layout(const Dims& dm, const Geometry& ge) {
+    Layout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    const size_t nb = (size_t)dm.n * 8, rb = (size_t)dm.rows * 8;
+    L.scal = take(sizeof(Scal));
+    L.x = take(nb); L.g = take(nb); L.l = take(nb); L.u = take(nb); L.d = take(nb); L.p1 = take(nb); L.p2 = take(nb);
+    L.mask = take((size_t)dm.n);
+    L.S = take(nb * dm.m); L.Y = take(nb * dm.m);
+    L.row = take(rb); L.t = take(rb); L.psi = take(rb);
+    int wparts = ge.gemvt_row_blocks;
+    if (ge.fused_ok && ge.fused_blocks > wparts) wparts = ge.fused_blocks;
+    L.wpart = take((size_t)wparts * dm.cols * 8);
+    int lparts = ge.gemv_blocks;
+    if (ge.fused_ok && ge.fused_blocks > lparts) lparts = ge.fused_blocks;
+    if (ge.ls_blocks > lparts) lparts = ge.ls_blocks;
+    L.losspart = take((size_t)lparts * 8);
+    L.grampart = take((size_t)ge.gram_blocks * gram_entries(dm.m) * 8);
+    size_t red = (size_t)ge.dir_blocks * 8;
+    if ((size_t)ge.upd_blocks * 2 > red) red = (size_t)ge.upd_blocks * 2;
+    L.redpart = take(red * 8);
+    L.lspart = take((size_t)ge.ls_blocks * kLsBatch * 8);
+    L.total = off;
+    return L;
+}
+
+Dims make_dims(int64_t n, int m, const lbfgsb_objective* o) {
+    Dims dm{};
+    dm.n = n; dm.rows = o->rows; dm.cols = o->cols; dm.ld = o->ld; dm.m = m; dm.kind = o->kind; dm.dtype = o->dtype;
+    dm.lambda = o->lambda; dm.mu = o->mu;
+    return dm;
+}
+
+hipError_t read_scal(lbfgsb_solver* s) {
+    hipError_t e = hipMemcpyAsync(s->h_scal, s->bf.scal, sizeof(Scal), hipMemcpyDeviceToHost, s->stream);
+    if (e != hipSuccess) return e;
+    return hipStreamSynchronize(s->stream);
+}
+
+// Uploads a fresh scalar block (host template in h_scal) and waits for it.
+hipError_t write_scal(lbfgsb_solver* s) {
+    hipError_t e = hipMemcpyAsync(s->bf.scal, s->h_scal, sizeof(Scal), hipMemcpyHostToDevice, s->stream);
+    if (e != hipSuccess) return e;
+    return hipStreamSynchronize(s->stream);
+}
+
+void fill_info(const Scal& sc, lbfgsb_info* info) {
+    info->status = sc.status; info->iters = sc.iters; info->fevals = sc.fevals; info->f = sc.f;
+    info->pg2 = sc.pg2; info->pginf = sc.pginf; info->n_fixed = sc.n_fixed; info->branch = sc.branch;
+    info->backtracks = sc.backtracks; info->pairs_used = sc.pairs_used; info->memory_resets = sc.memory_resets;
+    info->alpha = sc.alpha; info->alpha_ub = sc.alpha_ub; info->gp = sc.gp;
+}
+
+struct TimedScope {
+    lbfgsb_solver* s;
+    bool on;
+    explicit TimedScope(lbfgsb_solver* s_) : s(s_), on(s_->timing && s_->timed < kMaxTimed) {
+        if (on) (void)hipEventRecord(s->ev0[s->timed], s->stream);
+    }
+    ~TimedScope() {
+        if (on) { (void)hipEventRecord(s->ev1[s->timed], s->stream); s->timed++; }
+    }
+};
+
+APassArgs base_args(const lbfgsb_solver* s) {
+    APassArgs a{};
+    a.A = s->obj.A; a.b = s->obj.b; a.p1 = s->bf.p1; a.p2 = s->bf.p2;
+    a.split = s->dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT;
+    return a;
+}
+
+// f, g (and the residual / margins) from scratch at the current x.
+void enqueue_eval(lbfgsb_solver* s, int check_status) {
+    APassArgs a = base_args(s);
+    a.va = s->bf.x;
+    a.vb = a.split ? s->bf.x + s->dm.cols : nullptr;
+    a.select_p = 0;
+    a.mode = is_quadratic(s->dm.kind) ? kRowLsqEval : kRowLogiEval;
+    a.check_status = check_status;
+    if (s->use_fused) {
+        TimedScope ts(s);
+        launch_fused(s->dm, s->ge, s->bf, a, s->stream);
+    } else {
+        { TimedScope ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream); }
+        { TimedScope ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, check_status, s->stream); }
+    }
+    launch_eval_finish(s->dm, s->ge, s->bf, s->stream);
+}
+
+// One iteration of Algorithm 1 as a fixed sequence of launches; nothing here waits for the device.
+void enqueue_step(lbfgsb_solver* s) {
+    const bool quad = is_quadratic(s->dm.kind);
+    if (quad && s->options.refresh_every > 0 && s->steps_since_refresh >= s->options.refresh_every) {
+        enqueue_eval(s, 1);
+        s->steps_since_refresh = 0;
+    }
+    launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
+    launch_dir(s->dm, s->op, s->ge, s->bf, 0, s->stream);
+    APassArgs a = base_args(s);
+    a.select_p = 1;
+    a.check_status = 1;
+    if (quad) {
+        a.mode = kRowDir;
+        if (s->use_fused) {
+            TimedScope ts(s);
+            launch_fused(s->dm, s->ge, s->bf, a, s->stream);
+        } else {
+            { TimedScope ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream); }
+            { TimedScope ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.t, 1, s->stream); }
+        }
+        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->stream);
+    } else {
+        a.mode = kRowLogiDir;
+        { TimedScope ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream); }
+        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, s->stream);
+        launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
+        { TimedScope ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream); }
+        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.ls_blocks, s->stream);
+    }
+    s->steps_since_refresh++;
+}
+
+void fresh_scal(lbfgsb_solver* s) {
+    std::memset(s->h_scal, 0, sizeof(Scal));
+    s->h_scal->status = LBFGSB_RUNNING;
+    s->h_scal->alpha_ub = 1.0;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lbfgsb_last_error(void) { return g_err.c_str(); }
+
+void lbfgsb_default_options(lbfgsb_options* o) {
+    if (!o) return;
+    o->eps = 1e-10; o->armijo_c1 = 1e-4; o->backtrack = 0.5; o->max_backtracks = 60; o->tol = 1e-8;
+    o->tol_relative = 0; o->max_iter = 1000; o->refresh_every = 32; o->poll_every = 8; o->a_pass = LBFGSB_APASS_AUTO;
+}
+
+size_t lbfgsb_workspace_bytes(int64_t n, int m, const lbfgsb_objective* obj, const lbfgsb_options* opt) {
+    (void)opt;
+    if (check_objective(n, m, obj) != LBFGSB_OK) return 0;
+    const Dims dm = make_dims(n, m, obj);
+    const Geometry ge = make_geometry(dm, obj->A);
+    return make_layout(dm, ge).total;
+}
+
+int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const double* u, const lbfgsb_objective* obj,
+                  const lbfgsb_options* opt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail(LBFGSB_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int rc = check_objective(n, m, obj);
+    if (rc) return rc;
+    if (!l || !u || !obj->A || !obj->b || !workspace) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
+    lbfgsb_options o;
+    if (opt) o = *opt; else lbfgsb_default_options(&o);
+    rc = check_options(&o);
+    if (rc) return rc;
+    if ((uintptr_t)workspace % 256) return fail(LBFGSB_E_INVALID_ARG, "workspace must be 256-byte aligned");
+    const int esz = obj->dtype == LBFGSB_F32 ? 4 : 8;
+    if ((uintptr_t)obj->A % esz || (uintptr_t)obj->b % 8 || (uintptr_t)l % 8 || (uintptr_t)u % 8)
+        return fail(LBFGSB_E_INVALID_ARG, "misaligned device pointer");
+
+    lbfgsb_solver* s = new (std::nothrow) lbfgsb_solver();
+    if (!s) return fail(LBFGSB_E_INVALID_ARG, "out of host memory");
+    s->dm = make_dims(n, m, obj);
+    s->options = o;
+    s->op = Opts{o.eps, o.armijo_c1, o.backtrack, o.tol, o.max_backtracks, o.tol_relative, o.max_iter};
+    s->obj = *obj;
+    s->ge = make_geometry(s->dm, obj->A);
+    s->stream = (hipStream_t)hip_stream;
+    s->h_scal = nullptr;
+    s->steps_since_refresh = 0;
+    s->x_set = false;
+    s->timing = false;
+    s->timed = 0;
+    const Layout L = make_layout(s->dm, s->ge);
+    if (workspace_bytes < L.total) {
+        delete s;
+        return fail(LBFGSB_E_INVALID_ARG, "workspace too small: %zu < %zu bytes", workspace_bytes, L.total);
+    }
+    const bool quad = is_quadratic(s->dm.kind);
+    if (o.a_pass == LBFGSB_APASS_FUSED && !(s->ge.fused_ok && quad)) {
+        delete s;
+        return fail(LBFGSB_E_UNSUPPORTED, "the fused A pass does not support this objective/shape");
+    }
+    s->use_fused = quad && s->ge.fused_ok && o.a_pass != LBFGSB_APASS_TWO_PASS;
+    s->ge.w_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemvt_row_blocks;
+    s->ge.loss_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemv_blocks;
+
+    char* w = (char*)workspace;
+    Buffers& b = s->bf;
+    b.scal = (Scal*)(w + L.scal);
+    b.x = (double*)(w + L.x); b.g = (double*)(w + L.g); b.l = (double*)(w + L.l); b.u = (double*)(w + L.u);
+    b.d = (double*)(w + L.d); b.p1 = (double*)(w + L.p1); b.p2 = (double*)(w + L.p2);
+    b.mask = (uint8_t*)(w + L.mask);
+    b.S = (double*)(w + L.S); b.Y = (double*)(w + L.Y);
+    b.row = (double*)(w + L.row); b.t = (double*)(w + L.t); b.psi = (double*)(w + L.psi);
+    b.wpart = (double*)(w + L.wpart); b.losspart = (double*)(w + L.losspart);
+    b.grampart = (double*)(w + L.grampart); b.redpart = (double*)(w + L.redpart); b.lspart = (double*)(w + L.lspart);
+
+    auto bail = [&](int code) { lbfgsb_destroy(s); return code; };
+    {
+        hipError_t e = hipHostMalloc((void**)&s->h_scal, sizeof(Scal), hipHostMallocDefault);
+        if (e != hipSuccess) { s->h_scal = nullptr; return bail(fail(LBFGSB_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e))); }
+    }
+    // validate the bounds on the host
+    std::vector<double> hl((size_t)n), hu((size_t)n);
+    hipError_t e = hipMemcpyAsync(hl.data(), l, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(hu.data(), u, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(s->stream);
+    if (e != hipSuccess) return bail(fail(LBFGSB_E_HIP, "reading the bounds: %s", hipGetErrorString(e)));
+    for (int64_t i = 0; i < n; ++i)
+        if (!(hl[(size_t)i] <= hu[(size_t)i]))
+            return bail(fail(LBFGSB_E_BOUNDS, "bounds cross or are NaN at index %lld (l = %g, u = %g)", (long long)i,
+                             hl[(size_t)i], hu[(size_t)i]));
+    // the workspace starts from all-zero memory (fill kernel: no memset node ever enters a captured graph)
+    launch_fill_zero(workspace, L.total, s->stream);
+    e = hipMemcpyAsync(b.l, l, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(b.u, u, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(s->stream);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) return bail(fail(LBFGSB_E_HIP, "initialising the workspace: %s", hipGetErrorString(e)));
+    *out = s;
+    return LBFGSB_OK;
+}
+
+void lbfgsb_destroy(lbfgsb_solver* s) {
+    if (!s) return;
+    for (hipEvent_t ev : s->ev0) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : s->ev1) (void)hipEventDestroy(ev);
+    if (s->h_scal) (void)hipHostFree(s->h_scal);
+    delete s;
+}
+
+int lbfgsb_set_x(lbfgsb_solver* s, const double* x0) {
+    if (!s || !x0) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    const int64_t n = s->dm.n;
+    std::vector<double> hx((size_t)n), hl((size_t)n), hu((size_t)n);
+    HIP_TRY(hipMemcpyAsync(hx.data(), x0, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
+    HIP_TRY(hipMemcpyAsync(hl.data(), s->bf.l, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
+    HIP_TRY(hipMemcpyAsync(hu.data(), s->bf.u, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    for (int64_t i = 0; i < n; ++i) {
+        const double v = hx[(size_t)i];
+        if (!(v >= hl[(size_t)i]) || !(v <= hu[(size_t)i]))
+            return fail(LBFGSB_E_INFEASIBLE_X0, "x0[%lld] = %g is outside [%g, %g]", (long long)i, v, hl[(size_t)i],
+                        hu[(size_t)i]);
+    }
+    HIP_TRY(hipMemcpyAsync(s->bf.x, x0, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream));
+    fresh_scal(s);
+    HIP_TRY(write_scal(s));
+    enqueue_eval(s, 0);
+    s->steps_since_refresh = 0;
+    HIP_TRY(hipMemcpyAsync(hx.data(), s->bf.g, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
+    HIP_TRY(read_scal(s));
+    HIP_TRY(hipGetLastError());
+    bool finite = std::isfinite(s->h_scal->f);
+    for (int64_t i = 0; finite && i < n; ++i) finite = std::isfinite(hx[(size_t)i]);
+    if (!finite) { s->x_set = false; return fail(LBFGSB_E_NONFINITE, "f or grad f is not finite at x0"); }
+    s->x_set = true;
+    return LBFGSB_OK;
+}
+
+int lbfgsb_step(lbfgsb_solver* s, lbfgsb_info* info) {
+    if (!s) return fail(LBFGSB_E_INVALID_ARG, "solver is NULL");
+    if (!s->x_set) return fail(LBFGSB_E_INVALID_ARG, "lbfgsb_set_x has not been called");
+    enqueue_step(s);
+    if (info) {
+        HIP_TRY(read_scal(s));
+        HIP_TRY(hipGetLastError());
+        fill_info(*s->h_scal, info);
+    }
+    return LBFGSB_OK;
+}
+
+int lbfgsb_solve(lbfgsb_solver* s, lbfgsb_info* info) {
+    if (!s) return fail(LBFGSB_E_INVALID_ARG, "solver is NULL");
+    if (!s->x_set) return fail(LBFGSB_E_INVALID_ARG, "lbfgsb_set_x has not been called");
+    const bool quad = is_quadratic(s->dm.kind);
+    const long long cap = 2ll * s->options.max_iter + 64;   // accepted iterations + memory-reset retries
+    long long steps = 0;
+    for (;;) {
+        for (int k = 0; k < s->options.poll_every; ++k) enqueue_step(s);
+        steps += s->options.poll_every;
+        HIP_TRY(read_scal(s));
+        int st = s->h_scal->status;
+        if (st == LBFGSB_CONVERGED && quad && s->steps_since_refresh > 0 && s->h_scal->iters > 0) {
+            // the stopping quantity was computed from a gradient carried by recurrence: recompute
+            // residual and gradient from x and test again before declaring convergence
+            launch_set_status(s->bf, LBFGSB_RUNNING, s->stream);
+            enqueue_eval(s, 0);
+            s->steps_since_refresh = 0;
+            launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
+            HIP_TRY(read_scal(s));
+            st = s->h_scal->status;
+        }
+        if (st != LBFGSB_RUNNING) break;
+        if (steps >= cap) break;
+    }
+    HIP_TRY(hipGetLastError());
+    if (info) fill_info(*s->h_scal, info);
+    return LBFGSB_OK;
+}
+
+int lbfgsb_get_info(lbfgsb_solver* s, lbfgsb_info* info) {
+    if (!s || !info) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    HIP_TRY(read_scal(s));
+    fill_info(*s->h_scal, info);
+    return LBFGSB_OK;
+}
+
+int lbfgsb_get_x(lbfgsb_solver* s, double* x_out) {
+    if (!s || !x_out) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    HIP_TRY(hipMemcpyAsync(x_out, s->bf.x, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
+    return LBFGSB_OK;
+}
+
+int lbfgsb_get_g(lbfgsb_solver* s, double* g_out) {
+    if (!s || !g_out) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    HIP_TRY(hipMemcpyAsync(g_out, s->bf.g, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
+    return LBFGSB_OK;
+}
+
+int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable) {
+    if (!s) return fail(LBFGSB_E_INVALID_ARG, "solver is NULL");
+    if (enable && s->ev0.empty()) {
+        s->ev0.resize(kMaxTimed);
+        s->ev1.resize(kMaxTimed);
+        for (int i = 0; i < kMaxTimed; ++i) {
+            HIP_TRY(hipEventCreate(&s->ev0[i]));
+            HIP_TRY(hipEventCreate(&s->ev1[i]));
+        }
+    }
+    s->timing = enable != 0;
+    s->timed = 0;
+    return LBFGSB_OK;
+}
+
+int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count, double* total_ms, double* bytes_per_pass) {
+    if (!s || !count || !total_ms || !bytes_per_pass) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    double tot = 0.0;
+    for (int i = 0; i < s->timed; ++i) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, s->ev0[i], s->ev1[i]));
+        tot += ms;
+    }
+    *count = s->timed;
+    *total_ms = tot;
+    *bytes_per_pass = (double)s->dm.rows * (double)s->dm.cols * (s->dm.dtype == LBFGSB_F32 ? 4.0 : 8.0);
+    return LBFGSB_OK;
+}
+
+const char* lbfgsb_apass_name(const lbfgsb_solver* s) { return s && s->use_fused ? "fused" : "two_pass"; }
+
+// ---- primitive-level hooks ------------------------------------------------------------------------------
+
+int lbfgsb_dbg_fg(lbfgsb_solver* s, const double* x, double* f_host, double* g, double* rowvec) {
+    if (!s || !x || !f_host || !g) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    s->x_set = false;
+    HIP_TRY(hipMemcpyAsync(s->bf.x, x, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
+    fresh_scal(s);
+    HIP_TRY(write_scal(s));
+    enqueue_eval(s, 0);
+    HIP_TRY(hipMemcpyAsync(g, s->bf.g, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
+    if (rowvec) HIP_TRY(hipMemcpyAsync(rowvec, s->bf.row, (size_t)s->dm.rows * 8, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(read_scal(s));
+    HIP_TRY(hipGetLastError());
+    *f_host = s->h_scal->f;
+    return LBFGSB_OK;
+}
+
+int lbfgsb_dbg_free_mask(lbfgsb_solver* s, const double* x, const double* g, uint8_t* mask) {
+    if (!s || !x || !g || !mask) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    s->x_set = false;
+    HIP_TRY(hipMemcpyAsync(s->bf.x, x, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(hipMemcpyAsync(s->bf.g, g, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
+    fresh_scal(s);
+    HIP_TRY(write_scal(s));
+    launch_gram(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream);
+    HIP_TRY(hipMemcpyAsync(mask, s->bf.mask, (size_t)s->dm.n, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    HIP_TRY(hipGetLastError());
+    return LBFGSB_OK;
+}
+
+int lbfgsb_dbg_two_loop(lbfgsb_solver* s, const double* S, const double* Y, const double* ynorm2, int npairs,
+                        const double* g, const uint8_t* mask, double* d, int* pairs_used) {
+    if (!s || !g || !mask || !d) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    if (npairs < 0 || npairs > s->dm.m) return fail(LBFGSB_E_INVALID_ARG, "npairs must be in 0..m");
+    if (npairs > 0 && (!S || !Y || !ynorm2)) return fail(LBFGSB_E_INVALID_ARG, "NULL pair arrays");
+    s->x_set = false;
+    const size_t nb = (size_t)s->dm.n * 8;
+    fresh_scal(s);
+    if (npairs > 0) {
+        HIP_TRY(hipMemcpyAsync(s->bf.S, S, nb * npairs, hipMemcpyDeviceToDevice, s->stream));
+        HIP_TRY(hipMemcpyAsync(s->bf.Y, Y, nb * npairs, hipMemcpyDeviceToDevice, s->stream));
+        HIP_TRY(hipMemcpyAsync(s->h_scal->ynorm2, ynorm2, (size_t)npairs * 8, hipMemcpyDeviceToHost, s->stream));
+        HIP_TRY(hipStreamSynchronize(s->stream));
+    }
+    s->h_scal->count = npairs;
+    s->h_scal->head = npairs % s->dm.m;
+    HIP_TRY(write_scal(s));
+    HIP_TRY(hipMemcpyAsync(s->bf.g, g, nb, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(hipMemcpyAsync(s->bf.mask, mask, (size_t)s->dm.n, hipMemcpyDeviceToDevice, s->stream));
+    launch_gram(s->dm, s->op, s->ge, s->bf, 1, 0, s->stream);
+    launch_dir(s->dm, s->op, s->ge, s->bf, 0, s->stream);
+    HIP_TRY(hipMemcpyAsync(d, s->bf.d, nb, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(read_scal(s));
+    HIP_TRY(hipGetLastError());
+    if (pairs_used) *pairs_used = s->h_scal->pairs_used;
+    return LBFGSB_OK;
+}
+
+int lbfgsb_dbg_project_direction(lbfgsb_solver* s, const double* x, const double* g, const double* d, double* p,
+                                 int* branch, double* alpha_ub) {
+    if (!s || !x || !g || !d || !p) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    s->x_set = false;
+    const size_t nb = (size_t)s->dm.n * 8;
+    HIP_TRY(hipMemcpyAsync(s->bf.x, x, nb, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(hipMemcpyAsync(s->bf.g, g, nb, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(hipMemcpyAsync(s->bf.d, d, nb, hipMemcpyDeviceToDevice, s->stream));
+    fresh_scal(s);
+    HIP_TRY(write_scal(s));
+    launch_dir(s->dm, s->op, s->ge, s->bf, 1, s->stream);
+    HIP_TRY(read_scal(s));
+    HIP_TRY(hipGetLastError());
+    const int br = s->h_scal->branch;
+    HIP_TRY(hipMemcpyAsync(p, br == 1 ? s->bf.p1 : s->bf.p2, nb, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    if (branch) *branch = br;
+    if (alpha_ub) *alpha_ub = s->h_scal->alpha_ub;
+    return LBFGSB_OK;
+}
+
+}  // extern "C"

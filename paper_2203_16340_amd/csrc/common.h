@@ -1,0 +1,212 @@
+// Shared declarations of the HIP implementation: device-resident solver state, reduction
+// helpers, and the launchers each translation unit exports to the C-ABI layer.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lbfgsb.h"
+
+namespace lb {
+
+constexpr int kMaxM = LBFGSB_MAX_M;
+constexpr int kMaxV = 64;          // 2*m + 1 <= 64 vectors enter the batched two-loop
+constexpr int kBlock = 256;        // threads per workgroup of every vector kernel (4 waves of 64)
+constexpr int kWaves = kBlock / 64;
+constexpr int kLsBatch = 8;        // step lengths the logistic line search evaluates per sweep over the rows
+
+// Which per-kernel arrival counter (Scal::counters) a kernel uses to find its last workgroup.
+enum { kCntGram = 0, kCntDir, kCntUpdate, kCntEvalFinish, kCntLs, kCntCount };
+
+// All scalars of the iteration live here, in device memory, so that no data-dependent decision
+// needs the host.  Only the last workgroup of a kernel to finish ever writes it; every other
+// workgroup has read what it needs before it signals arrival.
+struct Scal {
+    int status;             // LBFGSB_RUNNING ...
+    int head;               // ring slot the next pair is written to
+    int count;              // stored pairs (<= m)
+    int branch;             // Algorithm 2 branch of the current direction (1 or 2)
+    int tol_resolved;       // tol_abs has been fixed (first free-set evaluation after set_x)
+    int backtracks;
+    int pairs_used;
+    int memory_resets;
+    int ls_ok;              // the last line search found an acceptable step
+    int pad0;
+    long long iters;
+    long long fevals;
+    long long n_fixed;
+    double f;
+    double gp;              // <g, p> for the selected p
+    double alpha_ub;        // step bound for the selected p
+    double alpha;           // accepted step
+    double pg2, pginf, tol_abs;
+    double xp, pp;          // <x, p>, <p, p> for the selected p (separable terms of the line search)
+    double ynorm2[kMaxM + 1];   // ||y||^2 over the full vector, per ring slot
+    double delta[kMaxV];        // coefficients of q = sum_j delta_j b_j in the batched two-loop
+    unsigned counters[kCntCount];
+};
+
+struct Dims {
+    int64_t n, rows, cols, ld;
+    int m, kind, dtype;
+    double lambda, mu;
+};
+
+struct Opts {
+    double eps, c1, backtrack, tol;
+    int max_backtracks, tol_relative, max_iter;
+};
+
+// ---- reductions ---------------------------------------------------------------------------------
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ double wave_min(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmin(v, __shfl_xor(v, o));
+    return v;
+}
+
+// Sum of K values over a workgroup of NW waves; every thread gets the totals.  The order of the
+// additions is fixed (butterfly inside a wave, waves in index order), so results are bit-reproducible.
+template <int K, int NW>
+__device__ __forceinline__ void block_sum(double (&v)[K], double* lds /* NW*K doubles */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int k = 0; k < K; ++k) v[k] = wave_sum(v[k]);
+    __syncthreads();   // protect lds against readers of a previous use
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) lds[wave * K + k] = v[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) t += lds[w * K + k];
+        v[k] = t;
+    }
+}
+
+// Signals that this workgroup's partial results are in memory and tells whether it is the last
+// one of the grid to do so.  The last workgroup then sees every other workgroup's partials
+// (release fence + relaxed device-scope atomic + acquire fence) and resets the counter for the
+// next launch.  Must be called by all threads of the workgroup.
+__device__ __forceinline__ bool arrive_is_last(unsigned* counter, int* lds_flag) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned total = gridDim.x * gridDim.y;
+        unsigned old = atomicAdd(counter, 1u);
+        *lds_flag = (old == total - 1u);
+    }
+    __syncthreads();
+    const bool last = *lds_flag != 0;
+    if (last) {
+        __threadfence();
+        if (threadIdx.x == 0) *counter = 0u;
+    }
+    return last;
+}
+
+__device__ __forceinline__ double clampd(double v, double lo, double hi) {
+    return v < lo ? lo : (v > hi ? hi : v);
+}
+
+__device__ __forceinline__ double softplus_d(double t) { return fmax(t, 0.0) + log1p(exp(-fabs(t))); }
+__device__ __forceinline__ double sigmoid_d(double t) {
+    if (t >= 0.0) return 1.0 / (1.0 + exp(-t));
+    const double e = exp(t);
+    return e / (1.0 + e);
+}
+
+// ---- launch geometry decided once at creation -------------------------------------------------------
+
+struct Geometry {
+    // two-pass A kernels
+    int gemv_blocks;        // workgroups of the row-dot kernel (each writes one loss partial)
+    int gemvt_col_tiles;    // column tiles of the transposed kernel
+    int gemvt_row_blocks;   // row blocks of the transposed kernel = partial vectors per column
+    int64_t gemvt_rows_per_block;
+    int vec;                // elements per 16-byte load (1 if alignment forbids vector loads)
+    // fused A kernel
+    int fused_ok;           // shape fits the fused kernel
+    int fused_variant;      // index into the instantiation table
+    int fused_blocks;       // workgroups = partial vectors per column and loss partials
+    // vector kernels
+    int gram_blocks, dir_blocks, upd_blocks, fin_blocks, ls_blocks;
+    // partial counts consumers have to sum
+    int w_parts;            // partial vectors per column written by the A pass in use
+    int loss_parts;         // loss partials written by the A pass in use
+};
+
+// Device arrays carved out of the caller's workspace.
+struct Buffers {
+    Scal* scal;
+    double *x, *g, *l, *u, *d, *p1, *p2;
+    uint8_t* mask;
+    double *S, *Y;          // m x n rings
+    double *row;            // residual A v - b (least squares) or margins (logistic), rows entries
+    double *t;              // A p, rows entries
+    double *psi;            // per-row weights of the transposed product, rows entries
+    double *wpart;          // w_parts x cols partial columns of A^T psi
+    double *losspart;       // loss partials of the A pass
+    double *grampart;       // gram_blocks x gram_entries
+    double *redpart;        // partials of the direction / update / finish kernels
+    double *lspart;         // ls_blocks x kLsBatch
+};
+
+// ---- launchers (defined in apass.hip / vec.hip) -------------------------------------------------------
+
+enum RowMode {
+    kRowLsqEval = 0,   // u = a_r.v; res = u - b_r -> row, psi; loss += 0.5 res^2
+    kRowDir = 1,       // u = a_r.v -> t, psi;            loss += u^2
+    kRowLogiEval = 2,  // u = a_r.v -> row (margin); psi = -y sigma(-y u)/rows; loss += softplus(-y u)/rows
+    kRowLogiDir = 3    // u = a_r.v -> t only (no transposed product follows)
+};
+
+struct APassArgs {
+    const void* A;
+    const double* b;
+    const double* va;       // v = va[c] - (vb ? vb[c] : 0)
+    const double* vb;
+    const double* p1;       // when select_p != 0: va/vb are taken from p1 or p2 according to Scal::branch
+    const double* p2;
+    int select_p;
+    int split;              // L1SPLIT: vb = va + cols
+    int mode;               // RowMode
+    int check_status;       // skip all work unless Scal::status == RUNNING
+};
+
+void launch_gemv(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st);
+// w partials = A^T psi_src (psi_src: Buffers::psi after an evaluation, Buffers::t after a direction pass)
+void launch_gemvt_from(const Dims& dm, const Geometry& ge, const Buffers& bf, const void* A, const double* psi_src,
+                       int check_status, hipStream_t st);
+bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks);
+void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st);
+
+void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+void launch_set_status(const Buffers& bf, int status, hipStream_t st);
+void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, hipStream_t st);
+void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int use_given_mask,
+                 int evaluate_stop, hipStream_t st);
+void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st);
+void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, hipStream_t st);
+void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
+                        hipStream_t st);
+void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* labels, hipStream_t st);
+void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, hipStream_t st);
+
+int gram_entries(int m);          // doubles per workgroup partial of the Gram kernel
+int gram_blocks_for(int64_t n);
+
+}  // namespace lb

@@ -1,0 +1,247 @@
+"""Parity of each per-iteration primitive of the HIP path with the CPU oracle on identical
+injected inputs, through the C-ABI hooks (lbfgsb_dbg_*).
+
+Tolerances (normwise relative, ||got - ref||_2 / ||ref||_2): 1e-12 for fp64-stored matrices and
+for everything that does not touch the matrix, 1e-5 for fp32-stored matrices.  Index and mask
+results are compared bit-exactly.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2203_16340_amd as L
+import workloads
+from gpu_helpers import DEV, make_solver, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL64, TOL32 = 1e-12, 1e-5
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _solver_or_skip(*args, **kw):
+    try:
+        return make_solver(*args, **kw)
+    except L.LbfgsbError as e:
+        if e.code == L.E_UNSUPPORTED:
+            pytest.skip("shape not supported by the fused A pass")
+        raise
+
+
+# ---- objective value, gradient, residual ----------------------------------------------------------
+
+FG_SHAPES = [
+    # rows, cols: several row groups / column tiles plus ragged tails; odd cols force scalar loads
+    (1, 1), (3, 2), (37, 5), (200, 100), (1037, 517), (1037, 520), (777, 2048), (4099, 1030), (300, 5000),
+]
+
+
+@pytest.mark.parametrize("a_pass", [L.APASS_TWO_PASS, L.APASS_FUSED], ids=["two_pass", "fused"])
+@pytest.mark.parametrize("dtype", [np.float64, np.float32], ids=["f64", "f32"])
+@pytest.mark.parametrize("kind", [L.OBJ_LSQ, L.OBJ_LSQ_L1SPLIT, L.OBJ_LOGISTIC_L2], ids=["lsq", "l1split", "logistic"])
+@pytest.mark.parametrize("rows,cols", FG_SHAPES)
+def test_fg_parity(rows, cols, kind, dtype, a_pass):
+    if a_pass == L.APASS_FUSED and kind == L.OBJ_LOGISTIC_L2:
+        pytest.skip("the fused pass serves the quadratic objectives")
+    rng = np.random.default_rng(rows * 7919 + cols * 31 + kind)
+    A = rng.standard_normal((rows, cols)).astype(dtype)
+    if kind == L.OBJ_LOGISTIC_L2:
+        b = np.where(rng.random(rows) < 0.5, -1.0, 1.0)
+    else:
+        b = rng.standard_normal(rows)
+    n = 2 * cols if kind == L.OBJ_LSQ_L1SPLIT else cols
+    lam, mu = 0.3, 0.01
+    x = rng.standard_normal(n)
+    l = np.full(n, -np.inf); u = np.full(n, np.inf)
+    s = _solver_or_skip(kind, A, b, l, u, 3, lam=lam, mu=mu, a_pass=a_pass)
+    f, g, row = s.dbg_fg(to_dev(x), want_rowvec=True)
+    torch.cuda.synchronize()
+    obj = oracle.Objective(kind, A, b, lam, mu)
+    f_ref, g_ref, row_ref = oracle.fg(obj, x, want_rowvec=True)
+    tol = TOL64 if dtype == np.float64 else TOL32
+    assert abs(f - f_ref) <= tol * abs(f_ref)
+    assert rel_err(g.cpu().numpy(), g_ref) <= tol
+    assert rel_err(row.cpu().numpy(), row_ref) <= tol
+    # fp32 storage still accumulates in fp64: far tighter than the stated bound
+    assert rel_err(g.cpu().numpy(), g_ref) <= 1e-11
+    s.close()
+
+
+@pytest.mark.parametrize("a_pass", [L.APASS_TWO_PASS, L.APASS_FUSED], ids=["two_pass", "fused"])
+def test_fg_with_leading_dimension_and_split(a_pass):
+    rng = np.random.default_rng(4)
+    big = rng.standard_normal((333, 260))
+    A_dev = to_dev(big)[:, :250]                         # ld = 260 > cols = 250
+    b = rng.standard_normal(333)
+    x = rng.standard_normal(500)
+    s = _solver_or_skip(L.OBJ_LSQ_L1SPLIT, A_dev, b, np.zeros(500), np.full(500, np.inf), 4, lam=0.7, a_pass=a_pass)
+    f, g = s.dbg_fg(to_dev(x))
+    obj = oracle.Objective(oracle.LSQ_L1SPLIT, np.ascontiguousarray(big[:, :250]), b, lam=0.7)
+    f_ref, g_ref = oracle.fg(obj, x)
+    assert abs(f - f_ref) <= TOL64 * abs(f_ref) and rel_err(g.cpu().numpy(), g_ref) <= TOL64
+    s.close()
+
+
+# ---- Eq. (ws) --------------------------------------------------------------------------------------
+
+def _tiny_solver(n, l, u, m=3, **opts):
+    """A solver whose matrix is a single zero row: the hooks under test never touch it."""
+    return make_solver(L.OBJ_LSQ, np.zeros((1, n)), np.zeros(1), l, u, m, **opts)
+
+
+def test_free_mask_truth_table_bit_exact():
+    cases = []
+    with open(os.path.join(GOLDEN, "free_set_truth_table.txt")) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if line:
+                cases.append([float(t) for t in line.split()])
+    x, l, u, g, free = map(np.array, zip(*cases))
+    s = _tiny_solver(len(x), l, u, eps=0.125)
+    mask = s.dbg_free_mask(to_dev(x), to_dev(g)).cpu().numpy()
+    assert mask.tolist() == free.astype(np.uint8).tolist()
+    s.close()
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 8191, 40000])
+def test_free_mask_random_bit_exact(n):
+    rng = np.random.default_rng(n)
+    eps = 1e-3
+    l = np.where(rng.random(n) < 0.2, -np.inf, rng.normal(size=n))
+    u = np.where(rng.random(n) < 0.2, np.inf, np.where(np.isfinite(l), l, 0.0) + rng.random(n) * 2)
+    lo = np.where(np.isfinite(l), l, -3.0); hi = np.where(np.isfinite(u), u, 3.0)
+    x = lo + rng.random(n) * (hi - lo)
+    pick = rng.integers(0, 5, n)
+    x = np.where((pick == 0) & np.isfinite(l), l, x)
+    x = np.where((pick == 1) & np.isfinite(u), u, x)
+    x = np.where((pick == 2) & np.isfinite(l), np.minimum(l + 0.5 * eps, hi), x)
+    g = rng.normal(size=n) * (rng.random(n) > 0.1)
+    s = _tiny_solver(n, l, u, eps=eps)
+    got = s.dbg_free_mask(to_dev(x), to_dev(g)).cpu().numpy()
+    assert np.array_equal(got, oracle.free_mask(x, g, l, u, eps))
+    s.close()
+
+
+# ---- Algorithm 3 -----------------------------------------------------------------------------------
+
+def _spd_pairs(rng, n, k, cond=50.0):
+    d = np.linspace(1.0, cond, n)
+    S = rng.normal(size=(k, n))
+    # Y = H S for the SPD matrix H = diag(d) + 0.3 * (1 1^T)/n
+    Y = S * d + 0.3 * S.sum(axis=1, keepdims=True) / n
+    return S, Y
+
+
+def _two_loop_case(n, k, m, seed, frac_bad=0.3, eps=1e-10):
+    rng = np.random.default_rng(seed)
+    S, Y = _spd_pairs(rng, n, k)
+    for i in range(k):
+        if rng.random() < frac_bad:
+            Y[i] = -Y[i] if rng.random() < 0.5 else rng.normal(size=n)
+    mask = (rng.random(n) < 0.7).astype(np.uint8)
+    g = rng.normal(size=n)
+    yn = np.einsum("ij,ij->i", Y, Y)
+    return S, Y, yn, g, mask
+
+
+@pytest.mark.parametrize("n,k,m", [(1, 0, 3), (5, 1, 1), (64, 3, 5), (65, 5, 5), (1000, 10, 10), (4097, 7, 10),
+                                   (20000, 20, 20), (40000, 10, 10), (513, 31, 31)])
+def test_two_loop_parity_synthetic_pairs(n, k, m):
+    S, Y, yn, g, mask = _two_loop_case(n, k, m, seed=n + 13 * k)
+    eps = 1e-10
+    s = _tiny_solver(n, np.full(n, -np.inf), np.full(n, np.inf), m=m, eps=eps)
+    d, used = s.dbg_two_loop(to_dev(S) if k else None, to_dev(Y) if k else None, to_dev(yn) if k else None,
+                             to_dev(g), to_dev(mask))
+    d_ref, used_ref = oracle.two_loop(S, Y, g, mask, eps, ynorm2=yn)
+    assert used == used_ref
+    d = d.cpu().numpy()
+    assert np.all(d[mask == 0] == 0.0)
+    assert rel_err(d, d_ref) <= TOL64
+    s.close()
+
+
+def test_two_loop_gate_decisions_match_at_the_margin():
+    """rho == eps*||y||^2 exactly: the strict '>' must reject on both sides."""
+    S = np.array([[1.0, 0.0]]); Y = np.array([[1.0, math.sqrt(99.0)]])
+    g = np.array([2.0, 5.0]); mask = np.array([1, 0], dtype=np.uint8); yn = np.array([100.0])
+    for eps, expect_used in ((0.01, 0), (0.0099, 1)):
+        s = _tiny_solver(2, np.full(2, -np.inf), np.full(2, np.inf), m=2, eps=eps)
+        d, used = s.dbg_two_loop(to_dev(S), to_dev(Y), to_dev(yn), to_dev(g), to_dev(mask))
+        d_ref, used_ref = oracle.two_loop(S, Y, g, mask, eps, ynorm2=yn)
+        assert used == used_ref == expect_used
+        assert d.cpu().numpy().tolist() == d_ref.tolist()
+        s.close()
+
+
+@pytest.mark.parametrize("name,scale,stops", [("C1", 1.0, (3, 12, 30, 45)), ("C2", 0.05, (5, 12)), ("C3", 0.03, (6, 15)),
+                                              ("C5", 0.02, (4, 10))])
+def test_two_loop_parity_on_oracle_trajectories(name, scale, stops):
+    """Pairs, gradient and free set as they really occur along a solve (nearly collinear pairs, tiny
+    steps near convergence): the batched recursion must still agree with the literal one."""
+    prob = workloads.config(name, scale=scale)
+    obj = oracle.Objective(prob.kind, prob.A, prob.b, prob.lam, prob.mu)
+    orc = oracle.Solver(obj, prob.l, prob.u, prob.x0, prob.m, oracle.default_options(tol=1e-9, max_iter=max(stops) + 1))
+    s = _tiny_solver(prob.n, prob.l, prob.u, m=prob.m)
+    checked = 0
+    while orc.step() == oracle.RUNNING:
+        k = orc.info.iters
+        if k in stops:
+            S, Y, yn = orc.S, orc.Y, orc.ynorm2
+            g = orc.g
+            mask = oracle.free_mask(orc.x, g, prob.l, prob.u, 1e-10)
+            d_ref, used_ref = oracle.two_loop(S, Y, g, mask, 1e-10, ynorm2=yn)
+            d, used = s.dbg_two_loop(to_dev(S), to_dev(Y), to_dev(yn), to_dev(g), to_dev(mask))
+            assert used == used_ref
+            assert rel_err(d.cpu().numpy(), d_ref) <= TOL64, f"{name} iteration {k}"
+            checked += 1
+    assert checked >= 2
+    orc.close(); s.close()
+
+
+# ---- Algorithm 2 -----------------------------------------------------------------------------------
+
+def test_project_direction_worked_cases():
+    with open(os.path.join(GOLDEN, "project_direction_cases.txt")) as fh:
+        lines = [ln.split("#")[0].strip() for ln in fh]
+    for line in filter(None, lines):
+        f = [t.strip() for t in line.split("|")]
+        vec = lambda t: np.array([float(v) for v in t.split()])
+        l, u, x, g, d, p_exp = vec(f[1]), vec(f[2]), vec(f[3]), vec(f[4]), vec(f[5]), vec(f[7])
+        s = _tiny_solver(len(x), l, u, eps=0.01)
+        p, br, ub = s.dbg_project_direction(to_dev(x), to_dev(g), to_dev(d))
+        assert br == int(f[6]), f[0]
+        np.testing.assert_allclose(p.cpu().numpy(), p_exp, rtol=0, atol=1e-15)
+        if math.isinf(float(f[8])):
+            assert ub == math.inf
+        else:
+            assert ub == pytest.approx(float(f[8]), rel=1e-14)
+        s.close()
+
+
+@pytest.mark.parametrize("n,seed", [(1, 0), (7, 1), (64, 2), (300, 3), (5000, 4), (40000, 5)])
+@pytest.mark.parametrize("dscale", [1e-7, 1e-3, 1.0])
+def test_project_direction_random_parity(n, seed, dscale):
+    rng = np.random.default_rng(seed * 101 + n)
+    eps = 1e-6
+    l = -rng.random(n); u = rng.random(n)
+    l[rng.random(n) < 0.1] = -np.inf
+    u[rng.random(n) < 0.1] = np.inf
+    lo = np.where(np.isfinite(l), l, -2.0); hi = np.where(np.isfinite(u), u, 2.0)
+    x = lo + rng.random(n) * (hi - lo)
+    snap = rng.integers(0, 4, n)
+    x = np.where((snap == 0) & np.isfinite(l), l, np.where((snap == 1) & np.isfinite(u), u, x))
+    g = rng.normal(size=n)
+    mask = oracle.free_mask(x, g, l, u, eps).astype(bool)
+    d = -g * rng.random(n) * dscale
+    d[~mask] = 0.0
+    s = _tiny_solver(n, l, u, eps=eps)
+    p, br, ub = s.dbg_project_direction(to_dev(x), to_dev(g), to_dev(d))
+    p_ref, br_ref, ub_ref = oracle.project_direction(x, g, d, l, u, eps)
+    assert br == br_ref
+    assert np.array_equal(p.cpu().numpy(), p_ref)          # elementwise fp64 ops: bit-exact
+    assert ub == ub_ref or ub == pytest.approx(ub_ref, rel=1e-15)
+    s.close()

@@ -1,0 +1,245 @@
+"""End-to-end parity of the HIP solver with the CPU oracle on the benchmark configurations.
+
+The two do not follow the same trajectory (reduction order and the Armijo test at the margin
+differ), so what is compared is what the method fixes: the final objective value (1e-8 relative
+for fp64-stored matrices, 1e-4 for fp32-stored ones), the final active set on the
+well-conditioned configurations, and the KKT conditions recomputed on the host with numpy.  The
+first iterations, where nothing is marginal yet, are compared step by step.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2203_16340_amd as L
+import workloads
+from gpu_helpers import DEV, active_set, host_gradient, host_objective, kkt_residual, make_solver, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+A_PASSES = [pytest.param(L.APASS_TWO_PASS, id="two_pass"), pytest.param(L.APASS_FUSED, id="fused")]
+
+
+def _gpu_solver(prob, a_pass, **opts):
+    try:
+        return L.solver_for_problem(prob, DEV, a_pass=a_pass, **opts)
+    except L.LbfgsbError as e:
+        if e.code == L.E_UNSUPPORTED:
+            pytest.skip("shape/objective not supported by the fused A pass")
+        raise
+
+
+def _compare_with_oracle(prob, a_pass, f_tol, same_active_set, kkt_tol, **opts):
+    ref = oracle.solve_problem(prob)
+    assert ref.info.status == oracle.CONVERGED
+    s = _gpu_solver(prob, a_pass, **opts)
+    info = s.solve()
+    x = s.x().cpu().numpy()
+    assert info.status == L.CONVERGED, info.as_dict()
+    assert abs(info.f - ref.info.f) <= f_tol * abs(ref.info.f), (info.f, ref.info.f)
+    # the reported f is the objective at the returned x
+    assert info.f == pytest.approx(host_objective(prob, x), rel=1e-9)
+    res, g = kkt_residual(prob, x)
+    assert res <= kkt_tol, res
+    # the solver's own stopping quantity agrees with the host's recomputation
+    mask = oracle.free_mask(x, g, prob.l, prob.u, 1e-10).astype(bool)
+    assert np.linalg.norm(g[mask]) <= 1.5 * max(info.pg2, 1e-300) + 1e-9 * np.linalg.norm(g)
+    if same_active_set:
+        assert np.array_equal(active_set(prob, x), active_set(prob, ref.x))
+    # iteration counts are of the same order (soft: trajectories differ)
+    assert info.iters <= 2 * ref.info.iters + 20
+    s.close()
+    return info, ref
+
+
+@pytest.mark.parametrize("a_pass", A_PASSES)
+def test_c1_full_size(a_pass):
+    prob = workloads.config("C1")                         # NNLS 200 x 100 fp64, m = 5, tol 1e-8 absolute
+    info, ref = _compare_with_oracle(prob, a_pass, 1e-8, True, 1e-8)
+    assert info.pg2 <= 1e-8
+
+
+@pytest.mark.parametrize("a_pass", A_PASSES)
+@pytest.mark.parametrize("name,scale,f_tol,same_set", [
+    ("C2", 0.1, 1e-8, True),      # 2000 x 500 fp64
+    ("C3", 0.05, 1e-8, False),    # 500 x 1000 -> 2000 variables (not strictly convex: active sets may differ)
+    ("C4", 0.02, 1e-4, False),    # 4000 x 40 fp32 logistic
+    ("C5", 0.02, 1e-4, True),     # 2000 x 400 fp32, box [0, 1]
+])
+def test_scaled_configs(name, scale, f_tol, same_set, a_pass):
+    prob = workloads.config(name, scale=scale)
+    prob.tol, prob.tol_relative = 1e-9, True              # tight enough that f agrees to the stated bound
+    if name == "C4" and a_pass == L.APASS_FUSED:
+        pytest.skip("the fused pass serves the quadratic objectives")
+    g0 = host_gradient(prob, prob.x0)
+    mask0 = oracle.free_mask(prob.x0, g0, prob.l, prob.u, 1e-10).astype(bool)
+    _compare_with_oracle(prob, a_pass, f_tol, same_set, 1e-8 * max(1.0, np.linalg.norm(g0[mask0])))
+
+
+@pytest.mark.parametrize("a_pass", A_PASSES)
+@pytest.mark.parametrize("name,scale", [("C1", 1.0), ("C2", 0.05), ("C3", 0.03), ("C4", 0.01), ("C5", 0.02)])
+def test_first_iterations_match_step_by_step(name, scale, a_pass):
+    """Iterations 1-3 from x0 = 0: same branch, same number of backtracks, same step length, and the
+    iterate within rounding."""
+    prob = workloads.config(name, scale=scale)
+    if name == "C4" and a_pass == L.APASS_FUSED:
+        pytest.skip("the fused pass serves the quadratic objectives")
+    obj = oracle.Objective(prob.kind, prob.A, prob.b, prob.lam, prob.mu)
+    orc = oracle.Solver(obj, prob.l, prob.u, prob.x0, prob.m, oracle.default_options(tol=0.0))
+    s = _gpu_solver(prob, a_pass, tol=0.0)
+    tol = 1e-10 if prob.A.dtype == np.float64 else 1e-6
+    for k in range(3):
+        assert orc.step() == oracle.RUNNING
+        info = s.step()
+        oi = orc.info
+        assert info.status == L.RUNNING and info.iters == k + 1
+        assert (info.branch, info.backtracks, info.pairs_used) == (oi.branch, oi.backtracks, oi.pairs_used)
+        assert info.alpha == pytest.approx(oi.alpha, rel=1e-12)
+        assert info.gp == pytest.approx(oi.gp, rel=tol)
+        assert info.f == pytest.approx(oi.f, rel=tol)
+        assert rel_err(s.x().cpu().numpy(), orc.x) <= tol
+        assert rel_err(s.g().cpu().numpy(), orc.g) <= tol * 10
+    orc.close(); s.close()
+
+
+def test_iterates_stay_feasible_and_objective_decreases():
+    prob = workloads.config("C5", scale=0.02)
+    s = L.solver_for_problem(prob, DEV, tol=1e-10, tol_relative=1)
+    f_prev = s.info().f
+    for _ in range(40):
+        info = s.step()
+        if info.status != L.RUNNING:
+            break
+        x = s.x().cpu().numpy()
+        assert np.all(x >= prob.l) and np.all(x <= prob.u)
+        assert info.f <= f_prev
+        assert info.gp < 0 and 0 < info.alpha <= min(1.0, info.alpha_ub)
+        f_prev = info.f
+    s.close()
+
+
+def test_async_steps_equal_synchronous_steps():
+    """lbfgsb_step(info = NULL) only enqueues; 12 of them give bit-identical state to 12 synchronised ones."""
+    prob = workloads.config("C2", scale=0.05)
+    a = L.solver_for_problem(prob, DEV, tol=0.0)
+    b = L.solver_for_problem(prob, DEV, tol=0.0)
+    for _ in range(12):
+        a.step(want_info=False)
+        b.step()
+    assert torch.equal(a.x(), b.x()) and torch.equal(a.g(), b.g())
+    assert a.info().f == b.info().f and a.info().iters == 12
+    a.close(); b.close()
+
+
+def test_runs_are_bit_reproducible():
+    prob = workloads.config("C3", scale=0.03)
+    xs = []
+    for _ in range(2):
+        s = L.solver_for_problem(prob, DEV)
+        s.solve()
+        xs.append(s.x().clone())
+        s.close()
+    assert torch.equal(xs[0], xs[1])
+
+
+def test_recurrence_refresh_keeps_residual_and_gradient_exact():
+    """Least-squares kinds carry r and g by recurrence; with refresh_every = 4 and with no refresh at
+    all the solver reaches the same optimum, and after a solve the carried gradient equals the
+    gradient recomputed from x."""
+    prob = workloads.config("C2", scale=0.05)
+    prob.tol, prob.tol_relative = 1e-10, True
+    outs = []
+    for refresh in (4, 0, 32):
+        s = L.solver_for_problem(prob, DEV, refresh_every=refresh)
+        info = s.solve()
+        assert info.status == L.CONVERGED
+        x = s.x().cpu().numpy()
+        g = s.g().cpu().numpy()
+        assert rel_err(g, host_gradient(prob, x)) <= 1e-9 or np.linalg.norm(g - host_gradient(prob, x)) <= 1e-9 * np.linalg.norm(host_gradient(prob, prob.x0))
+        outs.append((info.f, x))
+        s.close()
+    for f, x in outs[1:]:
+        assert f == pytest.approx(outs[0][0], rel=1e-10)
+        np.testing.assert_allclose(x, outs[0][1], rtol=0, atol=1e-7)
+
+
+# ---- degenerate and failure cases ----------------------------------------------------------------
+
+def test_error_codes_for_bad_problems():
+    A = np.eye(3); b = np.ones(3)
+    with pytest.raises(L.LbfgsbError) as e:
+        make_solver(L.OBJ_LSQ, A, b, np.array([0.0, 1.0, 0.0]), np.array([1.0, 0.5, 1.0]), 3)
+    assert e.value.code == L.E_BOUNDS
+    with pytest.raises(L.LbfgsbError) as e:
+        make_solver(L.OBJ_LSQ, A, b, np.array([0.0, np.nan, 0.0]), np.ones(3), 3)
+    assert e.value.code == L.E_BOUNDS
+    s = make_solver(L.OBJ_LSQ, A, b, np.zeros(3), np.ones(3), 3)
+    with pytest.raises(L.LbfgsbError) as e:
+        s.set_x(to_dev(np.array([0.5, 2.0, 0.5])))
+    assert e.value.code == L.E_INFEASIBLE_X0
+    with pytest.raises(L.LbfgsbError) as e:
+        s.set_x(to_dev(np.array([0.5, np.nan, 0.5])))
+    assert e.value.code == L.E_INFEASIBLE_X0
+    with pytest.raises(L.LbfgsbError) as e:
+        s.step()                                          # no iterate yet
+    assert e.value.code == L.E_INVALID_ARG
+    s.set_x(to_dev(np.full(3, 0.5)))                      # and it recovers
+    assert s.solve().status == L.CONVERGED
+    s.close()
+    Abad = np.eye(3); Abad[1, 1] = np.inf
+    s = make_solver(L.OBJ_LSQ, Abad, b, np.zeros(3), np.ones(3), 3)
+    with pytest.raises(L.LbfgsbError) as e:
+        s.set_x(to_dev(np.full(3, 0.5)))
+    assert e.value.code == L.E_NONFINITE
+    s.close()
+
+
+def test_max_iter_and_start_at_optimum():
+    prob = workloads.config("C1")
+    s = L.solver_for_problem(prob, DEV, max_iter=3)
+    info = s.solve()
+    assert info.status == L.MAX_ITER and info.iters == 3
+    s.close()
+    ref = oracle.solve_problem(prob, tol=1e-10)
+    prob.x0 = ref.x
+    s = L.solver_for_problem(prob, DEV)
+    info = s.solve()
+    assert info.status == L.CONVERGED and info.iters == 0
+    s.close()
+
+
+def test_coinciding_and_infinite_bounds():
+    rng = np.random.default_rng(77)
+    A = rng.normal(size=(30, 6)); b = rng.normal(size=30)
+    l = np.array([-np.inf, 0.2, 0.0, -1.0, 0.7, -np.inf]); u = np.array([np.inf, 0.2, 1.0, 1.0, 0.7, 0.0])
+    prob = workloads.Problem("pin", workloads.OBJ_LSQ, A, b, l, u, np.clip(np.zeros(6), l, u), m=3, tol=1e-10)
+    ref = oracle.solve_problem(prob)
+    s = L.solver_for_problem(prob, DEV)
+    info = s.solve()
+    x = s.x().cpu().numpy()
+    assert info.status == L.CONVERGED and x[1] == 0.2 and x[4] == 0.7
+    np.testing.assert_allclose(x, ref.x, rtol=0, atol=1e-8)
+    s.close()
+
+
+def test_unbounded_least_squares_gives_lstsq_solution():
+    rng = np.random.default_rng(31)
+    A = rng.normal(size=(300, 40)); b = rng.normal(size=300)
+    prob = workloads.Problem("free", workloads.OBJ_LSQ, A, b, np.full(40, -np.inf), np.full(40, np.inf), np.zeros(40),
+                             m=8, tol=1e-10)
+    s = L.solver_for_problem(prob, DEV)
+    info = s.solve()
+    assert info.status == L.CONVERGED and info.n_fixed == 0
+    np.testing.assert_allclose(s.x().cpu().numpy(), np.linalg.lstsq(A, b, rcond=None)[0], rtol=0, atol=1e-9)
+    s.close()
+
+
+def test_single_variable_and_single_row():
+    prob = workloads.Problem("one", workloads.OBJ_LSQ, np.array([[2.0]]), np.array([1.0]), np.array([0.0]),
+                             np.array([0.25]), np.array([0.0]), m=1, tol=1e-12)
+    s = L.solver_for_problem(prob, DEV)
+    info = s.solve()
+    assert info.status == L.CONVERGED and s.x().item() == 0.25
+    s.close()

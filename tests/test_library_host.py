@@ -1,0 +1,109 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and its argument validation answers with the documented error codes before any
+device work is attempted."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2203_16340_amd as L
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "lbfgsb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lbfgsb_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert len(names) >= 18 and "lbfgsb_create" in names and "lbfgsb_step" in names
+    lib = L.lib()
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in include/lbfgsb.h but not exported"
+    assert sorted(L.EXPORTS) == names            # the Python binding covers the same names
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """sizeof/offsetof as gcc sees include/lbfgsb.h against the ctypes mirrors: guards against a
+    field added or reordered on one side only."""
+    import subprocess
+    src = tmp_path / "sz.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "lbfgsb.h"\n'
+        'int main(void){printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(lbfgsb_objective), sizeof(lbfgsb_options),'
+        ' sizeof(lbfgsb_info), offsetof(lbfgsb_objective, lambda), offsetof(lbfgsb_options, a_pass),'
+        ' offsetof(lbfgsb_info, n_fixed), offsetof(lbfgsb_info, gp)); return 0;}\n')
+    exe = tmp_path / "sz"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    got = [int(t) for t in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [C.sizeof(L.Objective), C.sizeof(L.Options), C.sizeof(L.Info), L.Objective.lam.offset,
+                   L.Options.a_pass.offset, L.Info.n_fixed.offset, L.Info.gp.offset]
+
+
+def test_default_options():
+    o = L.default_options()
+    assert (o.eps, o.armijo_c1, o.backtrack, o.max_backtracks) == (1e-10, 1e-4, 0.5, 60)
+    assert (o.tol, o.tol_relative, o.max_iter, o.refresh_every, o.poll_every, o.a_pass) == (1e-8, 0, 1000, 32, 8, 0)
+
+
+def _obj(kind=0, dtype=0, rows=200, cols=100, ld=None, A=0x1000, b=0x2000):
+    return L.Objective(kind, dtype, rows, cols, cols if ld is None else ld, A, b, 0.0, 0.0)
+
+
+def test_workspace_bytes_validates_and_scales():
+    lib = L.lib()
+    o = L.default_options()
+    base = lib.lbfgsb_workspace_bytes(100, 5, C.byref(_obj()), C.byref(o))
+    assert base > 0 and base % 256 == 0
+    # room for 2*m*n doubles of pair memory at least
+    assert base >= 2 * 5 * 100 * 8
+    assert lib.lbfgsb_workspace_bytes(100, 10, C.byref(_obj()), C.byref(o)) > base
+    for bad in [dict(n=0), dict(n=101), dict(m=0), dict(m=32), dict(kind=7), dict(dtype=3), dict(rows=0), dict(ld=99)]:
+        n = bad.pop("n", 100)
+        m = bad.pop("m", 5)
+        assert lib.lbfgsb_workspace_bytes(n, m, C.byref(_obj(**bad)), C.byref(o)) == 0
+        assert lib.lbfgsb_last_error()
+    # the split objective has 2*cols variables
+    assert lib.lbfgsb_workspace_bytes(200, 5, C.byref(_obj(kind=1)), C.byref(o)) > 0
+    assert lib.lbfgsb_workspace_bytes(100, 5, C.byref(_obj(kind=1)), C.byref(o)) == 0
+
+
+def test_create_rejects_bad_arguments_before_touching_the_device():
+    lib = L.lib()
+    h = C.c_void_p()
+    o = L.default_options()
+    obj = _obj()
+    ws = 0x10000
+    rc = lib.lbfgsb_create(C.byref(h), 100, 5, None, 0x3000, C.byref(obj), C.byref(o), ws, 1 << 20, None)
+    assert rc == L.E_INVALID_ARG and not h
+    rc = lib.lbfgsb_create(C.byref(h), 100, 0, 0x3000, 0x4000, C.byref(obj), C.byref(o), ws, 1 << 20, None)
+    assert rc == L.E_INVALID_ARG
+    rc = lib.lbfgsb_create(C.byref(h), 100, 5, 0x3000, 0x4000, C.byref(obj), C.byref(o), ws + 8, 1 << 20, None)
+    assert rc == L.E_INVALID_ARG and b"aligned" in lib.lbfgsb_last_error()
+    rc = lib.lbfgsb_create(C.byref(h), 100, 5, 0x3000, 0x4000, C.byref(obj), C.byref(o), ws, 16, None)
+    assert rc == L.E_INVALID_ARG and b"too small" in lib.lbfgsb_last_error()
+    bad = L.default_options(backtrack=1.5)
+    rc = lib.lbfgsb_create(C.byref(h), 100, 5, 0x3000, 0x4000, C.byref(obj), C.byref(bad), ws, 1 << 20, None)
+    assert rc == L.E_INVALID_ARG
+    rc = lib.lbfgsb_create(None, 100, 5, 0x3000, 0x4000, C.byref(obj), C.byref(o), ws, 1 << 20, None)
+    assert rc == L.E_INVALID_ARG
+    # NULL solver handles are errors, never crashes; destroy(NULL) is a no-op
+    assert lib.lbfgsb_step(None, None) == L.E_INVALID_ARG
+    assert lib.lbfgsb_solve(None, None) == L.E_INVALID_ARG
+    assert lib.lbfgsb_set_x(None, None) == L.E_INVALID_ARG
+    assert lib.lbfgsb_get_info(None, None) == L.E_INVALID_ARG
+    lib.lbfgsb_destroy(None)
+
+
+def test_product_path_does_not_reach_the_oracle():
+    """The binding and the HIP sources never import, include or link anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_2203_16340_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text.replace("no fallback", ""), f"{fn} mentions the oracle"
