@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the modified L-BFGS-B hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--a-pass auto|two_pass|fused]
+
+A "step" is one iteration of Algorithm 1 (one lbfgsb_step call: free set, batched two-loop,
+projectDirection, the pass(es) over A, line search, update) on a synthetic problem that is already
+resident in HBM.  The default workload is the configuration the headline metric is quoted on:
+C2 = dense fp64 NNLS, A 20000 x 5000, m = 10.  Steps are timed in episodes that each start from
+x0 (an episode is never longer than the number of iterations the solver needs to reach the
+tolerance, so every timed step is a real iteration and none is a no-op after convergence).
+
+Prints ONE JSON line: iterations/s (`value`), the time to reach the relative KKT tolerance 1e-6
+(`time_to_kkt_ms`), the achieved fraction of the HBM roofline of the dominant kernel
+(`roofline`), and the CPU oracle timed on this host on a bounded sample (`cpu_baseline`).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "L-BFGS-B iters/sec + time-to-KKT 1e-6 (NNLS); achieved HBM GB/s vs peak"
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    "C1": "NNLS 200x100 fp64, m=5",
+    "C2": "NNLS 20000x5000 fp64, x* 80% zeros, m=10",
+    "C3": "L1-LS split 10000x20000 fp64 (40000 vars), m=10",
+    "C4": "box logistic 200000x2000 fp32, m=10",
+    "C5": "NNLS 100000x20000 fp32, box [0,1], m=20",
+}
+
+# HBM bytes per launch of the dominant kernel as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by the same counters read for a copy kernel of known size); filled in from the summaries
+# under profiles/ for the (config, a_pass) pairs that have been profiled, else null in the output.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(prob, budget_s: float):
+    """The oracle as it stands, single-threaded, on a bounded sample: iterations from x0 until
+    `budget_s` seconds have passed (at least one)."""
+    import oracle
+    obj = oracle.Objective(prob.kind, prob.A, prob.b, prob.lam, prob.mu)
+    opts = oracle.default_options(tol=prob.tol, tol_relative=int(prob.tol_relative))
+    t0 = time.perf_counter()
+    s = oracle.Solver(obj, prob.l, prob.u, prob.x0, prob.m, opts)     # includes the evaluation at x0
+    iters = 0
+    while time.perf_counter() - t0 < budget_s:
+        if s.step() != oracle.RUNNING:
+            break
+        iters = s.info.iters
+    elapsed = time.perf_counter() - t0
+    info = s.info
+    done = info.status != oracle.RUNNING
+    s.close()
+    return {
+        "value": iters / elapsed if elapsed > 0 else 0.0,
+        "unit": "iterations/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": (f"first {iters} iterations from x0 ({'to convergence' if done else 'stopped by the time budget'}), "
+                   f"{elapsed:.1f} s, {info.fevals} objective evaluations"),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C2", choices=sorted(WORKLOADS))
+    ap.add_argument("--a-pass", default="auto", choices=["auto", "two_pass", "fused"])
+    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink both matrix dimensions (debugging only)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2203_16340_amd as L
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    a_pass = {"auto": L.APASS_AUTO, "two_pass": L.APASS_TWO_PASS, "fused": L.APASS_FUSED}[args.a_pass]
+
+    t_gen = time.perf_counter()
+    prob = workloads.config(args.config, scale=args.scale)
+    t_gen = time.perf_counter() - t_gen
+    esz = prob.A.dtype.itemsize
+
+    # ---- time to the KKT tolerance (relative 1e-6), inputs resident in HBM
+    A_d, b_d = torch.from_numpy(prob.A).to(dev), torch.from_numpy(prob.b).to(dev)
+    l_d, u_d = torch.from_numpy(prob.l).to(dev), torch.from_numpy(prob.u).to(dev)
+    x0 = torch.from_numpy(prob.x0).to(dev)
+
+    def new_solver(**opts):
+        s_ = L.Solver(prob.kind, A_d, b_d, l_d, u_d, prob.m, lam=prob.lam, mu=prob.mu,
+                      options=L.default_options(a_pass=a_pass, **opts))
+        s_.set_x(x0)
+        return s_
+
+    solver = new_solver(tol=1e-6, tol_relative=1)
+    solver.solve()                                   # untimed first solve: loads code objects, warms caches
+    solver.set_x(x0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    info = solver.solve()
+    t_kkt = time.perf_counter() - t0
+    iters_to_kkt = int(info.iters)
+    x = solver.x().cpu().numpy()
+    # independent fp64 check of the returned point on the host
+
+    def host_grad(xv):
+        def mv(v):
+            out = np.empty(prob.rows)
+            step = max(1, (256 << 20) // (prob.cols * 8))
+            for r0 in range(0, prob.rows, step):
+                out[r0:r0 + step] = prob.A[r0:r0 + step].astype(np.float64, copy=False) @ v
+            return out
+
+        def rmv(w):
+            out = np.zeros(prob.cols)
+            step = max(1, (256 << 20) // (prob.cols * 8))
+            for r0 in range(0, prob.rows, step):
+                out += w[r0:r0 + step] @ prob.A[r0:r0 + step].astype(np.float64, copy=False)
+            return out
+        if prob.kind == workloads.OBJ_LSQ:
+            return rmv(mv(xv) - prob.b)
+        if prob.kind == workloads.OBJ_LSQ_L1SPLIT:
+            c = prob.cols
+            w = rmv(mv(xv[:c] - xv[c:]) - prob.b)
+            return np.concatenate([w + prob.lam, -w + prob.lam])
+        z = mv(xv)
+        sig = 0.5 * (1.0 - np.tanh(0.5 * prob.b * z))       # sigma(-y z)
+        return -rmv(prob.b * sig) / prob.rows + prob.mu * xv
+
+    g_host = host_grad(x)
+    g0_host = host_grad(prob.x0)
+    free0 = ~(((prob.x0 <= prob.l + 1e-10) & (g0_host >= 0)) | ((prob.x0 >= prob.u - 1e-10) & (g0_host <= 0)))
+    free = ~(((x <= prob.l + 1e-10) & (g_host >= 0)) | ((x >= prob.u - 1e-10) & (g_host <= 0)))
+    kkt_rel = float(np.linalg.norm(g_host[free]) / max(1.0, np.linalg.norm(g0_host[free0])))
+    kkt_inf = float(np.abs(x - np.clip(x - g_host, prob.l, prob.u)).max())
+    feasible = bool(np.all(x >= prob.l) and np.all(x <= prob.u))
+
+    # ---- K timed steps, in episodes from x0
+    timed = new_solver(tol=0.0, tol_relative=0, max_iter=10 ** 6)
+    episode = max(1, min(args.steps, iters_to_kkt if iters_to_kkt > 0 else args.steps))
+    for _ in range(args.warmup):
+        timed.step(want_info=False)
+    torch.cuda.synchronize()
+    timed.enable_apass_timing(2)
+    timed.enable_apass_timing(0)
+    done, total_s, valid = 0, 0.0, True
+    while done < args.steps:
+        k = min(episode, args.steps - done)
+        timed.set_x(x0)                      # untimed: back to x0, pair memory cleared
+        timed.enable_apass_timing(1)         # HIP events around every A-pass launch of the timed steps
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            timed.step(want_info=False)
+        torch.cuda.synchronize()
+        total_s += time.perf_counter() - t0
+        timed.enable_apass_timing(0)
+        st = timed.info()
+        if st.iters != k or st.status != L.RUNNING:
+            valid = False
+        done += k
+    n_launch, apass_ms, bytes_per_launch = timed.apass_timing()
+    ms_per_step = 1e3 * total_s / args.steps
+    apass_avg_ms = apass_ms / max(1, n_launch)
+    achieved = bytes_per_launch / (apass_avg_ms * 1e-3) / 1e9 if apass_avg_ms > 0 else 0.0
+    launches_per_step = n_launch / max(1, args.steps)
+    apass_name = timed.apass_name
+
+    out = {
+        "metric": METRIC,
+        "value": 1e3 / ms_per_step,
+        "unit": "iterations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{args.config}: {WORKLOADS[args.config]}" + (f" (scaled x{args.scale})" if args.scale != 1.0 else ""),
+            "rows": prob.rows, "cols": prob.cols, "n": prob.n, "m": prob.m,
+            "matrix_dtype": "f64" if esz == 8 else "f32",
+            "a_pass": apass_name, "a_pass_launches_per_step": launches_per_step,
+            "episode_steps": episode, "steps_valid": valid,
+        },
+        "time_to_kkt_ms": 1e3 * t_kkt,
+        "iters_to_kkt": iters_to_kkt,
+        "kkt": {"status": int(info.status), "rel_proj_grad_2norm_host": kkt_rel, "proj_grad_infnorm_host": kkt_inf,
+                "feasible": feasible, "f": info.f},
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "fused A pass (t = A p and w = A^T t in one read)" if apass_name == "fused"
+                      else "two-pass A kernels (row-dot, then transposed), one read of A per launch",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "bytes_per_launch": bytes_per_launch,
+            "avg_launch_ms": apass_avg_ms,
+            "launches_timed": n_launch,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, apass_name)),
+        },
+        "gen_seconds": t_gen,
+    }
+    timed.close()
+    solver.close()
+    if args.cpu_budget > 0:
+        out["cpu_baseline"] = cpu_baseline(prob, args.cpu_budget)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -162,10 +162,12 @@ int lbfgsb_get_g(lbfgsb_solver* s, double* g_out);
 void lbfgsb_destroy(lbfgsb_solver* s);
 
 /* ---- timing of the products with A (the kernels that dominate an iteration) ------------------
- * When enabled, every lbfgsb_step brackets its A-pass kernel launches with HIP events on the
- * solver's stream (at most 4096 pairs are kept).  lbfgsb_apass_timing synchronises and returns
- * how many passes were timed, their total duration in milliseconds and the bytes of A one pass
- * requests from memory (rows*cols*sizeof(element) times the number of reads of A in it). */
+ * While enabled, every launch of a kernel that reads A is bracketed with HIP events on the
+ * solver's stream (at most 4096 launches are kept; later ones are not recorded).  enable: 0 =
+ * pause (records kept), 1 = resume, 2 = discard the records and start.  lbfgsb_apass_timing
+ * synchronises and returns how many launches were timed, their total duration in milliseconds
+ * and the bytes of A one launch requests from memory (rows*cols*sizeof(element): each such
+ * kernel reads A exactly once). */
 int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable);
 int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count_host, double* total_ms_host, double* bytes_per_pass_host);
 /* Name of the A-pass organisation in use: "fused" or "two_pass" (host string). */

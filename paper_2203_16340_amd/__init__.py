@@ -222,8 +222,9 @@ class Solver:
         return out
 
     # -- timing of the A pass
-    def enable_apass_timing(self, enable: bool = True) -> None:
-        _check(lib().lbfgsb_enable_apass_timing(self._h, int(enable)))
+    def enable_apass_timing(self, mode: int = 2) -> None:
+        """0 = pause, 1 = resume, 2 = discard the records and start"""
+        _check(lib().lbfgsb_enable_apass_timing(self._h, int(mode)))
 
     def apass_timing(self):
         """(launches timed, total milliseconds, bytes of A one launch reads)"""

@@ -104,8 +104,8 @@ Geometry make_geometry(const Dims& dm, const void* A) {
     ge.gram_blocks = gram_blocks_for(dm.n);
     int64_t db = (dm.n + kBlock - 1) / kBlock;
     ge.dir_blocks = (int)(db > 256 ? 256 : db);
-    int64_t ub = (dm.cols + 31) / 32;
-    ge.upd_blocks = ge.fin_blocks = (int)(ub > 1024 ? 1024 : ub);
+    int64_t ub = (dm.cols + 15) / 16;   // 16 columns per workgroup in the column-sum kernels
+    ge.upd_blocks = ge.fin_blocks = (int)(ub > 2048 ? 2048 : ub);
     int64_t lb_ = (dm.rows + kBlock - 1) / kBlock;
     ge.ls_blocks = (int)(lb_ > 512 ? 512 : lb_);
     return ge;
@@ -451,7 +451,7 @@ int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable) {
         }
     }
     s->timing = enable != 0;
-    s->timed = 0;
+    if (enable == 2) s->timed = 0;
     return LBFGSB_OK;
 }
 

@@ -22,7 +22,9 @@ __host__ __device__ inline int gram_tiles(int V) {
 }
 int gram_entries(int m) { return 4 + 4 * gram_tiles(2 * m + 1); }
 int gram_blocks_for(int64_t n) {
-    int64_t b = (n + kGramE - 1) / kGramE;
+    // a few chunks per workgroup: the kernel is latency-bound, and every partial written here is
+    // read again by the last workgroup
+    int64_t b = (n + 4 * kGramE - 1) / (4 * kGramE);
     return (int)(b < 1 ? 1 : (b > 128 ? 128 : b));
 }
 
@@ -62,7 +64,6 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, Opts op, cons
                                                  Scal* __restrict__ scal, double* __restrict__ grampart, int NE,
                                                  int use_given_mask, int evaluate_stop) {
     __shared__ __align__(16) double tileb[kGramE * kMaxV];   // staged chunk [element][vector]; later G
-    __shared__ double maskf[kGramE];
     __shared__ const double* vecp[kMaxV];
     __shared__ double red[kWaves * 2];
     __shared__ double alpha_s[kMaxM + 1];
@@ -95,34 +96,42 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, Opts op, cons
     double pg2 = 0.0, pginf = 0.0, nfixed = 0.0;
     __syncthreads();
 
+    const int lane = tid & 63, wave = tid >> 6;
     for (int64_t e0 = (int64_t)blockIdx.x * kGramE; e0 < n; e0 += (int64_t)gridDim.x * kGramE) {
-        if (tid < kGramE) {
-            const int64_t e = e0 + tid;
-            double mf = 0.0;
-            if (e < n) {
-                const double xe = x[e], ge = g[e], le = l[e], ue = u[e];
-                int fr;
-                if (use_given_mask) {
-                    fr = mask[e] != 0;
-                } else {
-                    const bool at_lower = (xe <= le + op.eps) && (ge >= 0.0);
-                    const bool at_upper = (xe >= ue - op.eps) && (ge <= 0.0);
-                    fr = !(at_lower || at_upper);
-                    mask[e] = (uint8_t)fr;
-                }
-                mf = fr ? 1.0 : 0.0;
+        // every wave derives the free flag of element e0 + lane (wave 0 also records it); wave w then
+        // stages vectors w, w + 4, w + 8, ... of that element, all loads issued before any is used
+        const int64_t e = e0 + lane;
+        double mf = 0.0;
+        double stage[kMaxV / kWaves];
+        if (e < n) {
+#pragma unroll
+            for (int k = 0; k < kMaxV / kWaves; ++k) {
+                const int j = wave + kWaves * k;
+                stage[k] = j < V ? vecp[j][e] : 0.0;
+            }
+            const double xe = x[e], ge = g[e], le = l[e], ue = u[e];
+            int fr;
+            if (use_given_mask) {
+                fr = mask[e] != 0;
+            } else {
+                const bool at_lower = (xe <= le + op.eps) && (ge >= 0.0);
+                const bool at_upper = (xe >= ue - op.eps) && (ge <= 0.0);
+                fr = !(at_lower || at_upper);
+            }
+            mf = fr ? 1.0 : 0.0;
+            if (wave == 0) {
+                if (!use_given_mask) mask[e] = (uint8_t)fr;
                 if (fr) pg2 = fma(ge, ge, pg2); else nfixed += 1.0;
                 pginf = fmax(pginf, fabs(xe - clampd(xe - ge, le, ue)));
             }
-            maskf[tid] = mf;
+        } else {
+#pragma unroll
+            for (int k = 0; k < kMaxV / kWaves; ++k) stage[k] = 0.0;
         }
-        __syncthreads();
-        for (int idx = tid; idx < kGramE * Vp; idx += kBlock) {
-            const int j = idx / kGramE, el = idx - j * kGramE;
-            const int64_t e = e0 + el;
-            double v = 0.0;
-            if (j < V && e < n) v = vecp[j][e] * maskf[el];
-            tileb[el * Vp + j] = v;
+#pragma unroll
+        for (int k = 0; k < kMaxV / kWaves; ++k) {
+            const int j = wave + kWaves * k;
+            if (j < Vp) tileb[lane * Vp + j] = stage[k] * mf;
         }
         __syncthreads();
 #pragma unroll
@@ -171,27 +180,57 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, Opts op, cons
     // ---- last workgroup: total G, then the recursion on coefficients ----
     const int nb = gridDim.x;
     double* G = tileb;   // Vp x Vp, row-major
-    for (int q4 = tid; q4 < 4 * ntiles; q4 += kBlock) {
+    // 64 entries at a time; wave w sums the partials of workgroups w, w + 4, ... (8 loads in flight),
+    // the four wave results are added in wave order
+    __shared__ double wsum[kWaves][64];
+    for (int q0 = 0; q0 < 4 * ntiles; q0 += 64) {
+        const int q4 = q0 + lane;
         double s = 0.0;
-        for (int b = 0; b < nb; ++b) s += grampart[(int64_t)b * NE + 4 + q4];
-        int q = q4 >> 2, a = 0;
-        while (q >= T - a) { q -= T - a; ++a; }
-        const int row = 2 * a + ((q4 >> 1) & 1), col = 2 * (a + q) + (q4 & 1);
-        G[row * Vp + col] = s;
-        G[col * Vp + row] = s;
-    }
-    if (tid < 3) {
-        double s = 0.0;
-        for (int b = 0; b < nb; ++b) {
-            const double v = grampart[(int64_t)b * NE + tid];
-            s = (tid == 1) ? fmax(s, v) : s + v;
+        if (q4 < 4 * ntiles) {
+            const double* src = grampart + 4 + q4;
+            for (int b0 = wave; b0 < nb; b0 += kWaves * 8) {
+                double v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int b = b0 + kWaves * k;
+                    v[k] = b < nb ? src[(int64_t)b * NE] : 0.0;
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) s += v[k];
+            }
         }
-        red[tid] = s;
+        wsum[wave][lane] = s;
+        __syncthreads();
+        if (wave == 0 && q4 < 4 * ntiles) {
+            const double tot = ((wsum[0][lane] + wsum[1][lane]) + wsum[2][lane]) + wsum[3][lane];
+            int q = q4 >> 2, a = 0;
+            while (q >= T - a) { q -= T - a; ++a; }
+            const int row = 2 * a + ((q4 >> 1) & 1), col = 2 * (a + q) + (q4 & 1);
+            G[row * Vp + col] = tot;
+            G[col * Vp + row] = tot;
+        }
+        __syncthreads();
+    }
+    {
+        // per-workgroup statistics (at most 128 workgroups): one thread each, fixed-order reductions
+        const bool have = tid < nb;
+        double sv[2] = {have ? grampart[(int64_t)tid * NE] : 0.0, have ? grampart[(int64_t)tid * NE + 2] : 0.0};
+        double mx = have ? grampart[(int64_t)tid * NE + 1] : 0.0;
+        __shared__ double stat[kWaves * 2];
+        __shared__ double stat_mx[kWaves];
+        block_sum<2, kWaves>(sv, stat);
+        mx = wave_max(mx);
+        if (lane == 0) stat_mx[wave] = mx;
+        __syncthreads();
+        if (tid == 0) {
+            red[0] = sv[0];
+            red[1] = fmax(fmax(stat_mx[0], stat_mx[1]), fmax(stat_mx[2], stat_mx[3]));
+            red[2] = sv[1];
+        }
     }
     __syncthreads();
     if (tid < 64) {
         // lane j holds delta_j
-        const int lane = tid;
         double delta = (lane == 2 * c) ? 1.0 : 0.0;
         int used = 0;
         unsigned long long passmask = 0ull;
@@ -257,17 +296,17 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
                                                 Scal* __restrict__ scal, double* __restrict__ d,
                                                 double* __restrict__ p1, double* __restrict__ p2,
                                                 double* __restrict__ redpart, int d_given) {
-    __shared__ double delta_s[kMaxV];
-    __shared__ const double* vecp[kMaxV];
-    __shared__ double red[kWaves * 6];
+    __shared__ double delta_s[kMaxV + 8];
+    __shared__ const double* vecp[kMaxV + 8];
+    __shared__ double red[kWaves * 7];
     __shared__ int flag;
     if (scal->status != LBFGSB_RUNNING) return;
     const int tid = threadIdx.x;
     const int c = scal->count, head = scal->head;
     const int V = 2 * c + 1;
-    if (tid < V) {
-        vecp[tid] = ring_vec(tid, c, head, m, n, S, Y, g);
-        delta_s[tid] = scal->delta[tid];
+    if (tid < kMaxV + 8) {
+        vecp[tid] = tid < V ? ring_vec(tid, c, head, m, n, S, Y, g) : g;
+        delta_s[tid] = tid < V ? scal->delta[tid] : 0.0;
     }
     __syncthreads();
     double s[6] = {0, 0, 0, 0, 0, 0};
@@ -280,7 +319,13 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
             de = 0.0;
             if (mask[e]) {
                 double q = 0.0;
-                for (int j = 0; j < V; ++j) q = fma(delta_s[j], vecp[j][e], q);
+                for (int j0 = 0; j0 < V; j0 += 8) {
+                    double v[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] = j0 + k < V ? vecp[j0 + k][e] : 0.0;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) q = fma(delta_s[j0 + k], v[k], q);
+                }
                 de = -q;
             }
             d[e] = de;
@@ -310,13 +355,28 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
         part[6] = mn;
     }
     if (!arrive_is_last(&scal->counters[kCntDir], &flag)) return;
-    if (tid < 7) {
-        double t = (tid == 6) ? INFINITY : 0.0;
-        for (int b = 0; b < (int)gridDim.x; ++b) {
-            const double v = redpart[(int64_t)b * kDirRed + tid];
-            t = (tid == 6) ? fmin(t, v) : t + v;
+    {
+        // at most kBlock workgroups wrote partials: one thread each, then the fixed-order reductions
+        double t6[6];
+        double tmin = INFINITY;
+        const bool have = tid < (int)gridDim.x;
+#pragma unroll
+        for (int k = 0; k < 6; ++k) t6[k] = have ? redpart[(int64_t)tid * kDirRed + k] : 0.0;
+        if (have) tmin = redpart[(int64_t)tid * kDirRed + 6];
+        block_sum<6, kWaves>(t6, red);
+        tmin = wave_min(tmin);
+        __syncthreads();
+        if ((tid & 63) == 0) red[tid >> 6] = tmin;
+        __syncthreads();
+        if (tid == 0) {
+            tmin = red[0];
+            for (int w = 1; w < kWaves; ++w) tmin = fmin(tmin, red[w]);
         }
-        red[tid] = t;
+        __syncthreads();
+        if (tid == 0) {
+            for (int k = 0; k < 6; ++k) red[k] = t6[k];
+            red[6] = tmin;
+        }
     }
     __syncthreads();
     if (tid == 0) {
@@ -336,7 +396,7 @@ void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffer
 
 // ---- helpers shared by the column-wise consumers of the A pass ---------------------------------------------
 
-constexpr int kCX = 32;             // columns per workgroup
+constexpr int kCX = 16;             // columns per workgroup
 constexpr int kGY = kBlock / kCX;   // partial-row groups per workgroup
 
 // Sum over the A pass's partial columns for column c0 + (tid % kCX); valid in threads with tid < kCX.
@@ -345,8 +405,16 @@ __device__ __forceinline__ double column_sum(const double* __restrict__ wpart, i
     const int cx = threadIdx.x % kCX, gy = threadIdx.x / kCX;
     double s = 0.0;
     if (c < cols) {
-#pragma unroll 8
-        for (int k = gy; k < parts; k += kGY) s += wpart[(int64_t)k * cols + c];
+        for (int k0 = gy; k0 < parts; k0 += kGY * 8) {
+            double v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int kk = k0 + kGY * k;
+                v[k] = kk < parts ? wpart[(int64_t)kk * cols + c] : 0.0;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) s += v[k];
+        }
     }
     __syncthreads();
     lds[gy * kCX + cx] = s;
@@ -362,7 +430,13 @@ __device__ __forceinline__ double column_sum(const double* __restrict__ wpart, i
 // Sum of `count` doubles, identical in every workgroup that calls it (same order everywhere).
 __device__ __forceinline__ double sum_all(const double* __restrict__ v, int count, double* lds) {
     double s[1] = {0.0};
-    for (int k = threadIdx.x; k < count; k += kBlock) s[0] += v[k];
+    for (int k0 = threadIdx.x; k0 < count; k0 += kBlock * 8) {
+        double t[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t[k] = k0 + kBlock * k < count ? v[k0 + kBlock * k] : 0.0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s[0] += t[k];
+    }
     block_sum<1, kWaves>(s, lds);
     return s[0];
 }
