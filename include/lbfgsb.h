@@ -162,8 +162,9 @@ int lbfgsb_get_g(lbfgsb_solver* s, double* g_out);
 void lbfgsb_destroy(lbfgsb_solver* s);
 
 /* ---- timing of the products with A (the kernels that dominate an iteration) ------------------
- * While enabled, every launch of a kernel that reads A is bracketed with HIP events on the
- * solver's stream (at most 4096 launches are kept; later ones are not recorded).  enable: 0 =
+ * While enabled, every launch of a kernel that reads A carries a pair of HIP events attached to
+ * the dispatch itself (start and end of that kernel on the solver's stream, no extra stream
+ * markers) (at most 4096 launches are kept; later ones are not recorded).  enable: 0 =
  * pause (records kept), 1 = resume, 2 = discard the records and start.  lbfgsb_apass_timing
  * synchronises and returns how many launches were timed, their total duration in milliseconds
  * and the bytes of A one launch requests from memory (rows*cols*sizeof(element): each such

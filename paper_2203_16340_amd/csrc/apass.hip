@@ -98,38 +98,40 @@ __global__ __launch_bounds__(kBlock) void k_gemvt(const T* __restrict__ A, int64
 }
 
 template <typename T, int VEC>
-static void gemv_dispatch(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((k_gemv<T, VEC, 4>), dim3(ge.gemv_blocks), dim3(kBlock), 0, st, (const T*)a.A, dm.ld, dm.rows,
-                       dm.cols, a, bf.scal, bf.row, bf.t, bf.psi, bf.losspart);
+static void gemv_dispatch(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
+                          hipEvent_t ev0, hipEvent_t ev1) {
+    hipExtLaunchKernelGGL((k_gemv<T, VEC, 4>), dim3(ge.gemv_blocks), dim3(kBlock), 0, st, ev0, ev1, 0, (const T*)a.A,
+                          dm.ld, dm.rows, dm.cols, a, (const Scal*)bf.scal, bf.row, bf.t, bf.psi, bf.losspart);
 }
 
-void launch_gemv(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st) {
+void launch_gemv(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
+                 hipEvent_t ev0, hipEvent_t ev1) {
     if (dm.dtype == LBFGSB_F32) {
-        if (ge.vec > 1) gemv_dispatch<float, 4>(dm, ge, bf, a, st);
-        else gemv_dispatch<float, 1>(dm, ge, bf, a, st);
+        if (ge.vec > 1) gemv_dispatch<float, 4>(dm, ge, bf, a, st, ev0, ev1);
+        else gemv_dispatch<float, 1>(dm, ge, bf, a, st, ev0, ev1);
     } else {
-        if (ge.vec > 1) gemv_dispatch<double, 2>(dm, ge, bf, a, st);
-        else gemv_dispatch<double, 1>(dm, ge, bf, a, st);
+        if (ge.vec > 1) gemv_dispatch<double, 2>(dm, ge, bf, a, st, ev0, ev1);
+        else gemv_dispatch<double, 1>(dm, ge, bf, a, st, ev0, ev1);
     }
 }
 
 template <typename T, int VEC>
 static void gemvt_dispatch(const Dims& dm, const Geometry& ge, const Buffers& bf, const void* A, const double* psi,
-                           int check_status, hipStream_t st) {
-    hipLaunchKernelGGL((k_gemvt<T, VEC>), dim3(ge.gemvt_col_tiles, ge.gemvt_row_blocks), dim3(kBlock), 0, st,
-                       (const T*)A, dm.ld, dm.rows, dm.cols, psi, bf.wpart, ge.gemvt_rows_per_block, bf.scal,
-                       check_status);
+                           int check_status, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+    hipExtLaunchKernelGGL((k_gemvt<T, VEC>), dim3(ge.gemvt_col_tiles, ge.gemvt_row_blocks), dim3(kBlock), 0, st, ev0,
+                          ev1, 0, (const T*)A, dm.ld, dm.rows, dm.cols, psi, bf.wpart, ge.gemvt_rows_per_block,
+                          (const Scal*)bf.scal, check_status);
 }
 
 // psi_src: the per-row weights (bf.psi after an evaluation, bf.t after a direction pass).
 void launch_gemvt_from(const Dims& dm, const Geometry& ge, const Buffers& bf, const void* A, const double* psi_src,
-                       int check_status, hipStream_t st) {
+                       int check_status, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     if (dm.dtype == LBFGSB_F32) {
-        if (ge.vec > 1) gemvt_dispatch<float, 4>(dm, ge, bf, A, psi_src, check_status, st);
-        else gemvt_dispatch<float, 1>(dm, ge, bf, A, psi_src, check_status, st);
+        if (ge.vec > 1) gemvt_dispatch<float, 4>(dm, ge, bf, A, psi_src, check_status, st, ev0, ev1);
+        else gemvt_dispatch<float, 1>(dm, ge, bf, A, psi_src, check_status, st, ev0, ev1);
     } else {
-        if (ge.vec > 1) gemvt_dispatch<double, 2>(dm, ge, bf, A, psi_src, check_status, st);
-        else gemvt_dispatch<double, 1>(dm, ge, bf, A, psi_src, check_status, st);
+        if (ge.vec > 1) gemvt_dispatch<double, 2>(dm, ge, bf, A, psi_src, check_status, st, ev0, ev1);
+        else gemvt_dispatch<double, 1>(dm, ge, bf, A, psi_src, check_status, st, ev0, ev1);
     }
 }
 

@@ -101,7 +101,7 @@ Geometry make_geometry(const Dims& dm, const void* A) {
     ge.gemvt_rows_per_block = (dm.rows + rb - 1) / rb;
     ge.gemvt_row_blocks = (int)((dm.rows + ge.gemvt_rows_per_block - 1) / ge.gemvt_rows_per_block);
     ge.fused_ok = fused_shape_ok(dm, A, &ge.fused_variant, &ge.fused_blocks) ? 1 : 0;
-    ge.gram_blocks = gram_blocks_for(dm.n);
+    ge.gram_blocks = gram_blocks_for(dm.n, dm.m);
     int64_t db = (dm.n + kBlock - 1) / kBlock;
     ge.dir_blocks = (int)(db > 256 ? 256 : db);
     int64_t ub = (dm.cols + 15) / 16;   // 16 columns per workgroup in the column-sum kernels
@@ -148,7 +148,9 @@ Dims make_dims(int64_t n, int m, const lbfgsb_objective* o) {
     return dm;
 }
 
+// Reads the scalar block after applying any update the last step left pending.
 hipError_t read_scal(lbfgsb_solver* s) {
+    launch_commit(s->dm, s->bf, s->stream);
     hipError_t e = hipMemcpyAsync(s->h_scal, s->bf.scal, sizeof(Scal), hipMemcpyDeviceToHost, s->stream);
     if (e != hipSuccess) return e;
     return hipStreamSynchronize(s->stream);
@@ -168,14 +170,15 @@ void fill_info(const Scal& sc, lbfgsb_info* info) {
     info->alpha = sc.alpha; info->alpha_ub = sc.alpha_ub; info->gp = sc.gp;
 }
 
-struct TimedScope {
-    lbfgsb_solver* s;
-    bool on;
-    explicit TimedScope(lbfgsb_solver* s_) : s(s_), on(s_->timing && s_->timed < kMaxTimed) {
-        if (on) (void)hipEventRecord(s->ev0[s->timed], s->stream);
-    }
-    ~TimedScope() {
-        if (on) { (void)hipEventRecord(s->ev1[s->timed], s->stream); s->timed++; }
+// Events for the next launch of a kernel that reads A (null when timing is off or the store is full).
+struct TimedSlot {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    explicit TimedSlot(lbfgsb_solver* s) {
+        if (s->timing && s->timed < kMaxTimed) {
+            e0 = s->ev0[s->timed];
+            e1 = s->ev1[s->timed];
+            s->timed++;
+        }
     }
 };
 
@@ -188,6 +191,7 @@ APassArgs base_args(const lbfgsb_solver* s) {
 
 // f, g (and the residual / margins) from scratch at the current x.
 void enqueue_eval(lbfgsb_solver* s, int check_status) {
+    launch_commit(s->dm, s->bf, s->stream);   // a pending f must not overwrite the one computed here
     APassArgs a = base_args(s);
     a.va = s->bf.x;
     a.vb = a.split ? s->bf.x + s->dm.cols : nullptr;
@@ -195,11 +199,11 @@ void enqueue_eval(lbfgsb_solver* s, int check_status) {
     a.mode = is_quadratic(s->dm.kind) ? kRowLsqEval : kRowLogiEval;
     a.check_status = check_status;
     if (s->use_fused) {
-        TimedScope ts(s);
-        launch_fused(s->dm, s->ge, s->bf, a, s->stream);
+        TimedSlot ts(s);
+        launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
     } else {
-        { TimedScope ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream); }
-        { TimedScope ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, check_status, s->stream); }
+        { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
+        { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, check_status, s->stream, ts.e0, ts.e1); }
     }
     launch_eval_finish(s->dm, s->ge, s->bf, s->stream);
 }
@@ -219,19 +223,19 @@ void enqueue_step(lbfgsb_solver* s) {
     if (quad) {
         a.mode = kRowDir;
         if (s->use_fused) {
-            TimedScope ts(s);
-            launch_fused(s->dm, s->ge, s->bf, a, s->stream);
+            TimedSlot ts(s);
+            launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
         } else {
-            { TimedScope ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream); }
-            { TimedScope ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.t, 1, s->stream); }
+            { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
+            { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.t, 1, s->stream, ts.e0, ts.e1); }
         }
         launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->stream);
     } else {
         a.mode = kRowLogiDir;
-        { TimedScope ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream); }
+        { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
         launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, s->stream);
         launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
-        { TimedScope ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream); }
+        { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
         launch_update_logistic(s->dm, s->ge, s->bf, s->ge.ls_blocks, s->stream);
     }
     s->steps_since_refresh++;

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/lbfgsb.h"
@@ -31,7 +32,10 @@ struct Scal {
     int pairs_used;
     int memory_resets;
     int ls_ok;              // the last line search found an acceptable step
-    int pad0;
+    // update left pending by the quadratic update kernel (no workgroup of that kernel reads these);
+    // applied by the last workgroup of the next Gram kernel, or by k_commit
+    int pend_valid, pend_ok, pend_bt, pad0;
+    double pend_alpha, pend_f;
     long long iters;
     long long fevals;
     long long n_fixed;
@@ -98,24 +102,77 @@ __device__ __forceinline__ void block_sum(double (&v)[K], double* lds /* NW*K do
 }
 
 // Signals that this workgroup's partial results are in memory and tells whether it is the last
-// one of the grid to do so.  The last workgroup then sees every other workgroup's partials
-// (release fence + relaxed device-scope atomic + acquire fence) and resets the counter for the
-// next launch.  Must be called by all threads of the workgroup.
+// one of the grid to do so.  Every wave first waits for its own stores to be acknowledged; after the
+// barrier thread 0 alone issues the device-scope release fence (which writes the L2 back) and the
+// relaxed device-scope atomic, and in the last workgroup the acquire fence; the barrier that follows
+// extends that to the other waves.  Fencing in every wave instead costs ~60 ns per workgroup of
+// serialised time on MI355X.  The last workgroup resets the counter for the next launch.  Must be
+// called by all threads of the workgroup.
 __device__ __forceinline__ bool arrive_is_last(unsigned* counter, int* lds_flag) {
-    __threadfence();
+    __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0) expcnt(0) lgkmcnt(0): this wave's stores have reached L2
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned total = gridDim.x * gridDim.y;
-        unsigned old = atomicAdd(counter, 1u);
-        *lds_flag = (old == total - 1u);
+        __threadfence();
+        const unsigned total = gridDim.x * gridDim.y;
+        const unsigned old = atomicAdd(counter, 1u);
+        const int last = old == total - 1u;
+        if (last) {
+            __threadfence();
+            *counter = 0u;
+        }
+        *lds_flag = last;
     }
     __syncthreads();
-    const bool last = *lds_flag != 0;
-    if (last) {
-        __threadfence();
-        if (threadIdx.x == 0) *counter = 0u;
+    return *lds_flag != 0;
+}
+
+// Ring bookkeeping.  Logical vector j of [s^0..s^{c-1}, y^0..y^{c-1}, g], pair 0 being the oldest;
+// `head` is the slot the next pair goes to.
+__device__ __forceinline__ const double* ring_vec(int j, int c, int head, int m, int64_t n, const double* S,
+                                                  const double* Y, const double* g) {
+    if (j < c) return S + (int64_t)((head - c + j + 2 * m) % m) * n;
+    if (j < 2 * c) return Y + (int64_t)((head - c + (j - c) + 2 * m) % m) * n;
+    return g;
+}
+
+// head/count as they will be once a pending update has been applied.  ls_dead: the pending update is
+// a failed line search with no pair left to drop (the solver is about to stop).
+__device__ __forceinline__ void effective_ring(const Scal* s, int m, int& head, int& count, bool& ls_dead) {
+    head = s->head;
+    count = s->count;
+    ls_dead = false;
+    if (s->pend_valid) {
+        if (s->pend_ok) {
+            head = (head + 1) % m;
+            count = count < m ? count + 1 : m;
+        } else if (count > 0) {
+            count = 0;
+        } else {
+            ls_dead = true;
+        }
     }
-    return last;
+}
+
+// Applies the pending update: accepted step (pair stored at slot `head`), or an exhausted line search
+// (clear the pair memory and retry once from the steepest-descent direction, else stop).
+__device__ __forceinline__ void apply_pending(Scal* s, int m) {
+    if (!s->pend_valid) return;
+    s->pend_valid = 0;
+    s->ls_ok = s->pend_ok;
+    s->backtracks = s->pend_bt;
+    s->fevals += s->pend_bt + (s->pend_ok ? 1 : 0);
+    if (s->pend_ok) {
+        s->alpha = s->pend_alpha;
+        s->f = s->pend_f;
+        s->head = (s->head + 1) % m;
+        s->count = s->count < m ? s->count + 1 : m;
+        s->iters += 1;
+    } else if (s->count > 0) {
+        s->count = 0;
+        s->memory_resets += 1;
+    } else {
+        s->status = LBFGSB_LINESEARCH_FAILED;
+    }
 }
 
 __device__ __forceinline__ double clampd(double v, double lo, double hi) {
@@ -187,18 +244,23 @@ struct APassArgs {
     int check_status;       // skip all work unless Scal::status == RUNNING
 };
 
-void launch_gemv(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st);
+// ev0/ev1 (both or neither): HIP events attached to the dispatch itself, so that their difference is
+// the kernel's own duration
+void launch_gemv(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
+                 hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // w partials = A^T psi_src (psi_src: Buffers::psi after an evaluation, Buffers::t after a direction pass)
 void launch_gemvt_from(const Dims& dm, const Geometry& ge, const Buffers& bf, const void* A, const double* psi_src,
-                       int check_status, hipStream_t st);
+                       int check_status, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks);
-void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st);
+void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
+                  hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 
 void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 void launch_set_status(const Buffers& bf, int status, hipStream_t st);
 void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, hipStream_t st);
-void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int use_given_mask,
+void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int dbg_inputs,
                  int evaluate_stop, hipStream_t st);
+void launch_commit(const Dims& dm, const Buffers& bf, hipStream_t st);
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st);
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, hipStream_t st);
 void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
@@ -207,6 +269,6 @@ void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf,
 void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, hipStream_t st);
 
 int gram_entries(int m);          // doubles per workgroup partial of the Gram kernel
-int gram_blocks_for(int64_t n);
+int gram_blocks_for(int64_t n, int m);
 
 }  // namespace lb

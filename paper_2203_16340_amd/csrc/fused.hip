@@ -154,14 +154,14 @@ struct Variant {
     int dtype;       // LBFGSB_F64 / LBFGSB_F32
     int nt, kc, r;   // threads, 16-byte chunks per thread and row, rows per stage
     int wgs_per_cu;  // resident workgroups per compute unit the register budget allows
-    void (*launch)(const Dims&, int64_t, int, const Buffers&, const APassArgs&, hipStream_t);
+    void (*launch)(const Dims&, int64_t, int, const Buffers&, const APassArgs&, hipStream_t, hipEvent_t, hipEvent_t);
 };
 
 template <typename T, int NT, int KC, int R, int WPE>
 void launch_variant(const Dims& dm, int64_t rows_per_wg, int blocks, const Buffers& bf, const APassArgs& a,
-                    hipStream_t st) {
-    hipLaunchKernelGGL((k_fused<T, NT, KC, R, WPE>), dim3(blocks), dim3(NT), 0, st, (const T*)a.A, dm.ld, dm.rows, dm.cols,
-                       rows_per_wg, a, bf.scal, bf.row, bf.t, bf.wpart, bf.losspart);
+                    hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+    hipExtLaunchKernelGGL((k_fused<T, NT, KC, R, WPE>), dim3(blocks), dim3(NT), 0, st, ev0, ev1, 0, (const T*)a.A, dm.ld,
+                          dm.rows, dm.cols, rows_per_wg, a, (const Scal*)bf.scal, bf.row, bf.t, bf.wpart, bf.losspart);
 }
 
 // Ordered by capacity: the first variant whose NT*KC*VEC columns cover the row is used.
@@ -217,9 +217,10 @@ bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks) {
     return false;
 }
 
-void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st) {
+void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
+                  hipEvent_t ev0, hipEvent_t ev1) {
     const Variant& v = kVariants[ge.fused_variant];
-    v.launch(dm, rows_per_wg_for(dm, v), ge.fused_blocks, bf, a, st);
+    v.launch(dm, rows_per_wg_for(dm, v), ge.fused_blocks, bf, a, st, ev0, ev1);
 }
 
 }  // namespace lb
