@@ -307,6 +307,13 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
         return fail(LBFGSB_E_UNSUPPORTED, "the fused A pass does not support this objective/shape");
     }
     s->use_fused = quad && s->ge.fused_ok && o.a_pass != LBFGSB_APASS_TWO_PASS;
+    if (s->use_fused) {
+        const hipError_t fe = fused_prepare(s->dm, s->ge);
+        if (fe != hipSuccess) {
+            delete s;
+            return fail(LBFGSB_E_HIP, "preparing the fused A pass: %s", hipGetErrorString(fe));
+        }
+    }
     s->ge.w_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemvt_row_blocks;
     s->ge.loss_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemv_blocks;
 

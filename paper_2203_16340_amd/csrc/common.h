@@ -252,6 +252,7 @@ void launch_gemv(const Dims& dm, const Geometry& ge, const Buffers& bf, const AP
 void launch_gemvt_from(const Dims& dm, const Geometry& ge, const Buffers& bf, const void* A, const double* psi_src,
                        int check_status, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks);
+hipError_t fused_prepare(const Dims& dm, const Geometry& ge);   // once per solver, before the first launch_fused
 void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
                   hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 

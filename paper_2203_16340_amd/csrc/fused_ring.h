@@ -1,0 +1,238 @@
+// Fused single-read A pass for the quadratic objectives, software-pipelined.
+//
+// For f(x) = 0.5*||A v(x) - b||^2 (+ linear terms) one iteration needs t = A v_p and w = A^T t
+// (direction pass), and an evaluation needs r = A v - b and A^T r.  Both have the shape
+//     u_r = a_r . v,   psi_r = rowop(u_r),   w += a_r * psi_r      for every row r,
+// so a workgroup that owns WHOLE rows can keep a row on chip between its dot product and its
+// contribution to w, and A is read from HBM exactly once per pass instead of twice.
+//
+// What limits such a kernel on MI355X is not arithmetic but the bytes it keeps in flight: a row
+// cannot be released before its dot product has been reduced over the workgroup, so unless later
+// rows are already being loaded the memory system idles during every reduction.  On-chip storage
+// per compute unit is 512 KiB of vector registers and 160 KiB of LDS, and the per-column state
+// (v and the fp64 accumulators of w) already takes 16 bytes per column.  Layout chosen here:
+//   * v lives in LDS (read once per row by every thread: ~1/5 of the LDS bandwidth),
+//   * the accumulators of w live in registers (thread `tid` owns the 16-byte chunks
+//     (k*NT + tid), k = 0..KC-1, of every row: a wave reads 1 KiB contiguous per load),
+//   * the rest of the register file is a RING of NB slots, each holding this thread's chunks
+//     of one row fraction (a row is U slots of KCU chunks, KC = U*KCU).  A slot is refilled
+//     with the row fraction NB slots ahead as soon as its contribution to w has been taken,
+//     so loads stay in flight across the reduction and the barrier.
+// Rows are dealt to workgroups in contiguous ranges and processed R at a time (one barrier per R
+// rows).  Each workgroup writes its partial w (summed later in workgroup order, so results are
+// bit-reproducible) and one loss partial.
+//
+// Bytes: rows*cols*sizeof(T) read once, plus G*cols*8 written (G workgroups) and rows*8 for t or r.
+#pragma once
+
+#include "common.h"
+#include "apass_rowop.h"
+
+namespace lb {
+namespace ring {
+
+// 16 bytes of a row as the compiler's native vector types (the non-temporal load builtin takes these)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+template <typename T> struct Raw;
+template <> struct Raw<float> { using type = f32x4; };
+template <> struct Raw<double> { using type = f64x2; };
+
+__device__ __forceinline__ void widen(const f32x4& r, double (&o)[4]) { o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w; }
+__device__ __forceinline__ void widen(const f64x2& r, double (&o)[2]) { o[0] = r.x; o[1] = r.y; }
+__device__ __forceinline__ f32x4 zero_raw(const float*) { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+__device__ __forceinline__ f64x2 zero_raw(const double*) { return f64x2{0.0, 0.0}; }
+
+// Makes the compiler forget what it knows about a loaded fp32 chunk, so that it converts it to fp64 a
+// second time instead of holding both copies in registers.
+__device__ __forceinline__ void forget(f32x4& r) { asm volatile("" : "+v"(r)); }
+__device__ __forceinline__ void forget(f64x2&) {}
+
+constexpr int gcd_i(int a, int b) { return b == 0 ? a : gcd_i(b, a % b); }
+
+// row operation of the quadratic objectives on u = a_r . v (br = b[r], read ahead of time); every
+// thread computes psi, `writer` also stores the row entry.  Returns the row's loss contribution.
+__device__ __forceinline__ double quad_row_op(int mode, double u, double br, int64_t r, bool writer,
+                                              double* __restrict__ row, double* __restrict__ t, double& psi) {
+    if (mode == kRowDir) {
+        psi = u;
+        if (writer) t[r] = u;
+        return u * u;
+    }
+    const double res = u - br;
+    psi = res;
+    if (writer) row[r] = res;
+    return 0.5 * res * res;
+}
+
+// dynamic LDS a launch needs: v for `cols` columns, one all-zero chunk, then the reduction scratch
+constexpr int kPad = 4;
+template <int NT, int R>
+inline size_t lds_bytes(int64_t cols) {
+    return ((size_t)cols + kPad) * 8 + (size_t)2 * R * (NT / 64) * 8;
+}
+
+template <typename T, int NT, int KCU, int U, int R, int NB, int WPE>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
+void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t cols, int64_t rows_per_wg, APassArgs a,
+                  const Scal* __restrict__ scal, double* __restrict__ row, double* __restrict__ t,
+                  double* __restrict__ wpart, double* __restrict__ losspart) {
+    using RawT = typename Raw<T>::type;
+    constexpr int VEC = 16 / sizeof(T);
+    constexpr int KC = KCU * U;
+    constexpr int NW = NT / 64;
+    constexpr int SPS = R * U;                               // slots one stage (R rows) consumes
+    constexpr int STAGES = NB / gcd_i(NB, SPS);              // stages after which the ring is back at slot 0
+    static_assert(NB >= SPS, "the ring must hold at least one stage");
+    extern __shared__ __align__(16) double lds[];
+    double* vs = lds;                                        // v, `cols` entries, then kPad zeros
+    double* red = lds + cols + kPad;                         // [2][R][NW]
+    if (a.check_status && scal->status != LBFGSB_RUNNING) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const double *va, *vb;
+    resolve_v(a, scal, cols, va, vb);
+
+    for (int64_t c = tid; c < cols; c += NT) vs[c] = vb ? va[c] - vb[c] : va[c];
+    if (tid < kPad) vs[cols + tid] = 0.0;
+
+    // chunk k of this thread starts at column (k*NT + tid)*VEC.  A chunk at or past `cols` does not
+    // exist: its loads are redirected to the last chunk of the row (valid memory) and its v to the
+    // zero pad, so it adds nothing to a dot product, and its w is never stored.  No load is predicated.
+    const int c0 = tid * VEC;
+    constexpr int kStride = NT * VEC;
+    const int icols = (int)cols;
+    double w[KC][VEC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) w[k][j] = 0.0;
+
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_wg;
+    const int64_t r_end = r_begin + rows_per_wg < rows ? r_begin + rows_per_wg : rows;
+    if (r_begin >= r_end) return;                            // (the grid is sized so that this does not happen)
+    const int nstage = (int)((r_end - r_begin + R - 1) / R);
+
+    RawT raw[NB][KCU];
+    // fills a ring slot with row fraction j of local row lr (past the last row: that row again, whose
+    // psi is zero; the few repeated loads hit in L2)
+    auto fetch = [&](RawT (&dst)[KCU], int64_t lr, int j) {
+        const int64_t gr = r_begin + lr < r_end ? r_begin + lr : r_end - 1;
+        const char* rp = reinterpret_cast<const char*>(A + gr * ld);   // uniform: lives in scalar registers
+        // 32-bit byte offsets, recomputed at every use (two integer operations) rather than kept in
+        // registers; scalar base + 32-bit vector offset is the addressing form wanted here
+        unsigned cb = (unsigned)c0;
+        asm volatile("" : "+v"(cb));
+#pragma unroll
+        for (int k = 0; k < KCU; ++k) {
+            unsigned c = cb + (unsigned)((j * KCU + k) * kStride);
+            c = c < (unsigned)(icols - VEC) ? c : (unsigned)(icols - VEC);
+            dst[k] = __builtin_nontemporal_load(reinterpret_cast<const RawT*>(rp + c * (unsigned)sizeof(T)));
+        }
+    };
+    // b for the rows of a stage is read one stage ahead through the scalar unit (the row index is
+    // uniform and b never changes): scalar loads are not ordered with the vector loads of the ring,
+    // so waiting for one does not drain the rows in flight
+    typedef const double __attribute__((address_space(4))) * ConstB;
+    const bool need_b = a.mode != kRowDir;
+    auto read_b = [&](double (&dst)[R], int64_t lr) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t gr = r_begin + lr + r < r_end ? r_begin + lr + r : r_end - 1;
+            dst[r] = need_b ? *(ConstB)(uintptr_t)(a.b + gr) : 0.0;
+        }
+    };
+    double bcur[R];
+    read_b(bcur, 0);
+#pragma unroll
+    for (int s = 0; s < NB; ++s) fetch(raw[s], (s / SPS) * R + (s % SPS) / U, (s % SPS) % U);
+    __syncthreads();                                         // v is in LDS
+
+    double loss = 0.0;
+    int par = 0;
+    for (int st0 = 0; st0 < nstage; st0 += STAGES) {
+#pragma unroll
+        for (int ss = 0; ss < STAGES; ++ss) {
+            const int64_t lr0 = (int64_t)(st0 + ss) * R;     // first local row of the stage
+            double acc[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r] = 0.0;
+            // v does not change between rows, but holding it in registers is exactly what this kernel
+            // avoids: an offset the compiler cannot see through keeps the LDS reads inside the loop
+            int cb = c0;
+            asm volatile("" : "+v"(cb));
+#pragma unroll
+            for (int q = 0; q < SPS; ++q) {
+                const int slot = (ss * SPS + q) % NB;
+                const int r = q / U, j = q % U;
+#pragma unroll
+                for (int k = 0; k < KCU; ++k) {
+                    const int kk = j * KCU + k;
+                    int c = cb + kk * kStride;
+                    c = c < icols ? c : icols;               // zero pad for a chunk that does not exist
+                    double e[VEC];
+                    widen(raw[slot][k], e);
+#pragma unroll
+                    for (int i = 0; i < VEC; i += 2) {       // 16-byte LDS reads
+                        const double2 vv = *reinterpret_cast<const double2*>(vs + c + i);
+                        acc[r] = fma(e[i], vv.x, acc[r]);
+                        acc[r] = fma(e[i + 1], vv.y, acc[r]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
+            if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) red[(par * R + r) * NW + wave] = acc[r];
+            }
+            __syncthreads();
+            double bnext[R];
+            read_b(bnext, lr0 + R);
+            double psi[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                double u = 0.0;
+#pragma unroll
+                for (int q = 0; q < NW; ++q) u += red[(par * R + r) * NW + q];
+                psi[r] = 0.0;
+                if (r_begin + lr0 + r < r_end)
+                    loss += quad_row_op(a.mode, u, bcur[r], r_begin + lr0 + r, tid == 0, row, t, psi[r]);
+                bcur[r] = bnext[r];
+            }
+#pragma unroll
+            for (int q = 0; q < SPS; ++q) {
+                const int slot = (ss * SPS + q) % NB;
+                const int r = q / U, j = q % U;
+#pragma unroll
+                for (int k = 0; k < KCU; ++k) {
+                    const int kk = j * KCU + k;
+                    forget(raw[slot][k]);                    // fp32 data is widened again here rather than kept widened across the barrier
+                    double e[VEC];
+                    widen(raw[slot][k], e);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) w[kk][i] = fma(e[i], psi[r], w[kk][i]);
+                }
+                // the slot is free: refill it with the row fraction NB slots ahead.  The scheduling
+                // barriers keep the loads from being hoisted above the last use of the old contents
+                // (which would need a second set of registers for the slot)
+                const int g = ss * SPS + q + NB;             // slot sequence number relative to stage st0
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(raw[slot], (int64_t)(st0 + g / SPS) * R + (g % SPS) / U, (g % SPS) % U);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            par ^= 1;
+        }
+    }
+    double* out = wpart + (int64_t)blockIdx.x * cols + c0;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        if (c0 + k * kStride < icols) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) out[k * kStride + j] = w[k][j];
+        }
+    }
+    if (tid == 0) losspart[blockIdx.x] = loss;
+}
+
+}  // namespace ring
+}  // namespace lb
