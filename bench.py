@@ -40,7 +40,12 @@ WORKLOADS = {
 # HBM bytes per launch of the dominant kernel as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by the same counters read for a copy kernel of known size); filled in from the summaries
 # under profiles/ for the (config, a_pass) pairs that have been profiled, else null in the output.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    ("C2", "fused"): 8.374e8,      # profiles/c2_nnls_20000x5000_f64_fused_a_pass.md      (algorithmic 8.0e8)
+    ("C3", "fused"): 1.682e9,      # profiles/c3_l1ls_10000x20000_f64_fused_a_pass.md     (algorithmic 1.6e9)
+    ("C4", "two_pass"): 1.639e9,   # profiles/c4_logistic_200000x2000_f32_two_pass_gemv.md (algorithmic 1.6e9, mean of the two kernels)
+    ("C5", "fused"): 8.099e9,      # profiles/c5_nnls_100000x20000_f32_fused_a_pass.md    (algorithmic 8.0e9)
+}
 
 
 def cpu_baseline(prob, budget_s: float):
@@ -79,6 +84,9 @@ def main() -> int:
     ap.add_argument("--a-pass", default="auto", choices=["auto", "two_pass", "fused"])
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink both matrix dimensions (debugging only)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="after the timed region, copy a device buffer of this many MiB three times (a plain copy of "
+                         "known size against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
@@ -227,6 +235,15 @@ def main() -> int:
     }
     timed.close()
     solver.close()
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = int(src.numel())
+        del src, dst
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(prob, args.cpu_budget)
     else:
