@@ -220,8 +220,10 @@ def main() -> int:
                 "feasible": feasible, "f": info.f},
         "roofline": {
             "bound": "hbm",
-            "kernel": "fused A pass (t = A p and w = A^T t in one read)" if apass_name == "fused"
-                      else "two-pass A kernels (row-dot, then transposed), one read of A per launch",
+            "kernel": ("two-pass A kernels (row-dot, then transposed), one read of A per launch" if apass_name != "fused"
+                       else "fused A pass, logistic (t = X p, and X^T psi of the first trial step, in one read)"
+                       if prob.kind == workloads.OBJ_LOGISTIC_L2
+                       else "fused A pass (t = A p and w = A^T t in one read)"),
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",

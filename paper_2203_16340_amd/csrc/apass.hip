@@ -76,6 +76,7 @@ __global__ __launch_bounds__(kBlock) void k_gemvt(const T* __restrict__ A, int64
                                                   int64_t rows_per_block, const Scal* __restrict__ scal,
                                                   int check_status) {
     if (check_status && scal->status != LBFGSB_RUNNING) return;
+    if (check_status == 2 && scal->spec_ok) return;   // the speculative single-read pass already produced these columns
     const int64_t c = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
     if (c >= cols) return;
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;

@@ -186,6 +186,8 @@ APassArgs base_args(const lbfgsb_solver* s) {
     APassArgs a{};
     a.A = s->obj.A; a.b = s->obj.b; a.p1 = s->bf.p1; a.p2 = s->bf.p2;
     a.split = s->dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT;
+    a.c1 = s->op.c1;
+    a.mu = s->dm.mu;
     return a;
 }
 
@@ -230,6 +232,18 @@ void enqueue_step(lbfgsb_solver* s) {
             { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.t, 1, s->stream, ts.e0, ts.e1); }
         }
         launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->stream);
+    } else if (s->use_fused) {
+        // One read of X yields t = X p AND X^T psi for the first trial step min(1, alpha_ub); the last
+        // workgroup of that pass tests the Armijo condition for it.  Only if the step is rejected do the
+        // line search over the margins and a second (transposed) pass over X run; otherwise those two
+        // launches return at once.  The transposed pass is not among the timed launches: it reads A only
+        // in the iterations that backtrack.
+        a.mode = kRowLogiSpec;
+        { TimedSlot ts(s); launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
+        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, s->stream);
+        launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
+        launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 2, s->stream, nullptr, nullptr);
+        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.ls_blocks, s->stream);
     } else {
         a.mode = kRowLogiDir;
         { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
@@ -301,12 +315,11 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
         delete s;
         return fail(LBFGSB_E_INVALID_ARG, "workspace too small: %zu < %zu bytes", workspace_bytes, L.total);
     }
-    const bool quad = is_quadratic(s->dm.kind);
-    if (o.a_pass == LBFGSB_APASS_FUSED && !(s->ge.fused_ok && quad)) {
+    if (o.a_pass == LBFGSB_APASS_FUSED && !s->ge.fused_ok) {
         delete s;
-        return fail(LBFGSB_E_UNSUPPORTED, "the fused A pass does not support this objective/shape");
+        return fail(LBFGSB_E_UNSUPPORTED, "the fused A pass does not support this shape");
     }
-    s->use_fused = quad && s->ge.fused_ok && o.a_pass != LBFGSB_APASS_TWO_PASS;
+    s->use_fused = s->ge.fused_ok && o.a_pass != LBFGSB_APASS_TWO_PASS;
     if (s->use_fused) {
         const hipError_t fe = fused_prepare(s->dm, s->ge);
         if (fe != hipSuccess) {

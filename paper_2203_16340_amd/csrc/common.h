@@ -17,7 +17,7 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kLsBatch = 8;        // step lengths the logistic line search evaluates per sweep over the rows
 
 // Which per-kernel arrival counter (Scal::counters) a kernel uses to find its last workgroup.
-enum { kCntGram = 0, kCntDir, kCntUpdate, kCntEvalFinish, kCntLs, kCntCount };
+enum { kCntGram = 0, kCntDir, kCntUpdate, kCntEvalFinish, kCntLs, kCntSpec, kCntCount };
 
 // All scalars of the iteration live here, in device memory, so that no data-dependent decision
 // needs the host.  Only the last workgroup of a kernel to finish ever writes it; every other
@@ -34,7 +34,8 @@ struct Scal {
     int ls_ok;              // the last line search found an acceptable step
     // update left pending by the quadratic update kernel (no workgroup of that kernel reads these);
     // applied by the last workgroup of the next Gram kernel, or by k_commit
-    int pend_valid, pend_ok, pend_bt, pad0;
+    int pend_valid, pend_ok, pend_bt;
+    int spec_ok;            // logistic: the speculative single-read pass already holds the accepted step's X^T psi
     double pend_alpha, pend_f;
     long long iters;
     long long fevals;
@@ -228,7 +229,8 @@ enum RowMode {
     kRowLsqEval = 0,   // u = a_r.v; res = u - b_r -> row, psi; loss += 0.5 res^2
     kRowDir = 1,       // u = a_r.v -> t, psi;            loss += u^2
     kRowLogiEval = 2,  // u = a_r.v -> row (margin); psi = -y sigma(-y u)/rows; loss += softplus(-y u)/rows
-    kRowLogiDir = 3    // u = a_r.v -> t only (no transposed product follows)
+    kRowLogiDir = 3,   // u = a_r.v -> t only (no transposed product follows)
+    kRowLogiSpec = 4   // fused kernel only: u = a_r.v -> t; psi and loss for the first trial step min(1, alpha_ub)
 };
 
 struct APassArgs {
@@ -242,6 +244,7 @@ struct APassArgs {
     int split;              // L1SPLIT: vb = va + cols
     int mode;               // RowMode
     int check_status;       // skip all work unless Scal::status == RUNNING
+    double c1, mu;          // kRowLogiSpec: Armijo constant and regularisation weight for the test of the first trial step
 };
 
 // ev0/ev1 (both or neither): HIP events attached to the dispatch itself, so that their difference is

@@ -50,19 +50,57 @@ __device__ __forceinline__ void forget(f64x2&) {}
 
 constexpr int gcd_i(int a, int b) { return b == 0 ? a : gcd_i(b, a % b); }
 
-// row operation of the quadratic objectives on u = a_r . v (br = b[r], read ahead of time); every
-// thread computes psi, `writer` also stores the row entry.  Returns the row's loss contribution.
-__device__ __forceinline__ double quad_row_op(int mode, double u, double br, int64_t r, bool writer,
-                                              double* __restrict__ row, double* __restrict__ t, double& psi) {
-    if (mode == kRowDir) {
-        psi = u;
-        if (writer) t[r] = u;
-        return u * u;
+// The objective's per-row operation on u = a_r . v, as pure arithmetic (b and z are the row's entries of
+// the target/label vector and of the stored margins, read ahead of time):
+//   psi  : the row's weight in the transposed product,
+//   loss : the row's contribution to the loss partial,
+//   keep : the value stored for the row (into t for the direction modes, into row for the evaluations).
+// LOGI selects the family at compile time (the transcendental code of the logistic modes would
+// otherwise cost the quadratic kernels registers they need for the ring).
+template <bool LOGI>
+__device__ __forceinline__ void row_eval(int mode, double u, double b, double z, double alpha0, double invn,
+                                         double& psi, double& loss, double& keep) {
+    if constexpr (!LOGI) {
+        if (mode == kRowDir) {              // t = A p for the closed-form line search; w = A^T t
+            psi = u; loss = u * u; keep = u;
+        } else {                            // kRowLsqEval: r = A v - b; w = A^T r
+            const double res = u - b;
+            psi = res; loss = 0.5 * res * res; keep = res;
+        }
+    } else {
+        // one exponential serves sigma and softplus of the same argument
+        if (mode == kRowLogiEval) {         // margins z = X w; psi = -y sigma(-y z)/N
+            const double q = -b * u;
+            const double e = exp(-fabs(q));
+            psi = -b * ((q >= 0.0 ? 1.0 : e) / (1.0 + e)) * invn;
+            loss = (fmax(q, 0.0) + log1p(e)) * invn;
+            keep = u;
+        } else {                            // kRowLogiSpec: t = X p, and the weights of the FIRST trial step alpha0
+            // With q = -y z, dq = -y alpha0 t, s = sigma(q), em = expm1(dq) and D = s*em:
+            //   softplus(q + dq) - softplus(q) = log1p(D)   (no cancellation for small steps),
+            //   sigma(q + dq) = s (1 + em) / (1 + D).
+            // The wave leaves this form for the plain definitions only if some row has |dq| >= 30.
+            const double q = -b * z, dq = -b * alpha0 * u;
+            const double e = exp(-fabs(q));
+            const double sg = (q >= 0.0 ? 1.0 : e) / (1.0 + e);
+            keep = u;
+            if (__builtin_amdgcn_ballot_w64(fabs(dq) >= 30.0) == 0ull) {
+                const double em = expm1(dq);
+                const double D = sg * em;
+                loss = log1p(D) * invn;
+                psi = -b * (sg * (1.0 + em) / (1.0 + D)) * invn;
+            } else {
+                psi = -b * sigmoid_d(q + dq) * invn;
+                loss = (fabs(dq) < 30.0 ? log1p(sg * expm1(dq)) : softplus_d(q + dq) - softplus_d(q)) * invn;
+            }
+        }
     }
-    const double res = u - br;
-    psi = res;
-    if (writer) row[r] = res;
-    return 0.5 * res * res;
+}
+
+__device__ __forceinline__ double lane_bcast(double v, int l) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+    return __hiloint2double(hi, lo);
 }
 
 // dynamic LDS a launch needs: v for `cols` columns, one all-zero chunk, then the reduction scratch
@@ -72,10 +110,10 @@ inline size_t lds_bytes(int64_t cols) {
     return ((size_t)cols + kPad) * 8 + (size_t)2 * R * (NT / 64) * 8;
 }
 
-template <typename T, int NT, int KCU, int U, int R, int NB, int WPE>
+template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t cols, int64_t rows_per_wg, APassArgs a,
-                  const Scal* __restrict__ scal, double* __restrict__ row, double* __restrict__ t,
+                  Scal* __restrict__ scal, double* __restrict__ row, double* __restrict__ t,
                   double* __restrict__ wpart, double* __restrict__ losspart) {
     using RawT = typename Raw<T>::type;
     constexpr int VEC = 16 / sizeof(T);
@@ -84,6 +122,8 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     constexpr int SPS = R * U;                               // slots one stage (R rows) consumes
     constexpr int STAGES = NB / gcd_i(NB, SPS);              // stages after which the ring is back at slot 0
     static_assert(NB >= SPS, "the ring must hold at least one stage");
+    static_assert(R <= 16, "one lane per row of a stage evaluates the row operation");
+    __shared__ int last_flag;
     extern __shared__ __align__(16) double lds[];
     double* vs = lds;                                        // v, `cols` entries, then kPad zeros
     double* red = lds + cols + kPad;                         // [2][R][NW]
@@ -109,8 +149,7 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
 
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_wg;
     const int64_t r_end = r_begin + rows_per_wg < rows ? r_begin + rows_per_wg : rows;
-    if (r_begin >= r_end) return;                            // (the grid is sized so that this does not happen)
-    const int nstage = (int)((r_end - r_begin + R - 1) / R);
+    const int nstage = r_end > r_begin ? (int)((r_end - r_begin + R - 1) / R) : 0;   // (the grid is sized so that no range is empty)
 
     RawT raw[NB][KCU];
     // fills a ring slot with row fraction j of local row lr (past the last row: that row again, whose
@@ -129,20 +168,25 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             dst[k] = __builtin_nontemporal_load(reinterpret_cast<const RawT*>(rp + c * (unsigned)sizeof(T)));
         }
     };
-    // b for the rows of a stage is read one stage ahead through the scalar unit (the row index is
-    // uniform and b never changes): scalar loads are not ordered with the vector loads of the ring,
-    // so waiting for one does not drain the rows in flight
-    typedef const double __attribute__((address_space(4))) * ConstB;
-    const bool need_b = a.mode != kRowDir;
-    auto read_b = [&](double (&dst)[R], int64_t lr) {
+    // The row's entries of b (targets or labels) and, for the speculative logistic pass, of the stored
+    // margins are read one stage ahead through the scalar unit (the row index is uniform and neither
+    // vector is written by this kernel in the modes that read it): scalar loads are not ordered with
+    // the vector loads of the ring, so waiting for one does not drain the rows in flight.
+    typedef const double __attribute__((address_space(4))) * ConstD;
+    const int mode = a.mode;
+    const bool need_b = mode != kRowDir, need_z = LOGI && mode == kRowLogiSpec;
+    auto read_rows = [&](double (&db)[R], double (&dz)[R], int64_t lr) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int64_t gr = r_begin + lr + r < r_end ? r_begin + lr + r : r_end - 1;
-            dst[r] = need_b ? *(ConstB)(uintptr_t)(a.b + gr) : 0.0;
+            db[r] = need_b ? *(ConstD)(uintptr_t)(a.b + gr) : 0.0;
+            dz[r] = need_z ? *(ConstD)(uintptr_t)(row + gr) : 0.0;
         }
     };
-    double bcur[R];
-    read_b(bcur, 0);
+    const double alpha0 = need_z ? fmin(1.0, scal->alpha_ub) : 0.0;   // first trial step of the line search
+    const double invn = 1.0 / (double)rows;
+    double bcur[R], zcur[R];
+    read_rows(bcur, zcur, 0);
 #pragma unroll
     for (int s = 0; s < NB; ++s) fetch(raw[s], (s / SPS) * R + (s % SPS) / U, (s % SPS) % U);
     __syncthreads();                                         // v is in LDS
@@ -186,18 +230,35 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
                 for (int r = 0; r < R; ++r) red[(par * R + r) * NW + wave] = acc[r];
             }
             __syncthreads();
-            double bnext[R];
-            read_b(bnext, lr0 + R);
+            double bnext[R], znext[R];
+            read_rows(bnext, znext, lr0 + R);
+            // lane r (< R) of every wave evaluates the row operation of row r of the stage -- the
+            // transcendental functions of the logistic modes run once per stage, not once per row --
+            // and the weights psi are handed to all lanes through scalar registers
+            const int rl = lane < R ? lane : 0;
+            double u = 0.0;
+#pragma unroll
+            for (int q = 0; q < NW; ++q) u += red[(par * R + rl) * NW + q];
+            double bl = bcur[0], zl = zcur[0];
+#pragma unroll
+            for (int r = 1; r < R; ++r) {
+                if (lane == r) { bl = bcur[r]; zl = zcur[r]; }
+            }
+            const int64_t grow = r_begin + lr0 + rl;
+            const bool valid = lane < R && grow < r_end;
+            double psil, lossl, keep;
+            row_eval<LOGI>(mode, u, bl, zl, alpha0, invn, psil, lossl, keep);
+            if (!valid) { psil = 0.0; lossl = 0.0; }
+            loss += lossl;
+            if (valid && wave == 0) {
+                if (mode == kRowDir || mode == kRowLogiSpec) t[grow] = keep; else row[grow] = keep;
+            }
             double psi[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                double u = 0.0;
-#pragma unroll
-                for (int q = 0; q < NW; ++q) u += red[(par * R + r) * NW + q];
-                psi[r] = 0.0;
-                if (r_begin + lr0 + r < r_end)
-                    loss += quad_row_op(a.mode, u, bcur[r], r_begin + lr0 + r, tid == 0, row, t, psi[r]);
+                psi[r] = lane_bcast(psil, r);
                 bcur[r] = bnext[r];
+                zcur[r] = znext[r];
             }
 #pragma unroll
             for (int q = 0; q < SPS; ++q) {
@@ -231,7 +292,33 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             for (int j = 0; j < VEC; ++j) out[k * kStride + j] = w[k][j];
         }
     }
+    loss = wave_sum(loss);                                   // lanes 0..R-1 of a wave hold the row losses
     if (tid == 0) losspart[blockIdx.x] = loss;
+
+    if (!LOGI || mode != kRowLogiSpec) return;
+    // Speculative logistic pass: w above is X^T psi for the first trial step alpha0 and the loss partials
+    // are the terms of f(x + alpha0 p) - f(x).  The last workgroup to finish tests the Armijo condition
+    // for alpha0; if it holds the iteration needs no second pass over X.
+    if (!arrive_is_last(&scal->counters[kCntSpec], &last_flag)) return;
+    double tot = 0.0;
+    for (int k0 = tid; k0 < (int)gridDim.x; k0 += NT) tot += losspart[k0];
+    tot = wave_sum(tot);
+    if (lane == 0) red[wave] = tot;
+    __syncthreads();
+    if (tid == 0) {
+        tot = 0.0;
+#pragma unroll
+        for (int q = 0; q < NW; ++q) tot += red[q];
+        const double df = tot + a.mu * alpha0 * (scal->xp + 0.5 * alpha0 * scal->pp);
+        const int ok = isfinite(df) && df <= a.c1 * alpha0 * scal->gp;
+        scal->spec_ok = ok;
+        if (ok) {
+            scal->ls_ok = 1;
+            scal->backtracks = 0;
+            scal->fevals += 1;
+            scal->alpha = alpha0;
+        }
+    }
 }
 
 }  // namespace ring

@@ -325,6 +325,7 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, const 
     __shared__ double sh_alpha;
     __shared__ int sh_done;
     if (scal->status != LBFGSB_RUNNING) return;
+    if (scal->spec_ok) return;   // the first trial step was accepted inside the speculative pass over X
     const int tid = threadIdx.x;
     const double a0 = fmin(1.0, scal->alpha_ub);
     double al[kLsBatch], s[kLsBatch];
@@ -417,7 +418,7 @@ void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf,
 }
 
 // x+ = P(x + alpha p), g+ = X^T psi + mu x+, pair (x+ - x, g+ - g), f+ from the new margins.
-__global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts, int loss_parts,
+__global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts_two_pass, int w_parts_spec, int loss_parts,
                                                             const double* __restrict__ wpart,
                                                             const double* __restrict__ losspart,
                                                             const double* __restrict__ p1, const double* __restrict__ p2,
@@ -434,6 +435,7 @@ __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts
     const double alpha = scal->alpha;
     const int slot = scal->head;
     const double* p = scal->branch == 1 ? p1 : p2;
+    const int w_parts = scal->spec_ok ? w_parts_spec : w_parts_two_pass;   // which kernel wrote the partial columns
     double sums[2] = {0.0, 0.0};   // ||y||^2, ||x+||^2
     if (ok) {
         double* Sn = S + (int64_t)slot * dm.n;
@@ -479,7 +481,8 @@ __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts
 }
 
 void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, hipStream_t st) {
-    hipLaunchKernelGGL(k_update_logistic, dim3(ge.upd_blocks), dim3(kBlock), 0, st, dm, ge.w_parts, loss_parts, bf.wpart,
+    hipLaunchKernelGGL(k_update_logistic, dim3(ge.upd_blocks), dim3(kBlock), 0, st, dm, ge.gemvt_row_blocks,
+                       ge.fused_blocks, loss_parts, bf.wpart,
                        bf.losspart, bf.p1, bf.p2, bf.l, bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, bf.redpart);
 }
 

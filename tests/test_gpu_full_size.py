@@ -1,6 +1,6 @@
 """Parity at the full sizes of the benchmark configurations C2-C5, in the launch configuration
-bench.py times (default options: fused single-read A pass for the least-squares kinds, two-pass
-kernels for the logistic one).
+bench.py times (default options: the fused single-read A pass, which for the logistic objective is the
+speculative pass that also carries the first trial step).
 
 A full oracle evaluation streams up to 8 GB through one core, so the oracle is asked for SAMPLED
 outputs it can compute one by one, each of them an exact output of the full-size problem:
@@ -58,7 +58,7 @@ def _feasible_point(prob, rng, dense):
 
 def test_expected_launch_configuration(full):
     name, prob, s = full
-    assert s.apass_name == ("two_pass" if name == "C4" else "fused")
+    assert s.apass_name == "fused"
 
 
 def test_rows_of_the_product_at_a_dense_point(full):

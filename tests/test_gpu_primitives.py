@@ -45,8 +45,6 @@ FG_SHAPES = [
 @pytest.mark.parametrize("kind", [L.OBJ_LSQ, L.OBJ_LSQ_L1SPLIT, L.OBJ_LOGISTIC_L2], ids=["lsq", "l1split", "logistic"])
 @pytest.mark.parametrize("rows,cols", FG_SHAPES)
 def test_fg_parity(rows, cols, kind, dtype, a_pass):
-    if a_pass == L.APASS_FUSED and kind == L.OBJ_LOGISTIC_L2:
-        pytest.skip("the fused pass serves the quadratic objectives")
     rng = np.random.default_rng(rows * 7919 + cols * 31 + kind)
     A = rng.standard_normal((rows, cols)).astype(dtype)
     if kind == L.OBJ_LOGISTIC_L2:

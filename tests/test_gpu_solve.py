@@ -71,8 +71,6 @@ def test_c1_full_size(a_pass):
 def test_scaled_configs(name, scale, f_tol, same_set, a_pass):
     prob = workloads.config(name, scale=scale)
     prob.tol, prob.tol_relative = 1e-9, True              # tight enough that f agrees to the stated bound
-    if name == "C4" and a_pass == L.APASS_FUSED:
-        pytest.skip("the fused pass serves the quadratic objectives")
     g0 = host_gradient(prob, prob.x0)
     mask0 = oracle.free_mask(prob.x0, g0, prob.l, prob.u, 1e-10).astype(bool)
     _compare_with_oracle(prob, a_pass, f_tol, same_set, 1e-8 * max(1.0, np.linalg.norm(g0[mask0])))
@@ -84,8 +82,6 @@ def test_first_iterations_match_step_by_step(name, scale, a_pass):
     """Iterations 1-3 from x0 = 0: same branch, same number of backtracks, same step length, and the
     iterate within rounding."""
     prob = workloads.config(name, scale=scale)
-    if name == "C4" and a_pass == L.APASS_FUSED:
-        pytest.skip("the fused pass serves the quadratic objectives")
     obj = oracle.Objective(prob.kind, prob.A, prob.b, prob.lam, prob.mu)
     orc = oracle.Solver(obj, prob.l, prob.u, prob.x0, prob.m, oracle.default_options(tol=0.0))
     s = _gpu_solver(prob, a_pass, tol=0.0)
