@@ -54,6 +54,13 @@ int gram_blocks_for(int64_t n, int m) {
     return (int)(b < 1 ? 1 : (b > 128 ? 128 : b));
 }
 
+// value of v in lane l (l uniform across the wave): a scalar-register read, not a trip through LDS
+__device__ __forceinline__ double lane_value(double v, int l) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ __forceinline__ void tile_of(int q, int T, int& ti, int& tj) {
     int a = 0;
     while (q >= T - a) { q -= T - a; ++a; }
@@ -236,7 +243,8 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
     const double* hp = grampart + (int64_t)tid * NE;
     double sv[3] = {have ? hp[0] : 0.0, have ? hp[2] : 0.0, have ? hp[3] : 0.0};
     double mx = have ? hp[1] : 0.0;
-    // one thread per entry adds the partials in workgroup order, 24 loads in flight
+    // one thread per entry adds the partials in workgroup order, 24 loads in flight (larger batches
+    // measured no faster: one compute unit's load bandwidth is the limit once there are ~100 partials)
     for (int q4 = tid; q4 < 4 * TT; q4 += kBlock) {
         const double* src = grampart + kHdr + q4;
         double s = 0.0;
@@ -292,14 +300,14 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
 #pragma unroll 4
         for (int k = c - 1; k >= 0; --k) {
             const double gsy = i < c ? G[i * Vp + (c + k)] : 0.0;   // <s_i, y_k>
-            double ak = __shfl(part_s * inv, k);
+            double ak = lane_value(part_s * inv, k);
             if (!((pm >> k) & 1ull)) ak = 0.0;
             if (i == k) alpha_i = ak;
             part_s = fma(-ak, gsy, part_s);
         }
         if (i < c) alpha_s[i] = alpha_i;
         double gamma = 1.0;
-        if (c > 0 && ((pm >> (c - 1)) & 1ull)) gamma = __shfl(rho / yn, c - 1);
+        if (c > 0 && ((pm >> (c - 1)) & 1ull)) gamma = lane_value(rho / yn, c - 1);
         // <y_i, gamma (g - sum_k alpha_k y_k)>
         double by = 0.0;
         {
@@ -316,7 +324,7 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
 #pragma unroll 4
         for (int k = 0; k < c; ++k) {
             const double gys = i < c ? G[(c + i) * Vp + k] : 0.0;   // <y_i, s_k>
-            double ck = __shfl(alpha_i - by * inv, k);
+            double ck = lane_value(alpha_i - by * inv, k);
             if (!((pm >> k) & 1ull)) ck = 0.0;
             if (i == k) coef_s = ck;
             if (i > k) by = fma(ck, gys, by);
