@@ -103,6 +103,73 @@ __device__ __forceinline__ double lane_bcast(double v, int l) {
     return __hiloint2double(hi, lo);
 }
 
+// After the barrier of a stage: lane r (< R) of EVERY wave sums the partial dot products of row r of the
+// stage and evaluates its row operation -- the transcendental functions of the logistic modes run once
+// per stage, not once per row -- wave 0 stores the row's entry of t / row, and the weights psi are
+// handed to all lanes through scalar registers.  red: [R][NW] partial dot products of this stage;
+// bcur/zcur: the rows' entries of b and of the stored margins; row0: global index of the stage's first row.
+template <int R, int NW, bool LOGI>
+__device__ __forceinline__ void stage_row_op(const double* red, int lane, int wave, int mode, const double (&bcur)[R],
+                                             const double (&zcur)[R], int64_t row0, int64_t r_end, double alpha0,
+                                             double invn, double* __restrict__ row, double* __restrict__ t,
+                                             double& loss, double (&psi)[R]) {
+    const int rl = lane < R ? lane : 0;
+    double u = 0.0;
+#pragma unroll
+    for (int q = 0; q < NW; ++q) u += red[rl * NW + q];
+    // lane r takes entry r: a chain of selects on values made opaque first (left transparent, the compiler
+    // turns the chain into an array in scratch memory indexed by the lane, i.e. into vector memory traffic
+    // in the middle of the stage)
+    double bl = 0.0, zl = 0.0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        double bv = bcur[r], zv = zcur[r];
+        asm volatile("" : "+v"(bv), "+v"(zv));
+        if (lane == r) { bl = bv; zl = zv; }
+    }
+    const int64_t grow = row0 + rl;
+    const bool valid = lane < R && grow < r_end;
+    double psil, lossl, keep;
+    row_eval<LOGI>(mode, u, bl, zl, alpha0, invn, psil, lossl, keep);
+    if (!valid) { psil = 0.0; lossl = 0.0; }
+    loss += lossl;
+    if (valid && wave == 0) {
+        if (mode == kRowDir || mode == kRowLogiSpec) t[grow] = keep; else row[grow] = keep;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) psi[r] = lane_bcast(psil, r);
+}
+
+// Speculative logistic pass: the partial columns are X^T psi for the first trial step alpha0 and the loss
+// partials are the terms of f(x + alpha0 p) - f(x).  The last workgroup to finish tests the Armijo
+// condition for alpha0; if it holds the iteration needs no second pass over X.  Called by all threads.
+template <int NT>
+__device__ __forceinline__ void spec_decide(Scal* __restrict__ scal, const APassArgs& a, double alpha0,
+                                            const double* __restrict__ losspart, double* red, int* last_flag) {
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (!arrive_is_last(&scal->counters[kCntSpec], last_flag)) return;
+    double tot = 0.0;
+    for (int k0 = tid; k0 < (int)gridDim.x; k0 += NT) tot += losspart[k0];
+    tot = wave_sum(tot);
+    if (lane == 0) red[wave] = tot;
+    __syncthreads();
+    if (tid == 0) {
+        tot = 0.0;
+#pragma unroll
+        for (int q = 0; q < NW; ++q) tot += red[q];
+        const double df = tot + a.mu * alpha0 * (scal->xp + 0.5 * alpha0 * scal->pp);
+        const int ok = isfinite(df) && df <= a.c1 * alpha0 * scal->gp;
+        scal->spec_ok = ok;
+        if (ok) {
+            scal->ls_ok = 1;
+            scal->backtracks = 0;
+            scal->fevals += 1;
+            scal->alpha = alpha0;
+        }
+    }
+}
+
 // dynamic LDS a launch needs: v for `cols` columns, one all-zero chunk, then the reduction scratch
 constexpr int kPad = 4;
 template <int NT, int R>
@@ -232,31 +299,11 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             __syncthreads();
             double bnext[R], znext[R];
             read_rows(bnext, znext, lr0 + R);
-            // lane r (< R) of every wave evaluates the row operation of row r of the stage -- the
-            // transcendental functions of the logistic modes run once per stage, not once per row --
-            // and the weights psi are handed to all lanes through scalar registers
-            const int rl = lane < R ? lane : 0;
-            double u = 0.0;
-#pragma unroll
-            for (int q = 0; q < NW; ++q) u += red[(par * R + rl) * NW + q];
-            double bl = bcur[0], zl = zcur[0];
-#pragma unroll
-            for (int r = 1; r < R; ++r) {
-                if (lane == r) { bl = bcur[r]; zl = zcur[r]; }
-            }
-            const int64_t grow = r_begin + lr0 + rl;
-            const bool valid = lane < R && grow < r_end;
-            double psil, lossl, keep;
-            row_eval<LOGI>(mode, u, bl, zl, alpha0, invn, psil, lossl, keep);
-            if (!valid) { psil = 0.0; lossl = 0.0; }
-            loss += lossl;
-            if (valid && wave == 0) {
-                if (mode == kRowDir || mode == kRowLogiSpec) t[grow] = keep; else row[grow] = keep;
-            }
             double psi[R];
+            stage_row_op<R, NW, LOGI>(red + par * R * NW, lane, wave, mode, bcur, zcur, r_begin + lr0, r_end, alpha0,
+                                      invn, row, t, loss, psi);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                psi[r] = lane_bcast(psil, r);
                 bcur[r] = bnext[r];
                 zcur[r] = znext[r];
             }
@@ -295,30 +342,7 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     loss = wave_sum(loss);                                   // lanes 0..R-1 of a wave hold the row losses
     if (tid == 0) losspart[blockIdx.x] = loss;
 
-    if (!LOGI || mode != kRowLogiSpec) return;
-    // Speculative logistic pass: w above is X^T psi for the first trial step alpha0 and the loss partials
-    // are the terms of f(x + alpha0 p) - f(x).  The last workgroup to finish tests the Armijo condition
-    // for alpha0; if it holds the iteration needs no second pass over X.
-    if (!arrive_is_last(&scal->counters[kCntSpec], &last_flag)) return;
-    double tot = 0.0;
-    for (int k0 = tid; k0 < (int)gridDim.x; k0 += NT) tot += losspart[k0];
-    tot = wave_sum(tot);
-    if (lane == 0) red[wave] = tot;
-    __syncthreads();
-    if (tid == 0) {
-        tot = 0.0;
-#pragma unroll
-        for (int q = 0; q < NW; ++q) tot += red[q];
-        const double df = tot + a.mu * alpha0 * (scal->xp + 0.5 * alpha0 * scal->pp);
-        const int ok = isfinite(df) && df <= a.c1 * alpha0 * scal->gp;
-        scal->spec_ok = ok;
-        if (ok) {
-            scal->ls_ok = 1;
-            scal->backtracks = 0;
-            scal->fevals += 1;
-            scal->alpha = alpha0;
-        }
-    }
+    if (LOGI && mode == kRowLogiSpec) spec_decide<NT>(scal, a, alpha0, losspart, red, &last_flag);
 }
 
 }  // namespace ring
