@@ -25,10 +25,26 @@ LSQ, LSQ_L1SPLIT, LOGISTIC_L2 = 0, 1, 2
 F64, F32 = 0, 1
 
 
+class _Constraints(C.Structure):
+    _fields_ = [("n_eq", C.c_int64), ("n_in", C.c_int64), ("C", C.c_void_p), ("d", C.c_void_p),
+                ("E", C.c_void_p), ("e", C.c_void_p), ("lam", C.c_void_p), ("mu", C.c_void_p),
+                ("rho", C.c_double)]
+
+
 class _Objective(C.Structure):
     _fields_ = [("kind", C.c_int), ("dtype", C.c_int), ("rows", C.c_int64), ("cols", C.c_int64),
                 ("ld", C.c_int64), ("A", C.c_void_p), ("b", C.c_void_p), ("lam", C.c_double),
-                ("mu", C.c_double)]
+                ("mu", C.c_double), ("con", C.c_void_p)]
+
+
+class AuglagOptions(C.Structure):
+    _fields_ = [("rho0", C.c_double), ("ctol", C.c_double), ("max_outer", C.c_int)]
+
+
+class AuglagInfo(C.Structure):
+    _fields_ = [("status", C.c_int), ("outer", C.c_int), ("inner_iters", C.c_int64),
+                ("violation", C.c_double), ("rho", C.c_double), ("f", C.c_double), ("L", C.c_double),
+                ("pg2", C.c_double)]
 
 
 class Options(C.Structure):
@@ -98,6 +114,11 @@ def load():
             getattr(lib, name).argtypes = [C.c_void_p]
         lib.orc_npairs.restype = C.c_int
         lib.orc_npairs.argtypes = [C.c_void_p]
+        lib.orc_auglag_default_options.restype = None
+        lib.orc_auglag_default_options.argtypes = [C.POINTER(AuglagOptions)]
+        lib.orc_auglag_solve.restype = C.c_int
+        lib.orc_auglag_solve.argtypes = [C.c_int64, C.c_int, dp, dp, dp, C.POINTER(_Objective), C.POINTER(Options),
+                                         C.POINTER(AuglagOptions), C.POINTER(AuglagInfo)]
         _lib = lib
     return _lib
 
@@ -134,7 +155,25 @@ class Objective:
             raise ValueError("b must have one entry per row of A")
         self.kind = kind
         self.c = _Objective(kind, F64 if A.dtype == np.float64 else F32, A.shape[0], A.shape[1],
-                            A.strides[0] // A.itemsize, _ptr(A), _ptr(self.b), float(lam), float(mu))
+                            A.strides[0] // A.itemsize, _ptr(A), _ptr(self.b), float(lam), float(mu), None)
+        self.con = None
+
+    def set_constraints(self, C_eq=None, d=None, E_in=None, e=None, lam=None, mu=None, rho: float = 1.0):
+        """Attach linear constraints C x = d, E x <= e and a multiplier state (Eq. (augLag)): fg() then
+        evaluates the augmented Lagrangian.  The multiplier arrays are kept (and updated in place by
+        auglag_solve) as self.lam / self.mu."""
+        cols = self.A.shape[1]
+        self.C_eq = _f64(C_eq).reshape(-1, cols) if C_eq is not None else np.zeros((0, cols))
+        self.E_in = _f64(E_in).reshape(-1, cols) if E_in is not None else np.zeros((0, cols))
+        self.d = _f64(d).reshape(-1) if d is not None else np.zeros(0)
+        self.e = _f64(e).reshape(-1) if e is not None else np.zeros(0)
+        assert self.d.shape == (self.C_eq.shape[0],) and self.e.shape == (self.E_in.shape[0],)
+        self.lam = _f64(lam).copy() if lam is not None else np.zeros(self.C_eq.shape[0])
+        self.mu = _f64(mu).copy() if mu is not None else np.zeros(self.E_in.shape[0])
+        self.con = _Constraints(self.C_eq.shape[0], self.E_in.shape[0], _ptr(self.C_eq), _ptr(self.d),
+                                _ptr(self.E_in), _ptr(self.e), _ptr(self.lam), _ptr(self.mu), float(rho))
+        self.c.con = C.cast(C.pointer(self.con), C.c_void_p)
+        return self
 
     @property
     def n(self) -> int:
@@ -142,11 +181,13 @@ class Objective:
 
 
 def fg(obj: Objective, x, want_rowvec: bool = False):
-    """f(x), grad f(x) [, residual or margins]"""
+    """f(x), grad f(x) [, residual or margins (followed by the shifted constraint values when the
+    objective carries constraints)]"""
     x = _f64(x)
     assert x.shape == (obj.n,)
     g = np.empty(obj.n)
-    rv = np.empty(obj.A.shape[0]) if want_rowvec else None
+    ncon = (obj.con.n_eq + obj.con.n_in) if obj.con is not None else 0
+    rv = np.empty(obj.A.shape[0] + ncon) if want_rowvec else None
     f = load().orc_fg(C.byref(obj.c), _ptr(x), _ptr(g), _ptr(rv))
     return (f, g, rv) if want_rowvec else (f, g)
 
@@ -160,7 +201,8 @@ def f_only(obj: Objective, x) -> float:
 def delta_f(obj: Objective, x, xt, row) -> float:
     """f(xt) - f(x) from the cancellation-free row-wise identity; row = residuals/margins at x."""
     x, xt, row = _f64(x), _f64(xt), _f64(row)
-    assert x.shape == (obj.n,) and xt.shape == (obj.n,) and row.shape == (obj.A.shape[0],)
+    ncon = (obj.con.n_eq + obj.con.n_in) if obj.con is not None else 0
+    assert x.shape == (obj.n,) and xt.shape == (obj.n,) and row.shape == (obj.A.shape[0] + ncon,)
     return load().orc_delta_f(C.byref(obj.c), _ptr(x), _ptr(xt), _ptr(row))
 
 
@@ -274,3 +316,20 @@ def solve_problem(prob, **option_overrides) -> Result:
         return s.solve()
     finally:
         s.close()
+
+
+def auglag_solve(obj: Objective, l, u, x0, m: int, options: Optional[Options] = None, rho0: float = 1.0,
+                 ctol: float = 1e-8, max_outer: int = 100):
+    """Algorithm 4 on a least-squares objective with constraints attached by set_constraints().
+    Returns (x, lambda, mu, AuglagInfo)."""
+    assert obj.con is not None
+    x = _f64(x0).copy()
+    l, u = _f64(l), _f64(u)
+    ao = AuglagOptions(float(rho0), float(ctol), int(max_outer))
+    info = AuglagInfo()
+    opts = options if options is not None else default_options()
+    rc = load().orc_auglag_solve(obj.n, m, _ptr(l), _ptr(u), _ptr(x), C.byref(obj.c), C.byref(opts), C.byref(ao),
+                                 C.byref(info))
+    if rc != 0:
+        raise ValueError("oracle rejected the constrained problem")
+    return x, obj.lam.copy(), obj.mu.copy(), info

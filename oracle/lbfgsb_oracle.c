@@ -12,6 +12,9 @@
  *   - objectives: the NNLS section's least-squares objective (scaled by 1/2), its
  *     L1-regularised variant split into x = p - q, and the regularised empirical
  *     logistic risk of the fairness section restricted to a box       -> orc_fg
+ *   - Eq. (augLag) and Algorithm 4 (augmented Lagrangian algorithm, section "Complete
+ *     Framework" and appendix) for LINEAR constraints h(x) = C x - d = 0 and
+ *     g(x) = E x - e <= 0 on top of the least-squares objective     -> orc_fg, orc_auglag_solve
  *
  * Nothing here is blocked, fused or reordered: every objective value and gradient is
  * evaluated from scratch at every trial point, the two-loop recursion is the literal
@@ -43,6 +46,14 @@
  *     redone once from the steepest-descent direction; if that fails too the solver
  *     stops with ORC_LINESEARCH_FAILED.
  *
+ *   - Algorithm 4 says "update rho" and "until convergence" without formulas; the text says
+ *     rho is doubled when the infinity norm of the constraint violation is not halved in an
+ *     iteration.  Taken here: violation = max(||h(x)||_inf, ||max(g(x), 0)||_inf); the first
+ *     iteration compares with the violation at x^0; the loop stops when the violation is at most
+ *     ctol and the inner solve converged (or after max_outer iterations); every inner solve is
+ *     warm-started at the previous x with an empty pair memory and run to the box solver's own
+ *     tolerance; x^0 is the caller's (the listing's x^0 = 0 when that is feasible).
+ *
  * Parity pins (tests/test_oracle_*.py): KKT at the returned point, numpy lstsq when no
  * bound is active, brute-force active-set enumeration, scipy nnls / lsq_linear /
  * L-BFGS-B minimisers, dense BFGS-matrix construction for Algorithm 3, truth tables for
@@ -59,12 +70,24 @@ enum { ORC_LSQ = 0, ORC_LSQ_L1SPLIT = 1, ORC_LOGISTIC_L2 = 2 };
 enum { ORC_F64 = 0, ORC_F32 = 1 };
 enum { ORC_RUNNING = 0, ORC_CONVERGED = 1, ORC_MAX_ITER = 2, ORC_LINESEARCH_FAILED = 3 };
 
+/* Linear constraints and the multiplier state of Eq. (augLag):
+ *   h(x) = C x - d = 0 (n_eq rows),  g(x) = E x - e <= 0 (n_in rows),  C and E row-major with
+ *   `cols` columns.  When an objective carries one of these, orc_fg evaluates
+ *   L(x, lambda, mu, rho) = f(x) + rho/2 ||h(x) + lambda/rho||^2 + rho/2 ||(g(x) + mu/rho)_+||^2. */
+typedef struct {
+    int64_t n_eq, n_in;
+    const double *C, *d, *E, *e;
+    double *lambda, *mu;   /* n_eq / n_in entries, updated by orc_auglag_solve */
+    double rho;
+} orc_constraints;
+
 typedef struct {
     int kind, dtype;
     int64_t rows, cols, ld;
     const void* A;     /* row-major rows x cols, leading dimension ld */
     const double* b;   /* targets (least squares) or labels in {-1,+1} (logistic) */
     double lambda, mu;
+    const orc_constraints* con;   /* NULL: no constraints besides the box (ORC_LSQ only otherwise) */
 } orc_objective;
 
 typedef struct {
@@ -185,6 +208,26 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
         }
         free(acc);
     }
+    if (o->con && o->kind == ORC_LSQ) {
+        /* Eq. (augLag): the two penalty terms, their gradients C^T rho (h + lambda/rho) and
+         * E^T rho (g + mu/rho)_+, and (after the rows of A) the shifted constraint values in rowvec */
+        const orc_constraints* k = o->con;
+        nsum pen = {0.0, 0.0};
+        for (int64_t r = 0; r < k->n_eq + k->n_in; ++r) {
+            const int eq = r < k->n_eq;
+            const double* crow = eq ? k->C + r * cols : k->E + (r - k->n_eq) * cols;
+            nsum acc = {0.0, 0.0};
+            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&acc, crow[c], v[c]);
+            double a = eq ? ns_val(&acc) - k->d[r] + k->lambda[r] / k->rho
+                          : ns_val(&acc) - k->e[r - k->n_eq] + k->mu[r - k->n_eq] / k->rho;
+            if (rowvec) rowvec[rows + r] = a;
+            double act = eq ? a : (a > 0.0 ? a : 0.0);
+            ns_add(&pen, 0.5 * k->rho * act * act);
+            if (g)
+                for (int64_t c = 0; c < cols; ++c) g[c] += k->rho * act * crow[c];
+        }
+        f += ns_val(&pen);
+    }
     free(v);
     free(psi);
     return f;
@@ -213,6 +256,24 @@ double orc_delta_f(const orc_objective* o, const double* x, const double* xt, co
             else ns_add(&acc, softplus(a + da) - softplus(a));
         } else {
             ns_add_prod(&acc, dz, row[r] + 0.5 * dz);
+        }
+    }
+    if (o->con && o->kind == ORC_LSQ) {
+        /* rho/2 [(a + da)^2 - a^2] = rho da (a + da/2) for an equality row;
+         * rho/2 [(a + da)_+^2 - a_+^2] = rho/2 (p1 - p0)(p1 + p0) for an inequality row */
+        const orc_constraints* k = o->con;
+        for (int64_t r = 0; r < k->n_eq + k->n_in; ++r) {
+            const int eq = r < k->n_eq;
+            const double* crow = eq ? k->C + r * cols : k->E + (r - k->n_eq) * cols;
+            nsum dacc = {0.0, 0.0};
+            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&dacc, crow[c], dv[c]);
+            double da = ns_val(&dacc), a = row[rows + r];
+            if (eq) {
+                ns_add_prod(&acc, k->rho * da, a + 0.5 * da);
+            } else {
+                double p0 = a > 0.0 ? a : 0.0, p1 = a + da > 0.0 ? a + da : 0.0;
+                ns_add_prod(&acc, 0.5 * k->rho * (p1 - p0), p1 + p0);
+            }
         }
     }
     free(dv);
@@ -367,7 +428,7 @@ orc_solver* orc_create(int64_t n, int m, const double* l, const double* u, const
     s->g = (double*)malloc(nb); s->d = (double*)malloc(nb); s->p = (double*)malloc(nb);
     s->xt = (double*)malloc(nb); s->gt = (double*)malloc(nb);
     s->mask = (uint8_t*)malloc((size_t)n);
-    s->row = (double*)malloc(sizeof(double) * (size_t)(obj->rows > 0 ? obj->rows : 1));
+    s->row = (double*)malloc(sizeof(double) * (size_t)(obj->rows + (obj->con ? obj->con->n_eq + obj->con->n_in : 0) + 1));
     s->S = (double*)malloc(nb * (size_t)m); s->Y = (double*)malloc(nb * (size_t)m);
     s->ynorm2 = (double*)malloc(sizeof(double) * (size_t)m);
     memcpy(s->l, l, nb); memcpy(s->u, u, nb); memcpy(s->x, x0, nb);
@@ -489,3 +550,100 @@ const double* orc_S(const orc_solver* s) { return s->S; }
 const double* orc_Y(const orc_solver* s) { return s->Y; }
 const double* orc_ynorm2(const orc_solver* s) { return s->ynorm2; }
 int orc_npairs(const orc_solver* s) { return s->npairs; }
+
+/* ---- Algorithm 4: augmented Lagrangian algorithm ------------------------------------------ */
+
+typedef struct {
+    double rho0;        /* initial rho (the listing: 1) */
+    double ctol;        /* stop when the constraint violation is at most this and the inner solve converged */
+    int max_outer;
+} orc_auglag_options;
+
+typedef struct {
+    int status;             /* ORC_CONVERGED, ORC_MAX_ITER (outer limit) or the inner solver's failure status */
+    int outer;              /* outer iterations done */
+    int64_t inner_iters;    /* box-solver iterations, all outer iterations together */
+    double violation;       /* max(||h(x)||_inf, ||max(g(x), 0)||_inf) at the returned x */
+    double rho;
+    double f;               /* objective without the penalty terms */
+    double L;               /* augmented Lagrangian at the returned x with the multipliers it was minimised for */
+    double pg2;             /* the last inner solve's stopping quantity */
+} orc_auglag_info;
+
+void orc_auglag_default_options(orc_auglag_options* o) {
+    o->rho0 = 1.0;
+    o->ctol = 1e-8;
+    o->max_outer = 100;
+}
+
+/* h = C x - d and g = E x - e at x; returns max(||h||_inf, ||max(g, 0)||_inf) */
+static double constraint_values(const orc_constraints* k, int64_t cols, const double* x, double* h, double* g) {
+    double viol = 0.0;
+    for (int64_t r = 0; r < k->n_eq + k->n_in; ++r) {
+        const int eq = r < k->n_eq;
+        const double* crow = eq ? k->C + r * cols : k->E + (r - k->n_eq) * cols;
+        nsum acc = {0.0, 0.0};
+        for (int64_t c = 0; c < cols; ++c) ns_add_prod(&acc, crow[c], x[c]);
+        if (eq) {
+            h[r] = ns_val(&acc) - k->d[r];
+            if (fabs(h[r]) > viol) viol = fabs(h[r]);
+        } else {
+            g[r - k->n_eq] = ns_val(&acc) - k->e[r - k->n_eq];
+            if (g[r - k->n_eq] > viol) viol = g[r - k->n_eq];
+        }
+    }
+    return viol;
+}
+
+/* Algorithm 4 on an ORC_LSQ objective that carries constraints (obj->con; its lambda and mu arrays are
+ * the multiplier state: set to zero here, updated in place, returned).  x: in = x^0 (feasible for the
+ * box), out = the result. */
+int orc_auglag_solve(int64_t n, int m, const double* l, const double* u, double* x, const orc_objective* obj,
+                     const orc_options* opt, const orc_auglag_options* aopt, orc_auglag_info* info) {
+    memset(info, 0, sizeof *info);
+    if (!obj || obj->kind != ORC_LSQ || !obj->con || n != obj->cols) return -1;
+    orc_constraints* k = (orc_constraints*)obj->con;   /* the multiplier state is the caller's, mutable */
+    orc_auglag_options ao;
+    if (aopt) ao = *aopt; else orc_auglag_default_options(&ao);
+    double* h = (double*)malloc(sizeof(double) * (size_t)(k->n_eq + 1));
+    double* g = (double*)malloc(sizeof(double) * (size_t)(k->n_in + 1));
+    for (int64_t r = 0; r < k->n_eq; ++r) k->lambda[r] = 0.0;
+    for (int64_t r = 0; r < k->n_in; ++r) k->mu[r] = 0.0;
+    k->rho = ao.rho0;
+    double viol_prev = constraint_values(k, obj->cols, x, h, g);
+    info->status = ORC_MAX_ITER;
+    info->violation = viol_prev;
+    for (int it = 0; it < ao.max_outer; ++it) {
+        /* x^{k+1} = argmin over the box of L(., lambda^k, mu^k, rho) by Algorithm 1 */
+        orc_solver* s = orc_create(n, m, l, u, x, obj, opt);
+        if (!s) { free(h); free(g); return -1; }
+        int st = orc_solve(s);
+        memcpy(x, s->x, sizeof(double) * (size_t)n);
+        info->inner_iters += s->info.iters;
+        info->L = s->f;
+        info->pg2 = s->info.pg2;
+        orc_destroy(s);
+        info->outer = it + 1;
+        if (st == ORC_LINESEARCH_FAILED) { info->status = st; break; }
+        /* lambda^{k+1} = lambda^k + rho h(x^{k+1});  mu^{k+1} = (mu^k + rho g(x^{k+1}))_+ */
+        double viol = constraint_values(k, obj->cols, x, h, g);
+        for (int64_t r = 0; r < k->n_eq; ++r) k->lambda[r] += k->rho * h[r];
+        for (int64_t r = 0; r < k->n_in; ++r) {
+            double v = k->mu[r] + k->rho * g[r];
+            k->mu[r] = v > 0.0 ? v : 0.0;
+        }
+        info->violation = viol;
+        if (viol <= ao.ctol && st == ORC_CONVERGED) { info->status = ORC_CONVERGED; break; }
+        /* rho is doubled when the violation was not halved in this iteration */
+        if (viol > 0.5 * viol_prev) k->rho *= 2.0;
+        viol_prev = viol;
+    }
+    info->rho = k->rho;
+    {
+        orc_objective plain = *obj;
+        plain.con = NULL;
+        info->f = orc_fg(&plain, x, NULL, NULL);
+    }
+    free(h); free(g);
+    return 0;
+}
