@@ -61,6 +61,8 @@ typedef struct {
     const double* b;     /* device, rows entries: targets (least squares) or labels (logistic), borrowed */
     double lambda;       /* L1SPLIT only */
     double mu;           /* LOGISTIC_L2 only */
+    const double* row_weight; /* device, rows entries or NULL (= all ones), borrowed; least-squares kinds only:
+                                 f = 0.5*sum_r row_weight_r*(A v - b)_r^2 (+ lambda*sum(p+q)) */
 } lbfgsb_objective;
 
 /* how the products with A are organised (results agree to rounding) */
@@ -160,6 +162,59 @@ int lbfgsb_get_g(lbfgsb_solver* s, double* g_out);
 
 /* Frees the host object (the workspace stays the caller's).  NULL is a no-op. */
 void lbfgsb_destroy(lbfgsb_solver* s);
+
+/* ---- augmented Lagrangian algorithm -------------------------------------------------------------
+ * The paper's section "Complete Framework" (Eq. (augLag)) and Algorithm 4 of its appendix, for LINEAR
+ * equality constraints on the least-squares objective:
+ *     minimise 0.5*||A x - b||^2  subject to  C x = d,  l <= x <= u.
+ * Every outer iteration minimises  L(x, lambda, rho) = 0.5*||A x - b||^2 + rho/2*||C x - d + lambda/rho||^2
+ * over the box with the solver above (warm-started at the previous x, pair memory cleared), then sets
+ * lambda += rho*(C x - d), and doubles rho when ||C x - d||_inf was not halved by the iteration (the first
+ * iteration is compared with the violation at x0).  It stops when the violation is at most ctol and the
+ * inner solve converged, or after max_outer iterations.  An inequality row e_r . x <= f_r is passed as the
+ * equality e_r . x + s_r = f_r with one more variable s_r >= 0 (minimising L over s_r gives the (.)_+ term
+ * of Eq. (augLag) and the multiplier update mu = (mu + rho g)_+).
+ *
+ * The objective handed to lbfgsb_auglag_create is the STACKED problem: kind LSQ, A = [A; C] with
+ * rows = data rows + n_eq, b = [b; d], row_weight NULL.  A and b are borrowed as before; the targets and
+ * weights the algorithm rewrites live in the workspace.  info.status uses the LBFGSB_* termination codes
+ * (LBFGSB_MAX_ITER: outer limit reached). */
+typedef struct lbfgsb_auglag lbfgsb_auglag;   /* opaque, host object */
+
+typedef struct {
+    double rho0;       /* initial penalty parameter, default 1 (Algorithm 4) */
+    double ctol;       /* tolerance on ||C x - d||_inf, default 1e-8 */
+    int max_outer;     /* default 100 */
+} lbfgsb_auglag_options;
+
+typedef struct {           /* HOST struct */
+    int status;            /* LBFGSB_CONVERGED, LBFGSB_MAX_ITER or LBFGSB_LINESEARCH_FAILED */
+    int outer;             /* outer iterations done */
+    int64_t inner_iters;   /* iterations of the box solver, all outer iterations together */
+    double violation;      /* ||C x - d||_inf at the returned x */
+    double rho;            /* final penalty parameter */
+    double f;              /* 0.5*||A x - b||^2 at the returned x */
+    double L;              /* augmented Lagrangian at the returned x for the multipliers it was minimised with */
+    double pg2;            /* stopping quantity of the last inner solve */
+} lbfgsb_auglag_info;
+
+void lbfgsb_auglag_default_options(lbfgsb_auglag_options* opt);
+/* workspace for the inner solver plus the targets, weights and multipliers (0 on invalid arguments) */
+size_t lbfgsb_auglag_workspace_bytes(int64_t n, int m, const lbfgsb_objective* stacked_host, int64_t n_eq,
+                                     const lbfgsb_options* opt_host);
+/* opt_host: options of the inner box solver (tol, tol_relative, max_iter per outer iteration, ...); may be NULL */
+int lbfgsb_auglag_create(lbfgsb_auglag** out, int64_t n, int m, const double* l, const double* u,
+                         const lbfgsb_objective* stacked_host, int64_t n_eq, const lbfgsb_options* opt_host,
+                         const lbfgsb_auglag_options* al_opt_host, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+/* Runs Algorithm 4 from x0 (device, n entries, feasible for the box) with lambda = 0, rho = rho0.  The host
+ * reads two scalars per outer iteration; everything else stays on the device.  Synchronises. */
+int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info* info_host);
+int lbfgsb_auglag_get_x(lbfgsb_auglag* al, double* x_out);            /* device, n entries */
+int lbfgsb_auglag_get_lambda(lbfgsb_auglag* al, double* lambda_out);  /* device, n_eq entries */
+/* the box solver inside (owned by al): for lbfgsb_get_info, lbfgsb_apass_timing, ... */
+lbfgsb_solver* lbfgsb_auglag_inner(lbfgsb_auglag* al);
+void lbfgsb_auglag_destroy(lbfgsb_auglag* al);
 
 /* ---- timing of the products with A (the kernels that dominate an iteration) ------------------
  * While enabled, every launch of a kernel that reads A carries a pair of HIP events attached to

@@ -25,13 +25,27 @@ EXPORTS = [
     "lbfgsb_step", "lbfgsb_solve", "lbfgsb_get_info", "lbfgsb_get_x", "lbfgsb_get_g", "lbfgsb_destroy",
     "lbfgsb_enable_apass_timing", "lbfgsb_apass_timing", "lbfgsb_apass_name", "lbfgsb_dbg_fg",
     "lbfgsb_dbg_free_mask", "lbfgsb_dbg_two_loop", "lbfgsb_dbg_project_direction",
+    "lbfgsb_auglag_default_options", "lbfgsb_auglag_workspace_bytes", "lbfgsb_auglag_create", "lbfgsb_auglag_solve",
+    "lbfgsb_auglag_get_x", "lbfgsb_auglag_get_lambda", "lbfgsb_auglag_inner", "lbfgsb_auglag_destroy",
 ]
 
 
 class Objective(C.Structure):
     _fields_ = [("kind", C.c_int), ("dtype", C.c_int), ("rows", C.c_int64), ("cols", C.c_int64),
                 ("ld", C.c_int64), ("A", C.c_void_p), ("b", C.c_void_p), ("lam", C.c_double),
-                ("mu", C.c_double)]
+                ("mu", C.c_double), ("row_weight", C.c_void_p)]
+
+
+class AuglagOptions(C.Structure):
+    _fields_ = [("rho0", C.c_double), ("ctol", C.c_double), ("max_outer", C.c_int)]
+
+
+class AuglagInfo(C.Structure):
+    _fields_ = [("status", C.c_int), ("outer", C.c_int), ("inner_iters", C.c_int64), ("violation", C.c_double),
+                ("rho", C.c_double), ("f", C.c_double), ("L", C.c_double), ("pg2", C.c_double)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_}
 
 
 class Options(C.Structure):
@@ -106,6 +120,23 @@ def lib():
         L.lbfgsb_dbg_two_loop.argtypes = [vp, vp, vp, vp, C.c_int, vp, vp, vp, C.POINTER(C.c_int)]
         L.lbfgsb_dbg_project_direction.restype = C.c_int
         L.lbfgsb_dbg_project_direction.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_int), C.POINTER(dbl)]
+        L.lbfgsb_auglag_default_options.restype = None
+        L.lbfgsb_auglag_default_options.argtypes = [C.POINTER(AuglagOptions)]
+        L.lbfgsb_auglag_workspace_bytes.restype = C.c_size_t
+        L.lbfgsb_auglag_workspace_bytes.argtypes = [i64, C.c_int, C.POINTER(Objective), i64, C.POINTER(Options)]
+        L.lbfgsb_auglag_create.restype = C.c_int
+        L.lbfgsb_auglag_create.argtypes = [C.POINTER(vp), i64, C.c_int, vp, vp, C.POINTER(Objective), i64,
+                                           C.POINTER(Options), C.POINTER(AuglagOptions), vp, C.c_size_t, vp]
+        L.lbfgsb_auglag_solve.restype = C.c_int
+        L.lbfgsb_auglag_solve.argtypes = [vp, vp, C.POINTER(AuglagInfo)]
+        L.lbfgsb_auglag_get_x.restype = C.c_int
+        L.lbfgsb_auglag_get_x.argtypes = [vp, vp]
+        L.lbfgsb_auglag_get_lambda.restype = C.c_int
+        L.lbfgsb_auglag_get_lambda.argtypes = [vp, vp]
+        L.lbfgsb_auglag_inner.restype = vp
+        L.lbfgsb_auglag_inner.argtypes = [vp]
+        L.lbfgsb_auglag_destroy.restype = None
+        L.lbfgsb_auglag_destroy.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -143,7 +174,7 @@ class Solver:
     """
 
     def __init__(self, kind: int, A, b, l, u, m: int, *, lam: float = 0.0, mu: float = 0.0,
-                 options: Optional[Options] = None):
+                 options: Optional[Options] = None, row_weight=None):
         import torch
         if not (isinstance(A, torch.Tensor) and A.is_cuda and A.dim() == 2 and A.stride(1) == 1
                 and A.dtype in (torch.float64, torch.float32)):
@@ -156,8 +187,10 @@ class Solver:
         _dev_f64(u, "u", self.n)
         self.device = A.device
         self.options = options if options is not None else default_options()
+        self._w = _dev_f64(row_weight, "row_weight", rows) if row_weight is not None else None
         self._obj = Objective(kind, F64 if A.dtype == torch.float64 else F32, rows, cols,
-                              A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), float(lam), float(mu))
+                              A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), float(lam), float(mu),
+                              self._w.data_ptr() if self._w is not None else None)
         self._h = C.c_void_p()
         with torch.cuda.device(self.device):
             nbytes = lib().lbfgsb_workspace_bytes(self.n, m, C.byref(self._obj), C.byref(self.options))
@@ -276,6 +309,79 @@ class Solver:
                                                   _dev_f64(d, "d", self.n).data_ptr(), p.data_ptr(), C.byref(br),
                                                   C.byref(ub)))
         return p, br.value, ub.value
+
+
+class Auglag:
+    """lbfgsb_auglag_*: Algorithm 4 for  min 0.5||A x - b||^2  s.t.  C x = d, l <= x <= u.
+
+    A_stacked: (data rows + n_eq, cols) CUDA tensor holding [A; C]; b_stacked: [b; d] (float64 CUDA)."""
+
+    def __init__(self, A_stacked, b_stacked, n_eq: int, l, u, m: int, *, options: Optional[Options] = None,
+                 rho0: float = 1.0, ctol: float = 1e-8, max_outer: int = 100):
+        import torch
+        A = A_stacked
+        if not (isinstance(A, torch.Tensor) and A.is_cuda and A.dim() == 2 and A.stride(1) == 1
+                and A.dtype in (torch.float64, torch.float32)):
+            raise TypeError("A_stacked must be a 2-d float64/float32 CUDA tensor with unit column stride")
+        rows, cols = A.shape
+        self.n, self.n_eq, self.m = cols, int(n_eq), m
+        self._A, self._b = A, _dev_f64(b_stacked, "b_stacked", rows)
+        _dev_f64(l, "l", cols)
+        _dev_f64(u, "u", cols)
+        self.device = A.device
+        self.options = options if options is not None else default_options()
+        self.al_options = AuglagOptions(float(rho0), float(ctol), int(max_outer))
+        self._obj = Objective(OBJ_LSQ, F64 if A.dtype == torch.float64 else F32, rows, cols,
+                              A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), 0.0, 0.0, None)
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            nbytes = lib().lbfgsb_auglag_workspace_bytes(self.n, m, C.byref(self._obj), self.n_eq, C.byref(self.options))
+            if nbytes == 0:
+                raise LbfgsbError(E_INVALID_ARG, lib().lbfgsb_last_error().decode())
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self._stream = torch.cuda.current_stream(self.device)
+            _check(lib().lbfgsb_auglag_create(C.byref(self._h), self.n, m, l.data_ptr(), u.data_ptr(),
+                                              C.byref(self._obj), self.n_eq, C.byref(self.options),
+                                              C.byref(self.al_options), self.workspace.data_ptr(), nbytes,
+                                              C.c_void_p(self._stream.cuda_stream)))
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h:
+            lib().lbfgsb_auglag_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def solve(self, x0) -> AuglagInfo:
+        info = AuglagInfo()
+        _check(lib().lbfgsb_auglag_solve(self._h, _dev_f64(x0, "x0", self.n).data_ptr(), C.byref(info)))
+        return info
+
+    def x(self):
+        import torch
+        out = torch.empty(self.n, dtype=torch.float64, device=self.device)
+        _check(lib().lbfgsb_auglag_get_x(self._h, out.data_ptr()))
+        return out
+
+    def lam(self):
+        import torch
+        out = torch.empty(max(self.n_eq, 1), dtype=torch.float64, device=self.device)
+        _check(lib().lbfgsb_auglag_get_lambda(self._h, out.data_ptr()))
+        return out[:self.n_eq]
+
+    def inner_apass_timing(self, mode: Optional[int] = None):
+        """mode given: lbfgsb_enable_apass_timing on the inner solver; else its (launches, ms, bytes per launch)"""
+        h = lib().lbfgsb_auglag_inner(self._h)
+        if mode is not None:
+            _check(lib().lbfgsb_enable_apass_timing(h, int(mode)))
+            return None
+        cnt, ms, by = C.c_int64(0), C.c_double(0.0), C.c_double(0.0)
+        _check(lib().lbfgsb_apass_timing(h, C.byref(cnt), C.byref(ms), C.byref(by)))
+        return cnt.value, ms.value, by.value
 
 
 def solver_for_problem(prob, device="cuda:0", **option_overrides) -> Solver:

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kBlock) void k_gemv(const T* __restrict__ A, int64_
             const double tot = wave_sum(acc[k]);
             if (lane == k) mine = tot;
         }
-        if (lane < R && r0 + lane < rows) loss += row_op(a.mode, mine, r0 + lane, rows, a.b, row, t, psi);
+        if (lane < R && r0 + lane < rows) loss += row_op(a.mode, mine, r0 + lane, rows, a.b, a.w, row, t, psi);
     }
     double lv[1] = {loss};
     block_sum<1, kWaves>(lv, lds);

@@ -40,18 +40,22 @@ __device__ __forceinline__ void resolve_v(const APassArgs& a, const Scal* scal, 
 
 // The objective's per-row operation on u = a_r . v.  Returns the row's loss contribution.
 __device__ __forceinline__ double row_op(int mode, double u, int64_t r, int64_t rows, const double* __restrict__ b,
-                                         double* __restrict__ row, double* __restrict__ t,
-                                         double* __restrict__ psi) {
+                                         const double* __restrict__ w, double* __restrict__ row,
+                                         double* __restrict__ t, double* __restrict__ psi) {
     switch (mode) {
         case kRowLsqEval: {
             const double res = u - b[r];
+            const double wr = w ? w[r] : 1.0;
             row[r] = res;
-            psi[r] = res;
-            return 0.5 * res * res;
+            psi[r] = wr * res;
+            return 0.5 * wr * res * res;
         }
-        case kRowDir:
+        case kRowDir: {
+            const double wr = w ? w[r] : 1.0;
             t[r] = u;
-            return u * u;
+            psi[r] = wr * u;
+            return wr * u * u;
+        }
         case kRowLogiEval: {
             const double y = b[r];
             const double a = -y * u;

@@ -184,7 +184,8 @@ struct TimedSlot {
 
 APassArgs base_args(const lbfgsb_solver* s) {
     APassArgs a{};
-    a.A = s->obj.A; a.b = s->obj.b; a.p1 = s->bf.p1; a.p2 = s->bf.p2;
+    a.A = s->obj.A; a.b = s->obj.b; a.w = is_quadratic(s->dm.kind) ? s->obj.row_weight : nullptr;
+    a.p1 = s->bf.p1; a.p2 = s->bf.p2;
     a.split = s->dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT;
     a.c1 = s->op.c1;
     a.mu = s->dm.mu;
@@ -229,7 +230,7 @@ void enqueue_step(lbfgsb_solver* s) {
             launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
         } else {
             { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
-            { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.t, 1, s->stream, ts.e0, ts.e1); }
+            { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
         }
         launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->stream);
     } else if (s->use_fused) {
@@ -294,7 +295,8 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
     if (rc) return rc;
     if ((uintptr_t)workspace % 256) return fail(LBFGSB_E_INVALID_ARG, "workspace must be 256-byte aligned");
     const int esz = obj->dtype == LBFGSB_F32 ? 4 : 8;
-    if ((uintptr_t)obj->A % esz || (uintptr_t)obj->b % 8 || (uintptr_t)l % 8 || (uintptr_t)u % 8)
+    if ((uintptr_t)obj->A % esz || (uintptr_t)obj->b % 8 || (uintptr_t)obj->row_weight % 8 || (uintptr_t)l % 8 ||
+        (uintptr_t)u % 8)
         return fail(LBFGSB_E_INVALID_ARG, "misaligned device pointer");
 
     lbfgsb_solver* s = new (std::nothrow) lbfgsb_solver();
@@ -575,5 +577,238 @@ int lbfgsb_dbg_project_direction(lbfgsb_solver* s, const double* x, const double
     if (alpha_ub) *alpha_ub = s->h_scal->alpha_ub;
     return LBFGSB_OK;
 }
+
+
+// ---- augmented Lagrangian algorithm (Algorithm 4 of the appendix, Eq. (augLag)) ------------------------------
+//
+// Linear equality constraints h(x) = C x - d = 0 on the least-squares objective.  The rows of C are
+// appended to A, and   rho/2 ||C x - d + lambda/rho||^2   is then a block of least-squares rows with weight
+// rho and target d - lambda/rho: every outer iteration rewrites those targets and weights and runs the box
+// solver on  L(., lambda, rho) = 0.5 sum_r w_r (a_r . x - beta_r)^2,  so the single-read pass, the closed-form
+// line search and everything else of the path serve the constrained problem unchanged.
+
+}  // extern "C"
+
+struct lbfgsb_auglag {
+    lbfgsb_solver* inner;
+    lbfgsb_auglag_options ao;
+    int64_t rows_data, n_eq, n;
+    const double* bd;        // the caller's [b; d]
+    double *beta, *omega;    // targets and weights of all rows (workspace)
+    double *lambda, *red;    // multipliers; red[0] = violation, red[1] = penalty term
+    double* h_red;           // pinned host copy of red
+    double rho;
+    hipStream_t stream;
+};
+
+namespace {
+
+__global__ void k_al_init(int64_t rows, const double* __restrict__ bd, double* __restrict__ beta,
+                          double* __restrict__ omega) {
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += (int64_t)gridDim.x * blockDim.x) {
+        beta[r] = bd[r];
+        omega[r] = 1.0;
+    }
+}
+
+// targets d - lambda/rho and weights rho of the constraint rows for the next inner solve
+__global__ void k_al_prepare(int64_t rows_data, int64_t n_eq, double rho, const double* __restrict__ bd,
+                             const double* __restrict__ lambda, double* __restrict__ beta, double* __restrict__ omega) {
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_eq; r += (int64_t)gridDim.x * blockDim.x) {
+        beta[rows_data + r] = bd[rows_data + r] - lambda[r] / rho;
+        omega[rows_data + r] = rho;
+    }
+}
+
+// One workgroup.  row holds a_r . x - beta_r for every row, freshly evaluated at x.  For the constraint rows
+// h_r = row_r - lambda_r/rho; with update != 0 the multipliers become lambda + rho h.  red[0] = ||h||_inf,
+// red[1] = rho/2 sum (h + lambda/rho)^2 (the penalty term at the OLD multipliers).
+__global__ __launch_bounds__(kBlock) void k_al_update(int64_t rows_data, int64_t n_eq, double rho, int update,
+                                                      const double* __restrict__ row, double* __restrict__ lambda,
+                                                      double* __restrict__ red) {
+    __shared__ double lds[kWaves * 2];
+    double viol = 0.0, pen = 0.0;
+    for (int64_t r = threadIdx.x; r < n_eq; r += kBlock) {
+        const double a = row[rows_data + r];
+        const double h = a - lambda[r] / rho;
+        viol = fmax(viol, fabs(h));
+        pen = fma(a, a, pen);
+        if (update) lambda[r] += rho * h;
+    }
+    double pv[1] = {pen};
+    block_sum<1, kWaves>(pv, lds);
+    viol = wave_max(viol);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = viol;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double v = lds[0];
+        for (int w = 1; w < kWaves; ++w) v = fmax(v, lds[w]);
+        red[0] = v;
+        red[1] = 0.5 * rho * pv[0];
+    }
+}
+
+size_t al_extra_bytes(int64_t rows, int64_t n_eq) {
+    return align_up((size_t)rows * 8) * 2 + align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8) + align_up(64);
+}
+
+int check_al(int64_t n, const lbfgsb_objective* o, int64_t n_eq) {
+    if (!o) return fail(LBFGSB_E_INVALID_ARG, "objective is NULL");
+    if (o->kind != LBFGSB_OBJ_LSQ) return fail(LBFGSB_E_INVALID_ARG, "the augmented Lagrangian entry points take the least-squares objective");
+    if (n_eq < 0 || n_eq >= o->rows) return fail(LBFGSB_E_INVALID_ARG, "n_eq must be in 0..rows-1 (rows counts the constraint rows)");
+    if (o->row_weight) return fail(LBFGSB_E_INVALID_ARG, "row_weight must be NULL: the weights are the algorithm's");
+    (void)n;
+    return LBFGSB_OK;
+}
+
+// residual (all rows) and gradient recomputed from x unless they already are
+hipError_t al_fresh_eval(lbfgsb_solver* s) {
+    if (s->steps_since_refresh > 0) {
+        hipError_t e = read_scal(s);
+        if (e != hipSuccess) return e;
+        const int status = s->h_scal->status;
+        launch_set_status(s->bf, LBFGSB_RUNNING, s->stream);   // the evaluation's last kernel only runs in this state
+        enqueue_eval(s, 0);
+        launch_set_status(s->bf, status, s->stream);
+        s->steps_since_refresh = 0;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
+void lbfgsb_auglag_default_options(lbfgsb_auglag_options* o) {
+    if (!o) return;
+    o->rho0 = 1.0; o->ctol = 1e-8; o->max_outer = 100;
+}
+
+size_t lbfgsb_auglag_workspace_bytes(int64_t n, int m, const lbfgsb_objective* obj, int64_t n_eq,
+                                     const lbfgsb_options* opt) {
+    if (check_al(n, obj, n_eq) != LBFGSB_OK) return 0;
+    const size_t inner = lbfgsb_workspace_bytes(n, m, obj, opt);
+    return inner ? inner + al_extra_bytes(obj->rows, n_eq) : 0;
+}
+
+int lbfgsb_auglag_create(lbfgsb_auglag** out, int64_t n, int m, const double* l, const double* u,
+                         const lbfgsb_objective* obj, int64_t n_eq, const lbfgsb_options* opt,
+                         const lbfgsb_auglag_options* aopt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail(LBFGSB_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int rc = check_al(n, obj, n_eq);
+    if (rc) return rc;
+    lbfgsb_auglag_options ao;
+    if (aopt) ao = *aopt; else lbfgsb_auglag_default_options(&ao);
+    if (!(ao.rho0 > 0.0) || !(ao.ctol >= 0.0) || ao.max_outer < 1) return fail(LBFGSB_E_INVALID_ARG, "bad option value");
+    if (!workspace || !obj->b) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
+    const size_t inner_bytes = lbfgsb_workspace_bytes(n, m, obj, opt);
+    if (inner_bytes == 0) return LBFGSB_E_INVALID_ARG;
+    const size_t extra = al_extra_bytes(obj->rows, n_eq);
+    if (workspace_bytes < inner_bytes + extra)
+        return fail(LBFGSB_E_INVALID_ARG, "workspace too small: %zu < %zu bytes", workspace_bytes, inner_bytes + extra);
+    if ((uintptr_t)workspace % 256) return fail(LBFGSB_E_INVALID_ARG, "workspace must be 256-byte aligned");
+
+    lbfgsb_auglag* al = new (std::nothrow) lbfgsb_auglag();
+    if (!al) return fail(LBFGSB_E_INVALID_ARG, "out of host memory");
+    al->ao = ao; al->rows_data = obj->rows - n_eq; al->n_eq = n_eq; al->n = n; al->bd = obj->b;
+    al->stream = (hipStream_t)hip_stream; al->rho = ao.rho0; al->inner = nullptr; al->h_red = nullptr;
+    char* w = (char*)workspace + align_up(inner_bytes);
+    al->beta = (double*)w; w += align_up((size_t)obj->rows * 8);
+    al->omega = (double*)w; w += align_up((size_t)obj->rows * 8);
+    al->lambda = (double*)w; w += align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8);
+    al->red = (double*)w;
+    lbfgsb_objective inner_obj = *obj;
+    inner_obj.b = al->beta;
+    inner_obj.row_weight = al->omega;
+    rc = lbfgsb_create(&al->inner, n, m, l, u, &inner_obj, opt, workspace, inner_bytes, hip_stream);
+    if (rc) { delete al; return rc; }
+    hipError_t e = hipHostMalloc((void**)&al->h_red, 64, hipHostMallocDefault);
+    if (e != hipSuccess) { al->h_red = nullptr; lbfgsb_auglag_destroy(al); return fail(LBFGSB_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
+    int blocks = (int)((obj->rows + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(k_al_init, dim3(blocks), dim3(256), 0, al->stream, obj->rows, al->bd, al->beta, al->omega);
+    launch_fill_zero(al->lambda, align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8), al->stream);
+    e = hipStreamSynchronize(al->stream);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) { lbfgsb_auglag_destroy(al); return fail(LBFGSB_E_HIP, "initialising: %s", hipGetErrorString(e)); }
+    *out = al;
+    return LBFGSB_OK;
+}
+
+void lbfgsb_auglag_destroy(lbfgsb_auglag* al) {
+    if (!al) return;
+    lbfgsb_destroy(al->inner);
+    if (al->h_red) (void)hipHostFree(al->h_red);
+    delete al;
+}
+
+int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info* info) {
+    if (!al || !x0) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    lbfgsb_solver* s = al->inner;
+    lbfgsb_auglag_info out{};
+    out.status = LBFGSB_MAX_ITER;
+    const int pb = (int)((al->n_eq + 255) / 256) > 0 ? (int)((al->n_eq + 255) / 256) : 1;
+    // lambda^0 = 0, rho = rho0; the violation at x^0 is what the first iteration is compared with
+    launch_fill_zero(al->lambda, align_up((size_t)(al->n_eq > 0 ? al->n_eq : 1) * 8), al->stream);
+    al->rho = al->ao.rho0;
+    hipLaunchKernelGGL(k_al_prepare, dim3(pb), dim3(256), 0, al->stream, al->rows_data, al->n_eq, al->rho, al->bd,
+                       al->lambda, al->beta, al->omega);
+    int rc = lbfgsb_set_x(s, x0);
+    if (rc) return rc;
+    auto measure = [&](int update) -> hipError_t {
+        hipLaunchKernelGGL(k_al_update, dim3(1), dim3(kBlock), 0, al->stream, al->rows_data, al->n_eq, al->rho, update,
+                           s->bf.row, al->lambda, al->red);
+        hipError_t e = hipMemcpyAsync(al->h_red, al->red, 16, hipMemcpyDeviceToHost, al->stream);
+        if (e != hipSuccess) return e;
+        return hipStreamSynchronize(al->stream);
+    };
+    HIP_TRY(measure(0));
+    double viol_prev = al->h_red[0];
+    out.violation = viol_prev;
+    for (int it = 0; it < al->ao.max_outer; ++it) {
+        if (it > 0) {
+            // new targets/weights: the objective changed, so f and g are re-evaluated at x and the pair memory is cleared
+            hipLaunchKernelGGL(k_al_prepare, dim3(pb), dim3(256), 0, al->stream, al->rows_data, al->n_eq, al->rho, al->bd,
+                               al->lambda, al->beta, al->omega);
+            rc = lbfgsb_set_x(s, s->bf.x);
+            if (rc) return rc;
+        }
+        lbfgsb_info ii;
+        rc = lbfgsb_solve(s, &ii);
+        if (rc) return rc;
+        out.outer = it + 1;
+        out.inner_iters += ii.iters;
+        out.pg2 = ii.pg2;
+        if (ii.status == LBFGSB_LINESEARCH_FAILED) { out.status = ii.status; break; }
+        HIP_TRY(al_fresh_eval(s));
+        HIP_TRY(read_scal(s));
+        out.L = s->h_scal->f;
+        HIP_TRY(measure(1));                      // lambda += rho h(x); violation; penalty term
+        out.violation = al->h_red[0];
+        out.f = out.L - al->h_red[1];
+        if (out.violation <= al->ao.ctol && ii.status == LBFGSB_CONVERGED) { out.status = LBFGSB_CONVERGED; break; }
+        if (out.violation > 0.5 * viol_prev) al->rho *= 2.0;
+        viol_prev = out.violation;
+    }
+    out.rho = al->rho;
+    if (info) *info = out;
+    return LBFGSB_OK;
+}
+
+int lbfgsb_auglag_get_x(lbfgsb_auglag* al, double* x_out) {
+    if (!al) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    return lbfgsb_get_x(al->inner, x_out);
+}
+
+int lbfgsb_auglag_get_lambda(lbfgsb_auglag* al, double* lambda_out) {
+    if (!al || !lambda_out) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    if (al->n_eq > 0)
+        HIP_TRY(hipMemcpyAsync(lambda_out, al->lambda, (size_t)al->n_eq * 8, hipMemcpyDeviceToDevice, al->stream));
+    return LBFGSB_OK;
+}
+
+lbfgsb_solver* lbfgsb_auglag_inner(lbfgsb_auglag* al) { return al ? al->inner : nullptr; }
 
 }  // extern "C"

@@ -226,8 +226,8 @@ struct Buffers {
 // ---- launchers (defined in apass.hip / vec.hip) -------------------------------------------------------
 
 enum RowMode {
-    kRowLsqEval = 0,   // u = a_r.v; res = u - b_r -> row, psi; loss += 0.5 res^2
-    kRowDir = 1,       // u = a_r.v -> t, psi;            loss += u^2
+    kRowLsqEval = 0,   // u = a_r.v; res = u - b_r -> row; psi = w_r res; loss += 0.5 w_r res^2
+    kRowDir = 1,       // u = a_r.v -> t; psi = w_r u;              loss += w_r u^2
     kRowLogiEval = 2,  // u = a_r.v -> row (margin); psi = -y sigma(-y u)/rows; loss += softplus(-y u)/rows
     kRowLogiDir = 3,   // u = a_r.v -> t only (no transposed product follows)
     kRowLogiSpec = 4   // fused kernel only: u = a_r.v -> t; psi and loss for the first trial step min(1, alpha_ub)
@@ -236,6 +236,7 @@ enum RowMode {
 struct APassArgs {
     const void* A;
     const double* b;
+    const double* w;        // per-row weights of the least-squares kinds (null = all ones)
     const double* va;       // v = va[c] - (vb ? vb[c] : 0)
     const double* vb;
     const double* p1;       // when select_p != 0: va/vb are taken from p1 or p2 according to Scal::branch

@@ -61,11 +61,12 @@ template <bool LOGI>
 __device__ __forceinline__ void row_eval(int mode, double u, double b, double z, double alpha0, double invn,
                                          double& psi, double& loss, double& keep) {
     if constexpr (!LOGI) {
-        if (mode == kRowDir) {              // t = A p for the closed-form line search; w = A^T t
-            psi = u; loss = u * u; keep = u;
-        } else {                            // kRowLsqEval: r = A v - b; w = A^T r
+        // z carries the row's weight here (1 when the objective has none)
+        if (mode == kRowDir) {              // t = A p for the closed-form line search; w = A^T (weights * t)
+            psi = z * u; loss = psi * u; keep = u;
+        } else {                            // kRowLsqEval: r = A v - b; w = A^T (weights * r)
             const double res = u - b;
-            psi = res; loss = 0.5 * res * res; keep = res;
+            psi = z * res; loss = 0.5 * psi * res; keep = res;
         }
     } else {
         // one exponential serves sigma and softplus of the same argument
@@ -235,8 +236,8 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             dst[k] = __builtin_nontemporal_load(reinterpret_cast<const RawT*>(rp + c * (unsigned)sizeof(T)));
         }
     };
-    // The row's entries of b (targets or labels) and, for the speculative logistic pass, of the stored
-    // margins are read one stage ahead through the scalar unit (the row index is uniform and neither
+    // The row's entries of b (targets or labels) and of the row weights (quadratic kinds) or, for the
+    // speculative logistic pass, of the stored margins are read one stage ahead through the scalar unit (the row index is uniform and neither
     // vector is written by this kernel in the modes that read it): scalar loads are not ordered with
     // the vector loads of the ring, so waiting for one does not drain the rows in flight.
     typedef const double __attribute__((address_space(4))) * ConstD;
@@ -247,7 +248,8 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
         for (int r = 0; r < R; ++r) {
             const int64_t gr = r_begin + lr + r < r_end ? r_begin + lr + r : r_end - 1;
             db[r] = need_b ? *(ConstD)(uintptr_t)(a.b + gr) : 0.0;
-            dz[r] = need_z ? *(ConstD)(uintptr_t)(row + gr) : 0.0;
+            if constexpr (LOGI) dz[r] = need_z ? *(ConstD)(uintptr_t)(row + gr) : 0.0;
+            else dz[r] = a.w ? *(ConstD)(uintptr_t)(a.w + gr) : 1.0;
         }
     };
     const double alpha0 = need_z ? fmin(1.0, scal->alpha_ub) : 0.0;   // first trial step of the line search

@@ -1,0 +1,130 @@
+"""The augmented Lagrangian entry points (Eq. (augLag), Algorithm 4) against the CPU oracle.
+
+Parity levels: (i) the weighted least-squares evaluation that carries the penalty term, on identical
+inputs (1e-12 normwise); (ii) the whole algorithm on small constrained problems: minimiser, multipliers,
+objective, violation, number of outer iterations; (iii) inequality rows passed with slack columns against
+the oracle's explicit (.)_+ form; (iv) properties at a larger size.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2203_16340_amd as L
+import workloads
+from gpu_helpers import DEV, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("a_pass", [L.APASS_TWO_PASS, L.APASS_FUSED], ids=["two_pass", "fused"])
+@pytest.mark.parametrize("rows,cols,n_eq", [(300, 64, 3), (1000, 500, 1), (257, 130, 7)])
+def test_weighted_rows_evaluate_the_augmented_lagrangian(rows, cols, n_eq, a_pass):
+    rng = np.random.default_rng(rows + cols)
+    A, b = rng.standard_normal((rows, cols)), rng.standard_normal(rows)
+    C, d = rng.standard_normal((n_eq, cols)), rng.standard_normal(n_eq)
+    lam, rho = rng.standard_normal(n_eq), 3.5
+    ref = oracle.Objective(oracle.LSQ, A, b).set_constraints(C, d, lam=lam, rho=rho)
+    x = rng.standard_normal(cols)
+    f_ref, g_ref, row_ref = oracle.fg(ref, x, want_rowvec=True)
+    A_s = np.ascontiguousarray(np.vstack([A, C]))
+    b_s = np.concatenate([b, d - lam / rho])
+    w_s = np.concatenate([np.ones(rows), np.full(n_eq, rho)])
+    s = L.Solver(L.OBJ_LSQ, to_dev(A_s), to_dev(b_s), to_dev(np.full(cols, -np.inf)), to_dev(np.full(cols, np.inf)), 3,
+                 options=L.default_options(a_pass=a_pass), row_weight=to_dev(w_s))
+    f, g, row = s.dbg_fg(to_dev(x), want_rowvec=True)
+    assert abs(f - f_ref) <= 1e-12 * abs(f_ref)
+    assert rel_err(g.cpu().numpy(), g_ref) <= 1e-12
+    assert rel_err(row.cpu().numpy(), row_ref) <= 1e-12
+    s.close()
+
+
+def _run_gpu(cp, tol, ctol, max_outer=100, a_pass=L.APASS_AUTO):
+    A_s, b_s, n_eq, l_s, u_s, x0_s = cp.stacked()
+    al = L.Auglag(to_dev(A_s), to_dev(b_s), n_eq, to_dev(l_s), to_dev(u_s), cp.m,
+                  options=L.default_options(tol=tol, a_pass=a_pass), ctol=ctol, max_outer=max_outer)
+    info = al.solve(to_dev(x0_s))
+    x = al.x().cpu().numpy()
+    lam = al.lam().cpu().numpy()
+    al.close()
+    return x, lam, info
+
+
+def _run_oracle(cp, tol, ctol, max_outer=100):
+    obj = oracle.Objective(oracle.LSQ, cp.A, cp.b).set_constraints(cp.C, cp.d, cp.E, cp.e)
+    return oracle.auglag_solve(obj, cp.l, cp.u, cp.x0, cp.m, oracle.default_options(tol=tol), ctol=ctol,
+                               max_outer=max_outer)
+
+
+@pytest.mark.parametrize("a_pass", [L.APASS_TWO_PASS, L.APASS_FUSED], ids=["two_pass", "fused"])
+def test_least_squares_over_the_simplex(a_pass):
+    cp = workloads.simplex_lsq(400, 120, seed=11, m=6)
+    x_ref, lam_ref, _, iref = _run_oracle(cp, 1e-9, 1e-9)
+    x, lam, info = _run_gpu(cp, 1e-9, 1e-9, a_pass=a_pass)
+    assert iref.status == oracle.CONVERGED and info.status == L.CONVERGED, (info.as_dict())
+    assert info.violation <= 1e-9 and abs(x.sum() - 1.0) <= 1e-9 and np.all(x >= 0)
+    assert rel_err(x, x_ref) <= 1e-6
+    assert rel_err(lam, lam_ref) <= 1e-5
+    assert info.f == pytest.approx(iref.f, rel=1e-7)
+    assert np.array_equal(x <= 1e-10, x_ref <= 1e-10)
+    assert abs(info.outer - iref.outer) <= 1 and info.rho == iref.rho
+
+
+@pytest.mark.parametrize("seed,rows,cols,n_eq", [(21, 300, 80, 5), (22, 900, 257, 2)])
+def test_equality_constraints_with_an_active_box(seed, rows, cols, n_eq):
+    cp = workloads.constrained_lsq(rows, cols, n_eq, 0, seed=seed, m=8)
+    x_ref, lam_ref, _, iref = _run_oracle(cp, 1e-9, 1e-9)
+    x, lam, info = _run_gpu(cp, 1e-9, 1e-9)
+    assert iref.status == oracle.CONVERGED and info.status == L.CONVERGED, (info.as_dict())
+    assert info.violation <= 1e-9
+    assert np.all(x >= cp.l) and np.all(x <= cp.u)
+    assert rel_err(x, x_ref) <= 1e-6
+    assert rel_err(lam, lam_ref) <= 1e-5
+    assert info.f == pytest.approx(iref.f, rel=1e-7)
+    at_bound = lambda v: (v <= cp.l + 1e-10) | (v >= cp.u - 1e-10)
+    assert np.array_equal(at_bound(x), at_bound(x_ref))
+    assert abs(info.outer - iref.outer) <= 1
+    # KKT of the constrained problem, recomputed with numpy
+    grad = cp.A.T @ (cp.A @ x - cp.b) + cp.C.T @ lam
+    assert np.abs(x - np.clip(x - grad, cp.l, cp.u)).max() <= 1e-6
+
+
+def test_inequality_rows_through_slack_columns_match_the_explicit_form():
+    cp = workloads.constrained_lsq(200, 40, 1, 6, seed=31, m=6)
+    x_ref, lam_ref, mu_ref, iref = _run_oracle(cp, 1e-10, 1e-9, max_outer=200)
+    xs, lam, info = _run_gpu(cp, 1e-10, 1e-9, max_outer=200)
+    assert iref.status == oracle.CONVERGED and info.status == L.CONVERGED, (info.as_dict())
+    x, slack = xs[:cp.cols], xs[cp.cols:]
+    assert rel_err(x, x_ref) <= 1e-5
+    assert rel_err(lam[:1], lam_ref) <= 1e-4
+    np.testing.assert_allclose(lam[1:], mu_ref, rtol=1e-4, atol=1e-6)      # multipliers of the slack rows are the mu
+    assert np.all(lam[1:] >= -1e-9)
+    assert np.max(cp.E @ x - cp.e) <= 1e-8 and np.all(slack >= 0)
+    assert info.f == pytest.approx(iref.f, rel=1e-6)
+
+
+def test_properties_at_a_larger_size():
+    cp = workloads.simplex_lsq(5000, 1250, seed=41, budget=25.0, m=10)
+    x, lam, info = _run_gpu(cp, 1e-7, 1e-8)
+    assert info.status == L.CONVERGED, info.as_dict()
+    assert abs(x.sum() - 25.0) <= 1e-8 and np.all(x >= 0)
+    r = cp.A @ x - cp.b
+    assert info.f == pytest.approx(0.5 * r @ r, rel=1e-9)
+    grad = cp.A.T @ r + lam[0]
+    assert np.abs(x - np.clip(x - grad, cp.l, cp.u)).max() <= 1e-5
+    assert rel_err(x, cp.x_true) <= 0.05           # the data were generated from a point of this simplex
+
+
+def test_argument_errors():
+    A, b = to_dev(np.ones((6, 4))), to_dev(np.ones(6))
+    l, u = to_dev(np.zeros(4)), to_dev(np.ones(4))
+    with pytest.raises(L.LbfgsbError) as e:
+        L.Auglag(A, b, 6, l, u, 3)                  # every row a constraint: no objective left
+    assert e.value.code == L.E_INVALID_ARG
+    with pytest.raises(L.LbfgsbError) as e:
+        L.Auglag(A, b, -1, l, u, 3)
+    assert e.value.code == L.E_INVALID_ARG
+    al = L.Auglag(A, b, 0, l, u, 3)                 # no constraints: one outer iteration
+    info = al.solve(to_dev(np.zeros(4)))
+    assert info.status == L.CONVERGED and info.outer == 1 and info.violation == 0.0
+    al.close()

@@ -217,3 +217,79 @@ def config(name: str, *, scale: float = 1.0, a_out: Optional[np.ndarray] = None)
                     nonzero="uniform", upper=1.0, m=20, name="C5", tol=1e-6, tol_relative=True,
                     a_out=a_out)
     raise KeyError(name)
+
+
+# ---- linearly constrained least squares (for the augmented Lagrangian algorithm) ---------------
+
+@dataclass
+class ConstrainedProblem:
+    """min 0.5*||A x - b||^2  s.t.  C x = d,  E x <= e,  l <= x <= u."""
+    name: str
+    A: np.ndarray
+    b: np.ndarray
+    C: np.ndarray            # n_eq x cols
+    d: np.ndarray
+    E: np.ndarray            # n_in x cols
+    e: np.ndarray
+    l: np.ndarray
+    u: np.ndarray
+    x0: np.ndarray
+    m: int
+    x_true: Optional[np.ndarray] = None
+
+    @property
+    def rows(self) -> int:
+        return self.A.shape[0]
+
+    @property
+    def cols(self) -> int:
+        return self.A.shape[1]
+
+    def stacked(self):
+        """The same problem with equality rows appended to A and one slack column per inequality row:
+        variables [x; s], rows [A 0; C 0; E I], targets [b; d; e], bounds [l; 0] <= [x; s] <= [u; inf].
+        Returns (A_stacked, b_stacked, n_eq_total, l, u, x0)."""
+        n, ne, ni = self.cols, self.C.shape[0], self.E.shape[0]
+        top = np.hstack([self.A, np.zeros((self.rows, ni), dtype=self.A.dtype)])
+        mid = np.hstack([self.C.astype(self.A.dtype), np.zeros((ne, ni), dtype=self.A.dtype)])
+        bot = np.hstack([self.E.astype(self.A.dtype), np.eye(ni, dtype=self.A.dtype)])
+        A_s = np.ascontiguousarray(np.vstack([top, mid, bot]))
+        b_s = np.concatenate([self.b, self.d, self.e])
+        l_s = np.concatenate([self.l, np.zeros(ni)])
+        u_s = np.concatenate([self.u, np.full(ni, math.inf)])
+        s0 = np.maximum(self.e - self.E @ self.x0, 0.0) if ni else np.zeros(0)
+        return A_s, b_s, ne + ni, l_s, u_s, np.concatenate([self.x0, s0])
+
+
+def simplex_lsq(rows: int, cols: int, *, seed: int, dtype=np.float64, noise: float = 0.01, budget: float = 1.0,
+                m: int = 10) -> ConstrainedProblem:
+    """The example problem of the paper's section "Complete Framework": least squares subject to
+    sum(x) = budget, x >= 0.  A iid N(0,1); x* = budget * (sparse point of the simplex: 10 % non-zeros with
+    Dirichlet(1) weights); b = A x* + noise*N(0,1)."""
+    rng = np.random.default_rng(seed)
+    A = _normal_matrix(rng, rows, cols, np.dtype(dtype))
+    k = max(1, cols // 10)
+    support = np.sort(rng.permutation(cols)[:k])
+    x_true = np.zeros(cols)
+    x_true[support] = budget * rng.dirichlet(np.ones(k))
+    b = _matvec(A, x_true) + noise * rng.standard_normal(rows)
+    return ConstrainedProblem(name="simplex_lsq", A=A, b=b, C=np.ones((1, cols)), d=np.array([budget]),
+                              E=np.zeros((0, cols)), e=np.zeros(0), l=np.zeros(cols), u=np.full(cols, math.inf),
+                              x0=np.zeros(cols), m=m, x_true=x_true)
+
+
+def constrained_lsq(rows: int, cols: int, n_eq: int, n_in: int, *, seed: int, lower: float = 0.0, upper: float = 1.0,
+                    m: int = 10) -> ConstrainedProblem:
+    """Random linear constraints around a feasible point: A, C, E iid N(0,1) (C, E scaled by 1/sqrt(cols)),
+    x_feas ~ U(lower, upper), d = C x_feas, e = E x_feas + U(0, 0.5), b = A x_any + N(0,1) with x_any ~ N(0,1)."""
+    rng = np.random.default_rng(seed)
+    A = _normal_matrix(rng, rows, cols, np.dtype(np.float64))
+    C = rng.standard_normal((n_eq, cols)) / math.sqrt(cols)
+    E = rng.standard_normal((n_in, cols)) / math.sqrt(cols)
+    x_feas = lower + (upper - lower) * rng.random(cols)
+    d = C @ x_feas
+    e = E @ x_feas + 0.5 * rng.random(n_in)
+    b = _matvec(A, rng.standard_normal(cols)) + rng.standard_normal(rows)
+    x0 = np.clip(np.zeros(cols), lower, upper)
+    return ConstrainedProblem(name="constrained_lsq", A=A, b=b, C=C, d=d, E=E, e=e, l=np.full(cols, lower),
+                              u=np.full(cols, upper), x0=x0, m=m, x_true=x_feas)
