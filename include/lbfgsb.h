@@ -221,7 +221,8 @@ void lbfgsb_auglag_destroy(lbfgsb_auglag* al);
  * the dispatch itself (start and end of that kernel on the solver's stream, no extra stream
  * markers) (at most 4096 launches are kept; later ones are not recorded).  enable: 0 =
  * pause (records kept), 1 = resume, 2 = discard the records and start.  lbfgsb_apass_timing
- * synchronises and returns how many launches were timed, their total duration in milliseconds
+ * synchronises and returns how many launches were timed (launches that returned at once because the
+ * solver had already stopped -- duration below half of the longest -- are left out), their total duration in milliseconds
  * and the bytes of A one launch requests from memory (rows*cols*sizeof(element): each such
  * kernel reads A exactly once). */
 int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable);

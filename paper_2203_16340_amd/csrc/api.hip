@@ -484,13 +484,19 @@ int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable) {
 int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count, double* total_ms, double* bytes_per_pass) {
     if (!s || !count || !total_ms || !bytes_per_pass) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
     HIP_TRY(hipStreamSynchronize(s->stream));
-    double tot = 0.0;
+    // launches enqueued after the solver had stopped return at once without touching A: they are recognised
+    // by their duration (below half of the longest launch) and left out
+    std::vector<float> dur((size_t)s->timed);
+    float longest = 0.f;
     for (int i = 0; i < s->timed; ++i) {
-        float ms = 0.f;
-        HIP_TRY(hipEventElapsedTime(&ms, s->ev0[i], s->ev1[i]));
-        tot += ms;
+        HIP_TRY(hipEventElapsedTime(&dur[(size_t)i], s->ev0[i], s->ev1[i]));
+        if (dur[(size_t)i] > longest) longest = dur[(size_t)i];
     }
-    *count = s->timed;
+    double tot = 0.0;
+    int64_t n = 0;
+    for (int i = 0; i < s->timed; ++i)
+        if (dur[(size_t)i] >= 0.5f * longest) { tot += dur[(size_t)i]; ++n; }
+    *count = n;
     *total_ms = tot;
     *bytes_per_pass = (double)s->dm.rows * (double)s->dm.cols * (s->dm.dtype == LBFGSB_F32 ? 4.0 : 8.0);
     return LBFGSB_OK;

@@ -293,3 +293,14 @@ def constrained_lsq(rows: int, cols: int, n_eq: int, n_in: int, *, seed: int, lo
     x0 = np.clip(np.zeros(cols), lower, upper)
     return ConstrainedProblem(name="constrained_lsq", A=A, b=b, C=C, d=d, E=E, e=e, l=np.full(cols, lower),
                               u=np.full(cols, upper), x0=x0, m=m, x_true=x_feas)
+
+
+def constrained_config(name: str, *, scale: float = 1.0) -> ConstrainedProblem:
+    """AL2: the C2 recipe (NNLS 20000 x 5000 fp64, same seed) with the budget constraint sum(x) = sum(x*)."""
+    if name != "AL2":
+        raise KeyError(name)
+    base = config("C2", scale=scale)
+    cols = base.cols
+    return ConstrainedProblem(name="AL2", A=base.A, b=base.b, C=np.ones((1, cols)), d=np.array([base.x_true.sum()]),
+                              E=np.zeros((0, cols)), e=np.zeros(0), l=base.l, u=base.u, x0=base.x0, m=base.m,
+                              x_true=base.x_true)
