@@ -45,10 +45,11 @@ WORKLOADS = {
 # (scaled by the same counters read for a copy kernel of known size); filled in from the summaries
 # under profiles/ for the (config, a_pass) pairs that have been profiled, else null in the output.
 MEASURED_TRAFFIC_BYTES = {
-    ("C2", "fused"): 8.374e8,      # profiles/c2_nnls_20000x5000_f64_fused_a_pass.md      (algorithmic 8.0e8)
+    ("C2", "fused"): 8.365e8,      # profiles/c2_nnls_20000x5000_f64_fused_a_pass.md      (algorithmic 8.0e8)
     ("C3", "fused"): 1.682e9,      # profiles/c3_l1ls_10000x20000_f64_fused_a_pass.md     (algorithmic 1.6e9)
-    ("C4", "two_pass"): 1.639e9,   # profiles/c4_logistic_200000x2000_f32_two_pass_gemv.md (algorithmic 1.6e9, mean of the two kernels)
+    ("C4", "fused"): 1.624e9,      # profiles/c4_logistic_200000x2000_f32_fused_a_pass.md (algorithmic 1.6e9)
     ("C5", "fused"): 8.099e9,      # profiles/c5_nnls_100000x20000_f32_fused_a_pass.md    (algorithmic 8.0e9)
+    ("AL2", "fused"): 8.371e8,     # profiles/al2_auglag_20001x5000_f64_fused_a_pass.md   (algorithmic 8.0004e8)
 }
 
 
@@ -77,6 +78,21 @@ def cpu_baseline(prob, budget_s: float):
         "sample": (f"first {iters} iterations from x0 ({'to convergence' if done else 'stopped by the time budget'}), "
                    f"{elapsed:.1f} s, {info.fevals} objective evaluations"),
     }
+
+
+def calibration_copy(args, torch, dev, out) -> None:
+    """A plain device-to-device copy of known size, three times, against which rocprofv3's FETCH_SIZE /
+    WRITE_SIZE readings of the same run are scaled."""
+    if args.calibration_copy_mib <= 0:
+        return
+    src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    out["calibration_copy_bytes"] = int(src.numel())
+    del src, dst
 
 
 def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
@@ -124,10 +140,11 @@ def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
         "roofline": {"bound": "hbm", "kernel": "fused A pass with per-row weights (data rows and the constraint rows in one read)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": apass_avg_ms, "launches_timed": n_launch,
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "fused"))},
         "gen_seconds": t_gen,
     }
     al.close()
+    calibration_copy(args, torch, dev, out)
     if args.cpu_budget > 0:
         obj = oracle.Objective(oracle.LSQ, cp.A, cp.b).set_constraints(cp.C, cp.d, cp.E, cp.e)
         t0 = time.perf_counter()
@@ -306,15 +323,7 @@ def main() -> int:
     }
     timed.close()
     solver.close()
-    if args.calibration_copy_mib > 0:
-        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        out["calibration_copy_bytes"] = int(src.numel())
-        del src, dst
+    calibration_copy(args, torch, dev, out)
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(prob, args.cpu_budget)
     else:
