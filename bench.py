@@ -39,6 +39,10 @@ WORKLOADS = {
     "C3": "L1-LS split 10000x20000 fp64 (40000 vars), m=10",
     "C4": "box logistic 200000x2000 fp32, m=10",
     "C5": "NNLS 100000x20000 fp32, box [0,1], m=20",
+    # the paper's own NNLS recipes (context: its tables give seconds on other hardware)
+    "P1": "paper NNLS experiment (i), A 2900x8700 fp64 U(0,1), x sparsity 0.01, m=10",
+    "P2": "paper NNLS experiment (ii), A 29600x14800 fp64 Gaussian, x sparsity 0.1, m=10",
+    "P2b": "paper NNLS experiment (ii), A 44400x22200 fp64 Gaussian (7.9 GB), m=10",
 }
 
 # HBM bytes per launch of the dominant kernel as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
@@ -58,7 +62,7 @@ def cpu_baseline(prob, budget_s: float):
     `budget_s` seconds have passed (at least one)."""
     import oracle
     obj = oracle.Objective(prob.kind, prob.A, prob.b, prob.lam, prob.mu)
-    opts = oracle.default_options(tol=prob.tol, tol_relative=int(prob.tol_relative))
+    opts = oracle.default_options(tol=prob.tol, tol_relative=int(prob.tol_relative), max_iter=int(prob.max_iter))
     t0 = time.perf_counter()
     s = oracle.Solver(obj, prob.l, prob.u, prob.x0, prob.m, opts)     # includes the evaluation at x0
     iters = 0
@@ -206,7 +210,7 @@ def main() -> int:
         s_.set_x(x0)
         return s_
 
-    solver = new_solver(tol=1e-6, tol_relative=1)
+    solver = new_solver(tol=1e-6, tol_relative=1, max_iter=int(prob.max_iter))
     solver.solve()                                   # untimed first solve: loads code objects, warms caches
     solver.set_x(x0)
     torch.cuda.synchronize()

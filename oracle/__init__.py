@@ -308,7 +308,7 @@ class Solver:
 def solve_problem(prob, **option_overrides) -> Result:
     """Run the oracle on a workloads.Problem."""
     obj = Objective(prob.kind, prob.A, prob.b, prob.lam, prob.mu)
-    opts = default_options(tol=prob.tol, tol_relative=int(prob.tol_relative))
+    opts = default_options(tol=prob.tol, tol_relative=int(prob.tol_relative), max_iter=int(getattr(prob, "max_iter", 1000)))
     for k, v in option_overrides.items():
         setattr(opts, k, v)
     s = Solver(obj, prob.l, prob.u, prob.x0, prob.m, opts)

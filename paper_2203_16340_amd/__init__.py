@@ -392,7 +392,7 @@ def solver_for_problem(prob, device="cuda:0", **option_overrides) -> Solver:
     b = torch.from_numpy(prob.b).to(dev)
     l = torch.from_numpy(prob.l).to(dev)
     u = torch.from_numpy(prob.u).to(dev)
-    opts = default_options(tol=prob.tol, tol_relative=int(prob.tol_relative))
+    opts = default_options(tol=prob.tol, tol_relative=int(prob.tol_relative), max_iter=int(getattr(prob, "max_iter", 1000)))
     for k, v in option_overrides.items():
         if not hasattr(opts, k):
             raise AttributeError(k)

@@ -25,17 +25,18 @@ struct Variant {
     size_t (*lds)(int64_t cols);
 };
 
-template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI>
+template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI, int KR>
 void launch_variant(const Dims& dm, int64_t rows_per_wg, int blocks, size_t lds, const Buffers& bf, const APassArgs& a,
                     hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-    hipExtLaunchKernelGGL((ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, LOGI>), dim3(blocks), dim3(NT), lds, st, ev0, ev1,
+    hipExtLaunchKernelGGL((ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, LOGI, KR>), dim3(blocks), dim3(NT), lds, st, ev0, ev1,
                           0, (const T*)a.A, dm.ld, dm.rows, dm.cols, rows_per_wg, a, bf.scal, bf.row, bf.t, bf.wpart,
                           bf.losspart);
 }
 
-#define LB_VARIANT(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS)                                                    \
-    {dt, LOGI, NT, (KCU) * (U), R, WGS, (const void*)ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0>,  \
-     launch_variant<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0>, ring::lds_bytes<NT, R>}
+#define LB_VARIANT_KR(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, KR)                                                  \
+    {dt, LOGI, NT, (KCU) * (U), R, WGS, (const void*)ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0, KR>,   \
+     launch_variant<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0, KR>, ring::lds_bytes<T, NT, (KCU) * (U), KR, R>}
+#define LB_VARIANT(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS) LB_VARIANT_KR(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, 0)
 
 // Ordered by capacity within a (matrix type, objective family) group: the first variant of the group
 // whose NT*KC*VEC columns cover a row and whose LDS need (v for every column) fits is used.  The
@@ -45,6 +46,8 @@ const Variant kVariants[] = {
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 5, 1, 2, 4, 2, 1),    // cols <=  5120
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 10, 1, 1, 2, 2, 1),   // cols <= 10240
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 20, 1, 1, 1, 2, 1),   // cols <= 20480 (LDS: <= 20459)
+    LB_VARIANT_KR(LBFGSB_F64, 0, double, 512, 22, 1, 1, 1, 2, 1, 3),   // cols <= 22528, v of the last 3 chunks in registers
+    LB_VARIANT_KR(LBFGSB_F64, 0, double, 512, 24, 1, 1, 1, 2, 1, 5),   // cols <= 24576, v of the last 5 chunks in registers
     LB_VARIANT(LBFGSB_F32, 0, float, 256, 1, 1, 2, 4, 4, 4),     // cols <=  1024
     LB_VARIANT(LBFGSB_F32, 0, float, 256, 5, 1, 1, 2, 2, 2),     // cols <=  5120
     LB_VARIANT(LBFGSB_F32, 0, float, 512, 5, 1, 2, 4, 2, 1),     // cols <= 10240

@@ -171,14 +171,20 @@ __device__ __forceinline__ void spec_decide(Scal* __restrict__ scal, const APass
     }
 }
 
-// dynamic LDS a launch needs: v for `cols` columns, one all-zero chunk, then the reduction scratch
+// dynamic LDS a launch needs: v for the columns held there (all of them unless the variant keeps the v of
+// its last KR chunks per thread in registers), one all-zero chunk, then the reduction scratch
 constexpr int kPad = 4;
-template <int NT, int R>
+template <typename T, int NT, int KC, int KR>
+inline int64_t lds_cols(int64_t cols) {
+    const int64_t cap = (int64_t)(KC - KR) * NT * (16 / (int)sizeof(T));
+    return KR > 0 && cols > cap ? cap : cols;
+}
+template <typename T, int NT, int KC, int KR, int R>
 inline size_t lds_bytes(int64_t cols) {
-    return ((size_t)cols + kPad) * 8 + (size_t)2 * R * (NT / 64) * 8;
+    return ((size_t)lds_cols<T, NT, KC, KR>(cols) + kPad) * 8 + (size_t)2 * R * (NT / 64) * 8;
 }
 
-template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI>
+template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI, int KR = 0>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t cols, int64_t rows_per_wg, APassArgs a,
                   Scal* __restrict__ scal, double* __restrict__ row, double* __restrict__ t,
@@ -193,15 +199,28 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     static_assert(R <= 16, "one lane per row of a stage evaluates the row operation");
     __shared__ int last_flag;
     extern __shared__ __align__(16) double lds[];
-    double* vs = lds;                                        // v, `cols` entries, then kPad zeros
-    double* red = lds + cols + kPad;                         // [2][R][NW]
+    // Rows too wide for v to fit in LDS: the v of each thread's last KR chunks stays in registers instead
+    static_assert(KR == 0 || U == 1, "register-resident v is only combined with whole-row slots");
+    constexpr int KL = KC - KR;                              // chunks whose v is read from LDS
+    const int lcols = KR > 0 && cols > (int64_t)KL * NT * VEC ? KL * NT * VEC : (int)cols;
+    double* vs = lds;                                        // v, `lcols` entries, then kPad zeros
+    double* red = lds + lcols + kPad;                        // [2][R][NW]
     if (a.check_status && scal->status != LBFGSB_RUNNING) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const double *va, *vb;
     resolve_v(a, scal, cols, va, vb);
 
-    for (int64_t c = tid; c < cols; c += NT) vs[c] = vb ? va[c] - vb[c] : va[c];
-    if (tid < kPad) vs[cols + tid] = 0.0;
+    for (int c = tid; c < lcols; c += NT) vs[c] = vb ? va[c] - vb[c] : va[c];
+    if (tid < kPad) vs[lcols + tid] = 0.0;
+    double vreg[KR > 0 ? KR : 1][VEC];
+#pragma unroll
+    for (int k = 0; k < KR; ++k) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const int64_t c = (int64_t)((KL + k) * NT + tid) * VEC + j;
+            vreg[k][j] = c < cols ? (vb ? va[c] - vb[c] : va[c]) : 0.0;
+        }
+    }
 
     // chunk k of this thread starts at column (k*NT + tid)*VEC.  A chunk at or past `cols` does not
     // exist: its loads are redirected to the last chunk of the row (valid memory) and its v to the
@@ -280,10 +299,15 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
 #pragma unroll
                 for (int k = 0; k < KCU; ++k) {
                     const int kk = j * KCU + k;
-                    int c = cb + kk * kStride;
-                    c = c < icols ? c : icols;               // zero pad for a chunk that does not exist
                     double e[VEC];
                     widen(raw[slot][k], e);
+                    if (kk >= KL) {                          // (compile-time) v of this chunk is in registers
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) acc[r] = fma(e[i], vreg[kk - KL][i], acc[r]);
+                        continue;
+                    }
+                    int c = cb + kk * kStride;
+                    c = c < lcols ? c : lcols;               // zero pad for a chunk that does not exist
 #pragma unroll
                     for (int i = 0; i < VEC; i += 2) {       // 16-byte LDS reads
                         const double2 vv = *reinterpret_cast<const double2*>(vs + c + i);

@@ -37,6 +37,9 @@ def _solver_or_skip(*args, **kw):
 FG_SHAPES = [
     # rows, cols: several row groups / column tiles plus ragged tails; odd cols force scalar loads
     (1, 1), (3, 2), (37, 5), (200, 100), (1037, 517), (1037, 520), (777, 2048), (4099, 1030), (300, 5000),
+    # wide rows: every variant of the fused pass up to its widest (v partly in registers beyond 20459 columns;
+    # wider than 24576, or 20480 for fp32, only the two-pass kernels take the shape)
+    (523, 9000), (300, 20000), (261, 20456), (259, 22000), (130, 24576), (67, 24580),
 ]
 
 

@@ -76,6 +76,18 @@ def test_scaled_configs(name, scale, f_tol, same_set, a_pass):
     _compare_with_oracle(prob, a_pass, f_tol, same_set, 1e-8 * max(1.0, np.linalg.norm(g0[mask0])))
 
 
+@pytest.mark.parametrize("name,scale,same_set", [
+    ("P1", 0.05, False),   # the paper's NNLS experiment (i): 145 x 435, U(0,1) entries, singular Gram matrix (minimiser not unique)
+    ("P2", 0.02, True),    # the paper's NNLS experiment (ii): 592 x 296 Gaussian
+])
+def test_the_papers_nnls_recipes_scaled_down(name, scale, same_set):
+    prob = workloads.config(name, scale=scale)
+    prob.tol, prob.tol_relative = 1e-9, True
+    g0 = host_gradient(prob, prob.x0)
+    mask0 = oracle.free_mask(prob.x0, g0, prob.l, prob.u, 1e-10).astype(bool)
+    _compare_with_oracle(prob, L.APASS_AUTO, 1e-8, same_set, 1e-8 * max(1.0, np.linalg.norm(g0[mask0])))
+
+
 @pytest.mark.parametrize("a_pass", A_PASSES)
 @pytest.mark.parametrize("name,scale", [("C1", 1.0), ("C2", 0.05), ("C3", 0.03), ("C4", 0.01), ("C5", 0.02)])
 def test_first_iterations_match_step_by_step(name, scale, a_pass):

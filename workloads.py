@@ -44,6 +44,7 @@ class Problem:
     tol_relative: bool = False
     x_true: Optional[np.ndarray] = None
     meta: dict = field(default_factory=dict)
+    max_iter: int = 1000
 
     @property
     def rows(self) -> int:
@@ -199,7 +200,7 @@ def config(name: str, *, scale: float = 1.0, a_out: Optional[np.ndarray] = None)
     (same seed, same recipe) for parity cases the CPU oracle finishes in seconds."""
     def dim(v: int) -> int:
         return max(4, int(round(v * scale)))
-    seed = CONFIG_SEEDS[name]
+    seed = CONFIG_SEEDS.get(name, 0)
     if name == "C1":
         return nnls(dim(200), dim(100), seed=seed, zero_frac=0.5, nonzero="absnormal", m=5,
                     name="C1", tol=1e-8, tol_relative=False)
@@ -216,7 +217,20 @@ def config(name: str, *, scale: float = 1.0, a_out: Optional[np.ndarray] = None)
         return nnls(dim(100000), dim(20000), seed=seed, dtype=np.float32, zero_frac=0.9,
                     nonzero="uniform", upper=1.0, m=20, name="C5", tol=1e-6, tol_relative=True,
                     a_out=a_out)
-    raise KeyError(name)
+    # the paper's own NNLS recipes (section "Experiments"); `scale` multiplies the paper's parameter t.
+    # The paper's tables index instances by a "size" it does not define; the t values here make
+    # rows + cols equal to the largest size of each table (11600 and 44400), P2b makes rows equal to it.
+    if name == "P1":
+        p = paper_nnls_i(1.45 * scale, seed=2001)            # 2900 x 8700, U(0,1) entries, singular Gram matrix
+        p.max_iter = 200000                                  # non-isotropic rows: thousands of iterations
+    elif name == "P2":
+        p = paper_nnls_ii(44400.0 / 9000.0 * scale, seed=2002)   # 29600 x 14800 Gaussian
+    elif name == "P2b":
+        p = paper_nnls_ii(7.4 * scale, seed=2003)            # 44400 x 22200 Gaussian (7.9 GB): wider than the fused pass takes
+    else:
+        raise KeyError(name)
+    p.name = name
+    return p
 
 
 # ---- linearly constrained least squares (for the augmented Lagrangian algorithm) ---------------
