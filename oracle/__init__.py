@@ -21,7 +21,7 @@ _SRC = os.path.join(_HERE, "lbfgsb_oracle.c")
 _LIB = os.path.join(_HERE, "liblbfgsb_oracle.so")
 
 RUNNING, CONVERGED, MAX_ITER, LINESEARCH_FAILED = 0, 1, 2, 3
-LSQ, LSQ_L1SPLIT, LOGISTIC_L2 = 0, 1, 2
+LSQ, LSQ_L1SPLIT, LOGISTIC_L2, QP = 0, 1, 2, 3
 F64, F32 = 0, 1
 
 
@@ -34,7 +34,7 @@ class _Constraints(C.Structure):
 class _Objective(C.Structure):
     _fields_ = [("kind", C.c_int), ("dtype", C.c_int), ("rows", C.c_int64), ("cols", C.c_int64),
                 ("ld", C.c_int64), ("A", C.c_void_p), ("b", C.c_void_p), ("lam", C.c_double),
-                ("mu", C.c_double), ("con", C.c_void_p)]
+                ("mu", C.c_double), ("con", C.c_void_p), ("sign", C.c_void_p)]
 
 
 class AuglagOptions(C.Structure):
@@ -144,7 +144,7 @@ def default_options(**overrides) -> Options:
 class Objective:
     """Keeps the numpy arrays alive next to the C struct that points into them."""
 
-    def __init__(self, kind: int, A: np.ndarray, b: np.ndarray, lam: float = 0.0, mu: float = 0.0):
+    def __init__(self, kind: int, A: np.ndarray, b: np.ndarray, lam: float = 0.0, mu: float = 0.0, sign=None):
         if A.dtype not in (np.float64, np.float32) or A.ndim != 2:
             raise TypeError("A must be a 2-d float64 or float32 array")
         if A.strides[1] != A.itemsize or A.strides[0] % A.itemsize:
@@ -155,8 +155,16 @@ class Objective:
             raise ValueError("b must have one entry per row of A")
         self.kind = kind
         self.c = _Objective(kind, F64 if A.dtype == np.float64 else F32, A.shape[0], A.shape[1],
-                            A.strides[0] // A.itemsize, _ptr(A), _ptr(self.b), float(lam), float(mu), None)
+                            A.strides[0] // A.itemsize, _ptr(A), _ptr(self.b), float(lam), float(mu), None, None)
         self.con = None
+        self.sign = None
+        if sign is not None:
+            assert kind == QP
+            self.sign = _f64(sign)
+            assert self.sign.shape == (A.shape[1],)
+            self.c.sign = _ptr(self.sign)
+        if kind == QP:
+            assert A.shape[0] == A.shape[1], "the quadratic form needs a square (symmetric) matrix"
 
     def set_constraints(self, C_eq=None, d=None, E_in=None, e=None, lam=None, mu=None, rho: float = 1.0):
         """Attach linear constraints C x = d, E x <= e and a multiplier state (Eq. (augLag)): fg() then

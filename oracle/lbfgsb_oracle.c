@@ -12,9 +12,12 @@
  *   - objectives: the NNLS section's least-squares objective (scaled by 1/2), its
  *     L1-regularised variant split into x = p - q, and the regularised empirical
  *     logistic risk of the fairness section restricted to a box       -> orc_fg
+ *   - the dual SVM objective of the section "Dual SVM", 0.5 (a.y)^T K (a.y) - sum(a), as the
+ *     quadratic form ORC_QP                                           -> orc_fg
  *   - Eq. (augLag) and Algorithm 4 (augmented Lagrangian algorithm, section "Complete
  *     Framework" and appendix) for LINEAR constraints h(x) = C x - d = 0 and
- *     g(x) = E x - e <= 0 on top of the least-squares objective     -> orc_fg, orc_auglag_solve
+ *     g(x) = E x - e <= 0 on top of the least-squares or quadratic-form objective
+ *                                                                     -> orc_fg, orc_auglag_solve
  *
  * Nothing here is blocked, fused or reordered: every objective value and gradient is
  * evaluated from scratch at every trial point, the two-loop recursion is the literal
@@ -66,7 +69,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORC_LSQ = 0, ORC_LSQ_L1SPLIT = 1, ORC_LOGISTIC_L2 = 2 };
+enum { ORC_LSQ = 0, ORC_LSQ_L1SPLIT = 1, ORC_LOGISTIC_L2 = 2, ORC_QP = 3 };
 enum { ORC_F64 = 0, ORC_F32 = 1 };
 enum { ORC_RUNNING = 0, ORC_CONVERGED = 1, ORC_MAX_ITER = 2, ORC_LINESEARCH_FAILED = 3 };
 
@@ -87,7 +90,10 @@ typedef struct {
     const void* A;     /* row-major rows x cols, leading dimension ld */
     const double* b;   /* targets (least squares) or labels in {-1,+1} (logistic) */
     double lambda, mu;
-    const orc_constraints* con;   /* NULL: no constraints besides the box (ORC_LSQ only otherwise) */
+    const orc_constraints* con;   /* NULL: no constraints besides the box (ORC_LSQ and ORC_QP only otherwise) */
+    const double* sign;           /* ORC_QP: f = 0.5 (s.x)^T A (s.x) + b^T x with A symmetric (rows = cols), s = sign
+                                     (NULL = ones); with A a kernel matrix, s the labels and b = -1 this is the dual
+                                     SVM objective of the paper's section "Dual SVM" */
 } orc_objective;
 
 typedef struct {
@@ -166,7 +172,8 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
     double* v = (double*)malloc(sizeof(double) * (size_t)cols);   /* the vector A multiplies */
     double* psi = (double*)malloc(sizeof(double) * (size_t)(rows > 0 ? rows : 1));
     for (int64_t c = 0; c < cols; ++c)
-        v[c] = o->kind == ORC_LSQ_L1SPLIT ? x[c] - x[cols + c] : x[c];
+        v[c] = o->kind == ORC_LSQ_L1SPLIT ? x[c] - x[cols + c]
+             : (o->kind == ORC_QP && o->sign) ? o->sign[c] * x[c] : x[c];
 
     nsum fsum = {0.0, 0.0};
     for (int64_t r = 0; r < rows; ++r) {
@@ -177,6 +184,12 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
             double yr = o->b[r];
             ns_add(&fsum, softplus(-yr * z));
             psi[r] = -yr * sigmoid(-yr * z);
+            if (rowvec) rowvec[r] = z;
+        } else if (o->kind == ORC_QP) {
+            /* z = (A v)_r: f gets 0.5 v_r z + b_r x_r, the gradient entry is s_r z + b_r */
+            ns_add_prod(&fsum, 0.5 * v[r], z);
+            ns_add_prod(&fsum, o->b[r], x[r]);
+            psi[r] = z;
             if (rowvec) rowvec[r] = z;
         } else {
             double res = z - o->b[r];
@@ -195,7 +208,9 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
         f += o->lambda * ns_val(&l1);
     }
 
-    if (g) {
+    if (g && o->kind == ORC_QP) {
+        for (int64_t c = 0; c < cols; ++c) g[c] = (o->sign ? o->sign[c] : 1.0) * psi[c] + o->b[c];
+    } else if (g) {
         /* w = A^T psi, column by column as the definition says */
         nsum* acc = (nsum*)calloc((size_t)cols, sizeof(nsum));
         for (int64_t r = 0; r < rows; ++r)
@@ -208,7 +223,7 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
         }
         free(acc);
     }
-    if (o->con && o->kind == ORC_LSQ) {
+    if (o->con && (o->kind == ORC_LSQ || o->kind == ORC_QP)) {
         /* Eq. (augLag): the two penalty terms, their gradients C^T rho (h + lambda/rho) and
          * E^T rho (g + mu/rho)_+, and (after the rows of A) the shifted constraint values in rowvec */
         const orc_constraints* k = o->con;
@@ -217,7 +232,7 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
             const int eq = r < k->n_eq;
             const double* crow = eq ? k->C + r * cols : k->E + (r - k->n_eq) * cols;
             nsum acc = {0.0, 0.0};
-            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&acc, crow[c], v[c]);
+            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&acc, crow[c], x[c]);
             double a = eq ? ns_val(&acc) - k->d[r] + k->lambda[r] / k->rho
                           : ns_val(&acc) - k->e[r - k->n_eq] + k->mu[r - k->n_eq] / k->rho;
             if (rowvec) rowvec[rows + r] = a;
@@ -244,7 +259,7 @@ double orc_delta_f(const orc_objective* o, const double* x, const double* xt, co
     double* dv = (double*)malloc(sizeof(double) * (size_t)cols);
     for (int64_t c = 0; c < cols; ++c)
         dv[c] = o->kind == ORC_LSQ_L1SPLIT ? (xt[c] - x[c]) - (xt[cols + c] - x[cols + c])
-                                           : xt[c] - x[c];
+              : (o->kind == ORC_QP && o->sign) ? o->sign[c] * (xt[c] - x[c]) : xt[c] - x[c];
     nsum acc = {0.0, 0.0};
     for (int64_t r = 0; r < rows; ++r) {
         nsum dacc = {0.0, 0.0};
@@ -254,11 +269,15 @@ double orc_delta_f(const orc_objective* o, const double* x, const double* xt, co
             double a = -o->b[r] * row[r], da = -o->b[r] * dz;
             if (fabs(da) < 30.0) ns_add(&acc, log1p(sigmoid(a) * expm1(da)));
             else ns_add(&acc, softplus(a + da) - softplus(a));
+        } else if (o->kind == ORC_QP) {
+            /* 0.5 (v+dv)^T A (v+dv) - 0.5 v^T A v = dv^T (A v) + 0.5 dv^T (A dv) (A symmetric), plus b^T dx */
+            ns_add_prod(&acc, dv[r], row[r] + 0.5 * dz);
+            ns_add_prod(&acc, o->b[r], xt[r] - x[r]);
         } else {
             ns_add_prod(&acc, dz, row[r] + 0.5 * dz);
         }
     }
-    if (o->con && o->kind == ORC_LSQ) {
+    if (o->con && (o->kind == ORC_LSQ || o->kind == ORC_QP)) {
         /* rho/2 [(a + da)^2 - a^2] = rho da (a + da/2) for an equality row;
          * rho/2 [(a + da)_+^2 - a_+^2] = rho/2 (p1 - p0)(p1 + p0) for an inequality row */
         const orc_constraints* k = o->con;
@@ -266,7 +285,7 @@ double orc_delta_f(const orc_objective* o, const double* x, const double* xt, co
             const int eq = r < k->n_eq;
             const double* crow = eq ? k->C + r * cols : k->E + (r - k->n_eq) * cols;
             nsum dacc = {0.0, 0.0};
-            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&dacc, crow[c], dv[c]);
+            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&dacc, crow[c], xt[c] - x[c]);
             double da = ns_val(&dacc), a = row[rows + r];
             if (eq) {
                 ns_add_prod(&acc, k->rho * da, a + 0.5 * da);
@@ -601,7 +620,7 @@ static double constraint_values(const orc_constraints* k, int64_t cols, const do
 int orc_auglag_solve(int64_t n, int m, const double* l, const double* u, double* x, const orc_objective* obj,
                      const orc_options* opt, const orc_auglag_options* aopt, orc_auglag_info* info) {
     memset(info, 0, sizeof *info);
-    if (!obj || obj->kind != ORC_LSQ || !obj->con || n != obj->cols) return -1;
+    if (!obj || (obj->kind != ORC_LSQ && obj->kind != ORC_QP) || !obj->con || n != obj->cols) return -1;
     orc_constraints* k = (orc_constraints*)obj->con;   /* the multiplier state is the caller's, mutable */
     orc_auglag_options ao;
     if (aopt) ao = *aopt; else orc_auglag_default_options(&ao);
