@@ -50,7 +50,10 @@ enum { LBFGSB_F64 = 0, LBFGSB_F32 = 1 };
 enum {
     LBFGSB_OBJ_LSQ = 0,          /* f = 0.5*||A x - b||^2,                               n = cols   */
     LBFGSB_OBJ_LSQ_L1SPLIT = 1,  /* f = 0.5*||A(p-q) - b||^2 + lambda*sum(p+q), x=[p;q], n = 2*cols */
-    LBFGSB_OBJ_LOGISTIC_L2 = 2   /* f = (1/rows)*sum_i softplus(-b_i*(A x)_i) + mu/2*||x||^2, b_i in {-1,+1}, n = cols */
+    LBFGSB_OBJ_LOGISTIC_L2 = 2,  /* f = (1/rows)*sum_i softplus(-b_i*(A x)_i) + mu/2*||x||^2, b_i in {-1,+1}, n = cols */
+    LBFGSB_OBJ_QP = 3            /* f = 0.5*(s.x)^T A (s.x) + b^T x, A symmetric, rows = cols = n, s = sign (or ones).
+                                    With A a kernel matrix, s the labels and b = -1 this is the dual SVM objective of
+                                    the paper's section "Dual SVM".  One product with A per iteration (no transposed pass) */
 };
 
 typedef struct {
@@ -63,6 +66,16 @@ typedef struct {
     double mu;           /* LOGISTIC_L2 only */
     const double* row_weight; /* device, rows entries or NULL (= all ones), borrowed; least-squares kinds only:
                                  f = 0.5*sum_r row_weight_r*(A v - b)_r^2 (+ lambda*sum(p+q)) */
+    const double* sign;       /* device, n entries or NULL (= all ones), borrowed; LBFGSB_OBJ_QP only */
+    /* A few extra dense rows on top of a quadratic kind (LSQ, L1SPLIT, QP):
+     *   f += 0.5*sum_r extra_weight_r*(extra_rows_r . x - extra_target_r)^2,   r < n_extra <= 64.
+     * extra_rows: device, n_extra x n row-major fp64; extra_target, extra_weight: device, n_extra entries
+     * (weights NULL = ones).  All borrowed; target and weight may change between lbfgsb_set_x calls (this is
+     * how the augmented Lagrangian algorithm attaches its penalty term to the QP kind). */
+    int64_t n_extra;
+    const double* extra_rows;
+    const double* extra_target;
+    const double* extra_weight;
 } lbfgsb_objective;
 
 /* how the products with A are organised (results agree to rounding) */
@@ -210,6 +223,17 @@ int lbfgsb_auglag_create(lbfgsb_auglag** out, int64_t n, int m, const double* l,
                          const lbfgsb_objective* stacked_host, int64_t n_eq, const lbfgsb_options* opt_host,
                          const lbfgsb_auglag_options* al_opt_host, void* workspace, size_t workspace_bytes,
                          void* hip_stream);
+/* The same algorithm with the constraint rows passed separately: C (device, n_eq x n row-major fp64, n_eq <= 64)
+ * and d (device, n_eq entries), on top of any quadratic kind (LSQ, L1SPLIT, QP) given as it is -- nothing is
+ * stacked; the penalty term rides on the objective's extra rows.  This is how the dual SVM of the paper's
+ * section "Dual SVM" is solved: kind QP with the kernel matrix, the labels as sign and as the single
+ * constraint row, b = -1, 0 <= a <= c.  lbfgsb_auglag_info.f is then the objective without the penalty term. */
+size_t lbfgsb_auglag_rows_workspace_bytes(int64_t n, int m, const lbfgsb_objective* obj_host, int64_t n_eq,
+                                          const lbfgsb_options* opt_host);
+int lbfgsb_auglag_create_rows(lbfgsb_auglag** out, int64_t n, int m, const double* l, const double* u,
+                              const lbfgsb_objective* obj_host, int64_t n_eq, const double* C, const double* d,
+                              const lbfgsb_options* opt_host, const lbfgsb_auglag_options* al_opt_host,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
 /* Runs Algorithm 4 from x0 (device, n entries, feasible for the box) with lambda = 0, rho = rho0.  The host
  * reads two scalars per outer iteration; everything else stays on the device.  Synchronises. */
 int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info* info_host);

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblbfgsb.so")
 
 F64, F32 = 0, 1
-OBJ_LSQ, OBJ_LSQ_L1SPLIT, OBJ_LOGISTIC_L2 = 0, 1, 2
+OBJ_LSQ, OBJ_LSQ_L1SPLIT, OBJ_LOGISTIC_L2, OBJ_QP = 0, 1, 2, 3
 APASS_AUTO, APASS_TWO_PASS, APASS_FUSED = 0, 1, 2
 RUNNING, CONVERGED, MAX_ITER, LINESEARCH_FAILED = 0, 1, 2, 3
 OK, E_INVALID_ARG, E_BOUNDS, E_INFEASIBLE_X0, E_NONFINITE, E_HIP, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
@@ -27,13 +27,15 @@ EXPORTS = [
     "lbfgsb_dbg_free_mask", "lbfgsb_dbg_two_loop", "lbfgsb_dbg_project_direction",
     "lbfgsb_auglag_default_options", "lbfgsb_auglag_workspace_bytes", "lbfgsb_auglag_create", "lbfgsb_auglag_solve",
     "lbfgsb_auglag_get_x", "lbfgsb_auglag_get_lambda", "lbfgsb_auglag_inner", "lbfgsb_auglag_destroy",
+    "lbfgsb_auglag_rows_workspace_bytes", "lbfgsb_auglag_create_rows",
 ]
 
 
 class Objective(C.Structure):
     _fields_ = [("kind", C.c_int), ("dtype", C.c_int), ("rows", C.c_int64), ("cols", C.c_int64),
                 ("ld", C.c_int64), ("A", C.c_void_p), ("b", C.c_void_p), ("lam", C.c_double),
-                ("mu", C.c_double), ("row_weight", C.c_void_p)]
+                ("mu", C.c_double), ("row_weight", C.c_void_p), ("sign", C.c_void_p), ("n_extra", C.c_int64),
+                ("extra_rows", C.c_void_p), ("extra_target", C.c_void_p), ("extra_weight", C.c_void_p)]
 
 
 class AuglagOptions(C.Structure):
@@ -127,6 +129,11 @@ def lib():
         L.lbfgsb_auglag_create.restype = C.c_int
         L.lbfgsb_auglag_create.argtypes = [C.POINTER(vp), i64, C.c_int, vp, vp, C.POINTER(Objective), i64,
                                            C.POINTER(Options), C.POINTER(AuglagOptions), vp, C.c_size_t, vp]
+        L.lbfgsb_auglag_rows_workspace_bytes.restype = C.c_size_t
+        L.lbfgsb_auglag_rows_workspace_bytes.argtypes = [i64, C.c_int, C.POINTER(Objective), i64, C.POINTER(Options)]
+        L.lbfgsb_auglag_create_rows.restype = C.c_int
+        L.lbfgsb_auglag_create_rows.argtypes = [C.POINTER(vp), i64, C.c_int, vp, vp, C.POINTER(Objective), i64, vp, vp,
+                                                C.POINTER(Options), C.POINTER(AuglagOptions), vp, C.c_size_t, vp]
         L.lbfgsb_auglag_solve.restype = C.c_int
         L.lbfgsb_auglag_solve.argtypes = [vp, vp, C.POINTER(AuglagInfo)]
         L.lbfgsb_auglag_get_x.restype = C.c_int
@@ -174,7 +181,7 @@ class Solver:
     """
 
     def __init__(self, kind: int, A, b, l, u, m: int, *, lam: float = 0.0, mu: float = 0.0,
-                 options: Optional[Options] = None, row_weight=None):
+                 options: Optional[Options] = None, row_weight=None, sign=None, extra=None):
         import torch
         if not (isinstance(A, torch.Tensor) and A.is_cuda and A.dim() == 2 and A.stride(1) == 1
                 and A.dtype in (torch.float64, torch.float32)):
@@ -183,14 +190,28 @@ class Solver:
         self.n = 2 * cols if kind == OBJ_LSQ_L1SPLIT else cols
         self.rows, self.cols, self.m, self.kind = rows, cols, m, kind
         self._A, self._b = A, _dev_f64(b, "b", rows)
+        if kind == OBJ_QP and rows != cols:
+            raise ValueError("the quadratic form needs a square matrix")
         _dev_f64(l, "l", self.n)
         _dev_f64(u, "u", self.n)
         self.device = A.device
         self.options = options if options is not None else default_options()
         self._w = _dev_f64(row_weight, "row_weight", rows) if row_weight is not None else None
+        self._sign = _dev_f64(sign, "sign", self.n) if sign is not None else None
+        # extra = (rows E: (n_extra, n), targets: n_extra, weights: n_extra or None), float64 CUDA tensors
+        self._extra = extra
+        n_extra = 0 if extra is None else int(extra[0].shape[0])
+        if extra is not None:
+            _dev_f64(extra[0], "extra rows", n_extra * self.n)
+            _dev_f64(extra[1], "extra targets", n_extra)
+            if extra[2] is not None:
+                _dev_f64(extra[2], "extra weights", n_extra)
         self._obj = Objective(kind, F64 if A.dtype == torch.float64 else F32, rows, cols,
                               A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), float(lam), float(mu),
-                              self._w.data_ptr() if self._w is not None else None)
+                              self._w.data_ptr() if self._w is not None else None,
+                              self._sign.data_ptr() if self._sign is not None else None, n_extra,
+                              extra[0].data_ptr() if n_extra else None, extra[1].data_ptr() if n_extra else None,
+                              extra[2].data_ptr() if n_extra and extra[2] is not None else None)
         self._h = C.c_void_p()
         with torch.cuda.device(self.device):
             nbytes = lib().lbfgsb_workspace_bytes(self.n, m, C.byref(self._obj), C.byref(self.options))
@@ -332,7 +353,8 @@ class Auglag:
         self.options = options if options is not None else default_options()
         self.al_options = AuglagOptions(float(rho0), float(ctol), int(max_outer))
         self._obj = Objective(OBJ_LSQ, F64 if A.dtype == torch.float64 else F32, rows, cols,
-                              A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), 0.0, 0.0, None)
+                              A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), 0.0, 0.0, None, None, 0,
+                              None, None, None)
         self._h = C.c_void_p()
         with torch.cuda.device(self.device):
             nbytes = lib().lbfgsb_auglag_workspace_bytes(self.n, m, C.byref(self._obj), self.n_eq, C.byref(self.options))
@@ -382,6 +404,47 @@ class Auglag:
         cnt, ms, by = C.c_int64(0), C.c_double(0.0), C.c_double(0.0)
         _check(lib().lbfgsb_apass_timing(h, C.byref(cnt), C.byref(ms), C.byref(by)))
         return cnt.value, ms.value, by.value
+
+
+class AuglagRows(Auglag):
+    """lbfgsb_auglag_create_rows: Algorithm 4 with the constraint rows C x = d passed separately, on top of a
+    quadratic objective kind given as it is (e.g. OBJ_QP with the kernel matrix for the dual SVM)."""
+
+    def __init__(self, kind: int, A, b, C_rows, d, l, u, m: int, *, sign=None, lam: float = 0.0,
+                 options: Optional[Options] = None, rho0: float = 1.0, ctol: float = 1e-8, max_outer: int = 100):
+        import torch
+        if not (isinstance(A, torch.Tensor) and A.is_cuda and A.dim() == 2 and A.stride(1) == 1
+                and A.dtype in (torch.float64, torch.float32)):
+            raise TypeError("A must be a 2-d float64/float32 CUDA tensor with unit column stride")
+        rows, cols = A.shape
+        self.n = 2 * cols if kind == OBJ_LSQ_L1SPLIT else cols
+        self.n_eq, self.m = int(C_rows.shape[0]), m
+        self._A, self._b = A, _dev_f64(b, "b", rows)
+        self._C = _dev_f64(C_rows, "C", self.n_eq * self.n)
+        self._d = _dev_f64(d, "d", self.n_eq)
+        self._sign = _dev_f64(sign, "sign", self.n) if sign is not None else None
+        _dev_f64(l, "l", self.n)
+        _dev_f64(u, "u", self.n)
+        self.device = A.device
+        self.options = options if options is not None else default_options()
+        self.al_options = AuglagOptions(float(rho0), float(ctol), int(max_outer))
+        self._obj = Objective(kind, F64 if A.dtype == torch.float64 else F32, rows, cols,
+                              A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), float(lam), 0.0, None,
+                              self._sign.data_ptr() if self._sign is not None else None, 0, None, None, None)
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            nbytes = lib().lbfgsb_auglag_rows_workspace_bytes(self.n, m, C.byref(self._obj), self.n_eq,
+                                                              C.byref(self.options))
+            if nbytes == 0:
+                raise LbfgsbError(E_INVALID_ARG, lib().lbfgsb_last_error().decode())
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self._stream = torch.cuda.current_stream(self.device)
+            _check(lib().lbfgsb_auglag_create_rows(C.byref(self._h), self.n, m, l.data_ptr(), u.data_ptr(),
+                                                   C.byref(self._obj), self.n_eq,
+                                                   self._C.data_ptr() if self.n_eq else None,
+                                                   self._d.data_ptr() if self.n_eq else None, C.byref(self.options),
+                                                   C.byref(self.al_options), self.workspace.data_ptr(), nbytes,
+                                                   C.c_void_p(self._stream.cuda_stream)))
 
 
 def solver_for_problem(prob, device="cuda:0", **option_overrides) -> Solver:

@@ -46,6 +46,10 @@ __global__ __launch_bounds__(kBlock) void k_gemv(const T* __restrict__ A, int64_
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) v[j] -= vb[c + j];
             }
+            if (a.vs) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) v[j] *= a.vs[c + j];
+            }
 #pragma unroll
             for (int k = 0; k < R; ++k) {
                 double e[VEC];
@@ -60,7 +64,17 @@ __global__ __launch_bounds__(kBlock) void k_gemv(const T* __restrict__ A, int64_
             const double tot = wave_sum(acc[k]);
             if (lane == k) mine = tot;
         }
-        if (lane < R && r0 + lane < rows) loss += row_op(a.mode, mine, r0 + lane, rows, a.b, a.w, row, t, psi);
+        if (lane < R && r0 + lane < rows) {
+            const int64_t r = r0 + lane;
+            if (a.mode == kRowQpEval || a.mode == kRowQpDir) {
+                // symmetric quadratic form: the row index is also a column index, v_r = s_r z_r
+                const double vr = (va[r] - (vb ? vb[r] : 0.0)) * (a.vs ? a.vs[r] : 1.0);
+                if (a.mode == kRowQpEval) { row[r] = mine; loss += 0.5 * vr * mine; }
+                else { t[r] = mine; loss += vr * mine; }
+            } else {
+                loss += row_op(a.mode, mine, r, rows, a.b, a.w, row, t, psi);
+            }
+        }
     }
     double lv[1] = {loss};
     block_sum<1, kWaves>(lv, lds);

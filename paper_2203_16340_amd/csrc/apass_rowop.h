@@ -63,9 +63,11 @@ __device__ __forceinline__ double row_op(int mode, double u, int64_t r, int64_t 
             psi[r] = -y * sigmoid_d(a) / (double)rows;
             return softplus_d(a) / (double)rows;
         }
-        default:  // kRowLogiDir
+        case kRowLogiDir:
             t[r] = u;
             return 0.0;
+        default:
+            return 0.0;   // the QP modes need the row's own entry of v: see k_gemv
     }
 }
 

@@ -65,8 +65,14 @@ int check_objective(int64_t n, int m, const lbfgsb_objective* o) {
     if (!o) return fail(LBFGSB_E_INVALID_ARG, "objective is NULL");
     if (n <= 0) return fail(LBFGSB_E_INVALID_ARG, "n must be positive (got %lld)", (long long)n);
     if (m <= 0 || m > LBFGSB_MAX_M) return fail(LBFGSB_E_INVALID_ARG, "m must be in 1..%d (got %d)", LBFGSB_MAX_M, m);
-    if (o->kind < LBFGSB_OBJ_LSQ || o->kind > LBFGSB_OBJ_LOGISTIC_L2)
+    if (o->kind < LBFGSB_OBJ_LSQ || o->kind > LBFGSB_OBJ_QP)
         return fail(LBFGSB_E_INVALID_ARG, "unknown objective kind %d", o->kind);
+    if (o->kind == LBFGSB_OBJ_QP && o->rows != o->cols)
+        return fail(LBFGSB_E_INVALID_ARG, "the quadratic form needs a square matrix (got %lld x %lld)", (long long)o->rows,
+                    (long long)o->cols);
+    if (o->n_extra < 0 || o->n_extra > kMaxExtra) return fail(LBFGSB_E_INVALID_ARG, "n_extra must be in 0..%d", kMaxExtra);
+    if (o->n_extra > 0 && o->kind == LBFGSB_OBJ_LOGISTIC_L2)
+        return fail(LBFGSB_E_INVALID_ARG, "extra rows go with the quadratic objective kinds");
     if (o->dtype != LBFGSB_F64 && o->dtype != LBFGSB_F32) return fail(LBFGSB_E_INVALID_ARG, "unknown dtype %d", o->dtype);
     if (o->rows <= 0 || o->cols <= 0) return fail(LBFGSB_E_INVALID_ARG, "rows and cols must be positive");
     if (o->rows > (1ll << 31) - 1 || o->cols > (1ll << 31) - 1) return fail(LBFGSB_E_INVALID_ARG, "rows/cols exceed 2^31-1");
@@ -112,12 +118,13 @@ Geometry make_geometry(const Dims& dm, const void* A) {
 }
 
 struct Layout {
-    size_t scal, x, g, l, u, d, p1, p2, mask, S, Y, row, t, psi, wpart, losspart, grampart, redpart, lspart, total;
+    size_t scal, x, g, l, u, d, p1, p2, mask, S, Y, row, t, psi, wpart, losspart, grampart, redpart, lspart, wextra, xres, total;
 };
 
 Layout make_layout(const Dims& dm, const Geometry& ge) {
     Layout L{};
     size_t off = 0;
+    // (wextra / xres are appended at the end so that the offsets of everything else do not depend on n_extra)
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     const size_t nb = (size_t)dm.n * 8, rb = (size_t)dm.rows * 8;
     L.scal = take(sizeof(Scal));
@@ -137,6 +144,8 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     if ((size_t)ge.upd_blocks * 2 > red) red = (size_t)ge.upd_blocks * 2;
     L.redpart = take(red * 8);
     L.lspart = take((size_t)ge.ls_blocks * kLsBatch * 8);
+    L.wextra = take(dm.n_extra > 0 ? (size_t)dm.n * 8 : 8);
+    L.xres = take((size_t)(dm.n_extra + 1) * 8);
     L.total = off;
     return L;
 }
@@ -145,6 +154,7 @@ Dims make_dims(int64_t n, int m, const lbfgsb_objective* o) {
     Dims dm{};
     dm.n = n; dm.rows = o->rows; dm.cols = o->cols; dm.ld = o->ld; dm.m = m; dm.kind = o->kind; dm.dtype = o->dtype;
     dm.lambda = o->lambda; dm.mu = o->mu;
+    dm.n_extra = (int)o->n_extra;
     return dm;
 }
 
@@ -184,7 +194,9 @@ struct TimedSlot {
 
 APassArgs base_args(const lbfgsb_solver* s) {
     APassArgs a{};
-    a.A = s->obj.A; a.b = s->obj.b; a.w = is_quadratic(s->dm.kind) ? s->obj.row_weight : nullptr;
+    a.A = s->obj.A; a.b = s->obj.b;
+    a.w = (s->dm.kind == LBFGSB_OBJ_LSQ || s->dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT) ? s->obj.row_weight : nullptr;
+    a.vs = s->dm.kind == LBFGSB_OBJ_QP ? s->obj.sign : nullptr;
     a.p1 = s->bf.p1; a.p2 = s->bf.p2;
     a.split = s->dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT;
     a.c1 = s->op.c1;
@@ -199,16 +211,23 @@ void enqueue_eval(lbfgsb_solver* s, int check_status) {
     a.va = s->bf.x;
     a.vb = a.split ? s->bf.x + s->dm.cols : nullptr;
     a.select_p = 0;
-    a.mode = is_quadratic(s->dm.kind) ? kRowLsqEval : kRowLogiEval;
+    const bool qp = s->dm.kind == LBFGSB_OBJ_QP;
+    a.mode = qp ? kRowQpEval : (is_quadratic(s->dm.kind) ? kRowLsqEval : kRowLogiEval);
     a.check_status = check_status;
-    if (s->use_fused) {
+    if (qp) {
+        // symmetric matrix: the gradient needs the row products only
+        TimedSlot ts(s);
+        launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
+    } else if (s->use_fused) {
         TimedSlot ts(s);
         launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
     } else {
         { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
         { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, check_status, s->stream, ts.e0, ts.e1); }
     }
-    launch_eval_finish(s->dm, s->ge, s->bf, s->stream);
+    if (s->dm.n_extra > 0)
+        launch_extra_rows(s->dm, s->bf, s->obj.extra_rows, s->obj.extra_target, s->obj.extra_weight, 1, s->stream);
+    launch_eval_finish(s->dm, s->ge, s->bf, s->obj.b, s->obj.sign, s->stream);
 }
 
 // One iteration of Algorithm 1 as a fixed sequence of launches; nothing here waits for the device.
@@ -223,7 +242,13 @@ void enqueue_step(lbfgsb_solver* s) {
     APassArgs a = base_args(s);
     a.select_p = 1;
     a.check_status = 1;
-    if (quad) {
+    if (quad && s->dm.n_extra > 0)
+        launch_extra_rows(s->dm, s->bf, s->obj.extra_rows, s->obj.extra_target, s->obj.extra_weight, 0, s->stream);
+    if (s->dm.kind == LBFGSB_OBJ_QP) {
+        a.mode = kRowQpDir;
+        { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
+        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->obj.sign, s->stream);
+    } else if (quad) {
         a.mode = kRowDir;
         if (s->use_fused) {
             TimedSlot ts(s);
@@ -232,7 +257,7 @@ void enqueue_step(lbfgsb_solver* s) {
             { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
             { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
         }
-        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->stream);
+        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, nullptr, s->stream);
     } else if (s->use_fused) {
         // One read of X yields t = X p AND X^T psi for the first trial step min(1, alpha_ub); the last
         // workgroup of that pass tests the Armijo condition for it.  Only if the step is rejected do the
@@ -289,6 +314,8 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
     int rc = check_objective(n, m, obj);
     if (rc) return rc;
     if (!l || !u || !obj->A || !obj->b || !workspace) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
+    if (obj->n_extra > 0 && (!obj->extra_rows || !obj->extra_target))
+        return fail(LBFGSB_E_INVALID_ARG, "NULL extra_rows / extra_target");
     lbfgsb_options o;
     if (opt) o = *opt; else lbfgsb_default_options(&o);
     rc = check_options(&o);
@@ -329,6 +356,7 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
             return fail(LBFGSB_E_HIP, "preparing the fused A pass: %s", hipGetErrorString(fe));
         }
     }
+    if (s->dm.kind == LBFGSB_OBJ_QP) s->use_fused = 0;   // one product with the symmetric matrix per iteration: the row kernel alone
     s->ge.w_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemvt_row_blocks;
     s->ge.loss_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemv_blocks;
 
@@ -342,6 +370,7 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
     b.row = (double*)(w + L.row); b.t = (double*)(w + L.t); b.psi = (double*)(w + L.psi);
     b.wpart = (double*)(w + L.wpart); b.losspart = (double*)(w + L.losspart);
     b.grampart = (double*)(w + L.grampart); b.redpart = (double*)(w + L.redpart); b.lspart = (double*)(w + L.lspart);
+    b.wextra = (double*)(w + L.wextra); b.xres = (double*)(w + L.xres);
 
     auto bail = [&](int code) { lbfgsb_destroy(s); return code; };
     {
@@ -598,9 +627,12 @@ int lbfgsb_dbg_project_direction(lbfgsb_solver* s, const double* x, const double
 struct lbfgsb_auglag {
     lbfgsb_solver* inner;
     lbfgsb_auglag_options ao;
-    int64_t rows_data, n_eq, n;
-    const double* bd;        // the caller's [b; d]
-    double *beta, *omega;    // targets and weights of all rows (workspace)
+    int64_t n_eq, n;
+    // the constraint rows' targets d (caller's), and the targets / weights the algorithm rewrites (workspace):
+    // entries of the stacked matrix's row vectors, or the inner objective's extra rows
+    const double* d_c;
+    double *beta_c, *omega_c;
+    const double* res_c;     // where the inner solver leaves a_r . x - beta_r of the constraint rows after an evaluation
     double *lambda, *red;    // multipliers; red[0] = violation, red[1] = penalty term
     double* h_red;           // pinned host copy of red
     double rho;
@@ -618,24 +650,24 @@ __global__ void k_al_init(int64_t rows, const double* __restrict__ bd, double* _
 }
 
 // targets d - lambda/rho and weights rho of the constraint rows for the next inner solve
-__global__ void k_al_prepare(int64_t rows_data, int64_t n_eq, double rho, const double* __restrict__ bd,
-                             const double* __restrict__ lambda, double* __restrict__ beta, double* __restrict__ omega) {
+__global__ void k_al_prepare(int64_t n_eq, double rho, const double* __restrict__ d, const double* __restrict__ lambda,
+                             double* __restrict__ beta, double* __restrict__ omega) {
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_eq; r += (int64_t)gridDim.x * blockDim.x) {
-        beta[rows_data + r] = bd[rows_data + r] - lambda[r] / rho;
-        omega[rows_data + r] = rho;
+        beta[r] = d[r] - lambda[r] / rho;
+        omega[r] = rho;
     }
 }
 
-// One workgroup.  row holds a_r . x - beta_r for every row, freshly evaluated at x.  For the constraint rows
-// h_r = row_r - lambda_r/rho; with update != 0 the multipliers become lambda + rho h.  red[0] = ||h||_inf,
+// One workgroup.  res holds a_r . x - beta_r of the constraint rows, freshly evaluated at x:
+// h_r = res_r - lambda_r/rho; with update != 0 the multipliers become lambda + rho h.  red[0] = ||h||_inf,
 // red[1] = rho/2 sum (h + lambda/rho)^2 (the penalty term at the OLD multipliers).
-__global__ __launch_bounds__(kBlock) void k_al_update(int64_t rows_data, int64_t n_eq, double rho, int update,
-                                                      const double* __restrict__ row, double* __restrict__ lambda,
+__global__ __launch_bounds__(kBlock) void k_al_update(int64_t n_eq, double rho, int update,
+                                                      const double* __restrict__ res, double* __restrict__ lambda,
                                                       double* __restrict__ red) {
     __shared__ double lds[kWaves * 2];
     double viol = 0.0, pen = 0.0;
     for (int64_t r = threadIdx.x; r < n_eq; r += kBlock) {
-        const double a = row[rows_data + r];
+        const double a = res[r];
         const double h = a - lambda[r] / rho;
         viol = fmax(viol, fabs(h));
         pen = fma(a, a, pen);
@@ -661,11 +693,25 @@ size_t al_extra_bytes(int64_t rows, int64_t n_eq) {
 
 int check_al(int64_t n, const lbfgsb_objective* o, int64_t n_eq) {
     if (!o) return fail(LBFGSB_E_INVALID_ARG, "objective is NULL");
-    if (o->kind != LBFGSB_OBJ_LSQ) return fail(LBFGSB_E_INVALID_ARG, "the augmented Lagrangian entry points take the least-squares objective");
+    if (o->kind != LBFGSB_OBJ_LSQ) return fail(LBFGSB_E_INVALID_ARG, "lbfgsb_auglag_create takes the least-squares objective with the constraint rows stacked under A");
     if (n_eq < 0 || n_eq >= o->rows) return fail(LBFGSB_E_INVALID_ARG, "n_eq must be in 0..rows-1 (rows counts the constraint rows)");
     if (o->row_weight) return fail(LBFGSB_E_INVALID_ARG, "row_weight must be NULL: the weights are the algorithm's");
+    if (o->n_extra) return fail(LBFGSB_E_INVALID_ARG, "n_extra must be 0");
     (void)n;
     return LBFGSB_OK;
+}
+
+int check_al_rows(const lbfgsb_objective* o, int64_t n_eq, const double* C, const double* d) {
+    if (!o) return fail(LBFGSB_E_INVALID_ARG, "objective is NULL");
+    if (o->kind == LBFGSB_OBJ_LOGISTIC_L2) return fail(LBFGSB_E_INVALID_ARG, "the augmented Lagrangian entry points take the quadratic objective kinds");
+    if (n_eq < 0 || n_eq > kMaxExtra) return fail(LBFGSB_E_INVALID_ARG, "n_eq must be in 0..%d for constraint rows passed separately", kMaxExtra);
+    if (o->n_extra) return fail(LBFGSB_E_INVALID_ARG, "n_extra must be 0: the extra rows are the algorithm's");
+    if (n_eq > 0 && (!C || !d)) return fail(LBFGSB_E_INVALID_ARG, "NULL constraint rows / targets");
+    return LBFGSB_OK;
+}
+
+size_t al_rows_extra_bytes(int64_t n_eq) {
+    return 3 * align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8) + align_up(64);
 }
 
 // residual (all rows) and gradient recomputed from x unless they already are
@@ -718,24 +764,84 @@ int lbfgsb_auglag_create(lbfgsb_auglag** out, int64_t n, int m, const double* l,
 
     lbfgsb_auglag* al = new (std::nothrow) lbfgsb_auglag();
     if (!al) return fail(LBFGSB_E_INVALID_ARG, "out of host memory");
-    al->ao = ao; al->rows_data = obj->rows - n_eq; al->n_eq = n_eq; al->n = n; al->bd = obj->b;
+    const int64_t rows_data = obj->rows - n_eq;
+    al->ao = ao; al->n_eq = n_eq; al->n = n; al->d_c = obj->b + rows_data;
     al->stream = (hipStream_t)hip_stream; al->rho = ao.rho0; al->inner = nullptr; al->h_red = nullptr;
     char* w = (char*)workspace + align_up(inner_bytes);
-    al->beta = (double*)w; w += align_up((size_t)obj->rows * 8);
-    al->omega = (double*)w; w += align_up((size_t)obj->rows * 8);
+    double* beta = (double*)w; w += align_up((size_t)obj->rows * 8);
+    double* omega = (double*)w; w += align_up((size_t)obj->rows * 8);
+    al->beta_c = beta + rows_data; al->omega_c = omega + rows_data;
     al->lambda = (double*)w; w += align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8);
     al->red = (double*)w;
     lbfgsb_objective inner_obj = *obj;
-    inner_obj.b = al->beta;
-    inner_obj.row_weight = al->omega;
+    inner_obj.b = beta;
+    inner_obj.row_weight = omega;
     rc = lbfgsb_create(&al->inner, n, m, l, u, &inner_obj, opt, workspace, inner_bytes, hip_stream);
     if (rc) { delete al; return rc; }
+    al->res_c = al->inner->bf.row + rows_data;
     hipError_t e = hipHostMalloc((void**)&al->h_red, 64, hipHostMallocDefault);
     if (e != hipSuccess) { al->h_red = nullptr; lbfgsb_auglag_destroy(al); return fail(LBFGSB_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
     int blocks = (int)((obj->rows + 255) / 256);
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(k_al_init, dim3(blocks), dim3(256), 0, al->stream, obj->rows, al->bd, al->beta, al->omega);
+    hipLaunchKernelGGL(k_al_init, dim3(blocks), dim3(256), 0, al->stream, obj->rows, obj->b, beta, omega);
     launch_fill_zero(al->lambda, align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8), al->stream);
+    e = hipStreamSynchronize(al->stream);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) { lbfgsb_auglag_destroy(al); return fail(LBFGSB_E_HIP, "initialising: %s", hipGetErrorString(e)); }
+    *out = al;
+    return LBFGSB_OK;
+}
+
+size_t lbfgsb_auglag_rows_workspace_bytes(int64_t n, int m, const lbfgsb_objective* obj, int64_t n_eq,
+                                          const lbfgsb_options* opt) {
+    if (check_al_rows(obj, n_eq, (const double*)8, (const double*)8) != LBFGSB_OK) return 0;
+    lbfgsb_objective o = *obj;
+    o.n_extra = n_eq;
+    const size_t inner = lbfgsb_workspace_bytes(n, m, &o, opt);
+    return inner ? align_up(inner) + al_rows_extra_bytes(n_eq) : 0;
+}
+
+int lbfgsb_auglag_create_rows(lbfgsb_auglag** out, int64_t n, int m, const double* l, const double* u,
+                              const lbfgsb_objective* obj, int64_t n_eq, const double* C, const double* d,
+                              const lbfgsb_options* opt, const lbfgsb_auglag_options* aopt, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail(LBFGSB_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int rc = check_al_rows(obj, n_eq, C, d);
+    if (rc) return rc;
+    lbfgsb_auglag_options ao;
+    if (aopt) ao = *aopt; else lbfgsb_auglag_default_options(&ao);
+    if (!(ao.rho0 > 0.0) || !(ao.ctol >= 0.0) || ao.max_outer < 1) return fail(LBFGSB_E_INVALID_ARG, "bad option value");
+    if (!workspace) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
+    lbfgsb_objective inner_obj = *obj;
+    inner_obj.n_extra = n_eq;
+    inner_obj.extra_rows = C;
+    inner_obj.extra_target = (const double*)8;   // placeholders for the size computation; set below
+    const size_t inner_bytes = lbfgsb_workspace_bytes(n, m, &inner_obj, opt);
+    if (inner_bytes == 0) return LBFGSB_E_INVALID_ARG;
+    const size_t extra = al_rows_extra_bytes(n_eq);
+    if (workspace_bytes < align_up(inner_bytes) + extra)
+        return fail(LBFGSB_E_INVALID_ARG, "workspace too small: %zu < %zu bytes", workspace_bytes, align_up(inner_bytes) + extra);
+    if ((uintptr_t)workspace % 256) return fail(LBFGSB_E_INVALID_ARG, "workspace must be 256-byte aligned");
+
+    lbfgsb_auglag* al = new (std::nothrow) lbfgsb_auglag();
+    if (!al) return fail(LBFGSB_E_INVALID_ARG, "out of host memory");
+    const size_t slot = align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8);
+    al->ao = ao; al->n_eq = n_eq; al->n = n; al->d_c = d;
+    al->stream = (hipStream_t)hip_stream; al->rho = ao.rho0; al->inner = nullptr; al->h_red = nullptr;
+    char* w = (char*)workspace + align_up(inner_bytes);
+    al->beta_c = (double*)w; w += slot;
+    al->omega_c = (double*)w; w += slot;
+    al->lambda = (double*)w; w += slot;
+    al->red = (double*)w;
+    inner_obj.extra_target = al->beta_c;
+    inner_obj.extra_weight = al->omega_c;
+    rc = lbfgsb_create(&al->inner, n, m, l, u, &inner_obj, opt, workspace, inner_bytes, hip_stream);
+    if (rc) { delete al; return rc; }
+    al->res_c = al->inner->bf.xres;
+    hipError_t e = hipHostMalloc((void**)&al->h_red, 64, hipHostMallocDefault);
+    if (e != hipSuccess) { al->h_red = nullptr; lbfgsb_auglag_destroy(al); return fail(LBFGSB_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
+    launch_fill_zero(al->beta_c, 3 * slot, al->stream);
     e = hipStreamSynchronize(al->stream);
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) { lbfgsb_auglag_destroy(al); return fail(LBFGSB_E_HIP, "initialising: %s", hipGetErrorString(e)); }
@@ -759,13 +865,13 @@ int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info*
     // lambda^0 = 0, rho = rho0; the violation at x^0 is what the first iteration is compared with
     launch_fill_zero(al->lambda, align_up((size_t)(al->n_eq > 0 ? al->n_eq : 1) * 8), al->stream);
     al->rho = al->ao.rho0;
-    hipLaunchKernelGGL(k_al_prepare, dim3(pb), dim3(256), 0, al->stream, al->rows_data, al->n_eq, al->rho, al->bd,
-                       al->lambda, al->beta, al->omega);
+    hipLaunchKernelGGL(k_al_prepare, dim3(pb), dim3(256), 0, al->stream, al->n_eq, al->rho, al->d_c, al->lambda,
+                       al->beta_c, al->omega_c);
     int rc = lbfgsb_set_x(s, x0);
     if (rc) return rc;
     auto measure = [&](int update) -> hipError_t {
-        hipLaunchKernelGGL(k_al_update, dim3(1), dim3(kBlock), 0, al->stream, al->rows_data, al->n_eq, al->rho, update,
-                           s->bf.row, al->lambda, al->red);
+        hipLaunchKernelGGL(k_al_update, dim3(1), dim3(kBlock), 0, al->stream, al->n_eq, al->rho, update, al->res_c,
+                           al->lambda, al->red);
         hipError_t e = hipMemcpyAsync(al->h_red, al->red, 16, hipMemcpyDeviceToHost, al->stream);
         if (e != hipSuccess) return e;
         return hipStreamSynchronize(al->stream);
@@ -776,8 +882,8 @@ int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info*
     for (int it = 0; it < al->ao.max_outer; ++it) {
         if (it > 0) {
             // new targets/weights: the objective changed, so f and g are re-evaluated at x and the pair memory is cleared
-            hipLaunchKernelGGL(k_al_prepare, dim3(pb), dim3(256), 0, al->stream, al->rows_data, al->n_eq, al->rho, al->bd,
-                               al->lambda, al->beta, al->omega);
+            hipLaunchKernelGGL(k_al_prepare, dim3(pb), dim3(256), 0, al->stream, al->n_eq, al->rho, al->d_c, al->lambda,
+                               al->beta_c, al->omega_c);
             rc = lbfgsb_set_x(s, s->bf.x);
             if (rc) return rc;
         }

@@ -55,7 +55,10 @@ struct Dims {
     int64_t n, rows, cols, ld;
     int m, kind, dtype;
     double lambda, mu;
+    int n_extra;            // extra dense rows on top of a quadratic kind (0 = none)
 };
+
+constexpr int kMaxExtra = 64;
 
 struct Opts {
     double eps, c1, backtrack, tol;
@@ -221,6 +224,8 @@ struct Buffers {
     double *grampart;       // gram_blocks x gram_entries
     double *redpart;        // partials of the direction / update / finish kernels
     double *lspart;         // ls_blocks x kLsBatch
+    double *wextra;         // n: contribution of the extra rows to the columns of the gradient (or of its change)
+    double *xres;           // n_extra residuals e_r.x - target_r of the last evaluation, then [n_extra] the loss term
 };
 
 // ---- launchers (defined in apass.hip / vec.hip) -------------------------------------------------------
@@ -230,13 +235,16 @@ enum RowMode {
     kRowDir = 1,       // u = a_r.v -> t; psi = w_r u;              loss += w_r u^2
     kRowLogiEval = 2,  // u = a_r.v -> row (margin); psi = -y sigma(-y u)/rows; loss += softplus(-y u)/rows
     kRowLogiDir = 3,   // u = a_r.v -> t only (no transposed product follows)
-    kRowLogiSpec = 4   // fused kernel only: u = a_r.v -> t; psi and loss for the first trial step min(1, alpha_ub)
+    kRowLogiSpec = 4,  // fused kernel only: u = a_r.v -> t; psi and loss for the first trial step min(1, alpha_ub)
+    kRowQpEval = 5,    // two-pass row kernel only: u = a_r.v -> row; loss += 0.5 v_r u   (A symmetric, v = s.x)
+    kRowQpDir = 6      // two-pass row kernel only: u = a_r.v -> t;   loss += v_r u       (v = s.p)
 };
 
 struct APassArgs {
     const void* A;
     const double* b;
     const double* w;        // per-row weights of the least-squares kinds (null = all ones)
+    const double* vs;       // QP: v is multiplied entrywise by this sign vector (null = ones)
     const double* va;       // v = va[c] - (vb ? vb[c] : 0)
     const double* vb;
     const double* p1;       // when select_p != 0: va/vb are taken from p1 or p2 according to Scal::branch
@@ -262,12 +270,17 @@ void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const A
 
 void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 void launch_set_status(const Buffers& bf, int status, hipStream_t st);
-void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, hipStream_t st);
+void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* lin, const double* sign,
+                        hipStream_t st);   // lin, sign: QP only (linear term b, sign vector)
 void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int dbg_inputs,
                  int evaluate_stop, hipStream_t st);
 void launch_commit(const Dims& dm, const Buffers& bf, hipStream_t st);
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st);
-void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, hipStream_t st);
+void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
+                             hipStream_t st);
+// extra rows: e_r.z for z = x (eval != 0: residuals against the targets) or the selected direction (eval == 0)
+void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, const double* target, const double* weight,
+                       int eval, hipStream_t st);
 void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
                         hipStream_t st);
 void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* labels, hipStream_t st);

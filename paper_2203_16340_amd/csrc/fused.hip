@@ -90,6 +90,7 @@ int64_t rows_per_wg_for(const Dims& dm, const Variant& v) {
 bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks) {
     *variant = -1;
     *blocks = 0;
+    if (dm.kind == LBFGSB_OBJ_QP) return false;   // no transposed product: the row kernel alone serves it
     const int vec = dm.dtype == LBFGSB_F32 ? 4 : 2;
     if ((uintptr_t)A % 16 != 0 || dm.cols % vec != 0 || dm.ld % vec != 0) return false;   // needs 16-byte loads
     for (int i = 0; i < kNumVariants; ++i) {

@@ -188,7 +188,10 @@ __global__ __launch_bounds__(kBlock) void k_eval_finish(Dims dm, int w_parts, in
                                                         const double* __restrict__ wpart,
                                                         const double* __restrict__ losspart,
                                                         const double* __restrict__ x, double* __restrict__ g,
-                                                        Scal* __restrict__ scal, double* __restrict__ redpart) {
+                                                        Scal* __restrict__ scal, double* __restrict__ redpart,
+                                                        const double* __restrict__ lin, const double* __restrict__ sign,
+                                                        const double* __restrict__ wextra,
+                                                        const double* __restrict__ xres) {
     __shared__ double lds[kBlock];
     __shared__ double red[kWaves];
     __shared__ int flag;
@@ -199,12 +202,17 @@ __global__ __launch_bounds__(kBlock) void k_eval_finish(Dims dm, int w_parts, in
         const int64_t c = c0 + tid % kCX;
         const double w = column_sum(wpart, w_parts, dm.cols, c, lds);
         if (tid < kCX && c < dm.cols) {
+            // wextra: the extra rows' contribution E^T (weight * residual), one entry per variable
             if (dm.kind == LBFGSB_OBJ_LSQ) {
-                g[c] = w;
+                g[c] = w + (wextra ? wextra[c] : 0.0);
             } else if (dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT) {
-                g[c] = w + dm.lambda;
-                g[c + dm.cols] = -w + dm.lambda;
+                g[c] = w + dm.lambda + (wextra ? wextra[c] : 0.0);
+                g[c + dm.cols] = -w + dm.lambda + (wextra ? wextra[c + dm.cols] : 0.0);
                 reg += x[c] + x[c + dm.cols];
+            } else if (dm.kind == LBFGSB_OBJ_QP) {
+                // w = (A (s.x))_c (a single "partial": the row kernel's output); g = s w + b, f = loss + b.x
+                g[c] = (sign ? sign[c] : 1.0) * w + lin[c] + (wextra ? wextra[c] : 0.0);
+                reg = fma(lin[c], x[c], reg);
             } else {
                 const double xc = x[c];
                 g[c] = fma(dm.mu, xc, w);
@@ -222,14 +230,20 @@ __global__ __launch_bounds__(kBlock) void k_eval_finish(Dims dm, int w_parts, in
         double f = loss;
         if (dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT) f += dm.lambda * regt;
         else if (dm.kind == LBFGSB_OBJ_LOGISTIC_L2) f += 0.5 * dm.mu * regt;
+        else if (dm.kind == LBFGSB_OBJ_QP) f += regt;
+        if (xres) f += xres[dm.n_extra];   // 0.5 sum weight * residual^2 of the extra rows
         scal->f = f;
         scal->fevals += 1;
     }
 }
 
-void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, hipStream_t st) {
-    hipLaunchKernelGGL(k_eval_finish, dim3(ge.fin_blocks), dim3(kBlock), 0, st, dm, ge.w_parts, ge.loss_parts, bf.wpart,
-                       bf.losspart, bf.x, bf.g, bf.scal, bf.redpart);
+void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* lin, const double* sign,
+                        hipStream_t st) {
+    const bool qp = dm.kind == LBFGSB_OBJ_QP;
+    hipLaunchKernelGGL(k_eval_finish, dim3(ge.fin_blocks), dim3(kBlock), 0, st, dm, qp ? 1 : ge.w_parts, ge.loss_parts,
+                       qp ? (const double*)bf.row : (const double*)bf.wpart, bf.losspart, bf.x, bf.g, bf.scal, bf.redpart,
+                       lin, sign, dm.n_extra > 0 ? (const double*)bf.wextra : nullptr,
+                       dm.n_extra > 0 ? (const double*)bf.xres : nullptr);
 }
 
 // ---- quadratic objectives: closed-form Armijo search, then the update ---------------------------------------
@@ -246,7 +260,9 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
                                                              const double* __restrict__ l, const double* __restrict__ u,
                                                              double* __restrict__ x, double* __restrict__ g,
                                                              double* __restrict__ S, double* __restrict__ Y,
-                                                             Scal* __restrict__ scal) {
+                                                             Scal* __restrict__ scal, const double* __restrict__ sign,
+                                                             const double* __restrict__ wextra,
+                                                             const double* __restrict__ xres) {
     __shared__ double lds[kBlock];
     __shared__ double red[kWaves];
     __shared__ double ls_alpha;
@@ -256,7 +272,8 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
     const double gp = scal->gp, alpha_ub = scal->alpha_ub, f_old = scal->f;
     const int slot = scal->head;
     const double* p = scal->branch == 1 ? p1 : p2;
-    const double tt = sum_all(losspart, loss_parts, red);
+    // curvature along p: ||t||^2 (weighted) from the A pass, plus the extra rows' sum weight (e_r.p)^2
+    const double tt = sum_all(losspart, loss_parts, red) + (xres ? xres[dm.n_extra] : 0.0);
     if (tid == 0) {
         double a = fmin(1.0, alpha_ub);
         int ok = 0, bt = 0;
@@ -280,7 +297,10 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
                 const int nvar = dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT ? 2 : 1;
                 for (int h = 0; h < nvar; ++h) {
                     const int64_t i = c + h * dm.cols;
-                    const double y = alpha * (h ? -w : w);
+                    double wi = h ? -w : w;
+                    if (sign) wi *= sign[i];               // QP: the change of the gradient is s.(A (s.p))
+                    if (wextra) wi += wextra[i];
+                    const double y = alpha * wi;
                     const double xi = x[i];
                     const double xn = clampd(fma(alpha, p[i], xi), l[i], u[i]);
                     Sn[i] = xn - xi;
@@ -302,9 +322,60 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
     }
 }
 
-void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, hipStream_t st) {
-    hipLaunchKernelGGL(k_update_quadratic, dim3(ge.upd_blocks), dim3(kBlock), 0, st, dm, op, ge.w_parts, ge.loss_parts,
-                       bf.wpart, bf.losspart, bf.p1, bf.p2, bf.l, bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal);
+void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
+                             hipStream_t st) {
+    const bool qp = dm.kind == LBFGSB_OBJ_QP;   // its "partial columns" are the single vector t = A (s.p)
+    hipLaunchKernelGGL(k_update_quadratic, dim3(ge.upd_blocks), dim3(kBlock), 0, st, dm, op, qp ? 1 : ge.w_parts,
+                       ge.loss_parts, qp ? (const double*)bf.t : (const double*)bf.wpart, bf.losspart, bf.p1, bf.p2, bf.l,
+                       bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, qp ? sign : nullptr,
+                       dm.n_extra > 0 ? (const double*)bf.wextra : nullptr,
+                       dm.n_extra > 0 ? (const double*)bf.xres : nullptr);
+}
+
+// ---- extra dense rows ------------------------------------------------------------------------------------
+//
+// One workgroup.  z = x (eval) or the direction Algorithm 2 selected.  te_r = e_r . z; coefficient
+// c_r = weight_r (te_r - target_r) (eval) or weight_r te_r (direction);
+//   wextra[i] = sum_r c_r E[r][i],   xres[r] = te_r - target_r (eval only),
+//   xres[n_extra] = 0.5 sum weight_r (te_r - target_r)^2 (eval)  or  sum weight_r te_r^2 (direction).
+__global__ __launch_bounds__(kBlock) void k_extra_rows(Dims dm, const double* __restrict__ E,
+                                                       const double* __restrict__ target,
+                                                       const double* __restrict__ weight, int eval,
+                                                       const double* __restrict__ x, const double* __restrict__ p1,
+                                                       const double* __restrict__ p2, const Scal* __restrict__ scal,
+                                                       double* __restrict__ wextra, double* __restrict__ xres) {
+    __shared__ double red[kWaves];
+    __shared__ double coef[kMaxExtra];
+    if (!eval && scal->status != LBFGSB_RUNNING) return;
+    const int tid = threadIdx.x;
+    const double* z = eval ? x : (scal->branch == 1 ? p1 : p2);
+    double total = 0.0;
+    for (int r = 0; r < dm.n_extra; ++r) {
+        double s[1] = {0.0};
+        const double* er = E + (int64_t)r * dm.n;
+        for (int64_t i = tid; i < dm.n; i += kBlock) s[0] = fma(er[i], z[i], s[0]);
+        block_sum<1, kWaves>(s, red);
+        const double wr = weight ? weight[r] : 1.0;
+        const double res = eval ? s[0] - target[r] : s[0];
+        total += (eval ? 0.5 : 1.0) * wr * res * res;
+        if (tid == 0) {
+            coef[r] = wr * res;
+            if (eval) xres[r] = res;
+        }
+    }
+    __syncthreads();
+    for (int64_t i = tid; i < dm.n; i += kBlock) {
+        double acc = 0.0;
+        for (int r = 0; r < dm.n_extra; ++r) acc = fma(coef[r], E[(int64_t)r * dm.n + i], acc);
+        wextra[i] = acc;
+    }
+    if (tid == 0) xres[dm.n_extra] = total;
+}
+
+void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, const double* target, const double* weight,
+                       int eval, hipStream_t st) {
+    hipLaunchKernelGGL(k_extra_rows, dim3(1), dim3(kBlock), 0, st, dm, rows, target, weight, eval, bf.x, bf.p1, bf.p2,
+                       (const Scal*)bf.scal, bf.wextra, bf.xres);
 }
 
 // ---- logistic objective: line search on the margins --------------------------------------------------------

@@ -318,3 +318,42 @@ def constrained_config(name: str, *, scale: float = 1.0) -> ConstrainedProblem:
     return ConstrainedProblem(name="AL2", A=base.A, b=base.b, C=np.ones((1, cols)), d=np.array([base.x_true.sum()]),
                               E=np.zeros((0, cols)), e=np.zeros(0), l=base.l, u=base.u, x0=base.x0, m=base.m,
                               x_true=base.x_true)
+
+
+# ---- dual SVM (quadratic form with one equality constraint) -------------------------------------
+
+@dataclass
+class SvmProblem:
+    """min 0.5*(a.y)^T K (a.y) - sum(a)  s.t.  y^T a = 0,  0 <= a <= c   (the paper's section "Dual SVM")."""
+    name: str
+    K: np.ndarray            # n x n Gaussian kernel matrix
+    y: np.ndarray            # labels in {-1, +1}
+    c: float
+    m: int
+    X: Optional[np.ndarray] = None
+
+    @property
+    def n(self) -> int:
+        return self.K.shape[0]
+
+
+def svm_dual(n: int, dim: int = 20, *, seed: int, gamma: float = 1.0, c: float = 1.0, separation: float = 1.0,
+             dtype=np.float64, m: int = 10) -> SvmProblem:
+    """Two Gaussian classes in `dim` dimensions (identity covariance scaled by 1/dim, means +-separation/2 along a
+    random unit direction), labels alternating; K_ij = exp(-gamma*||x_i - x_j||^2) as in the paper (gamma = 1,
+    c = 1), built in row chunks."""
+    rng = np.random.default_rng(seed)
+    y = np.where(np.arange(n) % 2 == 0, 1.0, -1.0)
+    direction = rng.standard_normal(dim)
+    direction /= np.linalg.norm(direction)
+    X = rng.standard_normal((n, dim)) / math.sqrt(dim) + 0.5 * separation * y[:, None] * direction[None, :]
+    sq = (X * X).sum(1)
+    K = np.empty((n, n), dtype=dtype)
+    chunk = max(1, (128 << 20) // (n * 8))
+    for r0 in range(0, n, chunk):
+        r1 = min(n, r0 + chunk)
+        d2 = sq[r0:r1, None] + sq[None, :] - 2.0 * (X[r0:r1] @ X.T)
+        np.maximum(d2, 0.0, out=d2)
+        K[r0:r1] = np.exp(-gamma * d2)
+    K = 0.5 * (K + K.T) if n <= 4096 else K                  # exact symmetry (large n: symmetric up to rounding of the products)
+    return SvmProblem(name="svm_dual", K=K, y=y, c=c, m=m, X=X)
