@@ -18,6 +18,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -31,6 +32,7 @@ HBM_PEAK_GBS = 8000.0
 
 AL_WORKLOADS = {
     "AL2": "augmented Lagrangian: NNLS 20000x5000 fp64 (the C2 data) with the budget constraint sum(x) = sum(x*), m=10",
+    "SVM": "augmented Lagrangian: dual SVM, Gaussian kernel matrix 10000x10000 fp64 (gamma=1, c=1), y^T a = 0, m=10",
 }
 
 WORKLOADS = {
@@ -99,10 +101,74 @@ def calibration_copy(args, torch, dev, out) -> None:
     del src, dst
 
 
+def bench_svm(args, L, workloads, np, torch, dev, oracle) -> int:
+    """Whole runs of Algorithm 4 on the dual SVM (quadratic form + one equality row); a "step" is one iteration of
+    the box solver inside it."""
+    t_gen = time.perf_counter()
+    n = max(64, int(round(10000 * args.scale)))
+    sp = workloads.svm_dual(n, 20, seed=3001, separation=2.0)   # well-separated classes: a few hundred support vectors
+    t_gen = time.perf_counter() - t_gen
+    tol, ctol = 1e-6 * math.sqrt(n), 1e-8                  # gradient at a = 0 is -1: ||g0|| = sqrt(n)
+    K_d, y_d = torch.from_numpy(sp.K).to(dev), torch.from_numpy(sp.y).to(dev)
+    lin = torch.full((n,), -1.0, dtype=torch.float64, device=dev)
+    zero, upper = torch.zeros(n, dtype=torch.float64, device=dev), torch.full((n,), sp.c, dtype=torch.float64, device=dev)
+    al = L.AuglagRows(L.OBJ_QP, K_d, lin, y_d[None, :].contiguous(), torch.zeros(1, dtype=torch.float64, device=dev), zero,
+                      upper, sp.m, sign=y_d, options=L.default_options(tol=tol, max_iter=5000), ctol=ctol, max_outer=200)
+    al.solve(zero)                                          # untimed
+    al.inner_apass_timing(2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    info = al.solve(zero)
+    torch.cuda.synchronize()
+    t_run = time.perf_counter() - t0
+    al.inner_apass_timing(0)
+    n_launch, apass_ms, bytes_per_launch = al.inner_apass_timing()
+    a = al.x().cpu().numpy()
+    lam = al.lam().cpu().numpy()
+    dec = sp.K @ (a * sp.y) + lam[0]
+    free = (a > 1e-6) & (a < sp.c - 1e-6)
+    apass_avg_ms = apass_ms / max(1, n_launch)
+    achieved = bytes_per_launch / (apass_avg_ms * 1e-3) / 1e9 if apass_avg_ms > 0 else 0.0
+    out = {
+        "metric": METRIC, "value": info.inner_iters / t_run, "unit": "iterations/s", "n_gpus": 1,
+        "steps": int(info.inner_iters), "warmup": 0, "ms_per_step": 1e3 * t_run / max(1, info.inner_iters),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{args.config}: {AL_WORKLOADS[args.config]}" + (f" (scaled x{args.scale})" if args.scale != 1.0 else ""),
+                   "rows": n, "cols": n, "n_eq": 1, "m": sp.m, "inner_tol_abs": tol, "ctol": ctol},
+        "time_to_solution_ms": 1e3 * t_run, "outer_iterations": int(info.outer),
+        "kkt": {"status": int(info.status), "violation": float(info.violation), "rho": float(info.rho), "f": float(info.f),
+                "bias": float(lam[0]), "support_vectors": int((a > 1e-9).sum()), "free_support_vectors": int(free.sum()),
+                "max_margin_error_free_sv": float(np.abs(sp.y[free] * dec[free] - 1.0).max()) if free.any() else 0.0,
+                "training_accuracy": float(np.mean(np.sign(dec) == sp.y)),
+                "feasible_box": bool(np.all(a >= 0) and np.all(a <= sp.c))},
+        "roofline": {"bound": "hbm", "kernel": "row-product kernel (t = K (y.p), one read of the symmetric matrix per iteration)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "bytes_per_launch": bytes_per_launch, "avg_launch_ms": apass_avg_ms, "launches_timed": n_launch,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "two_pass"))},
+        "gen_seconds": t_gen,
+    }
+    al.close()
+    calibration_copy(args, torch, dev, out)
+    if args.cpu_budget > 0:
+        obj = oracle.Objective(oracle.QP, sp.K, -np.ones(n), sign=sp.y).set_constraints(sp.y[None, :], [0.0])
+        t0 = time.perf_counter()
+        _, _, _, oi = oracle.auglag_solve(obj, np.zeros(n), np.full(n, sp.c), np.zeros(n), sp.m,
+                                          oracle.default_options(tol=tol, max_iter=8), ctol=ctol, max_outer=1)
+        el = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": oi.inner_iters / el, "unit": "iterations/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {oi.inner_iters} box-solver iterations of the first outer iteration, {el:.1f} s"}
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
     """Whole runs of Algorithm 4 (augmented Lagrangian) on a constrained workload: a "step" is one iteration of
     the box solver inside it; `steps` is the number of such iterations one run needs (the flag is ignored)."""
     import oracle
+    if args.config == "SVM":
+        return bench_svm(args, L, workloads, np, torch, dev, oracle)
     t_gen = time.perf_counter()
     cp = workloads.constrained_config(args.config, scale=args.scale)
     t_gen = time.perf_counter() - t_gen

@@ -217,7 +217,8 @@ void enqueue_eval(lbfgsb_solver* s, int check_status) {
     if (qp) {
         // symmetric matrix: the gradient needs the row products only
         TimedSlot ts(s);
-        launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
+        if (s->use_fused) launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
+        else launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
     } else if (s->use_fused) {
         TimedSlot ts(s);
         launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
@@ -246,7 +247,11 @@ void enqueue_step(lbfgsb_solver* s) {
         launch_extra_rows(s->dm, s->bf, s->obj.extra_rows, s->obj.extra_target, s->obj.extra_weight, 0, s->stream);
     if (s->dm.kind == LBFGSB_OBJ_QP) {
         a.mode = kRowQpDir;
-        { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
+        {
+            TimedSlot ts(s);
+            if (s->use_fused) launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
+            else launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
+        }
         launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->obj.sign, s->stream);
     } else if (quad) {
         a.mode = kRowDir;
@@ -356,7 +361,6 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
             return fail(LBFGSB_E_HIP, "preparing the fused A pass: %s", hipGetErrorString(fe));
         }
     }
-    if (s->dm.kind == LBFGSB_OBJ_QP) s->use_fused = 0;   // one product with the symmetric matrix per iteration: the row kernel alone
     s->ge.w_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemvt_row_blocks;
     s->ge.loss_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemv_blocks;
 

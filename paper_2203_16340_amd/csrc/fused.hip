@@ -18,6 +18,7 @@ namespace {
 struct Variant {
     int dtype;          // LBFGSB_F64 / LBFGSB_F32
     int logistic;       // 1: the kernel instantiated for the logistic row operations, 0: for the quadratic ones
+    int trans;          // 1: with the transposed accumulation, 0: row products only (quadratic form, symmetric matrix)
     int nt, kc, r;      // threads, 16-byte chunks per thread and row, rows per stage
     int wgs_per_cu;     // workgroups per compute unit the launch is sized for
     const void* kernel; // for hipFuncSetAttribute
@@ -25,18 +26,21 @@ struct Variant {
     size_t (*lds)(int64_t cols);
 };
 
-template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI, int KR>
+template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI, int KR, bool TRANS>
 void launch_variant(const Dims& dm, int64_t rows_per_wg, int blocks, size_t lds, const Buffers& bf, const APassArgs& a,
                     hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-    hipExtLaunchKernelGGL((ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, LOGI, KR>), dim3(blocks), dim3(NT), lds, st, ev0, ev1,
+    hipExtLaunchKernelGGL((ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, LOGI, KR, TRANS>), dim3(blocks), dim3(NT), lds, st, ev0, ev1,
                           0, (const T*)a.A, dm.ld, dm.rows, dm.cols, rows_per_wg, a, bf.scal, bf.row, bf.t, bf.wpart,
                           bf.losspart);
 }
 
-#define LB_VARIANT_KR(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, KR)                                                  \
-    {dt, LOGI, NT, (KCU) * (U), R, WGS, (const void*)ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0, KR>,   \
-     launch_variant<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0, KR>, ring::lds_bytes<T, NT, (KCU) * (U), KR, R>}
-#define LB_VARIANT(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS) LB_VARIANT_KR(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, 0)
+#define LB_VARIANT_FULL(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, KR, TRANS)                                                \
+    {dt, LOGI, TRANS, NT, (KCU) * (U), R, WGS,                                                                              \
+     (const void*)ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0, KR, (TRANS) != 0>,                               \
+     launch_variant<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0, KR, (TRANS) != 0>, ring::lds_bytes<T, NT, (KCU) * (U), KR, R>}
+#define LB_VARIANT_KR(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, KR) LB_VARIANT_FULL(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, KR, 1)
+#define LB_VARIANT(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS) LB_VARIANT_FULL(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, 0, 1)
+#define LB_VARIANT_ROWS(dt, T, NT, KCU, U, R, NB, WPE, WGS) LB_VARIANT_FULL(dt, 0, T, NT, KCU, U, R, NB, WPE, WGS, 0, 0)
 
 // Ordered by capacity within a (matrix type, objective family) group: the first variant of the group
 // whose NT*KC*VEC columns cover a row and whose LDS need (v for every column) fits is used.  The
@@ -59,6 +63,15 @@ const Variant kVariants[] = {
     LB_VARIANT(LBFGSB_F32, 1, float, 256, 5, 1, 1, 2, 2, 2),     // cols <=  5120
     LB_VARIANT(LBFGSB_F32, 1, float, 512, 5, 1, 1, 2, 2, 1),     // cols <= 10240
     LB_VARIANT(LBFGSB_F32, 1, float, 512, 10, 1, 1, 1, 2, 1),    // cols <= 20480 (LDS: <= 20459)
+    // row products only: no accumulators of w, so the ring is deeper
+    LB_VARIANT_ROWS(LBFGSB_F64, double, 256, 2, 1, 4, 8, 4, 4),  // cols <=  1024
+    LB_VARIANT_ROWS(LBFGSB_F64, double, 512, 5, 1, 2, 8, 2, 1),  // cols <=  5120
+    LB_VARIANT_ROWS(LBFGSB_F64, double, 512, 10, 1, 1, 4, 2, 1), // cols <= 10240
+    LB_VARIANT_ROWS(LBFGSB_F64, double, 512, 20, 1, 1, 2, 2, 1), // cols <= 20480 (LDS: <= 20459)
+    LB_VARIANT_ROWS(LBFGSB_F32, float, 256, 1, 1, 4, 8, 4, 4),   // cols <=  1024
+    LB_VARIANT_ROWS(LBFGSB_F32, float, 256, 5, 1, 2, 8, 2, 2),   // cols <=  5120
+    LB_VARIANT_ROWS(LBFGSB_F32, float, 512, 5, 1, 2, 8, 2, 1),   // cols <= 10240
+    LB_VARIANT_ROWS(LBFGSB_F32, float, 512, 10, 1, 1, 4, 2, 1),  // cols <= 20480 (LDS: <= 20459)
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr size_t kLdsPerWorkgroup = 160 * 1024;   // gfx950
@@ -90,12 +103,13 @@ int64_t rows_per_wg_for(const Dims& dm, const Variant& v) {
 bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks) {
     *variant = -1;
     *blocks = 0;
-    if (dm.kind == LBFGSB_OBJ_QP) return false;   // no transposed product: the row kernel alone serves it
     const int vec = dm.dtype == LBFGSB_F32 ? 4 : 2;
     if ((uintptr_t)A % 16 != 0 || dm.cols % vec != 0 || dm.ld % vec != 0) return false;   // needs 16-byte loads
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant& v = kVariants[i];
-        if (v.dtype != dm.dtype || v.logistic != (dm.kind == LBFGSB_OBJ_LOGISTIC_L2)) continue;
+        if (v.dtype != dm.dtype || v.logistic != (dm.kind == LBFGSB_OBJ_LOGISTIC_L2) ||
+            v.trans != (dm.kind != LBFGSB_OBJ_QP))
+            continue;
         if ((int64_t)v.nt * v.kc * vec < dm.cols) continue;
         if (v.lds(dm.cols) > kLdsPerWorkgroup) continue;
         const int64_t rpw = rows_per_wg_for(dm, v);

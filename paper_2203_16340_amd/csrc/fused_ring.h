@@ -61,8 +61,12 @@ template <bool LOGI>
 __device__ __forceinline__ void row_eval(int mode, double u, double b, double z, double alpha0, double invn,
                                          double& psi, double& loss, double& keep) {
     if constexpr (!LOGI) {
-        // z carries the row's weight here (1 when the objective has none)
-        if (mode == kRowDir) {              // t = A p for the closed-form line search; w = A^T (weights * t)
+        // z carries the row's weight here (1 when the objective has none); in the quadratic-form modes the
+        // row's own entry of v (the row index is also a column index of the symmetric matrix)
+        if (mode == kRowQpEval || mode == kRowQpDir) {
+            psi = 0.0; keep = u;
+            loss = (mode == kRowQpEval ? 0.5 : 1.0) * z * u;
+        } else if (mode == kRowDir) {       // t = A p for the closed-form line search; w = A^T (weights * t)
             psi = z * u; loss = psi * u; keep = u;
         } else {                            // kRowLsqEval: r = A v - b; w = A^T (weights * r)
             const double res = u - b;
@@ -135,7 +139,7 @@ __device__ __forceinline__ void stage_row_op(const double* red, int lane, int wa
     if (!valid) { psil = 0.0; lossl = 0.0; }
     loss += lossl;
     if (valid && wave == 0) {
-        if (mode == kRowDir || mode == kRowLogiSpec) t[grow] = keep; else row[grow] = keep;
+        if (mode == kRowDir || mode == kRowLogiSpec || mode == kRowQpDir) t[grow] = keep; else row[grow] = keep;
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) psi[r] = lane_bcast(psil, r);
@@ -184,7 +188,9 @@ inline size_t lds_bytes(int64_t cols) {
     return ((size_t)lds_cols<T, NT, KC, KR>(cols) + kPad) * 8 + (size_t)2 * R * (NT / 64) * 8;
 }
 
-template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI, int KR = 0>
+// TRANS = false: the transposed accumulation is left out (quadratic form with a symmetric matrix: the row
+// products are all an iteration needs), and the registers it would take go to a deeper ring.
+template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI, int KR = 0, bool TRANS = true>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t cols, int64_t rows_per_wg, APassArgs a,
                   Scal* __restrict__ scal, double* __restrict__ row, double* __restrict__ t,
@@ -210,7 +216,7 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     const double *va, *vb;
     resolve_v(a, scal, cols, va, vb);
 
-    for (int c = tid; c < lcols; c += NT) vs[c] = vb ? va[c] - vb[c] : va[c];
+    for (int c = tid; c < lcols; c += NT) vs[c] = (vb ? va[c] - vb[c] : va[c]) * (a.vs ? a.vs[c] : 1.0);
     if (tid < kPad) vs[lcols + tid] = 0.0;
     double vreg[KR > 0 ? KR : 1][VEC];
 #pragma unroll
@@ -218,7 +224,7 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
             const int64_t c = (int64_t)((KL + k) * NT + tid) * VEC + j;
-            vreg[k][j] = c < cols ? (vb ? va[c] - vb[c] : va[c]) : 0.0;
+            vreg[k][j] = c < cols ? (vb ? va[c] - vb[c] : va[c]) * (a.vs ? a.vs[c] : 1.0) : 0.0;
         }
     }
 
@@ -228,9 +234,9 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     const int c0 = tid * VEC;
     constexpr int kStride = NT * VEC;
     const int icols = (int)cols;
-    double w[KC][VEC];
+    double w[TRANS ? KC : 1][VEC];
 #pragma unroll
-    for (int k = 0; k < KC; ++k)
+    for (int k = 0; k < (TRANS ? KC : 1); ++k)
 #pragma unroll
         for (int j = 0; j < VEC; ++j) w[k][j] = 0.0;
 
@@ -261,14 +267,23 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     // the vector loads of the ring, so waiting for one does not drain the rows in flight.
     typedef const double __attribute__((address_space(4))) * ConstD;
     const int mode = a.mode;
-    const bool need_b = mode != kRowDir, need_z = LOGI && mode == kRowLogiSpec;
+    const bool need_b = mode != kRowDir && mode != kRowQpEval && mode != kRowQpDir, need_z = LOGI && mode == kRowLogiSpec;
     auto read_rows = [&](double (&db)[R], double (&dz)[R], int64_t lr) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int64_t gr = r_begin + lr + r < r_end ? r_begin + lr + r : r_end - 1;
             db[r] = need_b ? *(ConstD)(uintptr_t)(a.b + gr) : 0.0;
-            if constexpr (LOGI) dz[r] = need_z ? *(ConstD)(uintptr_t)(row + gr) : 0.0;
-            else dz[r] = a.w ? *(ConstD)(uintptr_t)(a.w + gr) : 1.0;
+            if constexpr (LOGI) {
+                dz[r] = need_z ? *(ConstD)(uintptr_t)(row + gr) : 0.0;
+            } else if (mode == kRowQpEval || mode == kRowQpDir) {
+                // (v is not written by this kernel: the scalar reads are safe)
+                double vr = *(ConstD)(uintptr_t)(va + gr);
+                if (vb) vr -= *(ConstD)(uintptr_t)(vb + gr);
+                if (a.vs) vr *= *(ConstD)(uintptr_t)(a.vs + gr);
+                dz[r] = vr;
+            } else {
+                dz[r] = a.w ? *(ConstD)(uintptr_t)(a.w + gr) : 1.0;
+            }
         }
     };
     const double alpha0 = need_z ? fmin(1.0, scal->alpha_ub) : 0.0;   // first trial step of the line search
@@ -339,12 +354,13 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
                 const int r = q / U, j = q % U;
 #pragma unroll
                 for (int k = 0; k < KCU; ++k) {
+                    if constexpr (!TRANS) break;
                     const int kk = j * KCU + k;
                     forget(raw[slot][k]);                    // fp32 data is widened again here rather than kept widened across the barrier
                     double e[VEC];
                     widen(raw[slot][k], e);
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) w[kk][i] = fma(e[i], psi[r], w[kk][i]);
+                    for (int i = 0; i < VEC; ++i) w[TRANS ? kk : 0][i] = fma(e[i], psi[r], w[TRANS ? kk : 0][i]);
                 }
                 // the slot is free: refill it with the row fraction NB slots ahead.  The scheduling
                 // barriers keep the loads from being hoisted above the last use of the old contents
@@ -357,12 +373,14 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             par ^= 1;
         }
     }
-    double* out = wpart + (int64_t)blockIdx.x * cols + c0;
+    if constexpr (TRANS) {
+        double* out = wpart + (int64_t)blockIdx.x * cols + c0;
 #pragma unroll
-    for (int k = 0; k < KC; ++k) {
-        if (c0 + k * kStride < icols) {
+        for (int k = 0; k < KC; ++k) {
+            if (c0 + k * kStride < icols) {
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) out[k * kStride + j] = w[k][j];
+                for (int j = 0; j < VEC; ++j) out[k * kStride + j] = w[k][j];
+            }
         }
     }
     loss = wave_sum(loss);                                   // lanes 0..R-1 of a wave hold the row losses

@@ -353,7 +353,17 @@ __global__ __launch_bounds__(kBlock) void k_extra_rows(Dims dm, const double* __
     for (int r = 0; r < dm.n_extra; ++r) {
         double s[1] = {0.0};
         const double* er = E + (int64_t)r * dm.n;
-        for (int64_t i = tid; i < dm.n; i += kBlock) s[0] = fma(er[i], z[i], s[0]);
+        for (int64_t i0 = tid; i0 < dm.n; i0 += kBlock * 8) {   // 16 loads in flight per thread: the kernel is latency-bound
+            double ev[8], zv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int64_t i = i0 + (int64_t)k * kBlock;
+                ev[k] = i < dm.n ? er[i] : 0.0;
+                zv[k] = i < dm.n ? z[i] : 0.0;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) s[0] = fma(ev[k], zv[k], s[0]);
+        }
         block_sum<1, kWaves>(s, red);
         const double wr = weight ? weight[r] : 1.0;
         const double res = eval ? s[0] - target[r] : s[0];
@@ -364,10 +374,25 @@ __global__ __launch_bounds__(kBlock) void k_extra_rows(Dims dm, const double* __
         }
     }
     __syncthreads();
-    for (int64_t i = tid; i < dm.n; i += kBlock) {
-        double acc = 0.0;
-        for (int r = 0; r < dm.n_extra; ++r) acc = fma(coef[r], E[(int64_t)r * dm.n + i], acc);
-        wextra[i] = acc;
+    for (int64_t i0 = tid; i0 < dm.n; i0 += kBlock * 8) {
+        double acc[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] = 0.0;
+        for (int r = 0; r < dm.n_extra; ++r) {
+            double ev[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int64_t i = i0 + (int64_t)k * kBlock;
+                ev[k] = i < dm.n ? E[(int64_t)r * dm.n + i] : 0.0;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc[k] = fma(coef[r], ev[k], acc[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int64_t i = i0 + (int64_t)k * kBlock;
+            if (i < dm.n) wextra[i] = acc[k];
+        }
     }
     if (tid == 0) xres[dm.n_extra] = total;
 }
