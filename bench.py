@@ -56,6 +56,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("C4", "fused"): 1.624e9,      # profiles/c4_logistic_200000x2000_f32_fused_a_pass.md (algorithmic 1.6e9)
     ("C5", "fused"): 8.099e9,      # profiles/c5_nnls_100000x20000_f32_fused_a_pass.md    (algorithmic 8.0e9)
     ("AL2", "fused"): 8.371e8,     # profiles/al2_auglag_20001x5000_f64_fused_a_pass.md   (algorithmic 8.0004e8)
+    ("SVM", "fused"): 8.634e8,     # profiles/svm_dual_10000x10000_f64_row_products_pass.md (algorithmic 8.0e8)
 }
 
 
@@ -141,10 +142,10 @@ def bench_svm(args, L, workloads, np, torch, dev, oracle) -> int:
                 "max_margin_error_free_sv": float(np.abs(sp.y[free] * dec[free] - 1.0).max()) if free.any() else 0.0,
                 "training_accuracy": float(np.mean(np.sign(dec) == sp.y)),
                 "feasible_box": bool(np.all(a >= 0) and np.all(a <= sp.c))},
-        "roofline": {"bound": "hbm", "kernel": "row-product kernel (t = K (y.p), one read of the symmetric matrix per iteration)",
+        "roofline": {"bound": "hbm", "kernel": "row-products-only instantiation of the ring kernel (t = K (y.p), one read of the symmetric matrix per iteration)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": apass_avg_ms, "launches_timed": n_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "two_pass"))},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "fused"))},
         "gen_seconds": t_gen,
     }
     al.close()
