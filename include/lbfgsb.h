@@ -81,7 +81,7 @@ typedef struct {
 /* how the products with A are organised (results agree to rounding) */
 enum {
     LBFGSB_APASS_AUTO = 0,     /* fused single read of A when the shape allows it (16-byte aligned rows of at most
-                                  20459 columns; 10240 for an fp64 logistic matrix), else two passes */
+                                  20428 columns; 10240 for an fp64 logistic matrix), else two passes */
     LBFGSB_APASS_TWO_PASS = 1, /* t = A v, then w = A^T psi: A is read twice per evaluation and per iteration */
     LBFGSB_APASS_FUSED = 2     /* force the fused kernel; lbfgsb_create fails if the shape does not fit.  For the
                                   logistic objective an iteration's single read yields t = A p and A^T psi of the first

@@ -49,29 +49,29 @@ const Variant kVariants[] = {
     LB_VARIANT(LBFGSB_F64, 0, double, 256, 2, 1, 2, 4, 4, 4),    // cols <=  1024
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 5, 1, 2, 4, 2, 1),    // cols <=  5120
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 10, 1, 1, 2, 2, 1),   // cols <= 10240
-    LB_VARIANT(LBFGSB_F64, 0, double, 512, 20, 1, 1, 1, 2, 1),   // cols <= 20480 (LDS: <= 20459)
+    LB_VARIANT(LBFGSB_F64, 0, double, 512, 20, 1, 1, 1, 2, 1),   // cols <= 20480 (LDS: <= 20428)
     LB_VARIANT_KR(LBFGSB_F64, 0, double, 512, 22, 1, 1, 1, 2, 1, 3),   // cols <= 22528, v of the last 3 chunks in registers
     LB_VARIANT_KR(LBFGSB_F64, 0, double, 512, 24, 1, 1, 1, 2, 1, 5),   // cols <= 24576, v of the last 5 chunks in registers
     LB_VARIANT(LBFGSB_F32, 0, float, 256, 1, 1, 2, 4, 4, 4),     // cols <=  1024
     LB_VARIANT(LBFGSB_F32, 0, float, 256, 5, 1, 1, 2, 2, 2),     // cols <=  5120
     LB_VARIANT(LBFGSB_F32, 0, float, 512, 5, 1, 2, 4, 2, 1),     // cols <= 10240
-    LB_VARIANT(LBFGSB_F32, 0, float, 512, 10, 1, 1, 2, 2, 1),    // cols <= 20480 (LDS: <= 20459)
+    LB_VARIANT(LBFGSB_F32, 0, float, 512, 10, 1, 1, 2, 2, 1),    // cols <= 20480 (LDS: <= 20428)
     LB_VARIANT(LBFGSB_F64, 1, double, 256, 2, 1, 4, 8, 2, 2),    // cols <=  1024
     LB_VARIANT(LBFGSB_F64, 1, double, 512, 5, 1, 1, 2, 2, 1),    // cols <=  5120
     LB_VARIANT(LBFGSB_F64, 1, double, 512, 10, 1, 1, 1, 2, 1),   // cols <= 10240
     LB_VARIANT(LBFGSB_F32, 1, float, 256, 2, 1, 4, 8, 2, 2),     // cols <=  2048
     LB_VARIANT(LBFGSB_F32, 1, float, 256, 5, 1, 1, 2, 2, 2),     // cols <=  5120
     LB_VARIANT(LBFGSB_F32, 1, float, 512, 5, 1, 1, 2, 2, 1),     // cols <= 10240
-    LB_VARIANT(LBFGSB_F32, 1, float, 512, 10, 1, 1, 1, 2, 1),    // cols <= 20480 (LDS: <= 20459)
+    LB_VARIANT(LBFGSB_F32, 1, float, 512, 10, 1, 1, 1, 2, 1),    // cols <= 20480 (LDS: <= 20428)
     // row products only: no accumulators of w, so the ring is deeper
     LB_VARIANT_ROWS(LBFGSB_F64, double, 256, 2, 1, 4, 8, 4, 4),  // cols <=  1024
     LB_VARIANT_ROWS(LBFGSB_F64, double, 512, 5, 1, 2, 8, 2, 1),  // cols <=  5120
     LB_VARIANT_ROWS(LBFGSB_F64, double, 512, 10, 1, 1, 4, 2, 1), // cols <= 10240
-    LB_VARIANT_ROWS(LBFGSB_F64, double, 512, 20, 1, 1, 2, 2, 1), // cols <= 20480 (LDS: <= 20459)
+    LB_VARIANT_ROWS(LBFGSB_F64, double, 512, 20, 1, 1, 2, 2, 1), // cols <= 20480 (LDS: <= 20428)
     LB_VARIANT_ROWS(LBFGSB_F32, float, 256, 1, 1, 4, 8, 4, 4),   // cols <=  1024
     LB_VARIANT_ROWS(LBFGSB_F32, float, 256, 5, 1, 2, 8, 2, 2),   // cols <=  5120
     LB_VARIANT_ROWS(LBFGSB_F32, float, 512, 5, 1, 2, 8, 2, 1),   // cols <= 10240
-    LB_VARIANT_ROWS(LBFGSB_F32, float, 512, 10, 1, 1, 4, 2, 1),  // cols <= 20480 (LDS: <= 20459)
+    LB_VARIANT_ROWS(LBFGSB_F32, float, 512, 10, 1, 1, 4, 2, 1),  // cols <= 20480 (LDS: <= 20428)
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr size_t kLdsPerWorkgroup = 160 * 1024;   // gfx950
@@ -111,7 +111,7 @@ bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks) {
             v.trans != (dm.kind != LBFGSB_OBJ_QP))
             continue;
         if ((int64_t)v.nt * v.kc * vec < dm.cols) continue;
-        if (v.lds(dm.cols) > kLdsPerWorkgroup) continue;
+        if (v.lds(dm.cols) > kLdsPerWorkgroup - 256) continue;   // (a few bytes of static LDS come on top)
         const int64_t rpw = rows_per_wg_for(dm, v);
         *variant = i;
         *blocks = (int)((dm.rows + rpw - 1) / rpw);
@@ -120,10 +120,17 @@ bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks) {
     return false;
 }
 
-// The kernels use more dynamic LDS than the default limit of a launch: raise it once per solver.
+// The kernels use more dynamic LDS than the default limit of a launch.  The limit is a property of the
+// kernel, not of a solver, and several solvers of different widths may share a variant: it is raised to the
+// most the variant can ever ask for (its widest row, capped by what a workgroup can have).
 hipError_t fused_prepare(const Dims& dm, const Geometry& ge) {
     const Variant& v = kVariants[ge.fused_variant];
-    return hipFuncSetAttribute(v.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds(dm.cols));
+    const int vec = v.dtype == LBFGSB_F32 ? 4 : 2;
+    size_t most = v.lds((int64_t)v.nt * v.kc * vec);
+    const size_t cap = kLdsPerWorkgroup - 256;   // the kernels also hold a few bytes of static LDS
+    if (most > cap) most = cap;
+    if (v.lds(dm.cols) > most) most = v.lds(dm.cols);
+    return hipFuncSetAttribute(v.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
 }
 
 void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,

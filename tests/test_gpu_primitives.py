@@ -37,7 +37,7 @@ def _solver_or_skip(*args, **kw):
 FG_SHAPES = [
     # rows, cols: several row groups / column tiles plus ragged tails; odd cols force scalar loads
     (1, 1), (3, 2), (37, 5), (200, 100), (1037, 517), (1037, 520), (777, 2048), (4099, 1030), (300, 5000),
-    # wide rows: every variant of the fused pass up to its widest (v partly in registers beyond 20459 columns;
+    # wide rows: every variant of the fused pass up to its widest (v partly in registers beyond 20428 columns;
     # wider than 24576, or 20480 for fp32, only the two-pass kernels take the shape)
     (523, 9000), (300, 20000), (261, 20456), (259, 22000), (130, 24576), (67, 24580),
 ]
@@ -70,6 +70,25 @@ def test_fg_parity(rows, cols, kind, dtype, a_pass):
     # fp32 storage still accumulates in fp64: far tighter than the stated bound
     assert rel_err(g.cpu().numpy(), g_ref) <= 1e-11
     s.close()
+
+
+def test_solvers_of_different_widths_share_a_kernel_variant():
+    """The dynamic-LDS limit is a property of the kernel: creating a narrower solver that uses the same
+    variant must not shrink what the wider solver's launches may ask for."""
+    rng = np.random.default_rng(3)
+    wide_A, wide_b = rng.standard_normal((40, 20000)), rng.standard_normal(40)
+    narrow_A, narrow_b = rng.standard_normal((40, 11000)), rng.standard_normal(40)
+    inf = lambda n: (np.full(n, -np.inf), np.full(n, np.inf))
+    wide = make_solver(L.OBJ_LSQ, wide_A, wide_b, *inf(20000), 3, a_pass=L.APASS_FUSED)
+    narrow = make_solver(L.OBJ_LSQ, narrow_A, narrow_b, *inf(11000), 3, a_pass=L.APASS_FUSED)
+    for s, A, b in ((wide, wide_A, wide_b), (narrow, narrow_A, narrow_b), (wide, wide_A, wide_b)):
+        x = rng.standard_normal(A.shape[1])
+        f, g = s.dbg_fg(to_dev(x))
+        f_ref, g_ref = oracle.fg(oracle.Objective(oracle.LSQ, A, b), x)
+        assert abs(f - f_ref) <= 1e-12 * abs(f_ref)
+        assert rel_err(g.cpu().numpy(), g_ref) <= 1e-12
+    wide.close()
+    narrow.close()
 
 
 @pytest.mark.parametrize("a_pass", [L.APASS_TWO_PASS, L.APASS_FUSED], ids=["two_pass", "fused"])
