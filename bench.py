@@ -102,7 +102,7 @@ def calibration_copy(args, torch, dev, out) -> None:
     del src, dst
 
 
-def bench_svm(args, L, workloads, np, torch, dev, oracle) -> int:
+def bench_svm(args, L, workloads, np, torch, dev) -> int:
     """Whole runs of Algorithm 4 on the dual SVM (quadratic form + one equality row); a "step" is one iteration of
     the box solver inside it."""
     t_gen = time.perf_counter()
@@ -151,6 +151,7 @@ def bench_svm(args, L, workloads, np, torch, dev, oracle) -> int:
     al.close()
     calibration_copy(args, torch, dev, out)
     if args.cpu_budget > 0:
+        import oracle   # the CPU-baseline leg is the only part of the benchmark that touches the oracle
         obj = oracle.Objective(oracle.QP, sp.K, -np.ones(n), sign=sp.y).set_constraints(sp.y[None, :], [0.0])
         t0 = time.perf_counter()
         _, _, _, oi = oracle.auglag_solve(obj, np.zeros(n), np.full(n, sp.c), np.zeros(n), sp.m,
@@ -167,9 +168,8 @@ def bench_svm(args, L, workloads, np, torch, dev, oracle) -> int:
 def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
     """Whole runs of Algorithm 4 (augmented Lagrangian) on a constrained workload: a "step" is one iteration of
     the box solver inside it; `steps` is the number of such iterations one run needs (the flag is ignored)."""
-    import oracle
     if args.config == "SVM":
-        return bench_svm(args, L, workloads, np, torch, dev, oracle)
+        return bench_svm(args, L, workloads, np, torch, dev)
     t_gen = time.perf_counter()
     cp = workloads.constrained_config(args.config, scale=args.scale)
     t_gen = time.perf_counter() - t_gen
@@ -217,6 +217,7 @@ def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
     al.close()
     calibration_copy(args, torch, dev, out)
     if args.cpu_budget > 0:
+        import oracle   # the CPU-baseline leg is the only part of the benchmark that touches the oracle
         obj = oracle.Objective(oracle.LSQ, cp.A, cp.b).set_constraints(cp.C, cp.d, cp.E, cp.e)
         t0 = time.perf_counter()
         _, _, _, oi = oracle.auglag_solve(obj, cp.l, cp.u, cp.x0, cp.m, oracle.default_options(tol=tol), ctol=ctol, max_outer=1)

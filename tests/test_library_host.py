@@ -44,6 +44,42 @@ def test_struct_layouts_match_the_header(tmp_path):
                    L.Options.a_pass.offset, L.Info.n_fixed.offset, L.Info.gp.offset]
 
 
+def test_auglag_struct_layouts_and_argument_checks(tmp_path):
+    import subprocess
+    src = tmp_path / "sz2.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "lbfgsb.h"\n'
+        'int main(void){printf("%zu %zu %zu %zu %zu\\n", sizeof(lbfgsb_auglag_options), sizeof(lbfgsb_auglag_info),'
+        ' offsetof(lbfgsb_auglag_info, violation), offsetof(lbfgsb_objective, n_extra),'
+        ' offsetof(lbfgsb_objective, extra_weight)); return 0;}\n')
+    exe = tmp_path / "sz2"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    got = [int(t) for t in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [C.sizeof(L.AuglagOptions), C.sizeof(L.AuglagInfo), L.AuglagInfo.violation.offset,
+                   L.Objective.n_extra.offset, L.Objective.extra_weight.offset]
+    lib = L.lib()
+    ao = L.AuglagOptions()
+    lib.lbfgsb_auglag_default_options(C.byref(ao))
+    assert (ao.rho0, ao.ctol, ao.max_outer) == (1.0, 1e-8, 100)
+    o = L.default_options()
+    stacked = _obj(rows=203, cols=100)
+    plain = lib.lbfgsb_workspace_bytes(100, 5, C.byref(stacked), C.byref(o))
+    assert lib.lbfgsb_auglag_workspace_bytes(100, 5, C.byref(stacked), 3, C.byref(o)) > plain
+    assert lib.lbfgsb_auglag_workspace_bytes(100, 5, C.byref(stacked), 203, C.byref(o)) == 0      # no data row left
+    assert lib.lbfgsb_auglag_workspace_bytes(100, 5, C.byref(_obj(kind=2, rows=203)), 3, C.byref(o)) == 0
+    assert lib.lbfgsb_auglag_rows_workspace_bytes(100, 5, C.byref(_obj()), 3, C.byref(o)) > plain - 203 * 8 * 3
+    assert lib.lbfgsb_auglag_rows_workspace_bytes(100, 5, C.byref(_obj()), 65, C.byref(o)) == 0   # at most 64 separate rows
+    assert lib.lbfgsb_auglag_rows_workspace_bytes(100, 5, C.byref(_obj(kind=2)), 1, C.byref(o)) == 0
+    # the quadratic form needs a square matrix
+    assert lib.lbfgsb_workspace_bytes(100, 5, C.byref(_obj(kind=3, rows=100, cols=100)), C.byref(o)) > 0
+    assert lib.lbfgsb_workspace_bytes(100, 5, C.byref(_obj(kind=3, rows=200, cols=100)), C.byref(o)) == 0
+    h = C.c_void_p()
+    assert lib.lbfgsb_auglag_create(C.byref(h), 100, 5, 0x3000, 0x4000, C.byref(stacked), -1, C.byref(o), C.byref(ao),
+                                    0x10000, 1 << 24, None) == L.E_INVALID_ARG
+    assert lib.lbfgsb_auglag_solve(None, None, None) == L.E_INVALID_ARG
+    lib.lbfgsb_auglag_destroy(None)
+
+
 def test_default_options():
     o = L.default_options()
     assert (o.eps, o.armijo_c1, o.backtrack, o.max_backtracks) == (1e-10, 1e-4, 0.5, 60)
