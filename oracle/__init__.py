@@ -21,14 +21,14 @@ _SRC = os.path.join(_HERE, "lbfgsb_oracle.c")
 _LIB = os.path.join(_HERE, "liblbfgsb_oracle.so")
 
 RUNNING, CONVERGED, MAX_ITER, LINESEARCH_FAILED = 0, 1, 2, 3
-LSQ, LSQ_L1SPLIT, LOGISTIC_L2, QP = 0, 1, 2, 3
+LSQ, LSQ_L1SPLIT, LOGISTIC_L2, QP, OT_GAUSS, OT_ENTROPY = 0, 1, 2, 3, 4, 5
 F64, F32 = 0, 1
 
 
 class _Constraints(C.Structure):
     _fields_ = [("n_eq", C.c_int64), ("n_in", C.c_int64), ("C", C.c_void_p), ("d", C.c_void_p),
                 ("E", C.c_void_p), ("e", C.c_void_p), ("lam", C.c_void_p), ("mu", C.c_void_p),
-                ("rho", C.c_double)]
+                ("rho", C.c_double), ("marginals", C.c_int)]
 
 
 class _Objective(C.Structure):
@@ -144,16 +144,19 @@ def default_options(**overrides) -> Options:
 class Objective:
     """Keeps the numpy arrays alive next to the C struct that points into them."""
 
-    def __init__(self, kind: int, A: np.ndarray, b: np.ndarray, lam: float = 0.0, mu: float = 0.0, sign=None):
+    def __init__(self, kind: int, A: np.ndarray, b: Optional[np.ndarray] = None, lam: float = 0.0, mu: float = 0.0,
+                 sign=None):
         if A.dtype not in (np.float64, np.float32) or A.ndim != 2:
             raise TypeError("A must be a 2-d float64 or float32 array")
         if A.strides[1] != A.itemsize or A.strides[0] % A.itemsize:
             A = np.ascontiguousarray(A)
         self.A = A
-        self.b = _f64(b)
+        self.transport = kind in (OT_GAUSS, OT_ENTROPY)   # A is the cost matrix M, b is not read
+        self.b = _f64(b) if b is not None else np.zeros(A.shape[0])
         if self.b.shape != (A.shape[0],):
             raise ValueError("b must have one entry per row of A")
         self.kind = kind
+        self.nrow = 0 if self.transport else A.shape[0]   # objective's own entries of the row vector
         self.c = _Objective(kind, F64 if A.dtype == np.float64 else F32, A.shape[0], A.shape[1],
                             A.strides[0] // A.itemsize, _ptr(A), _ptr(self.b), float(lam), float(mu), None, None)
         self.con = None
@@ -170,6 +173,7 @@ class Objective:
         """Attach linear constraints C x = d, E x <= e and a multiplier state (Eq. (augLag)): fg() then
         evaluates the augmented Lagrangian.  The multiplier arrays are kept (and updated in place by
         auglag_solve) as self.lam / self.mu."""
+        assert not self.transport, "the transport kinds take set_marginals()"
         cols = self.A.shape[1]
         self.C_eq = _f64(C_eq).reshape(-1, cols) if C_eq is not None else np.zeros((0, cols))
         self.E_in = _f64(E_in).reshape(-1, cols) if E_in is not None else np.zeros((0, cols))
@@ -179,7 +183,20 @@ class Objective:
         self.lam = _f64(lam).copy() if lam is not None else np.zeros(self.C_eq.shape[0])
         self.mu = _f64(mu).copy() if mu is not None else np.zeros(self.E_in.shape[0])
         self.con = _Constraints(self.C_eq.shape[0], self.E_in.shape[0], _ptr(self.C_eq), _ptr(self.d),
-                                _ptr(self.E_in), _ptr(self.e), _ptr(self.lam), _ptr(self.mu), float(rho))
+                                _ptr(self.E_in), _ptr(self.e), _ptr(self.lam), _ptr(self.mu), float(rho), 0)
+        self.c.con = C.cast(C.pointer(self.con), C.c_void_p)
+        return self
+
+    def set_marginals(self, u, v, lam=None, rho: float = 1.0):
+        """Transport kinds: attach the marginal constraints P 1 = u, P^T 1 = v (rows + cols equality rows, in
+        that order) and a multiplier state; fg() then evaluates the augmented Lagrangian of Eq. (augLag)."""
+        assert self.transport
+        rows, cols = self.A.shape
+        self.d = np.concatenate([_f64(u).reshape(-1), _f64(v).reshape(-1)])
+        assert self.d.shape == (rows + cols,)
+        self.lam = _f64(lam).copy() if lam is not None else np.zeros(rows + cols)
+        self.mu = np.zeros(0)
+        self.con = _Constraints(rows + cols, 0, None, _ptr(self.d), None, None, _ptr(self.lam), None, float(rho), 1)
         self.c.con = C.cast(C.pointer(self.con), C.c_void_p)
         return self
 
@@ -195,7 +212,7 @@ def fg(obj: Objective, x, want_rowvec: bool = False):
     assert x.shape == (obj.n,)
     g = np.empty(obj.n)
     ncon = (obj.con.n_eq + obj.con.n_in) if obj.con is not None else 0
-    rv = np.empty(obj.A.shape[0] + ncon) if want_rowvec else None
+    rv = np.empty(obj.nrow + ncon) if want_rowvec else None
     f = load().orc_fg(C.byref(obj.c), _ptr(x), _ptr(g), _ptr(rv))
     return (f, g, rv) if want_rowvec else (f, g)
 
@@ -210,7 +227,7 @@ def delta_f(obj: Objective, x, xt, row) -> float:
     """f(xt) - f(x) from the cancellation-free row-wise identity; row = residuals/margins at x."""
     x, xt, row = _f64(x), _f64(xt), _f64(row)
     ncon = (obj.con.n_eq + obj.con.n_in) if obj.con is not None else 0
-    assert x.shape == (obj.n,) and xt.shape == (obj.n,) and row.shape == (obj.A.shape[0] + ncon,)
+    assert x.shape == (obj.n,) and xt.shape == (obj.n,) and row.shape == (obj.nrow + ncon,)
     return load().orc_delta_f(C.byref(obj.c), _ptr(x), _ptr(xt), _ptr(row))
 
 
@@ -328,7 +345,7 @@ def solve_problem(prob, **option_overrides) -> Result:
 
 def auglag_solve(obj: Objective, l, u, x0, m: int, options: Optional[Options] = None, rho0: float = 1.0,
                  ctol: float = 1e-8, max_outer: int = 100):
-    """Algorithm 4 on a least-squares objective with constraints attached by set_constraints().
+    """Algorithm 4 on an objective with constraints attached by set_constraints() / set_marginals().
     Returns (x, lambda, mu, AuglagInfo)."""
     assert obj.con is not None
     x = _f64(x0).copy()

@@ -18,6 +18,10 @@
  *     Framework" and appendix) for LINEAR constraints h(x) = C x - d = 0 and
  *     g(x) = E x - e <= 0 on top of the least-squares or quadratic-form objective
  *                                                                     -> orc_fg, orc_auglag_solve
+ *   - the regularised optimal-transport objective of the section "Joint Probability
+ *     Distribution", <M,P> + lambda r(P) over a matrix P >= 0 stored row by row, r the Gaussian
+ *     (0.5 sum P^2) or the entropy (sum P log P) regulariser, with the marginal constraints
+ *     P 1 = u, P^T 1 = v as the equality constraints of Algorithm 4      -> orc_fg, orc_auglag_solve
  *
  * Nothing here is blocked, fused or reordered: every objective value and gradient is
  * evaluated from scratch at every trial point, the two-loop recursion is the literal
@@ -69,7 +73,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORC_LSQ = 0, ORC_LSQ_L1SPLIT = 1, ORC_LOGISTIC_L2 = 2, ORC_QP = 3 };
+enum { ORC_LSQ = 0, ORC_LSQ_L1SPLIT = 1, ORC_LOGISTIC_L2 = 2, ORC_QP = 3, ORC_OT_GAUSS = 4, ORC_OT_ENTROPY = 5 };
 enum { ORC_F64 = 0, ORC_F32 = 1 };
 enum { ORC_RUNNING = 0, ORC_CONVERGED = 1, ORC_MAX_ITER = 2, ORC_LINESEARCH_FAILED = 3 };
 
@@ -82,6 +86,8 @@ typedef struct {
     const double *C, *d, *E, *e;
     double *lambda, *mu;   /* n_eq / n_in entries, updated by orc_auglag_solve */
     double rho;
+    int marginals;         /* transport kinds: the n_eq = rows + cols equality constraints are the marginals
+                              P 1 = d[0..rows), P^T 1 = d[rows..rows+cols) of the rows x cols matrix x; C is not read */
 } orc_constraints;
 
 typedef struct {
@@ -90,10 +96,13 @@ typedef struct {
     const void* A;     /* row-major rows x cols, leading dimension ld */
     const double* b;   /* targets (least squares) or labels in {-1,+1} (logistic) */
     double lambda, mu;
-    const orc_constraints* con;   /* NULL: no constraints besides the box (ORC_LSQ and ORC_QP only otherwise) */
+    const orc_constraints* con;   /* NULL: no constraints besides the box (otherwise: ORC_LSQ, ORC_QP, transport kinds) */
     const double* sign;           /* ORC_QP: f = 0.5 (s.x)^T A (s.x) + b^T x with A symmetric (rows = cols), s = sign
                                      (NULL = ones); with A a kernel matrix, s the labels and b = -1 this is the dual
                                      SVM objective of the paper's section "Dual SVM" */
+    /* ORC_OT_GAUSS / ORC_OT_ENTROPY: A is the rows x cols cost matrix M, the variable is the rows x cols matrix P
+     * (row-major, n = rows*cols), f = sum M_ij P_ij + lambda sum phi(P_ij), phi(p) = p^2/2 or p log p (0 at p = 0);
+     * b is not read */
 } orc_objective;
 
 typedef struct {
@@ -161,14 +170,108 @@ static inline double sigmoid(double t) {
 
 /* ---- objectives -------------------------------------------------------------------------- */
 
+static inline int is_transport(const orc_objective* o) { return o->kind == ORC_OT_GAUSS || o->kind == ORC_OT_ENTROPY; }
+
 int64_t orc_num_vars(const orc_objective* o) {
+    if (is_transport(o)) return o->rows * o->cols;
     return o->kind == ORC_LSQ_L1SPLIT ? 2 * o->cols : o->cols;
+}
+
+/* entries of the row vector that belong to the objective itself (the constraint values follow them) */
+static inline int64_t obj_rows(const orc_objective* o) { return is_transport(o) ? 0 : o->rows; }
+
+/* (row r of the constraint matrix) . z: a dense row of C or E; or, for the marginal constraints, the sum
+ * of row r of the rows x cols matrix z (r < rows) or of its column r - rows */
+static double con_dot(const orc_constraints* k, const orc_objective* o, int64_t r, const double* z) {
+    nsum acc = {0.0, 0.0};
+    if (k->marginals) {
+        if (r < o->rows) for (int64_t j = 0; j < o->cols; ++j) ns_add(&acc, z[r * o->cols + j]);
+        else for (int64_t i = 0; i < o->rows; ++i) ns_add(&acc, z[i * o->cols + (r - o->rows)]);
+    } else {
+        const double* crow = r < k->n_eq ? k->C + r * o->cols : k->E + (r - k->n_eq) * o->cols;
+        for (int64_t c = 0; c < o->cols; ++c) ns_add_prod(&acc, crow[c], z[c]);
+    }
+    return ns_val(&acc);
+}
+
+/* g += coef * (row r of the constraint matrix) */
+static void con_axpy(const orc_constraints* k, const orc_objective* o, int64_t r, double coef, double* g) {
+    if (k->marginals) {
+        if (r < o->rows) for (int64_t j = 0; j < o->cols; ++j) g[r * o->cols + j] += coef;
+        else for (int64_t i = 0; i < o->rows; ++i) g[i * o->cols + (r - o->rows)] += coef;
+    } else {
+        const double* crow = r < k->n_eq ? k->C + r * o->cols : k->E + (r - k->n_eq) * o->cols;
+        for (int64_t c = 0; c < o->cols; ++c) g[c] += coef * crow[c];
+    }
+}
+
+/* Eq. (augLag): the two penalty terms at x (returned), their gradients C^T rho (h + lambda/rho) and
+ * E^T rho (g + mu/rho)_+ added to g (if given), and the shifted constraint values h + lambda/rho,
+ * g + mu/rho written to shifted[0 .. n_eq + n_in) (if given) */
+static double penalty_terms(const orc_objective* o, const double* x, double* g, double* shifted) {
+    const orc_constraints* k = o->con;
+    nsum pen = {0.0, 0.0};
+    for (int64_t r = 0; r < k->n_eq + k->n_in; ++r) {
+        const int eq = r < k->n_eq;
+        double a = eq ? con_dot(k, o, r, x) - k->d[r] + k->lambda[r] / k->rho
+                      : con_dot(k, o, r, x) - k->e[r - k->n_eq] + k->mu[r - k->n_eq] / k->rho;
+        if (shifted) shifted[r] = a;
+        double act = eq ? a : (a > 0.0 ? a : 0.0);
+        ns_add(&pen, 0.5 * k->rho * act * act);
+        if (g) con_axpy(k, o, r, k->rho * act, g);
+    }
+    return ns_val(&pen);
+}
+
+/* change of the penalty terms from x to xt, without cancellation; shifted = the values penalty_terms left at x:
+ *   rho/2 [(a + da)^2 - a^2] = rho da (a + da/2) for an equality row;
+ *   rho/2 [(a + da)_+^2 - a_+^2] = rho/2 (p1 - p0)(p1 + p0) for an inequality row */
+static double penalty_delta(const orc_objective* o, const double* x, const double* xt, const double* shifted) {
+    const orc_constraints* k = o->con;
+    const int64_t n = orc_num_vars(o);
+    double* dx = (double*)malloc(sizeof(double) * (size_t)n);
+    for (int64_t i = 0; i < n; ++i) dx[i] = xt[i] - x[i];
+    nsum acc = {0.0, 0.0};
+    for (int64_t r = 0; r < k->n_eq + k->n_in; ++r) {
+        double da = con_dot(k, o, r, dx), a = shifted[r];
+        if (r < k->n_eq) {
+            ns_add_prod(&acc, k->rho * da, a + 0.5 * da);
+        } else {
+            double p0 = a > 0.0 ? a : 0.0, p1 = a + da > 0.0 ? a + da : 0.0;
+            ns_add_prod(&acc, 0.5 * k->rho * (p1 - p0), p1 + p0);
+        }
+    }
+    free(dx);
+    return ns_val(&acc);
+}
+
+/* the transport objective <M,P> + lambda sum phi(P_ij) and its gradient M + lambda phi'(P) */
+static double transport_fg(const orc_objective* o, const double* x, double* g) {
+    nsum fsum = {0.0, 0.0};
+    for (int64_t i = 0; i < o->rows; ++i)
+        for (int64_t j = 0; j < o->cols; ++j) {
+            const double p = x[i * o->cols + j], mij = a_at(o, i, j);
+            ns_add_prod(&fsum, mij, p);
+            if (o->kind == ORC_OT_GAUSS) {
+                ns_add_prod(&fsum, 0.5 * o->lambda * p, p);
+                if (g) g[i * o->cols + j] = mij + o->lambda * p;
+            } else {
+                if (p > 0.0) ns_add_prod(&fsum, o->lambda * p, log(p));
+                if (g) g[i * o->cols + j] = mij + o->lambda * (log(p) + 1.0);
+            }
+        }
+    return ns_val(&fsum);
 }
 
 /* f(x); if g != NULL also grad f(x); if rowvec != NULL it receives the residual A v - b
  * (least squares) or the margins X w (logistic), one entry per row. */
 double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec) {
     const int64_t rows = o->rows, cols = o->cols;
+    if (is_transport(o)) {
+        double f = transport_fg(o, x, g);
+        if (o->con) f += penalty_terms(o, x, g, rowvec);
+        return f;
+    }
     double* v = (double*)malloc(sizeof(double) * (size_t)cols);   /* the vector A multiplies */
     double* psi = (double*)malloc(sizeof(double) * (size_t)(rows > 0 ? rows : 1));
     for (int64_t c = 0; c < cols; ++c)
@@ -223,26 +326,8 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
         }
         free(acc);
     }
-    if (o->con && (o->kind == ORC_LSQ || o->kind == ORC_QP)) {
-        /* Eq. (augLag): the two penalty terms, their gradients C^T rho (h + lambda/rho) and
-         * E^T rho (g + mu/rho)_+, and (after the rows of A) the shifted constraint values in rowvec */
-        const orc_constraints* k = o->con;
-        nsum pen = {0.0, 0.0};
-        for (int64_t r = 0; r < k->n_eq + k->n_in; ++r) {
-            const int eq = r < k->n_eq;
-            const double* crow = eq ? k->C + r * cols : k->E + (r - k->n_eq) * cols;
-            nsum acc = {0.0, 0.0};
-            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&acc, crow[c], x[c]);
-            double a = eq ? ns_val(&acc) - k->d[r] + k->lambda[r] / k->rho
-                          : ns_val(&acc) - k->e[r - k->n_eq] + k->mu[r - k->n_eq] / k->rho;
-            if (rowvec) rowvec[rows + r] = a;
-            double act = eq ? a : (a > 0.0 ? a : 0.0);
-            ns_add(&pen, 0.5 * k->rho * act * act);
-            if (g)
-                for (int64_t c = 0; c < cols; ++c) g[c] += k->rho * act * crow[c];
-        }
-        f += ns_val(&pen);
-    }
+    if (o->con && (o->kind == ORC_LSQ || o->kind == ORC_QP))
+        f += penalty_terms(o, x, g, rowvec ? rowvec + rows : NULL);   /* after the rows of A in rowvec */
     free(v);
     free(psi);
     return f;
@@ -256,6 +341,31 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
  * plus the difference of the separable terms (lambda*sum x, mu/2*||x||^2). */
 double orc_delta_f(const orc_objective* o, const double* x, const double* xt, const double* row) {
     const int64_t rows = o->rows, cols = o->cols, n = orc_num_vars(o);
+    if (is_transport(o)) {
+        /* entry by entry, dp = pt - p:  M dp;  Gaussian: (pt^2 - p^2)/2 = dp (p + dp/2);
+         * entropy: pt log pt - p log p = dp log pt + p log(pt/p) when both are positive */
+        nsum acc = {0.0, 0.0};
+        for (int64_t i = 0; i < rows; ++i)
+            for (int64_t j = 0; j < cols; ++j) {
+                const double p = x[i * cols + j], pt = xt[i * cols + j], dp = pt - p;
+                ns_add_prod(&acc, a_at(o, i, j), dp);
+                if (o->kind == ORC_OT_GAUSS) {
+                    ns_add_prod(&acc, o->lambda * dp, p + 0.5 * dp);
+                } else {
+                    if (p > 0.0 && pt > 0.0) {
+                        ns_add_prod(&acc, o->lambda * dp, log(pt));
+                        ns_add_prod(&acc, o->lambda * p, log1p(dp / p));
+                    } else if (pt > 0.0) {
+                        ns_add_prod(&acc, o->lambda * pt, log(pt));     /* p = 0 */
+                    } else if (p > 0.0) {
+                        ns_add_prod(&acc, -o->lambda * p, log(p));      /* pt = 0 */
+                    }
+                }
+            }
+        double df = ns_val(&acc);
+        if (o->con) df += penalty_delta(o, x, xt, row);
+        return df;
+    }
     double* dv = (double*)malloc(sizeof(double) * (size_t)cols);
     for (int64_t c = 0; c < cols; ++c)
         dv[c] = o->kind == ORC_LSQ_L1SPLIT ? (xt[c] - x[c]) - (xt[cols + c] - x[cols + c])
@@ -277,26 +387,9 @@ double orc_delta_f(const orc_objective* o, const double* x, const double* xt, co
             ns_add_prod(&acc, dz, row[r] + 0.5 * dz);
         }
     }
-    if (o->con && (o->kind == ORC_LSQ || o->kind == ORC_QP)) {
-        /* rho/2 [(a + da)^2 - a^2] = rho da (a + da/2) for an equality row;
-         * rho/2 [(a + da)_+^2 - a_+^2] = rho/2 (p1 - p0)(p1 + p0) for an inequality row */
-        const orc_constraints* k = o->con;
-        for (int64_t r = 0; r < k->n_eq + k->n_in; ++r) {
-            const int eq = r < k->n_eq;
-            const double* crow = eq ? k->C + r * cols : k->E + (r - k->n_eq) * cols;
-            nsum dacc = {0.0, 0.0};
-            for (int64_t c = 0; c < cols; ++c) ns_add_prod(&dacc, crow[c], xt[c] - x[c]);
-            double da = ns_val(&dacc), a = row[rows + r];
-            if (eq) {
-                ns_add_prod(&acc, k->rho * da, a + 0.5 * da);
-            } else {
-                double p0 = a > 0.0 ? a : 0.0, p1 = a + da > 0.0 ? a + da : 0.0;
-                ns_add_prod(&acc, 0.5 * k->rho * (p1 - p0), p1 + p0);
-            }
-        }
-    }
     free(dv);
     double df = ns_val(&acc);
+    if (o->con && (o->kind == ORC_LSQ || o->kind == ORC_QP)) df += penalty_delta(o, x, xt, row + rows);
     if (o->kind == ORC_LOGISTIC_L2) {
         nsum reg = {0.0, 0.0};
         for (int64_t i = 0; i < n; ++i) ns_add_prod(&reg, xt[i] - x[i], xt[i] + x[i]);
@@ -447,7 +540,7 @@ orc_solver* orc_create(int64_t n, int m, const double* l, const double* u, const
     s->g = (double*)malloc(nb); s->d = (double*)malloc(nb); s->p = (double*)malloc(nb);
     s->xt = (double*)malloc(nb); s->gt = (double*)malloc(nb);
     s->mask = (uint8_t*)malloc((size_t)n);
-    s->row = (double*)malloc(sizeof(double) * (size_t)(obj->rows + (obj->con ? obj->con->n_eq + obj->con->n_in : 0) + 1));
+    s->row = (double*)malloc(sizeof(double) * (size_t)(obj_rows(obj) + (obj->con ? obj->con->n_eq + obj->con->n_in : 0) + 1));
     s->S = (double*)malloc(nb * (size_t)m); s->Y = (double*)malloc(nb * (size_t)m);
     s->ynorm2 = (double*)malloc(sizeof(double) * (size_t)m);
     memcpy(s->l, l, nb); memcpy(s->u, u, nb); memcpy(s->x, x0, nb);
@@ -596,31 +689,32 @@ void orc_auglag_default_options(orc_auglag_options* o) {
 }
 
 /* h = C x - d and g = E x - e at x; returns max(||h||_inf, ||max(g, 0)||_inf) */
-static double constraint_values(const orc_constraints* k, int64_t cols, const double* x, double* h, double* g) {
+static double constraint_values(const orc_objective* o, const double* x, double* h, double* g) {
+    const orc_constraints* k = o->con;
     double viol = 0.0;
     for (int64_t r = 0; r < k->n_eq + k->n_in; ++r) {
-        const int eq = r < k->n_eq;
-        const double* crow = eq ? k->C + r * cols : k->E + (r - k->n_eq) * cols;
-        nsum acc = {0.0, 0.0};
-        for (int64_t c = 0; c < cols; ++c) ns_add_prod(&acc, crow[c], x[c]);
-        if (eq) {
-            h[r] = ns_val(&acc) - k->d[r];
+        if (r < k->n_eq) {
+            h[r] = con_dot(k, o, r, x) - k->d[r];
             if (fabs(h[r]) > viol) viol = fabs(h[r]);
         } else {
-            g[r - k->n_eq] = ns_val(&acc) - k->e[r - k->n_eq];
+            g[r - k->n_eq] = con_dot(k, o, r, x) - k->e[r - k->n_eq];
             if (g[r - k->n_eq] > viol) viol = g[r - k->n_eq];
         }
     }
     return viol;
 }
 
-/* Algorithm 4 on an ORC_LSQ objective that carries constraints (obj->con; its lambda and mu arrays are
+/* Algorithm 4 on a least-squares, quadratic-form or transport objective that carries constraints (obj->con; its lambda and mu arrays are
  * the multiplier state: set to zero here, updated in place, returned).  x: in = x^0 (feasible for the
  * box), out = the result. */
 int orc_auglag_solve(int64_t n, int m, const double* l, const double* u, double* x, const orc_objective* obj,
                      const orc_options* opt, const orc_auglag_options* aopt, orc_auglag_info* info) {
     memset(info, 0, sizeof *info);
-    if (!obj || (obj->kind != ORC_LSQ && obj->kind != ORC_QP) || !obj->con || n != obj->cols) return -1;
+    if (!obj || (obj->kind != ORC_LSQ && obj->kind != ORC_QP && !is_transport(obj)) || !obj->con ||
+        n != orc_num_vars(obj))
+        return -1;
+    if (obj->con->marginals && (!is_transport(obj) || obj->con->n_eq != obj->rows + obj->cols || obj->con->n_in != 0))
+        return -1;
     orc_constraints* k = (orc_constraints*)obj->con;   /* the multiplier state is the caller's, mutable */
     orc_auglag_options ao;
     if (aopt) ao = *aopt; else orc_auglag_default_options(&ao);
@@ -629,7 +723,7 @@ int orc_auglag_solve(int64_t n, int m, const double* l, const double* u, double*
     for (int64_t r = 0; r < k->n_eq; ++r) k->lambda[r] = 0.0;
     for (int64_t r = 0; r < k->n_in; ++r) k->mu[r] = 0.0;
     k->rho = ao.rho0;
-    double viol_prev = constraint_values(k, obj->cols, x, h, g);
+    double viol_prev = constraint_values(obj, x, h, g);
     info->status = ORC_MAX_ITER;
     info->violation = viol_prev;
     for (int it = 0; it < ao.max_outer; ++it) {
@@ -645,7 +739,7 @@ int orc_auglag_solve(int64_t n, int m, const double* l, const double* u, double*
         info->outer = it + 1;
         if (st == ORC_LINESEARCH_FAILED) { info->status = st; break; }
         /* lambda^{k+1} = lambda^k + rho h(x^{k+1});  mu^{k+1} = (mu^k + rho g(x^{k+1}))_+ */
-        double viol = constraint_values(k, obj->cols, x, h, g);
+        double viol = constraint_values(obj, x, h, g);
         for (int64_t r = 0; r < k->n_eq; ++r) k->lambda[r] += k->rho * h[r];
         for (int64_t r = 0; r < k->n_in; ++r) {
             double v = k->mu[r] + k->rho * g[r];

@@ -357,3 +357,86 @@ def svm_dual(n: int, dim: int = 20, *, seed: int, gamma: float = 1.0, c: float =
         K[r0:r1] = np.exp(-gamma * d2)
     K = 0.5 * (K + K.T) if n <= 4096 else K                  # exact symmetry (large n: symmetric up to rounding of the products)
     return SvmProblem(name="svm_dual", K=K, y=y, c=c, m=m, X=X)
+
+
+# ---- joint probability distribution (regularised optimal transport) -----------------------------
+
+OBJ_OT_GAUSS = 4     # <M,P> + lam/2*sum(P^2)        over the rows x cols matrix P (row-major), n = rows*cols
+OBJ_OT_ENTROPY = 5   # <M,P> + lam*sum(P log P)
+
+
+@dataclass
+class TransportProblem:
+    """min <M,P> + lam*r(P)  s.t.  P 1 = u,  P^T 1 = v,  P >= lower   (the paper's section "Joint Probability
+    Distribution"); r the Gaussian (0.5*sum P^2) or the entropy (sum P log P) regulariser."""
+    name: str
+    kind: int                # OBJ_OT_GAUSS / OBJ_OT_ENTROPY
+    M: np.ndarray            # rows x cols cost matrix
+    u: np.ndarray            # rows, sums to one
+    v: np.ndarray            # cols, sums to one
+    lam: float
+    lower: float             # 0 for the Gaussian regulariser; a tiny positive number for the entropy (log P)
+    m: int
+
+    @property
+    def rows(self) -> int:
+        return self.M.shape[0]
+
+    @property
+    def cols(self) -> int:
+        return self.M.shape[1]
+
+    @property
+    def n(self) -> int:
+        return self.M.size
+
+    @property
+    def l(self) -> np.ndarray:
+        return np.full(self.n, self.lower)
+
+    @property
+    def ub(self) -> np.ndarray:
+        return np.full(self.n, math.inf)
+
+    @property
+    def x0(self) -> np.ndarray:
+        return np.full(self.n, self.lower)     # Algorithm 4's x^0 = 0, moved onto the lower bound
+
+
+def _gauss_pdf(t, mean, sd):
+    return np.exp(-0.5 * ((t - mean) / sd) ** 2) / (sd * math.sqrt(2.0 * math.pi))
+
+
+def joint_probability(size: int, *, dataset: int = 1, reg: str = "gauss", seed: int = 0, lam: float = 0.5,
+                      dtype=np.float64, m: int = 10, lower: Optional[float] = None) -> TransportProblem:
+    """The two synthetic families of the paper's joint-probability experiment, lambda = 1/2.
+    dataset 1 (rows = cols = size): on the grid t_k = (k + 0.5)/size, u = a Gaussian N(0.5, 0.12^2) and
+      v = an equal mixture of N(0.3, 0.06^2) and N(0.7, 0.08^2), both discretised (density at the grid points,
+      normalised to sum one); cost M = u u^T.  (The paper names the shapes, not their parameters.)  No random draw.
+    dataset 2 (rows = 2*size, cols = size): u, v ~ U(0,1) normalised to sum one, M ~ U(0,1) entrywise.
+      Draw order: u, v, M (row chunks)."""
+    kind = {"gauss": OBJ_OT_GAUSS, "entropy": OBJ_OT_ENTROPY}[reg]
+    if dataset == 1:
+        t = (np.arange(size) + 0.5) / size
+        u = _gauss_pdf(t, 0.5, 0.12)
+        v = 0.5 * _gauss_pdf(t, 0.3, 0.06) + 0.5 * _gauss_pdf(t, 0.7, 0.08)
+        u /= u.sum()
+        v /= v.sum()
+        M = np.ascontiguousarray(np.outer(u, u).astype(dtype))
+    elif dataset == 2:
+        rng = np.random.default_rng(seed)
+        rows, cols = 2 * size, size
+        u = rng.random(rows)
+        v = rng.random(cols)
+        u /= u.sum()
+        v /= v.sum()
+        M = np.empty((rows, cols), dtype=dtype)
+        chunk = max(1, (64 << 20) // (cols * 8))
+        for r0 in range(0, rows, chunk):
+            r1 = min(rows, r0 + chunk)
+            M[r0:r1] = rng.random((r1 - r0, cols)).astype(dtype)
+    else:
+        raise KeyError(dataset)
+    if lower is None:
+        lower = 0.0 if kind == OBJ_OT_GAUSS else 1e-30
+    return TransportProblem(name=f"jp{dataset}_{reg}_{size}", kind=kind, M=M, u=u, v=v, lam=lam, lower=lower, m=m)
