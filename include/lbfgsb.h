@@ -51,9 +51,19 @@ enum {
     LBFGSB_OBJ_LSQ = 0,          /* f = 0.5*||A x - b||^2,                               n = cols   */
     LBFGSB_OBJ_LSQ_L1SPLIT = 1,  /* f = 0.5*||A(p-q) - b||^2 + lambda*sum(p+q), x=[p;q], n = 2*cols */
     LBFGSB_OBJ_LOGISTIC_L2 = 2,  /* f = (1/rows)*sum_i softplus(-b_i*(A x)_i) + mu/2*||x||^2, b_i in {-1,+1}, n = cols */
-    LBFGSB_OBJ_QP = 3            /* f = 0.5*(s.x)^T A (s.x) + b^T x, A symmetric, rows = cols = n, s = sign (or ones).
+    LBFGSB_OBJ_QP = 3,           /* f = 0.5*(s.x)^T A (s.x) + b^T x, A symmetric, rows = cols = n, s = sign (or ones).
                                     With A a kernel matrix, s the labels and b = -1 this is the dual SVM objective of
                                     the paper's section "Dual SVM".  One product with A per iteration (no transposed pass) */
+    /* The regularised optimal-transport objective of the paper's section "Joint Probability Distribution" over a
+     * rows x cols matrix P stored row by row as the variable vector (n = rows*cols); A is the cost matrix M (used
+     * entry by entry: there is no matrix-vector product), lambda > 0 the regularisation parameter:
+     *     f = <M,P> + lambda*sum_ij phi(P_ij) + 0.5*sum_k row_weight_k*((K P)_k - b_k)^2,   K P = [P 1; P^T 1],
+     * phi(p) = p^2/2 (Gaussian regulariser) or p*log(p) (entropy; needs l > 0).  b and row_weight have rows + cols
+     * entries (row sums first); row_weight NULL drops the last term (b is then not read).  That term is how the
+     * marginal constraints P 1 = u, P^T 1 = v enter through the augmented Lagrangian (lbfgsb_auglag_create_marginals);
+     * b and row_weight may change between lbfgsb_set_x calls. */
+    LBFGSB_OBJ_OT_GAUSS = 4,
+    LBFGSB_OBJ_OT_ENTROPY = 5
 };
 
 typedef struct {
@@ -62,7 +72,7 @@ typedef struct {
     int64_t rows, cols, ld;
     const void* A;       /* device, row-major, borrowed */
     const double* b;     /* device, rows entries: targets (least squares) or labels (logistic), borrowed */
-    double lambda;       /* L1SPLIT only */
+    double lambda;       /* L1SPLIT, OT_GAUSS, OT_ENTROPY */
     double mu;           /* LOGISTIC_L2 only */
     const double* row_weight; /* device, rows entries or NULL (= all ones), borrowed; least-squares kinds only:
                                  f = 0.5*sum_r row_weight_r*(A v - b)_r^2 (+ lambda*sum(p+q)) */
@@ -234,6 +244,17 @@ int lbfgsb_auglag_create_rows(lbfgsb_auglag** out, int64_t n, int m, const doubl
                               const lbfgsb_objective* obj_host, int64_t n_eq, const double* C, const double* d,
                               const lbfgsb_options* opt_host, const lbfgsb_auglag_options* al_opt_host,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
+/* The same algorithm for the marginal constraints of the transport kinds (section "Joint Probability
+ * Distribution"):  minimise <M,P> + lambda*r(P)  subject to  P 1 = u,  P^T 1 = v,  l <= P <= u_box.
+ * obj_host: kind OT_GAUSS or OT_ENTROPY with A = M, lambda; its b and row_weight are ignored (the algorithm owns
+ * them).  marginals: device, rows + cols entries [u; v], borrowed.  The rows + cols multipliers come back from
+ * lbfgsb_auglag_get_lambda in the same order.  n_eq = rows + cols structured constraints cost two small sum
+ * kernels per evaluation, however many there are. */
+size_t lbfgsb_auglag_marginals_workspace_bytes(int m, const lbfgsb_objective* obj_host, const lbfgsb_options* opt_host);
+int lbfgsb_auglag_create_marginals(lbfgsb_auglag** out, int m, const double* l, const double* u,
+                                   const lbfgsb_objective* obj_host, const double* marginals,
+                                   const lbfgsb_options* opt_host, const lbfgsb_auglag_options* al_opt_host,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 /* Runs Algorithm 4 from x0 (device, n entries, feasible for the box) with lambda = 0, rho = rho0.  The host
  * reads two scalars per outer iteration; everything else stays on the device.  Synchronises. */
 int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info* info_host);
@@ -251,7 +272,9 @@ void lbfgsb_auglag_destroy(lbfgsb_auglag* al);
  * synchronises and returns how many launches were timed (launches that returned at once because the
  * solver had already stopped -- duration below half of the longest -- are left out), their total duration in milliseconds
  * and the bytes of A one launch requests from memory (rows*cols*sizeof(element): each such
- * kernel reads A exactly once). */
+ * kernel reads A exactly once).  The transport kinds have no such kernel: there the Gram kernel of the batched
+ * two-loop recursion (the longest kernel of an iteration) is timed instead, and the bytes are what it moves
+ * once all m pairs are stored: n*((2m + 4)*8 + 1). */
 int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable);
 int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count_host, double* total_ms_host, double* bytes_per_pass_host);
 /* Name of the A-pass organisation in use: "fused" or "two_pass" (host string). */
@@ -264,7 +287,8 @@ const char* lbfgsb_apass_name(const lbfgsb_solver* s);
  * synchronise. */
 
 /* f(x) -> *f_host, grad f(x) -> g (n entries); rowvec (rows entries, may be NULL) receives
- * A v - b (least squares) or the margins A x (logistic). */
+ * A v - b (least squares) or the margins A x (logistic); for the transport kinds it has rows + cols entries
+ * and receives K P - b. */
 int lbfgsb_dbg_fg(lbfgsb_solver* s, const double* x, double* f_host, double* g, double* rowvec);
 
 /* Eq. (ws): mask[i] = 1 if i is free at (x, g), else 0. */

@@ -343,7 +343,7 @@ double orc_delta_f(const orc_objective* o, const double* x, const double* xt, co
     const int64_t rows = o->rows, cols = o->cols, n = orc_num_vars(o);
     if (is_transport(o)) {
         /* entry by entry, dp = pt - p:  M dp;  Gaussian: (pt^2 - p^2)/2 = dp (p + dp/2);
-         * entropy: pt log pt - p log p = dp log pt + p log(pt/p) when both are positive */
+         * entropy: pt log pt - p log p = dp log pt + p log(pt/p) when both are positive and |dp| <= p/2 */
         nsum acc = {0.0, 0.0};
         for (int64_t i = 0; i < rows; ++i)
             for (int64_t j = 0; j < cols; ++j) {
@@ -352,9 +352,14 @@ double orc_delta_f(const orc_objective* o, const double* x, const double* xt, co
                 if (o->kind == ORC_OT_GAUSS) {
                     ns_add_prod(&acc, o->lambda * dp, p + 0.5 * dp);
                 } else {
-                    if (p > 0.0 && pt > 0.0) {
+                    if (p > 0.0 && pt > 0.0 && fabs(dp) <= 0.5 * p) {
                         ns_add_prod(&acc, o->lambda * dp, log(pt));
                         ns_add_prod(&acc, o->lambda * p, log1p(dp / p));
+                    } else if (p > 0.0 && pt > 0.0) {
+                        /* a large relative change: the two values differ enough to be subtracted directly (and
+                         * the split form would add +-huge terms, or log(0) once dp/p rounds to -1) */
+                        ns_add_prod(&acc, o->lambda * pt, log(pt));
+                        ns_add_prod(&acc, -o->lambda * p, log(p));
                     } else if (pt > 0.0) {
                         ns_add_prod(&acc, o->lambda * pt, log(pt));     /* p = 0 */
                     } else if (p > 0.0) {

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblbfgsb.so")
 
 F64, F32 = 0, 1
-OBJ_LSQ, OBJ_LSQ_L1SPLIT, OBJ_LOGISTIC_L2, OBJ_QP = 0, 1, 2, 3
+OBJ_LSQ, OBJ_LSQ_L1SPLIT, OBJ_LOGISTIC_L2, OBJ_QP, OBJ_OT_GAUSS, OBJ_OT_ENTROPY = 0, 1, 2, 3, 4, 5
 APASS_AUTO, APASS_TWO_PASS, APASS_FUSED = 0, 1, 2
 RUNNING, CONVERGED, MAX_ITER, LINESEARCH_FAILED = 0, 1, 2, 3
 OK, E_INVALID_ARG, E_BOUNDS, E_INFEASIBLE_X0, E_NONFINITE, E_HIP, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
@@ -28,6 +28,7 @@ EXPORTS = [
     "lbfgsb_auglag_default_options", "lbfgsb_auglag_workspace_bytes", "lbfgsb_auglag_create", "lbfgsb_auglag_solve",
     "lbfgsb_auglag_get_x", "lbfgsb_auglag_get_lambda", "lbfgsb_auglag_inner", "lbfgsb_auglag_destroy",
     "lbfgsb_auglag_rows_workspace_bytes", "lbfgsb_auglag_create_rows",
+    "lbfgsb_auglag_marginals_workspace_bytes", "lbfgsb_auglag_create_marginals",
 ]
 
 
@@ -134,6 +135,11 @@ def lib():
         L.lbfgsb_auglag_create_rows.restype = C.c_int
         L.lbfgsb_auglag_create_rows.argtypes = [C.POINTER(vp), i64, C.c_int, vp, vp, C.POINTER(Objective), i64, vp, vp,
                                                 C.POINTER(Options), C.POINTER(AuglagOptions), vp, C.c_size_t, vp]
+        L.lbfgsb_auglag_marginals_workspace_bytes.restype = C.c_size_t
+        L.lbfgsb_auglag_marginals_workspace_bytes.argtypes = [C.c_int, C.POINTER(Objective), C.POINTER(Options)]
+        L.lbfgsb_auglag_create_marginals.restype = C.c_int
+        L.lbfgsb_auglag_create_marginals.argtypes = [C.POINTER(vp), C.c_int, vp, vp, C.POINTER(Objective), vp,
+                                                     C.POINTER(Options), C.POINTER(AuglagOptions), vp, C.c_size_t, vp]
         L.lbfgsb_auglag_solve.restype = C.c_int
         L.lbfgsb_auglag_solve.argtypes = [vp, vp, C.POINTER(AuglagInfo)]
         L.lbfgsb_auglag_get_x.restype = C.c_int
@@ -187,16 +193,19 @@ class Solver:
                 and A.dtype in (torch.float64, torch.float32)):
             raise TypeError("A must be a 2-d float64/float32 CUDA tensor with unit column stride")
         rows, cols = A.shape
-        self.n = 2 * cols if kind == OBJ_LSQ_L1SPLIT else cols
+        transport = kind in (OBJ_OT_GAUSS, OBJ_OT_ENTROPY)   # A = cost matrix; b, row_weight: rows + cols marginal terms
+        self.n = rows * cols if transport else (2 * cols if kind == OBJ_LSQ_L1SPLIT else cols)
         self.rows, self.cols, self.m, self.kind = rows, cols, m, kind
-        self._A, self._b = A, _dev_f64(b, "b", rows)
+        self.row_entries = rows + cols if transport else rows
+        self._A = A
+        self._b = _dev_f64(b, "b", self.row_entries) if (b is not None or not transport) else None
         if kind == OBJ_QP and rows != cols:
             raise ValueError("the quadratic form needs a square matrix")
         _dev_f64(l, "l", self.n)
         _dev_f64(u, "u", self.n)
         self.device = A.device
         self.options = options if options is not None else default_options()
-        self._w = _dev_f64(row_weight, "row_weight", rows) if row_weight is not None else None
+        self._w = _dev_f64(row_weight, "row_weight", self.row_entries) if row_weight is not None else None
         self._sign = _dev_f64(sign, "sign", self.n) if sign is not None else None
         # extra = (rows E: (n_extra, n), targets: n_extra, weights: n_extra or None), float64 CUDA tensors
         self._extra = extra
@@ -207,7 +216,8 @@ class Solver:
             if extra[2] is not None:
                 _dev_f64(extra[2], "extra weights", n_extra)
         self._obj = Objective(kind, F64 if A.dtype == torch.float64 else F32, rows, cols,
-                              A.stride(0) if rows > 1 else cols, A.data_ptr(), self._b.data_ptr(), float(lam), float(mu),
+                              A.stride(0) if rows > 1 else cols, A.data_ptr(),
+                              self._b.data_ptr() if self._b is not None else None, float(lam), float(mu),
                               self._w.data_ptr() if self._w is not None else None,
                               self._sign.data_ptr() if self._sign is not None else None, n_extra,
                               extra[0].data_ptr() if n_extra else None, extra[1].data_ptr() if n_extra else None,
@@ -294,7 +304,7 @@ class Solver:
     def dbg_fg(self, x, want_rowvec: bool = False):
         import torch
         g = torch.empty(self.n, dtype=torch.float64, device=self.device)
-        row = torch.empty(self.rows, dtype=torch.float64, device=self.device) if want_rowvec else None
+        row = torch.empty(self.row_entries, dtype=torch.float64, device=self.device) if want_rowvec else None
         f = C.c_double(0.0)
         _check(lib().lbfgsb_dbg_fg(self._h, _dev_f64(x, "x", self.n).data_ptr(), C.byref(f), g.data_ptr(),
                                    row.data_ptr() if row is not None else None))
@@ -445,6 +455,42 @@ class AuglagRows(Auglag):
                                                    self._d.data_ptr() if self.n_eq else None, C.byref(self.options),
                                                    C.byref(self.al_options), self.workspace.data_ptr(), nbytes,
                                                    C.c_void_p(self._stream.cuda_stream)))
+
+
+class AuglagMarginals(Auglag):
+    """lbfgsb_auglag_create_marginals: Algorithm 4 for  min <M,P> + lam r(P)  s.t.  P 1 = u, P^T 1 = v, l <= P <= ub
+    (kind OBJ_OT_GAUSS or OBJ_OT_ENTROPY).  M: (rows, cols) CUDA tensor; marginals: [u; v] (float64 CUDA);
+    l, ub and x0: rows*cols entries, row-major."""
+
+    def __init__(self, kind: int, M, marginals, l, u, m: int, *, lam: float, options: Optional[Options] = None,
+                 rho0: float = 1.0, ctol: float = 1e-8, max_outer: int = 100):
+        import torch
+        if not (isinstance(M, torch.Tensor) and M.is_cuda and M.dim() == 2 and M.stride(1) == 1
+                and M.dtype in (torch.float64, torch.float32)):
+            raise TypeError("M must be a 2-d float64/float32 CUDA tensor with unit column stride")
+        rows, cols = M.shape
+        self.n, self.n_eq, self.m = rows * cols, rows + cols, m
+        self._A = M
+        self._d = _dev_f64(marginals, "marginals", rows + cols)
+        _dev_f64(l, "l", self.n)
+        _dev_f64(u, "u", self.n)
+        self.device = M.device
+        self.options = options if options is not None else default_options()
+        self.al_options = AuglagOptions(float(rho0), float(ctol), int(max_outer))
+        self._obj = Objective(kind, F64 if M.dtype == torch.float64 else F32, rows, cols,
+                              M.stride(0) if rows > 1 else cols, M.data_ptr(), None, float(lam), 0.0, None, None, 0,
+                              None, None, None)
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            nbytes = lib().lbfgsb_auglag_marginals_workspace_bytes(m, C.byref(self._obj), C.byref(self.options))
+            if nbytes == 0:
+                raise LbfgsbError(E_INVALID_ARG, lib().lbfgsb_last_error().decode())
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self._stream = torch.cuda.current_stream(self.device)
+            _check(lib().lbfgsb_auglag_create_marginals(C.byref(self._h), m, l.data_ptr(), u.data_ptr(),
+                                                        C.byref(self._obj), self._d.data_ptr(), C.byref(self.options),
+                                                        C.byref(self.al_options), self.workspace.data_ptr(), nbytes,
+                                                        C.c_void_p(self._stream.cuda_stream)))
 
 
 def solver_for_problem(prob, device="cuda:0", **option_overrides) -> Solver:

@@ -59,25 +59,31 @@ struct lbfgsb_solver {
 
 namespace {
 
-bool is_quadratic(int kind) { return kind != LBFGSB_OBJ_LOGISTIC_L2; }
+// objective is a quadratic along every direction: closed-form line search, gradient carried by recurrence
+bool is_quadratic(int kind) { return kind != LBFGSB_OBJ_LOGISTIC_L2 && kind != LBFGSB_OBJ_OT_ENTROPY; }
 
 int check_objective(int64_t n, int m, const lbfgsb_objective* o) {
     if (!o) return fail(LBFGSB_E_INVALID_ARG, "objective is NULL");
     if (n <= 0) return fail(LBFGSB_E_INVALID_ARG, "n must be positive (got %lld)", (long long)n);
     if (m <= 0 || m > LBFGSB_MAX_M) return fail(LBFGSB_E_INVALID_ARG, "m must be in 1..%d (got %d)", LBFGSB_MAX_M, m);
-    if (o->kind < LBFGSB_OBJ_LSQ || o->kind > LBFGSB_OBJ_QP)
+    if (o->kind < LBFGSB_OBJ_LSQ || o->kind > LBFGSB_OBJ_OT_ENTROPY)
         return fail(LBFGSB_E_INVALID_ARG, "unknown objective kind %d", o->kind);
     if (o->kind == LBFGSB_OBJ_QP && o->rows != o->cols)
         return fail(LBFGSB_E_INVALID_ARG, "the quadratic form needs a square matrix (got %lld x %lld)", (long long)o->rows,
                     (long long)o->cols);
     if (o->n_extra < 0 || o->n_extra > kMaxExtra) return fail(LBFGSB_E_INVALID_ARG, "n_extra must be in 0..%d", kMaxExtra);
-    if (o->n_extra > 0 && o->kind == LBFGSB_OBJ_LOGISTIC_L2)
-        return fail(LBFGSB_E_INVALID_ARG, "extra rows go with the quadratic objective kinds");
+    if (o->n_extra > 0 && (o->kind == LBFGSB_OBJ_LOGISTIC_L2 || is_transport(o->kind)))
+        return fail(LBFGSB_E_INVALID_ARG, "extra rows go with the least-squares and quadratic-form kinds");
+    if (is_transport(o->kind) && !(o->lambda > 0.0))
+        return fail(LBFGSB_E_INVALID_ARG, "the transport kinds need lambda > 0");
     if (o->dtype != LBFGSB_F64 && o->dtype != LBFGSB_F32) return fail(LBFGSB_E_INVALID_ARG, "unknown dtype %d", o->dtype);
     if (o->rows <= 0 || o->cols <= 0) return fail(LBFGSB_E_INVALID_ARG, "rows and cols must be positive");
     if (o->rows > (1ll << 31) - 1 || o->cols > (1ll << 31) - 1) return fail(LBFGSB_E_INVALID_ARG, "rows/cols exceed 2^31-1");
     if (o->ld < o->cols) return fail(LBFGSB_E_INVALID_ARG, "ld (%lld) < cols (%lld)", (long long)o->ld, (long long)o->cols);
-    const int64_t expect = o->kind == LBFGSB_OBJ_LSQ_L1SPLIT ? 2 * o->cols : o->cols;
+    if (is_transport(o->kind) && o->rows > ((1ll << 40) / o->cols))
+        return fail(LBFGSB_E_INVALID_ARG, "rows*cols exceeds 2^40 variables");
+    const int64_t expect = is_transport(o->kind) ? o->rows * o->cols
+                         : o->kind == LBFGSB_OBJ_LSQ_L1SPLIT ? 2 * o->cols : o->cols;
     if (n != expect) return fail(LBFGSB_E_INVALID_ARG, "n = %lld does not match the objective (%lld variables)", (long long)n, (long long)expect);
     return LBFGSB_OK;
 }
@@ -106,14 +112,25 @@ Geometry make_geometry(const Dims& dm, const void* A) {
     if (rb < 1) rb = 1;
     ge.gemvt_rows_per_block = (dm.rows + rb - 1) / rb;
     ge.gemvt_row_blocks = (int)((dm.rows + ge.gemvt_rows_per_block - 1) / ge.gemvt_rows_per_block);
-    ge.fused_ok = fused_shape_ok(dm, A, &ge.fused_variant, &ge.fused_blocks) ? 1 : 0;
+    ge.fused_ok = !is_transport(dm.kind) && fused_shape_ok(dm, A, &ge.fused_variant, &ge.fused_blocks) ? 1 : 0;
     ge.gram_blocks = gram_blocks_for(dm.n, dm.m);
     int64_t db = (dm.n + kBlock - 1) / kBlock;
-    ge.dir_blocks = (int)(db > 256 ? 256 : db);
+    ge.dir_blocks = (int)(db > kDirBlocksMax ? kDirBlocksMax : db);
     int64_t ub = (dm.cols + 15) / 16;   // 16 columns per workgroup in the column-sum kernels
     ge.upd_blocks = ge.fin_blocks = (int)(ub > 2048 ? 2048 : ub);
     int64_t lb_ = (dm.rows + kBlock - 1) / kBlock;
     ge.ls_blocks = (int)(lb_ > 512 ? 512 : lb_);
+    if (is_transport(dm.kind)) {
+        int rpw = 1;
+        while (rpw < kOtRpwMax && (dm.rows + rpw - 1) / rpw > 512) rpw *= 2;
+        ge.ot_rpw = rpw;
+        ge.ot_row_blocks = (int)((dm.rows + rpw - 1) / rpw);
+        int64_t cb = (dm.cols + kCX - 1) / kCX;
+        ge.ot_col_blocks = (int)(cb > 2048 ? 2048 : cb);
+        ge.ot_el_blocks = (int)(dm.rows > 2048 ? 2048 : dm.rows);
+        int64_t eb = (dm.n + kBlock - 1) / kBlock;
+        ge.ls_blocks = (int)(eb > 1024 ? 1024 : eb);
+    }
     return ge;
 }
 
@@ -126,7 +143,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     size_t off = 0;
     // (wextra / xres are appended at the end so that the offsets of everything else do not depend on n_extra)
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-    const size_t nb = (size_t)dm.n * 8, rb = (size_t)dm.rows * 8;
+    const size_t nb = (size_t)dm.n * 8, rb = (size_t)row_entries(dm.kind, dm.rows, dm.cols) * 8;
     L.scal = take(sizeof(Scal));
     L.x = take(nb); L.g = take(nb); L.l = take(nb); L.u = take(nb); L.d = take(nb); L.p1 = take(nb); L.p2 = take(nb);
     L.mask = take((size_t)dm.n);
@@ -134,14 +151,17 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     L.row = take(rb); L.t = take(rb); L.psi = take(rb);
     int wparts = ge.gemvt_row_blocks;
     if (ge.fused_ok && ge.fused_blocks > wparts) wparts = ge.fused_blocks;
+    if (is_transport(dm.kind)) wparts = ge.ot_row_blocks;
     L.wpart = take((size_t)wparts * dm.cols * 8);
     int lparts = ge.gemv_blocks;
     if (ge.fused_ok && ge.fused_blocks > lparts) lparts = ge.fused_blocks;
     if (ge.ls_blocks > lparts) lparts = ge.ls_blocks;
+    if (is_transport(dm.kind) && ge.ot_row_blocks + ge.ot_col_blocks > lparts) lparts = ge.ot_row_blocks + ge.ot_col_blocks;
     L.losspart = take((size_t)lparts * 8);
     L.grampart = take((size_t)ge.gram_blocks * gram_entries(dm.m) * 8);
     size_t red = (size_t)ge.dir_blocks * 8;
     if ((size_t)ge.upd_blocks * 2 > red) red = (size_t)ge.upd_blocks * 2;
+    if (is_transport(dm.kind) && (size_t)ge.ot_el_blocks > red) red = (size_t)ge.ot_el_blocks;
     L.redpart = take(red * 8);
     L.lspart = take((size_t)ge.ls_blocks * kLsBatch * 8);
     L.wextra = take(dm.n_extra > 0 ? (size_t)dm.n * 8 : 8);
@@ -204,9 +224,19 @@ APassArgs base_args(const lbfgsb_solver* s) {
     return a;
 }
 
+OtArgs ot_args(const lbfgsb_solver* s) {
+    return OtArgs{s->obj.A, s->obj.b, s->obj.row_weight};
+}
+
 // f, g (and the residual / margins) from scratch at the current x.
 void enqueue_eval(lbfgsb_solver* s, int check_status) {
     launch_commit(s->dm, s->bf, s->stream);   // a pending f must not overwrite the one computed here
+    if (is_transport(s->dm.kind)) {
+        const OtArgs oa = ot_args(s);
+        launch_ot_sums(s->dm, s->ge, s->bf, oa, 1, check_status, s->stream);
+        launch_ot_eval_finish(s->dm, s->ge, s->bf, oa, s->stream);
+        return;
+    }
     APassArgs a = base_args(s);
     a.va = s->bf.x;
     a.vb = a.split ? s->bf.x + s->dm.cols : nullptr;
@@ -237,6 +267,18 @@ void enqueue_step(lbfgsb_solver* s) {
     if (quad && s->options.refresh_every > 0 && s->steps_since_refresh >= s->options.refresh_every) {
         enqueue_eval(s, 1);
         s->steps_since_refresh = 0;
+    }
+    if (is_transport(s->dm.kind)) {
+        // no matrix product: the iteration streams the pair memory twice (Gram matrix, direction) and the
+        // iterate-sized vectors a few times.  The Gram kernel is the longest and the one that is timed.
+        { TimedSlot ts(s); launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream, ts.e0, ts.e1); }
+        launch_dir(s->dm, s->op, s->ge, s->bf, 0, s->stream);
+        const OtArgs oa = ot_args(s);
+        launch_ot_sums(s->dm, s->ge, s->bf, oa, 0, 1, s->stream);
+        if (quad) launch_ot_update_gauss(s->dm, s->op, s->ge, s->bf, oa, s->stream);
+        else launch_ot_step_entropy(s->dm, s->op, s->ge, s->bf, oa, s->stream);
+        s->steps_since_refresh++;
+        return;
     }
     launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
     launch_dir(s->dm, s->op, s->ge, s->bf, 0, s->stream);
@@ -292,6 +334,40 @@ void fresh_scal(lbfgsb_solver* s) {
     s->h_scal->alpha_ub = 1.0;
 }
 
+// trusted: x0 is the solver's own iterate (feasible by construction): only f is checked for finiteness and
+// nothing iterate-sized crosses to the host
+int set_x_impl(lbfgsb_solver* s, const double* x0, bool trusted) {
+    const int64_t n = s->dm.n;
+    std::vector<double> hx;
+    if (!trusted) {
+        std::vector<double> hl((size_t)n), hu((size_t)n);
+        hx.resize((size_t)n);
+        HIP_TRY(hipMemcpyAsync(hx.data(), x0, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
+        HIP_TRY(hipMemcpyAsync(hl.data(), s->bf.l, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
+        HIP_TRY(hipMemcpyAsync(hu.data(), s->bf.u, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
+        HIP_TRY(hipStreamSynchronize(s->stream));
+        for (int64_t i = 0; i < n; ++i) {
+            const double v = hx[(size_t)i];
+            if (!(v >= hl[(size_t)i]) || !(v <= hu[(size_t)i]))
+                return fail(LBFGSB_E_INFEASIBLE_X0, "x0[%lld] = %g is outside [%g, %g]", (long long)i, v, hl[(size_t)i],
+                            hu[(size_t)i]);
+        }
+    }
+    if (x0 != s->bf.x) HIP_TRY(hipMemcpyAsync(s->bf.x, x0, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream));
+    fresh_scal(s);
+    HIP_TRY(write_scal(s));
+    enqueue_eval(s, 0);
+    s->steps_since_refresh = 0;
+    if (!trusted) HIP_TRY(hipMemcpyAsync(hx.data(), s->bf.g, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
+    HIP_TRY(read_scal(s));
+    HIP_TRY(hipGetLastError());
+    bool finite = std::isfinite(s->h_scal->f);
+    for (int64_t i = 0; finite && !trusted && i < n; ++i) finite = std::isfinite(hx[(size_t)i]);
+    if (!finite) { s->x_set = false; return fail(LBFGSB_E_NONFINITE, "f or grad f is not finite at x0"); }
+    s->x_set = true;
+    return LBFGSB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -318,7 +394,9 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
     *out = nullptr;
     int rc = check_objective(n, m, obj);
     if (rc) return rc;
-    if (!l || !u || !obj->A || !obj->b || !workspace) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
+    const bool ot = is_transport(obj->kind);
+    if (!l || !u || !obj->A || !workspace) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
+    if (ot ? (obj->row_weight && !obj->b) : !obj->b) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer (b)");
     if (obj->n_extra > 0 && (!obj->extra_rows || !obj->extra_target))
         return fail(LBFGSB_E_INVALID_ARG, "NULL extra_rows / extra_target");
     lbfgsb_options o;
@@ -391,6 +469,11 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
         if (!(hl[(size_t)i] <= hu[(size_t)i]))
             return bail(fail(LBFGSB_E_BOUNDS, "bounds cross or are NaN at index %lld (l = %g, u = %g)", (long long)i,
                              hl[(size_t)i], hu[(size_t)i]));
+    if (obj->kind == LBFGSB_OBJ_OT_ENTROPY)
+        for (int64_t i = 0; i < n; ++i)
+            if (!(hl[(size_t)i] > 0.0))
+                return bail(fail(LBFGSB_E_BOUNDS, "the entropy regulariser needs l > 0 (l[%lld] = %g)", (long long)i,
+                                 hl[(size_t)i]));
     // the workspace starts from all-zero memory (fill kernel: no memset node ever enters a captured graph)
     launch_fill_zero(workspace, L.total, s->stream);
     e = hipMemcpyAsync(b.l, l, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream);
@@ -412,31 +495,7 @@ void lbfgsb_destroy(lbfgsb_solver* s) {
 
 int lbfgsb_set_x(lbfgsb_solver* s, const double* x0) {
     if (!s || !x0) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
-    const int64_t n = s->dm.n;
-    std::vector<double> hx((size_t)n), hl((size_t)n), hu((size_t)n);
-    HIP_TRY(hipMemcpyAsync(hx.data(), x0, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
-    HIP_TRY(hipMemcpyAsync(hl.data(), s->bf.l, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
-    HIP_TRY(hipMemcpyAsync(hu.data(), s->bf.u, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
-    HIP_TRY(hipStreamSynchronize(s->stream));
-    for (int64_t i = 0; i < n; ++i) {
-        const double v = hx[(size_t)i];
-        if (!(v >= hl[(size_t)i]) || !(v <= hu[(size_t)i]))
-            return fail(LBFGSB_E_INFEASIBLE_X0, "x0[%lld] = %g is outside [%g, %g]", (long long)i, v, hl[(size_t)i],
-                        hu[(size_t)i]);
-    }
-    HIP_TRY(hipMemcpyAsync(s->bf.x, x0, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream));
-    fresh_scal(s);
-    HIP_TRY(write_scal(s));
-    enqueue_eval(s, 0);
-    s->steps_since_refresh = 0;
-    HIP_TRY(hipMemcpyAsync(hx.data(), s->bf.g, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
-    HIP_TRY(read_scal(s));
-    HIP_TRY(hipGetLastError());
-    bool finite = std::isfinite(s->h_scal->f);
-    for (int64_t i = 0; finite && i < n; ++i) finite = std::isfinite(hx[(size_t)i]);
-    if (!finite) { s->x_set = false; return fail(LBFGSB_E_NONFINITE, "f or grad f is not finite at x0"); }
-    s->x_set = true;
-    return LBFGSB_OK;
+    return set_x_impl(s, x0, false);
 }
 
 int lbfgsb_step(lbfgsb_solver* s, lbfgsb_info* info) {
@@ -532,6 +591,9 @@ int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count, double* total_ms, doub
     *count = n;
     *total_ms = tot;
     *bytes_per_pass = (double)s->dm.rows * (double)s->dm.cols * (s->dm.dtype == LBFGSB_F32 ? 4.0 : 8.0);
+    // transport kinds: the timed kernel is the Gram kernel; with all m pairs stored it reads the 2m pair vectors
+    // and x, g, l, u once each and writes the one-byte free mask
+    if (is_transport(s->dm.kind)) *bytes_per_pass = (double)s->dm.n * ((2.0 * s->dm.m + 4.0) * 8.0 + 1.0);
     return LBFGSB_OK;
 }
 
@@ -547,7 +609,9 @@ int lbfgsb_dbg_fg(lbfgsb_solver* s, const double* x, double* f_host, double* g, 
     HIP_TRY(write_scal(s));
     enqueue_eval(s, 0);
     HIP_TRY(hipMemcpyAsync(g, s->bf.g, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
-    if (rowvec) HIP_TRY(hipMemcpyAsync(rowvec, s->bf.row, (size_t)s->dm.rows * 8, hipMemcpyDeviceToDevice, s->stream));
+    if (rowvec)
+        HIP_TRY(hipMemcpyAsync(rowvec, s->bf.row, (size_t)row_entries(s->dm.kind, s->dm.rows, s->dm.cols) * 8,
+                               hipMemcpyDeviceToDevice, s->stream));
     HIP_TRY(read_scal(s));
     HIP_TRY(hipGetLastError());
     *f_host = s->h_scal->f;
@@ -853,6 +917,62 @@ int lbfgsb_auglag_create_rows(lbfgsb_auglag** out, int64_t n, int m, const doubl
     return LBFGSB_OK;
 }
 
+size_t lbfgsb_auglag_marginals_workspace_bytes(int m, const lbfgsb_objective* obj, const lbfgsb_options* opt) {
+    if (!obj || !is_transport(obj->kind)) { fail(LBFGSB_E_INVALID_ARG, "the marginal constraints go with the transport kinds"); return 0; }
+    lbfgsb_objective o = *obj;
+    o.n_extra = 0;
+    const size_t inner = lbfgsb_workspace_bytes(o.rows * o.cols, m, &o, opt);
+    return inner ? align_up(inner) + al_rows_extra_bytes(o.rows + o.cols) : 0;
+}
+
+int lbfgsb_auglag_create_marginals(lbfgsb_auglag** out, int m, const double* l, const double* u,
+                                   const lbfgsb_objective* obj, const double* marginals, const lbfgsb_options* opt,
+                                   const lbfgsb_auglag_options* aopt, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream) {
+    if (!out) return fail(LBFGSB_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!obj || !is_transport(obj->kind)) return fail(LBFGSB_E_INVALID_ARG, "the marginal constraints go with the transport kinds");
+    if (!marginals || !workspace) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
+    lbfgsb_auglag_options ao;
+    if (aopt) ao = *aopt; else lbfgsb_auglag_default_options(&ao);
+    if (!(ao.rho0 > 0.0) || !(ao.ctol >= 0.0) || ao.max_outer < 1) return fail(LBFGSB_E_INVALID_ARG, "bad option value");
+    lbfgsb_objective inner_obj = *obj;
+    inner_obj.n_extra = 0;
+    inner_obj.b = nullptr;
+    inner_obj.row_weight = nullptr;
+    const int64_t n = obj->rows * obj->cols, n_eq = obj->rows + obj->cols;
+    const size_t inner_bytes = lbfgsb_workspace_bytes(n, m, &inner_obj, opt);
+    if (inner_bytes == 0) return LBFGSB_E_INVALID_ARG;
+    const size_t extra = al_rows_extra_bytes(n_eq);
+    if (workspace_bytes < align_up(inner_bytes) + extra)
+        return fail(LBFGSB_E_INVALID_ARG, "workspace too small: %zu < %zu bytes", workspace_bytes, align_up(inner_bytes) + extra);
+    if ((uintptr_t)workspace % 256) return fail(LBFGSB_E_INVALID_ARG, "workspace must be 256-byte aligned");
+
+    lbfgsb_auglag* al = new (std::nothrow) lbfgsb_auglag();
+    if (!al) return fail(LBFGSB_E_INVALID_ARG, "out of host memory");
+    const size_t slot = align_up((size_t)n_eq * 8);
+    al->ao = ao; al->n_eq = n_eq; al->n = n; al->d_c = marginals;
+    al->stream = (hipStream_t)hip_stream; al->rho = ao.rho0; al->inner = nullptr; al->h_red = nullptr;
+    char* w = (char*)workspace + align_up(inner_bytes);
+    al->beta_c = (double*)w; w += slot;
+    al->omega_c = (double*)w; w += slot;
+    al->lambda = (double*)w; w += slot;
+    al->red = (double*)w;
+    inner_obj.b = al->beta_c;
+    inner_obj.row_weight = al->omega_c;
+    int rc = lbfgsb_create(&al->inner, n, m, l, u, &inner_obj, opt, workspace, inner_bytes, hip_stream);
+    if (rc) { delete al; return rc; }
+    al->res_c = al->inner->bf.row;
+    hipError_t e = hipHostMalloc((void**)&al->h_red, 64, hipHostMallocDefault);
+    if (e != hipSuccess) { al->h_red = nullptr; lbfgsb_auglag_destroy(al); return fail(LBFGSB_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
+    launch_fill_zero(al->beta_c, 3 * slot, al->stream);
+    e = hipStreamSynchronize(al->stream);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) { lbfgsb_auglag_destroy(al); return fail(LBFGSB_E_HIP, "initialising: %s", hipGetErrorString(e)); }
+    *out = al;
+    return LBFGSB_OK;
+}
+
 void lbfgsb_auglag_destroy(lbfgsb_auglag* al) {
     if (!al) return;
     lbfgsb_destroy(al->inner);
@@ -888,7 +1008,7 @@ int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info*
             // new targets/weights: the objective changed, so f and g are re-evaluated at x and the pair memory is cleared
             hipLaunchKernelGGL(k_al_prepare, dim3(pb), dim3(256), 0, al->stream, al->n_eq, al->rho, al->d_c, al->lambda,
                                al->beta_c, al->omega_c);
-            rc = lbfgsb_set_x(s, s->bf.x);
+            rc = set_x_impl(s, s->bf.x, true);
             if (rc) return rc;
         }
         lbfgsb_info ii;

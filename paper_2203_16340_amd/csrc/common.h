@@ -18,6 +18,8 @@ constexpr int kLsBatch = 8;        // step lengths the logistic line search eval
 
 // Which per-kernel arrival counter (Scal::counters) a kernel uses to find its last workgroup.
 enum { kCntGram = 0, kCntDir, kCntUpdate, kCntEvalFinish, kCntLs, kCntSpec, kCntCount };
+constexpr int kDirBlocksMax = 1024;   // workgroups of the direction kernel, at most
+constexpr int kOtRpwMax = 16;      // rows of P one workgroup of the marginal-sum kernel owns, at most
 
 // All scalars of the iteration live here, in device memory, so that no data-dependent decision
 // needs the host.  Only the last workgroup of a kernel to finish ever writes it; every other
@@ -59,6 +61,14 @@ struct Dims {
 };
 
 constexpr int kMaxExtra = 64;
+
+__host__ __device__ inline bool is_transport(int kind) {
+    return kind == LBFGSB_OBJ_OT_GAUSS || kind == LBFGSB_OBJ_OT_ENTROPY;
+}
+// entries of the row vectors (Buffers::row, t, psi): rows of A, or the rows + cols marginals of the transport kinds
+__host__ __device__ inline int64_t row_entries(int kind, int64_t rows, int64_t cols) {
+    return is_transport(kind) ? rows + cols : rows;
+}
 
 struct Opts {
     double eps, c1, backtrack, tol;
@@ -190,6 +200,53 @@ __device__ __forceinline__ double sigmoid_d(double t) {
     return e / (1.0 + e);
 }
 
+// ---- helpers shared by the column-wise consumers of the A pass ---------------------------------------------
+
+constexpr int kCX = 16;             // columns per workgroup
+constexpr int kGY = kBlock / kCX;   // partial-row groups per workgroup
+
+// Sum over the A pass's partial columns for column c0 + (tid % kCX); valid in threads with tid < kCX.
+__device__ __forceinline__ double column_sum(const double* __restrict__ wpart, int parts, int64_t cols, int64_t c,
+                                             double* lds /* kBlock doubles */) {
+    const int cx = threadIdx.x % kCX, gy = threadIdx.x / kCX;
+    double s = 0.0;
+    if (c < cols) {
+        for (int k0 = gy; k0 < parts; k0 += kGY * 8) {
+            double v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int kk = k0 + kGY * k;
+                v[k] = kk < parts ? wpart[(int64_t)kk * cols + c] : 0.0;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) s += v[k];
+        }
+    }
+    __syncthreads();
+    lds[gy * kCX + cx] = s;
+    __syncthreads();
+    double tot = 0.0;
+    if (gy == 0) {
+#pragma unroll
+        for (int k = 0; k < kGY; ++k) tot += lds[k * kCX + cx];
+    }
+    return tot;
+}
+
+// Sum of `count` doubles, identical in every workgroup that calls it (same order everywhere).
+__device__ __forceinline__ double sum_all(const double* __restrict__ v, int count, double* lds) {
+    double s[1] = {0.0};
+    for (int k0 = threadIdx.x; k0 < count; k0 += kBlock * 8) {
+        double t[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t[k] = k0 + kBlock * k < count ? v[k0 + kBlock * k] : 0.0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s[0] += t[k];
+    }
+    block_sum<1, kWaves>(s, lds);
+    return s[0];
+}
+
 // ---- launch geometry decided once at creation -------------------------------------------------------
 
 struct Geometry {
@@ -205,6 +262,9 @@ struct Geometry {
     int fused_blocks;       // workgroups = partial vectors per column and loss partials
     // vector kernels
     int gram_blocks, dir_blocks, upd_blocks, fin_blocks, ls_blocks;
+    // transport kinds: workgroups of the marginal-sum kernel (each owns ot_rpw consecutive rows of P), of the
+    // column-sum kernel, and of the entrywise kernels
+    int ot_row_blocks, ot_rpw, ot_col_blocks, ot_el_blocks;
     // partial counts consumers have to sum
     int w_parts;            // partial vectors per column written by the A pass in use
     int loss_parts;         // loss partials written by the A pass in use
@@ -273,7 +333,7 @@ void launch_set_status(const Buffers& bf, int status, hipStream_t st);
 void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* lin, const double* sign,
                         hipStream_t st);   // lin, sign: QP only (linear term b, sign vector)
 void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int dbg_inputs,
-                 int evaluate_stop, hipStream_t st);
+                 int evaluate_stop, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 void launch_commit(const Dims& dm, const Buffers& bf, hipStream_t st);
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st);
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
@@ -285,6 +345,22 @@ void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, cons
                         hipStream_t st);
 void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* labels, hipStream_t st);
 void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, hipStream_t st);
+
+// transport kinds (transport.hip).  M: cost matrix; beta/omega: targets and weights of the rows + cols marginal
+// terms (omega null = no such terms).  eval: z = x, residuals against beta -> Buffers::row; else z = the selected
+// direction, K z -> Buffers::t.  Loss partials: ot_row_blocks + ot_col_blocks entries.
+struct OtArgs {
+    const void* M;
+    const double* beta;
+    const double* omega;
+};
+void launch_ot_sums(const Dims& dm, const Geometry& ge, const Buffers& bf, const OtArgs& a, int eval, int check_status,
+                    hipStream_t st);
+void launch_ot_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, const OtArgs& a, hipStream_t st);
+void launch_ot_update_gauss(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const OtArgs& a,
+                            hipStream_t st);
+void launch_ot_step_entropy(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const OtArgs& a,
+                            hipStream_t st);
 
 int gram_entries(int m);          // doubles per workgroup partial of the Gram kernel
 int gram_blocks_for(int64_t n, int m);

@@ -48,10 +48,13 @@ size_t gram_lds_bytes(int m) {
     if (d < 1024) d = 1024;
     return d * 8;
 }
+// Few workgroups keep the last one's sum over the partials short, which is what matters while the vectors are
+// short; from 2^17 entries on, reading the vectors dominates and the whole chip is put to it.
 int gram_blocks_for(int64_t n, int m) {
     const int e = gram_chunk(m);
     int64_t b = (n + e - 1) / e;
-    return (int)(b < 1 ? 1 : (b > 128 ? 128 : b));
+    const int64_t cap = n >= (1 << 17) ? 512 : 128;
+    return (int)(b < 1 ? 1 : (b > cap ? cap : b));
 }
 
 // value of v in lane l (l uniform across the wave): a scalar-register read, not a trip through LDS
@@ -238,11 +241,14 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
     const int nb = gridDim.x;
     double* G = dyn;   // Vp x Vp, row-major
     __shared__ double wsum[kWaves];
-    // statistics header of every workgroup: issued first, used after the G sums
-    const bool have = tid < nb;
-    const double* hp = grampart + (int64_t)tid * NE;
-    double sv[3] = {have ? hp[0] : 0.0, have ? hp[2] : 0.0, have ? hp[3] : 0.0};
-    double mx = have ? hp[1] : 0.0;
+    // statistics header of every workgroup (strided over the threads): issued first, used after the G sums
+    double sv[3] = {0.0, 0.0, 0.0};
+    double mx = 0.0;
+    for (int b = tid; b < nb; b += kBlock) {
+        const double* hp = grampart + (int64_t)b * NE;
+        sv[0] += hp[0]; sv[1] += hp[2]; sv[2] += hp[3];
+        mx = fmax(mx, hp[1]);
+    }
     // one thread per entry adds the partials in workgroup order, 24 loads in flight (larger batches
     // measured no faster: one compute unit's load bandwidth is the limit once there are ~100 partials)
     for (int q4 = tid; q4 < 4 * TT; q4 += kBlock) {
@@ -263,7 +269,7 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
     }
     LB_TICK(5);
     {
-        // per-workgroup statistics (at most 128 workgroups, one thread each): fixed-order reductions
+        // per-workgroup statistics: fixed-order reductions
         block_sum<3, kWaves>(sv, red);
         mx = wave_max(mx);
         __syncthreads();
@@ -361,10 +367,10 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
 }
 
 void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int dbg_inputs,
-                 int evaluate_stop, hipStream_t st) {
-    hipLaunchKernelGGL(k_gram, dim3(ge.gram_blocks), dim3(kBlock), gram_lds_bytes(dm.m), st, dm.n, dm.m, gram_chunk(dm.m),
-                       op, bf.x, bf.g, bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart, gram_entries(dm.m), dbg_inputs,
-                       evaluate_stop);
+                 int evaluate_stop, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+    hipExtLaunchKernelGGL(k_gram, dim3(ge.gram_blocks), dim3(kBlock), gram_lds_bytes(dm.m), st, ev0, ev1, 0, dm.n, dm.m,
+                          gram_chunk(dm.m), op, bf.x, bf.g, bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart,
+                          gram_entries(dm.m), dbg_inputs, evaluate_stop);
 }
 
 // Applies a pending update when nothing else is about to (before an evaluation from scratch, and

@@ -97,13 +97,14 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
     }
     if (!arrive_is_last(&scal->counters[kCntDir], &flag)) return;
     {
-        // at most kBlock workgroups wrote partials: one thread each, then the fixed-order reductions
-        double t6[6];
+        // the workgroups' partials, strided over the threads in a fixed order, then the fixed-order reductions
+        double t6[6] = {0, 0, 0, 0, 0, 0};
         double tmin = INFINITY;
-        const bool have = tid < (int)gridDim.x;
+        for (int b = tid; b < (int)gridDim.x; b += kBlock) {
 #pragma unroll
-        for (int k = 0; k < 6; ++k) t6[k] = have ? redpart[(int64_t)tid * kDirRed + k] : 0.0;
-        if (have) tmin = redpart[(int64_t)tid * kDirRed + 6];
+            for (int k = 0; k < 6; ++k) t6[k] += redpart[(int64_t)b * kDirRed + k];
+            tmin = fmin(tmin, redpart[(int64_t)b * kDirRed + 6]);
+        }
         block_sum<6, kWaves>(t6, red);
         tmin = wave_min(tmin);
         __syncthreads();
@@ -133,53 +134,6 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st) {
     hipLaunchKernelGGL(k_dir, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u, bf.mask,
                        bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given);
-}
-
-// ---- helpers shared by the column-wise consumers of the A pass ---------------------------------------------
-
-constexpr int kCX = 16;             // columns per workgroup
-constexpr int kGY = kBlock / kCX;   // partial-row groups per workgroup
-
-// Sum over the A pass's partial columns for column c0 + (tid % kCX); valid in threads with tid < kCX.
-__device__ __forceinline__ double column_sum(const double* __restrict__ wpart, int parts, int64_t cols, int64_t c,
-                                             double* lds /* kBlock doubles */) {
-    const int cx = threadIdx.x % kCX, gy = threadIdx.x / kCX;
-    double s = 0.0;
-    if (c < cols) {
-        for (int k0 = gy; k0 < parts; k0 += kGY * 8) {
-            double v[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int kk = k0 + kGY * k;
-                v[k] = kk < parts ? wpart[(int64_t)kk * cols + c] : 0.0;
-            }
-#pragma unroll
-            for (int k = 0; k < 8; ++k) s += v[k];
-        }
-    }
-    __syncthreads();
-    lds[gy * kCX + cx] = s;
-    __syncthreads();
-    double tot = 0.0;
-    if (gy == 0) {
-#pragma unroll
-        for (int k = 0; k < kGY; ++k) tot += lds[k * kCX + cx];
-    }
-    return tot;
-}
-
-// Sum of `count` doubles, identical in every workgroup that calls it (same order everywhere).
-__device__ __forceinline__ double sum_all(const double* __restrict__ v, int count, double* lds) {
-    double s[1] = {0.0};
-    for (int k0 = threadIdx.x; k0 < count; k0 += kBlock * 8) {
-        double t[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) t[k] = k0 + kBlock * k < count ? v[k0 + kBlock * k] : 0.0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) s[0] += t[k];
-    }
-    block_sum<1, kWaves>(s, lds);
-    return s[0];
 }
 
 // ---- after an evaluation pass: g and f ------------------------------------------------------------------

@@ -58,6 +58,11 @@ def test_value_gradient_and_difference_form(kind, with_marginals):
     for scale in (0.04, 1e-4, 1e-9):
         xt = x + scale * rng.standard_normal(x.size)
         assert oracle.delta_f(obj, x, xt, row) == pytest.approx(oracle.f_only(obj, xt) - f, rel=1e-6, abs=1e-14 * abs(f))
+    # a step onto a tiny positive bound (the relative change rounds to -1): still the difference of the values
+    xt = x.copy()
+    xt[:4] = 1e-30
+    assert np.isfinite(oracle.delta_f(obj, x, xt, row))
+    assert oracle.delta_f(obj, x, xt, row) == pytest.approx(oracle.f_only(obj, xt) - f, rel=1e-9)
     # entries at zero: 0 log 0 = 0, and the difference form handles a zero at either end
     xz, xt = x.copy(), x.copy()
     xz[:5] = 0.0
