@@ -50,6 +50,7 @@ struct lbfgsb_solver {
     Scal* h_scal;            // pinned host copy
     int use_fused;
     int steps_since_refresh;
+    long long steps_since_set_x;
     bool x_set;
     // timing
     bool timing;
@@ -158,7 +159,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     if (ge.ls_blocks > lparts) lparts = ge.ls_blocks;
     if (is_transport(dm.kind) && ge.ot_row_blocks + ge.ot_col_blocks > lparts) lparts = ge.ot_row_blocks + ge.ot_col_blocks;
     L.losspart = take((size_t)lparts * 8);
-    L.grampart = take((size_t)ge.gram_blocks * gram_entries(dm.m) * 8);
+    L.grampart = take(gram_partial_bytes(dm.n, dm.m));
     size_t red = (size_t)ge.dir_blocks * 8;
     if ((size_t)ge.upd_blocks * 2 > red) red = (size_t)ge.upd_blocks * 2;
     if (is_transport(dm.kind) && (size_t)ge.ot_el_blocks > red) red = (size_t)ge.ot_el_blocks;
@@ -203,8 +204,8 @@ void fill_info(const Scal& sc, lbfgsb_info* info) {
 // Events for the next launch of a kernel that reads A (null when timing is off or the store is full).
 struct TimedSlot {
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    explicit TimedSlot(lbfgsb_solver* s) {
-        if (s->timing && s->timed < kMaxTimed) {
+    explicit TimedSlot(lbfgsb_solver* s, bool wanted = true) {
+        if (wanted && s->timing && s->timed < kMaxTimed) {
             e0 = s->ev0[s->timed];
             e1 = s->ev1[s->timed];
             s->timed++;
@@ -271,13 +272,18 @@ void enqueue_step(lbfgsb_solver* s) {
     if (is_transport(s->dm.kind)) {
         // no matrix product: the iteration streams the pair memory twice (Gram matrix, direction) and the
         // iterate-sized vectors a few times.  The Gram kernel is the longest and the one that is timed.
-        { TimedSlot ts(s); launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream, ts.e0, ts.e1); }
+        // (timed only once the pair memory is full, so that every timed launch moves the same bytes)
+        {
+            TimedSlot ts(s, s->steps_since_set_x >= s->dm.m);
+            launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream, ts.e0, ts.e1);
+        }
         launch_dir(s->dm, s->op, s->ge, s->bf, 0, s->stream);
         const OtArgs oa = ot_args(s);
         launch_ot_sums(s->dm, s->ge, s->bf, oa, 0, 1, s->stream);
         if (quad) launch_ot_update_gauss(s->dm, s->op, s->ge, s->bf, oa, s->stream);
         else launch_ot_step_entropy(s->dm, s->op, s->ge, s->bf, oa, s->stream);
         s->steps_since_refresh++;
+        s->steps_since_set_x++;
         return;
     }
     launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
@@ -358,6 +364,7 @@ int set_x_impl(lbfgsb_solver* s, const double* x0, bool trusted) {
     HIP_TRY(write_scal(s));
     enqueue_eval(s, 0);
     s->steps_since_refresh = 0;
+    s->steps_since_set_x = 0;
     if (!trusted) HIP_TRY(hipMemcpyAsync(hx.data(), s->bf.g, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
     HIP_TRY(read_scal(s));
     HIP_TRY(hipGetLastError());
@@ -419,6 +426,7 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
     s->stream = (hipStream_t)hip_stream;
     s->h_scal = nullptr;
     s->steps_since_refresh = 0;
+    s->steps_since_set_x = 0;
     s->x_set = false;
     s->timing = false;
     s->timed = 0;
@@ -430,6 +438,13 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
     if (o.a_pass == LBFGSB_APASS_FUSED && !s->ge.fused_ok) {
         delete s;
         return fail(LBFGSB_E_UNSUPPORTED, "the fused A pass does not support this shape");
+    }
+    {
+        const hipError_t ge_ = gram_prepare(n, m);
+        if (ge_ != hipSuccess) {
+            delete s;
+            return fail(LBFGSB_E_HIP, "preparing the Gram kernel: %s", hipGetErrorString(ge_));
+        }
     }
     s->use_fused = s->ge.fused_ok && o.a_pass != LBFGSB_APASS_TWO_PASS;
     if (s->use_fused) {
@@ -591,9 +606,13 @@ int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count, double* total_ms, doub
     *count = n;
     *total_ms = tot;
     *bytes_per_pass = (double)s->dm.rows * (double)s->dm.cols * (s->dm.dtype == LBFGSB_F32 ? 4.0 : 8.0);
-    // transport kinds: the timed kernel is the Gram kernel; with all m pairs stored it reads the 2m pair vectors
-    // and x, g, l, u once each and writes the one-byte free mask
-    if (is_transport(s->dm.kind)) *bytes_per_pass = (double)s->dm.n * ((2.0 * s->dm.m + 4.0) * 8.0 + 1.0);
+    // transport kinds: the timed kernel is the Gram kernel, timed in iterations m, m+1, ... after lbfgsb_set_x, when
+    // all m pairs are stored.  It reads x, g, l, u and the newest y in full and writes the one-byte free mask; the
+    // 2m pair vectors are read at the free variables only (count taken from the last status the host has seen)
+    if (is_transport(s->dm.kind)) {
+        const double n_free = (double)(s->dm.n - s->h_scal->n_fixed);
+        *bytes_per_pass = (double)s->dm.n * 41.0 + n_free * 2.0 * s->dm.m * 8.0;
+    }
     return LBFGSB_OK;
 }
 

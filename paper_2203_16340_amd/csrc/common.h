@@ -19,6 +19,7 @@ constexpr int kLsBatch = 8;        // step lengths the logistic line search eval
 // Which per-kernel arrival counter (Scal::counters) a kernel uses to find its last workgroup.
 enum { kCntGram = 0, kCntDir, kCntUpdate, kCntEvalFinish, kCntLs, kCntSpec, kCntCount };
 constexpr int kDirBlocksMax = 1024;   // workgroups of the direction kernel, at most
+constexpr int kGramGroups = 16;    // large-n Gram kernel: groups of workgroups whose partials are summed first
 constexpr int kOtRpwMax = 16;      // rows of P one workgroup of the marginal-sum kernel owns, at most
 
 // All scalars of the iteration live here, in device memory, so that no data-dependent decision
@@ -51,6 +52,7 @@ struct Scal {
     double ynorm2[kMaxM + 1];   // ||y||^2 over the full vector, per ring slot
     double delta[kMaxV];        // coefficients of q = sum_j delta_j b_j in the batched two-loop
     unsigned counters[kCntCount];
+    unsigned gram_cnt[kGramGroups + 1];   // two-level arrival of the large-n Gram kernel: one per group, then the top
 };
 
 struct Dims {
@@ -122,12 +124,12 @@ __device__ __forceinline__ void block_sum(double (&v)[K], double* lds /* NW*K do
 // extends that to the other waves.  Fencing in every wave instead costs ~60 ns per workgroup of
 // serialised time on MI355X.  The last workgroup resets the counter for the next launch.  Must be
 // called by all threads of the workgroup.
-__device__ __forceinline__ bool arrive_is_last(unsigned* counter, int* lds_flag) {
+__device__ __forceinline__ bool arrive_is_last(unsigned* counter, int* lds_flag, unsigned expected = 0u) {
     __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0) expcnt(0) lgkmcnt(0): this wave's stores have reached L2
     __syncthreads();
     if (threadIdx.x == 0) {
         __threadfence();
-        const unsigned total = gridDim.x * gridDim.y;
+        const unsigned total = expected ? expected : gridDim.x * gridDim.y;   // expected: arrivals at this counter
         const unsigned old = atomicAdd(counter, 1u);
         const int last = old == total - 1u;
         if (last) {
@@ -362,7 +364,8 @@ void launch_ot_update_gauss(const Dims& dm, const Opts& op, const Geometry& ge, 
 void launch_ot_step_entropy(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const OtArgs& a,
                             hipStream_t st);
 
-int gram_entries(int m);          // doubles per workgroup partial of the Gram kernel
 int gram_blocks_for(int64_t n, int m);
+size_t gram_partial_bytes(int64_t n, int m);   // Buffers::grampart
+hipError_t gram_prepare(int64_t n, int m);     // once per solver, before the first launch_gram
 
 }  // namespace lb

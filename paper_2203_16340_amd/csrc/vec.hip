@@ -30,6 +30,58 @@ void launch_set_status(const Buffers& bf, int status, hipStream_t st) {
 
 constexpr int kDirRed = 8;   // p1.g, p1.p1, x.p1, p2.g, p2.p2, x.p2, min step bound of p2, unused
 
+// Partial sums of the direction kernels -> Algorithm 2's choice between the two candidate directions (last workgroup).
+__device__ __forceinline__ void dir_finish(double (&s)[6], double ub, double eps, Scal* __restrict__ scal,
+                                           double* __restrict__ redpart, double* red, int* flag_p) {
+    const int tid = threadIdx.x;
+    block_sum<6, kWaves>(s, red);
+    double mn = wave_min(ub);
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = mn;
+    __syncthreads();
+    if (tid == 0) {
+        mn = red[0];
+        for (int w = 1; w < kWaves; ++w) mn = fmin(mn, red[w]);
+        double* part = redpart + (int64_t)blockIdx.x * kDirRed;
+        for (int k = 0; k < 6; ++k) part[k] = s[k];
+        part[6] = mn;
+    }
+    if (!arrive_is_last(&scal->counters[kCntDir], flag_p)) return;
+    {
+        // the workgroups' partials, strided over the threads in a fixed order, then the fixed-order reductions
+        double t6[6] = {0, 0, 0, 0, 0, 0};
+        double tmin = INFINITY;
+        for (int b = tid; b < (int)gridDim.x; b += kBlock) {
+#pragma unroll
+            for (int k = 0; k < 6; ++k) t6[k] += redpart[(int64_t)b * kDirRed + k];
+            tmin = fmin(tmin, redpart[(int64_t)b * kDirRed + 6]);
+        }
+        block_sum<6, kWaves>(t6, red);
+        tmin = wave_min(tmin);
+        __syncthreads();
+        if ((tid & 63) == 0) red[tid >> 6] = tmin;
+        __syncthreads();
+        if (tid == 0) {
+            tmin = red[0];
+            for (int w = 1; w < kWaves; ++w) tmin = fmin(tmin, red[w]);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int k = 0; k < 6; ++k) red[k] = t6[k];
+            red[6] = tmin;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const double p1g = red[0], p1p1 = red[1];
+        if (p1g <= -eps * p1p1 && p1p1 >= eps) {
+            scal->branch = 1; scal->gp = p1g; scal->alpha_ub = 1.0; scal->pp = p1p1; scal->xp = red[2];
+        } else {
+            scal->branch = 2; scal->gp = red[3]; scal->alpha_ub = red[6]; scal->pp = red[4]; scal->xp = red[5];
+        }
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const double* __restrict__ x,
                                                 const double* __restrict__ g, const double* __restrict__ l,
                                                 const double* __restrict__ u, const uint8_t* __restrict__ mask,
@@ -83,55 +135,122 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
         if (b > 0.0) ub = fmin(ub, (ue - xe) / b);
         else if (b < 0.0) ub = fmin(ub, (le - xe) / b);
     }
-    block_sum<6, kWaves>(s, red);
-    double mn = wave_min(ub);
+    dir_finish(s, ub, op.eps, scal, redpart, red, &flag);
+}
+
+// The same for long vectors (n even, from 2^17 entries on): two elements per lane through 16-byte accesses; lanes
+// whose elements are fixed skip the pair memory.
+typedef double dir_f64x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void dir_element(double xe, double ge, double le, double ue, double de, double eps, double& a,
+                                            double& b, double (&s)[6], double& ub) {
+    a = clampd(xe + de, le, ue) - xe;
+    b = de;
+    if (de < 0.0 && xe <= le + eps) b = 0.0;
+    if (de > 0.0 && xe >= ue - eps) b = 0.0;
+    s[0] = fma(a, ge, s[0]); s[1] = fma(a, a, s[1]); s[2] = fma(xe, a, s[2]);
+    s[3] = fma(b, ge, s[3]); s[4] = fma(b, b, s[4]); s[5] = fma(xe, b, s[5]);
+    if (b > 0.0) ub = fmin(ub, (ue - xe) / b);
+    else if (b < 0.0) ub = fmin(ub, (le - xe) / b);
+}
+
+__global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op, const double* __restrict__ x,
+                                                      const double* __restrict__ g, const double* __restrict__ l,
+                                                      const double* __restrict__ u, const uint8_t* __restrict__ mask,
+                                                      const double* __restrict__ S, const double* __restrict__ Y,
+                                                      Scal* __restrict__ scal, double* __restrict__ d,
+                                                      double* __restrict__ p1, double* __restrict__ p2,
+                                                      double* __restrict__ redpart, int d_given) {
+    __shared__ double delta_s[kMaxV + 24];
+    __shared__ double red[kWaves * 7];
+    __shared__ int flag;
+#ifdef LB_EXP_DIRTICKS
+    const unsigned long long tk0 = wall_clock64();
+#endif
+    if (scal->status != LBFGSB_RUNNING) return;
+    const int tid = threadIdx.x;
+    const int c = scal->count, head = scal->head;
+    const int V = 2 * c + 1;
+    if (tid < kMaxV + 24) delta_s[tid] = tid < V ? scal->delta[tid] : 0.0;
     __syncthreads();
-    if ((tid & 63) == 0) red[tid >> 6] = mn;
-    __syncthreads();
-    if (tid == 0) {
-        mn = red[0];
-        for (int w = 1; w < kWaves; ++w) mn = fmin(mn, red[w]);
-        double* part = redpart + (int64_t)blockIdx.x * kDirRed;
-        for (int k = 0; k < 6; ++k) part[k] = s[k];
-        part[6] = mn;
-    }
-    if (!arrive_is_last(&scal->counters[kCntDir], &flag)) return;
-    {
-        // the workgroups' partials, strided over the threads in a fixed order, then the fixed-order reductions
-        double t6[6] = {0, 0, 0, 0, 0, 0};
-        double tmin = INFINITY;
-        for (int b = tid; b < (int)gridDim.x; b += kBlock) {
-#pragma unroll
-            for (int k = 0; k < 6; ++k) t6[k] += redpart[(int64_t)b * kDirRed + k];
-            tmin = fmin(tmin, redpart[(int64_t)b * kDirRed + 6]);
-        }
-        block_sum<6, kWaves>(t6, red);
-        tmin = wave_min(tmin);
-        __syncthreads();
-        if ((tid & 63) == 0) red[tid >> 6] = tmin;
-        __syncthreads();
-        if (tid == 0) {
-            tmin = red[0];
-            for (int w = 1; w < kWaves; ++w) tmin = fmin(tmin, red[w]);
-        }
-        __syncthreads();
-        if (tid == 0) {
-            for (int k = 0; k < 6; ++k) red[k] = t6[k];
-            red[6] = tmin;
-        }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        const double p1g = red[0], p1p1 = red[1];
-        if (p1g <= -op.eps * p1p1 && p1p1 >= op.eps) {
-            scal->branch = 1; scal->gp = p1g; scal->alpha_ub = 1.0; scal->pp = p1p1; scal->xp = red[2];
+    double s[6] = {0, 0, 0, 0, 0, 0};
+    double ub = INFINITY;
+    const int64_t nchunks = (n + 2 * kBlock - 1) / (2 * kBlock);
+    // the mask decides which lanes read the pair memory at all, so it (with x, g, l, u) is fetched one chunk ahead
+    auto pair_index = [&](int64_t ch, bool& in) -> int64_t {
+        const int64_t e = ch * (2 * kBlock) + 2 * tid;
+        in = ch < nchunks && e < n;                              // n is even: both elements or neither
+        return in ? e : n - 2;
+    };
+    bool in_next;
+    int64_t ec_next = pair_index(blockIdx.x, in_next);
+    dir_f64x2 xn = *reinterpret_cast<const dir_f64x2*>(x + ec_next), gn = *reinterpret_cast<const dir_f64x2*>(g + ec_next);
+    dir_f64x2 ln = *reinterpret_cast<const dir_f64x2*>(l + ec_next), un = *reinterpret_cast<const dir_f64x2*>(u + ec_next);
+    unsigned short mkn = *reinterpret_cast<const unsigned short*>(mask + ec_next);
+    for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+        const bool in = in_next;
+        const int64_t ec = ec_next, e = ec_next;
+        const dir_f64x2 xe = xn, ge = gn, le = ln, ue = un;
+        const unsigned short mk = in ? mkn : (unsigned short)0;
+        ec_next = pair_index(ch + gridDim.x, in_next);
+        xn = *reinterpret_cast<const dir_f64x2*>(x + ec_next); gn = *reinterpret_cast<const dir_f64x2*>(g + ec_next);
+        ln = *reinterpret_cast<const dir_f64x2*>(l + ec_next); un = *reinterpret_cast<const dir_f64x2*>(u + ec_next);
+        mkn = *reinterpret_cast<const unsigned short*>(mask + ec_next);
+        dir_f64x2 de;
+        if (d_given) {
+            de = *reinterpret_cast<const dir_f64x2*>(d + ec);
         } else {
-            scal->branch = 2; scal->gp = red[3]; scal->alpha_ub = red[6]; scal->pp = red[4]; scal->xp = red[5];
+            double q0 = 0.0, q1 = 0.0;
+            if (mk != 0) {                                       // lanes whose two elements are both fixed read nothing
+                // 24 vectors per round: with m <= 11 every load of an element is in flight at once
+                for (int j0 = 0; j0 < V; j0 += 24) {
+                    dir_f64x2 v[24];
+#pragma unroll
+                    for (int k = 0; k < 24; ++k) {
+                        v[k] = dir_f64x2{0.0, 0.0};
+                        if (j0 + k < V) v[k] = *reinterpret_cast<const dir_f64x2*>(ring_vec(j0 + k, c, head, m, n, S, Y, g) + ec);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 24; ++k) {
+                        q0 = fma(delta_s[j0 + k], v[k].x, q0);
+                        q1 = fma(delta_s[j0 + k], v[k].y, q1);
+                    }
+                }
+            }
+            de.x = (mk & 0xffu) ? -q0 : 0.0;
+            de.y = (mk >> 8) ? -q1 : 0.0;
+            if (in) *reinterpret_cast<dir_f64x2*>(d + e) = de;
+        }
+        if (in) {
+            double a0, b0, a1, b1;
+            dir_element(xe.x, ge.x, le.x, ue.x, de.x, op.eps, a0, b0, s, ub);
+            dir_element(xe.y, ge.y, le.y, ue.y, de.y, op.eps, a1, b1, s, ub);
+            *reinterpret_cast<dir_f64x2*>(p1 + e) = dir_f64x2{a0, a1};
+            *reinterpret_cast<dir_f64x2*>(p2 + e) = dir_f64x2{b0, b1};
         }
     }
+#ifdef LB_EXP_DIRTICKS
+    const unsigned long long tk1 = wall_clock64();
+    if (tid == 0 && blockIdx.x == 0) redpart[7] = (double)tk0;
+#endif
+    dir_finish(s, ub, op.eps, scal, redpart, red, &flag);
+#ifdef LB_EXP_DIRTICKS
+    // (only the last workgroup returns from dir_finish with flag set)
+    if (flag && tid == 0) {
+        const unsigned long long tk2 = wall_clock64();
+        scal->pg2 = (double)tk1 - redpart[7];     // kernel start (workgroup 0) -> last workgroup's loop done
+        scal->pginf = (double)(tk2 - tk1);        // tail
+        scal->f = (double)(tk1 - tk0);            // last workgroup's own prologue + loop
+    }
+#endif
 }
 
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st) {
+    if (dm.n >= (1 << 17) && dm.n % 2 == 0) {
+        hipLaunchKernelGGL(k_dir_pairs, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u,
+                           bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given);
+        return;
+    }
     hipLaunchKernelGGL(k_dir, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u, bf.mask,
                        bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given);
 }

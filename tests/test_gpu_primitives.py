@@ -127,7 +127,8 @@ def test_free_mask_truth_table_bit_exact():
     s.close()
 
 
-@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 8191, 40000])
+# (from 2^17 even entries on, the free set is evaluated inside the matrix-core Gram kernel: ragged last chunk, odd n)
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 8191, 40000, 131072, 200002, 131073, 1048610])
 def test_free_mask_random_bit_exact(n):
     rng = np.random.default_rng(n)
     eps = 1e-3
@@ -169,7 +170,11 @@ def _two_loop_case(n, k, m, seed, frac_bad=0.3, eps=1e-10):
 
 
 @pytest.mark.parametrize("n,k,m", [(1, 0, 3), (5, 1, 1), (64, 3, 5), (65, 5, 5), (1000, 10, 10), (4097, 7, 10),
-                                   (20000, 20, 20), (40000, 10, 10), (513, 31, 31)])
+                                   (20000, 20, 20), (40000, 10, 10), (513, 31, 31),
+                                   # matrix-core Gram kernel (n >= 2^17, even): one, two and four 16-vector blocks,
+                                   # memory not yet full, no pair at all, a last chunk of 2 elements; odd n (other kernel)
+                                   (131072, 5, 5), (200002, 10, 10), (140000, 3, 10), (131074, 12, 12), (150000, 20, 20),
+                                   (131200, 31, 31), (131072, 0, 10), (1048576, 7, 7), (131073, 6, 10)])
 def test_two_loop_parity_synthetic_pairs(n, k, m):
     S, Y, yn, g, mask = _two_loop_case(n, k, m, seed=n + 13 * k)
     eps = 1e-10
@@ -242,7 +247,7 @@ def test_project_direction_worked_cases():
         s.close()
 
 
-@pytest.mark.parametrize("n,seed", [(1, 0), (7, 1), (64, 2), (300, 3), (5000, 4), (40000, 5)])
+@pytest.mark.parametrize("n,seed", [(1, 0), (7, 1), (64, 2), (300, 3), (5000, 4), (40000, 5), (131072, 6), (200002, 7), (131073, 8)])
 @pytest.mark.parametrize("dscale", [1e-7, 1e-3, 1.0])
 def test_project_direction_random_parity(n, seed, dscale):
     rng = np.random.default_rng(seed * 101 + n)
