@@ -180,10 +180,12 @@ def bench_transport(args, L, workloads, np, torch, dev) -> int:
     t_gen = time.perf_counter()
     p = workloads.joint_probability(size, dataset=dataset, reg=reg, seed=4001)
     t_gen = time.perf_counter() - t_gen
-    # stopping rule: ||grad L [S]|| <= 1e-6 max(1, its value at x0) per inner solve, marginals to 1e-6 (the paper
-    # reports absolute errors of 1e-3 .. 1e-5 on this problem).  Entries of P are ~1e-6 at this size, so the
-    # entropy runs with the paper's epsilon below that scale (Eq. (ws) freezes a variable within epsilon of its bound).
-    tol, ctol = 1e-6, 1e-6
+    # Stopping rule.  Gaussian regulariser: ||grad L [S]|| <= 1e-6 max(1, its value at the inner solve's start), marginals
+    # to 1e-6.  Entropy: 1e-4 for both, the accuracy the paper reports for this experiment (absolute errors of 1e-3 ..
+    # 1e-5): its Hessian lambda/P spans many orders of magnitude, and pushed much further the penalty parameter has to
+    # grow until the inner solves stop converging.  Entries of P are ~1e-6 at this size, so the entropy runs with the
+    # paper's epsilon below that scale (Eq. (ws) freezes a variable within epsilon of its bound).
+    tol, ctol = (1e-6, 1e-6) if reg == "gauss" else (1e-4, 1e-4)
     eps = 1e-10 if reg == "gauss" else 1e-20
     M_d = torch.from_numpy(p.M).to(dev)
     marg = torch.from_numpy(np.concatenate([p.u, p.v])).to(dev)

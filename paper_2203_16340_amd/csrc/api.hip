@@ -128,9 +128,9 @@ Geometry make_geometry(const Dims& dm, const void* A) {
         ge.ot_row_blocks = (int)((dm.rows + rpw - 1) / rpw);
         int64_t cb = (dm.cols + kCX - 1) / kCX;
         ge.ot_col_blocks = (int)(cb > 2048 ? 2048 : cb);
-        ge.ot_el_blocks = (int)(dm.rows > 2048 ? 2048 : dm.rows);
+        ge.ot_el_blocks = (int)(dm.rows > 512 ? 512 : dm.rows);
         int64_t eb = (dm.n + kBlock - 1) / kBlock;
-        ge.ls_blocks = (int)(eb > 1024 ? 1024 : eb);
+        ge.ls_blocks = (int)(eb > 512 ? 512 : eb);
     }
     return ge;
 }
@@ -164,7 +164,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     if ((size_t)ge.upd_blocks * 2 > red) red = (size_t)ge.upd_blocks * 2;
     if (is_transport(dm.kind) && (size_t)ge.ot_el_blocks > red) red = (size_t)ge.ot_el_blocks;
     L.redpart = take(red * 8);
-    L.lspart = take((size_t)ge.ls_blocks * kLsBatch * 8);
+    L.lspart = take((size_t)ge.ls_blocks * 32 * 8);   // up to 32 step lengths per sweep (entropy line search)
     L.wextra = take(dm.n_extra > 0 ? (size_t)dm.n * 8 : 8);
     L.xres = take((size_t)(dm.n_extra + 1) * 8);
     L.total = off;

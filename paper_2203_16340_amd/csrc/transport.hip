@@ -202,53 +202,62 @@ __device__ __forceinline__ double entropy_h(double r) {
     return (1.0 + r) * log1p(r) - r;
 }
 
-__global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int loss_parts,
+// NTRY step lengths a0 backtrack^first, ... per sweep over (x, p).  The first launch tries two; further launches,
+// which return at once when an earlier one found the step, try the next kLsBatch and then kLsTail at a time (a
+// long run of rejected steps happens at a start on the lower bound, where p/x is huge).  Only beyond those does the
+// last workgroup of the last launch go on alone, one length at a time.
+constexpr int kLsTail = 26;   // 2 + kLsBatch + 2 kLsTail = 62 step lengths cover the default limit of 60 backtracks
+
+template <int NTRY>
+__global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int loss_parts, int first, int last_resort,
                                                           const double* __restrict__ losspart,
                                                           const double* __restrict__ x, const double* __restrict__ p1,
                                                           const double* __restrict__ p2, Scal* __restrict__ scal,
                                                           double* __restrict__ lspart) {
-    __shared__ double red[kWaves * kLsBatch];
+    __shared__ double red[kWaves * NTRY];
     __shared__ int flag;
     if (scal->status != LBFGSB_RUNNING) return;
+    if (first > 0 && scal->ls_ok) return;            // an earlier launch of this iteration found the step
     const int tid = threadIdx.x;
     const double* p = scal->branch == 1 ? p1 : p2;
-    const double a0 = fmin(1.0, scal->alpha_ub);
-    double al[kLsBatch], s[kLsBatch];
+    double al[NTRY], s[NTRY];
     {
-        double v = a0;
+        double v = fmin(1.0, scal->alpha_ub);
+        for (int k = 0; k < first; ++k) v *= op.backtrack;
 #pragma unroll
-        for (int k = 0; k < kLsBatch; ++k) { al[k] = v; s[k] = 0.0; v *= op.backtrack; }
+        for (int k = 0; k < NTRY; ++k) { al[k] = v; s[k] = 0.0; v *= op.backtrack; }
     }
     for (int64_t e = (int64_t)blockIdx.x * kBlock + tid; e < dm.n; e += (int64_t)gridDim.x * kBlock) {
         const double xe = x[e], ratio = p[e] / xe;
 #pragma unroll
-        for (int k = 0; k < kLsBatch; ++k) s[k] = fma(xe, entropy_h(al[k] * ratio), s[k]);
+        for (int k = 0; k < NTRY; ++k) s[k] = fma(xe, entropy_h(al[k] * ratio), s[k]);
     }
-    block_sum<kLsBatch, kWaves>(s, red);
+    block_sum<NTRY, kWaves>(s, red);
     if (tid == 0) {
 #pragma unroll
-        for (int k = 0; k < kLsBatch; ++k) lspart[(int64_t)blockIdx.x * kLsBatch + k] = s[k];
+        for (int k = 0; k < NTRY; ++k) lspart[(int64_t)blockIdx.x * NTRY + k] = s[k];
     }
     if (!arrive_is_last(&scal->counters[kCntLs], &flag)) return;
     const double gp = scal->gp;
     const double tt = sum_all(losspart, loss_parts, red);
-    double tot[kLsBatch];
+    double tot[NTRY];
 #pragma unroll
-    for (int k = 0; k < kLsBatch; ++k) tot[k] = 0.0;
+    for (int k = 0; k < NTRY; ++k) tot[k] = 0.0;
     for (int b = tid; b < (int)gridDim.x; b += kBlock) {
 #pragma unroll
-        for (int k = 0; k < kLsBatch; ++k) tot[k] += lspart[(int64_t)b * kLsBatch + k];
+        for (int k = 0; k < NTRY; ++k) tot[k] += lspart[(int64_t)b * NTRY + k];
     }
-    block_sum<kLsBatch, kWaves>(tot, red);
+    block_sum<NTRY, kWaves>(tot, red);
     int found = -1;
-    double a_acc = 0.0, df_acc = 0.0;
-    for (int k = 0; k < kLsBatch && k <= op.max_backtracks; ++k) {
+    double a_acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < NTRY; ++k) {
         const double df = al[k] * (gp + 0.5 * al[k] * tt) + dm.lambda * tot[k];
-        if (isfinite(df) && df <= op.c1 * al[k] * gp) { found = k; a_acc = al[k]; df_acc = df; break; }
+        if (found < 0 && first + k <= op.max_backtracks && isfinite(df) && df <= op.c1 * al[k] * gp) { found = first + k; a_acc = al[k]; }
     }
     // rare: continue one step length at a time (every thread holds the same totals: uniform control flow)
-    double av = al[kLsBatch - 1];
-    for (int k = kLsBatch; found < 0 && k <= op.max_backtracks; ++k) {
+    double av = al[NTRY - 1];
+    for (int k = first + NTRY; last_resort && found < 0 && k <= op.max_backtracks; ++k) {
         av *= op.backtrack;
         double sv[1] = {0.0};
         for (int64_t e = tid; e < dm.n; e += kBlock) {
@@ -257,15 +266,16 @@ __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int 
         }
         block_sum<1, kWaves>(sv, red);
         const double df = av * (gp + 0.5 * av * tt) + dm.lambda * sv[0];
-        if (isfinite(df) && df <= op.c1 * av * gp) { found = k; a_acc = av; df_acc = df; }
+        if (isfinite(df) && df <= op.c1 * av * gp) { found = k; a_acc = av; }
     }
     if (tid == 0) {
         scal->ls_ok = found >= 0;
-        scal->backtracks = found >= 0 ? found : op.max_backtracks + 1;
-        scal->fevals += found >= 0 ? found + 1 : op.max_backtracks + 1;
+        if (found >= 0 || last_resort) {
+            scal->backtracks = found >= 0 ? found : op.max_backtracks + 1;
+            scal->fevals += found >= 0 ? found + 1 : op.max_backtracks + 1;
+        }
         if (found >= 0) scal->alpha = a_acc;
     }
-    (void)df_acc;
 }
 
 // x+ = P(x + a p); g+ = M + lambda (log x+ + 1) + K^T (omega . (res + a K p)); pair; f+ from scratch at x+.
@@ -382,9 +392,18 @@ void launch_ot_update_gauss(const Dims& dm, const Opts& op, const Geometry& ge, 
 
 void launch_ot_step_entropy(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const OtArgs& a,
                             hipStream_t st) {
-    hipLaunchKernelGGL(k_ot_ls_entropy, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
-                       ge.ot_row_blocks + ge.ot_col_blocks, (const double*)bf.losspart, (const double*)bf.x,
+    hipLaunchKernelGGL(k_ot_ls_entropy<2>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
+                       ge.ot_row_blocks + ge.ot_col_blocks, 0, 0, (const double*)bf.losspart, (const double*)bf.x,
                        (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
+    hipLaunchKernelGGL(k_ot_ls_entropy<kLsBatch>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
+                       ge.ot_row_blocks + ge.ot_col_blocks, 2, 0, (const double*)bf.losspart, (const double*)bf.x,
+                       (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
+    hipLaunchKernelGGL(k_ot_ls_entropy<kLsTail>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
+                       ge.ot_row_blocks + ge.ot_col_blocks, 2 + kLsBatch, 0, (const double*)bf.losspart,
+                       (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
+    hipLaunchKernelGGL(k_ot_ls_entropy<kLsTail>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
+                       ge.ot_row_blocks + ge.ot_col_blocks, 2 + kLsBatch + kLsTail, 1, (const double*)bf.losspart,
+                       (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
     hipLaunchKernelGGL(k_ot_update_entropy, dim3(ge.ot_el_blocks), dim3(kBlock), 0, st, dm, a, (const double*)bf.row,
                        (const double*)bf.t, (const double*)bf.p1, (const double*)bf.p2, (const double*)bf.l,
                        (const double*)bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, bf.redpart);
