@@ -270,7 +270,7 @@ void lbfgsb_auglag_destroy(lbfgsb_auglag* al);
  * markers) (at most 4096 launches are kept; later ones are not recorded).  enable: 0 =
  * pause (records kept), 1 = resume, 2 = discard the records and start.  lbfgsb_apass_timing
  * synchronises and returns how many launches were timed (launches that returned at once because the
- * solver had already stopped -- duration below half of the longest -- are left out), their total duration in milliseconds
+ * solver had already stopped -- duration below half of the 90th-percentile duration -- are left out), their total duration in milliseconds
  * and the bytes of A one launch requests from memory (rows*cols*sizeof(element): each such
  * kernel reads A exactly once).  The transport kinds have no such kernel: there the Gram kernel of the batched
  * two-loop recursion (the longest kernel of an iteration) is timed instead, from the m-th iteration after
