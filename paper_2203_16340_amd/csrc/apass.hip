@@ -8,9 +8,15 @@
 //              blocks produce partial columns) reads A a second time.
 //   fused    : see fused.hip -- a workgroup owns whole rows, keeps them in registers between the
 //              row dot product and the transposed accumulation, so A is read once.
+// The two-pass kernels serve the shapes the fused kernel does not take (rows wider than its
+// registers and LDS hold, unaligned rows), the transposed product after a rejected first trial
+// step of the logistic objective (skipped when the fused pass's speculative step was accepted:
+// check_status == 2), and the row products of the symmetric quadratic form when forced.
 //
 // The per-row operations (RowMode) are what "compute f and grad f" of Algorithm 1 means for the
-// three objectives, and the t = A p needed by the closed-form line search of the quadratic ones.
+// objectives (least squares with optional per-row weights, L1-split, logistic, the symmetric
+// quadratic form with an optional sign vector applied to v), and the t = A p needed by the
+// closed-form line search of the quadratic ones.
 #include "common.h"
 #include "apass_rowop.h"
 

@@ -13,6 +13,11 @@
 // (pairs that fail the gate have alpha = beta = 0).  Both loops are triangular solves; lane i of one
 // wave owns row i, so a step is one broadcast and one multiply-add, with no cross-lane reduction.
 // G must be rebuilt every iteration because S changes; it costs one pass over the 2c+1 vectors.
+//
+// Three kernels build G, chosen by the length of the vectors: k_gram (tiles of G per thread, operands staged
+// through LDS; a few dozen workgroups, which is what short vectors want), and for n >= 2^17 (even) k_gram_wide
+// (m <= 10: element pairs per lane, entries of G divided among the waves) or k_gram_mfma (m > 10: matrix cores).
+// All three end in the same recursion on coefficients (recursion_on_coefficients).
 #include <cstddef>
 
 #include "common.h"
