@@ -80,6 +80,43 @@ def test_auglag_struct_layouts_and_argument_checks(tmp_path):
     lib.lbfgsb_auglag_destroy(None)
 
 
+def test_transport_kinds_argument_checks():
+    """The matrix-variable kinds: n = rows*cols, lambda > 0, no extra rows; the marginal-constraint entry point takes
+    these kinds only.  No device call is reached."""
+    lib = L.lib()
+    o = L.default_options()
+    ao = L.AuglagOptions()
+    lib.lbfgsb_auglag_default_options(C.byref(ao))
+
+    def ot(kind=L.OBJ_OT_GAUSS, rows=30, cols=20, lam=0.5, n_extra=0):
+        return L.Objective(kind, 0, rows, cols, cols, 0x1000, None, lam, 0.0, None, None, n_extra, None, None, None)
+
+    plain = lib.lbfgsb_workspace_bytes(600, 5, C.byref(ot()), C.byref(o))
+    assert plain > 2 * 5 * 600 * 8
+    assert lib.lbfgsb_workspace_bytes(600, 5, C.byref(ot(kind=L.OBJ_OT_ENTROPY)), C.byref(o)) == plain
+    assert lib.lbfgsb_workspace_bytes(20, 5, C.byref(ot()), C.byref(o)) == 0            # n is rows*cols, not cols
+    assert lib.lbfgsb_workspace_bytes(600, 5, C.byref(ot(lam=0.0)), C.byref(o)) == 0
+    assert b"lambda" in lib.lbfgsb_last_error()
+    assert lib.lbfgsb_workspace_bytes(600, 5, C.byref(ot(n_extra=1)), C.byref(o)) == 0
+    # long vectors take the other Gram kernels, whose partials are laid out differently: still a valid size
+    big = lib.lbfgsb_workspace_bytes(1000 * 1000, 10, C.byref(ot(rows=1000, cols=1000)), C.byref(o))
+    assert big > 2 * 10 * 10**6 * 8 and big % 256 == 0
+    assert lib.lbfgsb_workspace_bytes(1000 * 1000, 20, C.byref(ot(rows=1000, cols=1000)), C.byref(o)) > big
+    with_al = lib.lbfgsb_auglag_marginals_workspace_bytes(5, C.byref(ot()), C.byref(o))
+    assert with_al >= plain + 3 * 50 * 8
+    assert lib.lbfgsb_auglag_marginals_workspace_bytes(5, C.byref(_obj()), C.byref(o)) == 0       # least squares: wrong kind
+    h = C.c_void_p()
+    rc = lib.lbfgsb_auglag_create_marginals(C.byref(h), 5, 0x3000, 0x4000, C.byref(_obj()), 0x5000, C.byref(o), C.byref(ao),
+                                            0x10000, 1 << 24, None)
+    assert rc == L.E_INVALID_ARG and not h
+    rc = lib.lbfgsb_auglag_create_marginals(C.byref(h), 5, 0x3000, 0x4000, C.byref(ot()), None, C.byref(o), C.byref(ao),
+                                            0x10000, 1 << 24, None)
+    assert rc == L.E_INVALID_ARG
+    rc = lib.lbfgsb_auglag_create_marginals(C.byref(h), 5, 0x3000, 0x4000, C.byref(ot()), 0x5000, C.byref(o), C.byref(ao),
+                                            0x10000, 64, None)
+    assert rc == L.E_INVALID_ARG and b"too small" in lib.lbfgsb_last_error()
+
+
 def test_default_options():
     o = L.default_options()
     assert (o.eps, o.armijo_c1, o.backtrack, o.max_backtracks) == (1e-10, 1e-4, 0.5, 60)
