@@ -181,6 +181,64 @@ def test_properties_at_a_larger_size(dataset, reg):
           f"violation {info.violation:.2e}, rho {info.rho}", flush=True)
 
 
+# ---- at the sizes bench.py runs (10^6 and 2*10^6 variables): the long-vector Gram / direction kernels ----------------
+
+@pytest.mark.parametrize("dataset,reg", [(1, "gauss"), (2, "gauss"), (1, "entropy"), (2, "entropy")])
+def test_full_size_value_gradient_and_first_iterations(dataset, reg):
+    """The oracle's cost is linear in the number of variables here, so it evaluates the full-size problem itself:
+    value, gradient and marginal residuals at a feasible point, then the first iterations of Algorithm 1 step by step
+    (direction branch, step length, iterate, gradient) on the augmented Lagrangian with non-zero multipliers."""
+    p = workloads.joint_probability(1000, dataset=dataset, reg=reg, seed=4001)
+    rng = np.random.default_rng(5)
+    n, rho = p.n, 2.0
+    mult = 1e-4 * rng.standard_normal(p.rows + p.cols)
+    eps = 1e-10 if reg == "gauss" else 1e-20
+    ref_obj = oracle.Objective(p.kind, p.M, lam=p.lam).set_marginals(p.u, p.v, lam=mult, rho=rho)
+    x0 = np.where(rng.random(n) < 0.4, p.lower, rng.random(n) * 2.0 / n)
+    f_ref, g_ref, row_ref = oracle.fg(ref_obj, x0, want_rowvec=True)
+    s = _solver(p.kind, p.M, p.l, p.ub, p.m, p.lam, np.concatenate([p.u, p.v]) - mult / rho, np.full(p.rows + p.cols, rho),
+                tol=0.0, eps=eps)
+    f, g, row = s.dbg_fg(to_dev(x0), want_rowvec=True)
+    assert abs(f - f_ref) <= 1e-12 * max(abs(f_ref), 1e-3)
+    assert rel_err(g.cpu().numpy(), g_ref) <= 1e-12
+    assert rel_err(row.cpu().numpy(), row_ref) <= 1e-12
+    ref = oracle.Solver(ref_obj, p.l, p.ub, x0, p.m, oracle.default_options(tol=0.0, eps=eps))
+    s.set_x(to_dev(x0))
+    for it in range(14):          # past the point where the pair memory is full (m = 10)
+        ref.step()
+        info = s.step()
+        ri = ref.info
+        assert info.branch == ri.branch and info.backtracks == ri.backtracks, (it, info.as_dict())
+        assert info.alpha == pytest.approx(ri.alpha, rel=1e-9)
+        assert info.f == pytest.approx(ri.f, rel=1e-10, abs=1e-15), it
+        assert info.n_fixed == ri.n_fixed, it
+        assert rel_err(s.x().cpu().numpy(), ref.x) <= 1e-8, it
+        assert rel_err(s.g().cpu().numpy(), ref.g) <= 1e-8, it
+    ref.close()
+    s.close()
+
+
+@pytest.mark.parametrize("dataset", [1, 2])
+def test_full_size_solve_properties(dataset):
+    """bench.py's JP1G / JP2G run (same tolerances): a coupling with the dual structure of the Gaussian regulariser."""
+    p = workloads.joint_probability(1000, dataset=dataset, reg="gauss", seed=4001)
+    al = L.AuglagMarginals(p.kind, to_dev(p.M), to_dev(np.concatenate([p.u, p.v])), to_dev(p.l), to_dev(p.ub), p.m, lam=p.lam,
+                           options=L.default_options(tol=1e-6, tol_relative=1, max_iter=5000), ctol=1e-6, max_outer=100)
+    info = al.solve(to_dev(p.x0))
+    P = al.x().cpu().numpy().reshape(p.rows, p.cols)
+    mult = al.lam().cpu().numpy()
+    al.close()
+    assert info.status == L.CONVERGED, info.as_dict()
+    assert P.min() >= 0.0
+    assert np.abs(P.sum(1) - p.u).max() <= 1e-6 and np.abs(P.sum(0) - p.v).max() <= 1e-6
+    a, b = mult[:p.rows], mult[p.rows:]
+    closed = np.maximum(0.0, -(p.M + a[:, None] + b[None, :]) / p.lam)
+    # inner tolerance: ||grad L [S]|| <= 1e-6 max(1, start value); the start value of the last inner solve is below 1
+    assert np.abs(P - closed).max() <= 1.5e-6 / p.lam
+    assert info.f == pytest.approx(float((p.M * P).sum() + 0.5 * p.lam * (P * P).sum()), rel=1e-9)
+    print(f"[transport] full size ds{dataset}: outer {info.outer}, inner {info.inner_iters}, violation {info.violation:.2e}", flush=True)
+
+
 def test_entropy_rejects_a_zero_lower_bound():
     M = np.zeros((4, 5))
     with pytest.raises(L.LbfgsbError) as e:
