@@ -620,6 +620,7 @@ int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count, double* total_ms, doub
     return LBFGSB_OK;
 }
 
+
 const char* lbfgsb_apass_name(const lbfgsb_solver* s) { return s && s->use_fused ? "fused" : "two_pass"; }
 
 // ---- primitive-level hooks ------------------------------------------------------------------------------

@@ -355,12 +355,37 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
 // to finish adds the group's partials in index order into grampart + (gridDim.x + group) * NE, and the last
 // group to finish adds the group results, again in index order, into tot[0 .. NE) (LDS).  Returns true in that
 // one workgroup (after a barrier), false everywhere else.  No workgroup reads more than kGramGroupMax partials,
-// and the order of the additions does not depend on which workgroup finishes last.
+// and the order of the additions does not depend on which workgroup finishes last.  Grids of at most
+// kGramOneLevelMax workgroups skip the first level (each level costs two fences, an atomic and a dependent round of
+// loads: 6-7 us).
+constexpr int kGramOneLevelMax = 128;   // grids up to this size add their partials in one level
 constexpr int kGramGroupMax = 32;   // workgroups per group at most: grids of up to kGramGroups * kGramGroupMax
 
 __device__ __forceinline__ bool reduce_partials(double* __restrict__ grampart, int NE, Scal* __restrict__ scal, int* flag,
                                                 double* tot) {
     const int tid = threadIdx.x, nwg = gridDim.x;
+    if (nwg <= kGramOneLevelMax) {
+        // few workgroups: one level, the last one to finish adds all partials in index order
+        if (!arrive_is_last(&scal->gram_cnt[kGramGroups], flag, (unsigned)nwg)) return false;
+        for (int idx = tid; idx < NE; idx += kBlock) {
+            double t = idx == 1 ? -INFINITY : 0.0;
+            for (int k0 = 0; k0 < nwg; k0 += kGramGroupMax) {
+                double v[kGramGroupMax];
+#pragma unroll
+                for (int k = 0; k < kGramGroupMax; ++k) v[k] = k0 + k < nwg ? grampart[(int64_t)(k0 + k) * NE + idx] : (idx == 1 ? -INFINITY : 0.0);
+                if (idx == 1) {
+#pragma unroll
+                    for (int k = 0; k < kGramGroupMax; ++k) t = fmax(t, v[k]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < kGramGroupMax; ++k) t += v[k];
+                }
+            }
+            tot[idx] = t;
+        }
+        __syncthreads();
+        return true;
+    }
     const int gs = (nwg + kGramGroups - 1) / kGramGroups;
     const int ngroups = (nwg + gs - 1) / gs;
     const int grp = blockIdx.x / gs, gfirst = grp * gs;
@@ -518,11 +543,7 @@ __global__ __launch_bounds__(kBlock) void k_gram_mfma(int64_t n, int m, Opts op,
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const double val = (t & 1) ? v[b][t >> 1].y : v[b][t >> 1].x;
-#ifdef LB_EXP_NOMASK
-                const bool keep = kind[b] != 0; (void)b_free; (void)b_in;
-#else
                 const bool keep = kind[b] == 1 ? b_free : (kind[b] == 2 ? b_in : false);
-#endif
                 opnd[b] = keep ? val : 0.0;
             }
             int k = 0;
@@ -530,11 +551,7 @@ __global__ __launch_bounds__(kBlock) void k_gram_mfma(int64_t n, int m, Opts op,
             for (int a = 0; a < NB; ++a) {
 #pragma unroll
                 for (int b = a; b < NB; ++b, ++k) {
-#ifdef LB_EXP_NOMFMA
-                    if (b < nbk) acc[k][0] = fma(opnd[a], opnd[b], acc[k][0]);
-#else
                     if (b < nbk) acc[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(opnd[a], opnd[b], acc[k], 0, 0, 0);
-#endif
                 }
             }
         }
@@ -819,23 +836,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         w.active |= (1u << sl) | (1u << (kWideM + sl));
     }
     double* part = grampart + (int64_t)blockIdx.x * kWideNE;
-#ifdef LB_EXP_TICKS
-    const unsigned long long tk0 = wall_clock64();
-    if (tid == 0) part[4] = (double)tk0;
-#endif
     switch (wave) {
         case 0: wide_role<0, kWideH, 0, 0, true, 0>(w, op, x, l, u, mask, dbg_inputs, part, 0); break;
         case 1: wide_role<kWideH, kWideT - kWideH, 0, 0, true, 1>(w, op, x, l, u, mask, dbg_inputs, part, kWideOff1); break;
         case 2: wide_role<0, kWideH, 11, 5, false, 2>(w, op, x, l, u, mask, dbg_inputs, part, kWideOff2); break;
         default: wide_role<0, kWideH, 16, 5, false, 3>(w, op, x, l, u, mask, dbg_inputs, part, kWideOff3); break;
     }
-#ifdef LB_EXP_TICKS
-    const unsigned long long tk1 = wall_clock64();
-#endif
     if (!reduce_partials(grampart, kWideNE, scal, &flag, tot)) return;
-#ifdef LB_EXP_TICKS
-    const unsigned long long tk2 = wall_clock64();
-#endif
     // static slots -> the recursion's order (s oldest..newest, y oldest..newest, g)
     for (int idx = tid; idx < kWideEntries; idx += kBlock) {
         int a, b;
@@ -867,22 +874,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
     __syncthreads();
     recursion_on_coefficients(Gs, Vp, c, head, m, op, scal, red, alpha_s, dbg_inputs, evaluate_stop);
-#ifdef LB_EXP_TICKS
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned long long tk3 = wall_clock64();
-        scal->pg2 = (double)tk1 - grampart[4];          // kernel start (workgroup 0) -> this workgroup's partial written
-        scal->pginf = (double)(tk2 - tk1);              // two-level reduction
-        scal->f = (double)(tk3 - tk2);                  // assembly + recursion
-        scal->alpha = (double)(tk1 - tk0);              // this workgroup's own loop + epilogue
-    }
-#endif
 }
 
-bool gram_uses_wide(int64_t n, int m) { return n >= kMfmaMinN && n % 2 == 0 && m <= kWideM; }
+// (any even n: below 2^17 entries the grid stays small enough for the one-level sum of the partials)
+bool gram_uses_wide(int64_t n, int m) { return n % 2 == 0 && m <= kWideM; }
 int gram_wide_blocks(int64_t n) {
     const int64_t b = (n + 127) / 128;
-    return (int)(b > 512 ? 512 : b);
+    const int64_t cap = n >= kMfmaMinN ? 512 : kGramOneLevelMax;
+    return (int)(b > cap ? cap : b);
 }
 
 template <int NB>

@@ -164,9 +164,6 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
     __shared__ double delta_s[kMaxV + 24];
     __shared__ double red[kWaves * 7];
     __shared__ int flag;
-#ifdef LB_EXP_DIRTICKS
-    const unsigned long long tk0 = wall_clock64();
-#endif
     if (scal->status != LBFGSB_RUNNING) return;
     const int tid = threadIdx.x;
     const int c = scal->count, head = scal->head;
@@ -229,20 +226,7 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
             *reinterpret_cast<dir_f64x2*>(p2 + e) = dir_f64x2{b0, b1};
         }
     }
-#ifdef LB_EXP_DIRTICKS
-    const unsigned long long tk1 = wall_clock64();
-    if (tid == 0 && blockIdx.x == 0) redpart[7] = (double)tk0;
-#endif
     dir_finish(s, ub, op.eps, scal, redpart, red, &flag);
-#ifdef LB_EXP_DIRTICKS
-    // (only the last workgroup returns from dir_finish with flag set)
-    if (flag && tid == 0) {
-        const unsigned long long tk2 = wall_clock64();
-        scal->pg2 = (double)tk1 - redpart[7];     // kernel start (workgroup 0) -> last workgroup's loop done
-        scal->pginf = (double)(tk2 - tk1);        // tail
-        scal->f = (double)(tk1 - tk0);            // last workgroup's own prologue + loop
-    }
-#endif
 }
 
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st) {
