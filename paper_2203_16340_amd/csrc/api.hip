@@ -121,7 +121,7 @@ Geometry make_geometry(const Dims& dm, const void* A) {
     int64_t ub = (dm.cols + 15) / 16;   // 16 columns per workgroup in the column-sum kernels
     ge.upd_blocks = ge.fin_blocks = (int)(ub > 2048 ? 2048 : ub);
     int64_t lb_ = (dm.rows + kBlock - 1) / kBlock;
-    ge.ls_blocks = (int)(lb_ > 512 ? 512 : lb_);
+    ge.ls_blocks = (int)(lb_ > 128 ? 128 : lb_);   // (the line search ends in a single-address arrival: few workgroups)
     if (is_transport(dm.kind)) {
         int rpw = 1;
         while (rpw < kOtRpwMax && (dm.rows + rpw - 1) / rpw > 512) rpw *= 2;
@@ -221,8 +221,6 @@ APassArgs base_args(const lbfgsb_solver* s) {
     a.vs = s->dm.kind == LBFGSB_OBJ_QP ? s->obj.sign : nullptr;
     a.p1 = s->bf.p1; a.p2 = s->bf.p2;
     a.split = s->dm.kind == LBFGSB_OBJ_LSQ_L1SPLIT;
-    a.c1 = s->op.c1;
-    a.mu = s->dm.mu;
     return a;
 }
 
@@ -313,21 +311,20 @@ void enqueue_step(lbfgsb_solver* s) {
         }
         launch_update_quadratic(s->dm, s->op, s->ge, s->bf, nullptr, s->stream);
     } else if (s->use_fused) {
-        // One read of X yields t = X p AND X^T psi for the first trial step min(1, alpha_ub); the last
-        // workgroup of that pass tests the Armijo condition for it.  Only if the step is rejected do the
-        // line search over the margins and a second (transposed) pass over X run; otherwise those two
-        // launches return at once.  The transposed pass is not among the timed launches: it reads A only
-        // in the iterations that backtrack.
+        // One read of X yields t = X p AND X^T psi for the first trial step min(1, alpha_ub).  The line
+        // search over the margins then decides; only if it does not accept that first step does a second
+        // (transposed) pass over X run, otherwise that launch returns at once.  The transposed pass is not
+        // among the timed launches: it reads A only in the iterations that backtrack.
         a.mode = kRowLogiSpec;
         { TimedSlot ts(s); launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
-        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, s->stream);
+        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, s->stream);
         launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
         launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 2, s->stream, nullptr, nullptr);
         launch_update_logistic(s->dm, s->ge, s->bf, s->ge.ls_blocks, s->stream);
     } else {
         a.mode = kRowLogiDir;
         { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
-        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, s->stream);
+        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 0, s->stream);
         launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
         { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
         launch_update_logistic(s->dm, s->ge, s->bf, s->ge.ls_blocks, s->stream);

@@ -17,7 +17,7 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kLsBatch = 8;        // step lengths the logistic line search evaluates per sweep over the rows
 
 // Which per-kernel arrival counter (Scal::counters) a kernel uses to find its last workgroup.
-enum { kCntGram = 0, kCntDir, kCntUpdate, kCntEvalFinish, kCntLs, kCntSpec, kCntCount };
+enum { kCntGram = 0, kCntDir, kCntUpdate, kCntEvalFinish, kCntLs, kCntCount };
 // Grids of the kernels whose last workgroup finishes the job (arrive_is_last) stay at two workgroups per compute
 // unit: every workgroup ends with an atomic on one address, and those serialise (4096 workgroups measured 90 us
 // slower per launch than 512 on the same data).
@@ -41,7 +41,7 @@ struct Scal {
     // update left pending by the quadratic update kernel (no workgroup of that kernel reads these);
     // applied by the last workgroup of the next Gram kernel, or by k_commit
     int pend_valid, pend_ok, pend_bt;
-    int spec_ok;            // logistic: the speculative single-read pass already holds the accepted step's X^T psi
+    int spec_ok;            // logistic: the accepted step is the first trial step, whose X^T psi the single-read pass already holds
     double pend_alpha, pend_f;
     long long iters;
     long long fevals;
@@ -300,7 +300,7 @@ enum RowMode {
     kRowDir = 1,       // u = a_r.v -> t; psi = w_r u;              loss += w_r u^2
     kRowLogiEval = 2,  // u = a_r.v -> row (margin); psi = -y sigma(-y u)/rows; loss += softplus(-y u)/rows
     kRowLogiDir = 3,   // u = a_r.v -> t only (no transposed product follows)
-    kRowLogiSpec = 4,  // fused kernel only: u = a_r.v -> t; psi and loss for the first trial step min(1, alpha_ub)
+    kRowLogiSpec = 4,  // fused kernel only: u = a_r.v -> t; psi of the first trial step min(1, alpha_ub)
     kRowQpEval = 5,    // two-pass row kernel only: u = a_r.v -> row; loss += 0.5 v_r u   (A symmetric, v = s.x)
     kRowQpDir = 6      // two-pass row kernel only: u = a_r.v -> t;   loss += v_r u       (v = s.p)
 };
@@ -318,7 +318,6 @@ struct APassArgs {
     int split;              // L1SPLIT: vb = va + cols
     int mode;               // RowMode
     int check_status;       // skip all work unless Scal::status == RUNNING
-    double c1, mu;          // kRowLogiSpec: Armijo constant and regularisation weight for the test of the first trial step
 };
 
 // ev0/ev1 (both or neither): HIP events attached to the dispatch itself, so that their difference is
@@ -346,8 +345,9 @@ void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge,
 // extra rows: e_r.z for z = x (eval != 0: residuals against the targets) or the selected direction (eval == 0)
 void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, const double* target, const double* weight,
                        int eval, hipStream_t st);
+// spec != 0: the A pass already holds X^T psi of the first trial step (recorded in Scal::spec_ok if that step is accepted)
 void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
-                        hipStream_t st);
+                        int spec, hipStream_t st);
 void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* labels, hipStream_t st);
 void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, hipStream_t st);
 

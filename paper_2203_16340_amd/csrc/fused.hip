@@ -24,9 +24,13 @@ struct Variant {
     const void* kernel; // for hipFuncSetAttribute
     void (*launch)(const Dims&, int64_t, int, size_t, const Buffers&, const APassArgs&, hipStream_t, hipEvent_t, hipEvent_t);
     size_t (*lds)(int64_t cols);
+    // logistic only: the instantiation for the direction pass (same geometry, deeper ring: its row operation is
+    // one exponential and one division, which leaves the registers for it)
+    const void* kernel_dir;
+    void (*launch_dir)(const Dims&, int64_t, int, size_t, const Buffers&, const APassArgs&, hipStream_t, hipEvent_t, hipEvent_t);
 };
 
-template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI, int KR, bool TRANS>
+template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, int LOGI, int KR, bool TRANS>
 void launch_variant(const Dims& dm, int64_t rows_per_wg, int blocks, size_t lds, const Buffers& bf, const APassArgs& a,
                     hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     hipExtLaunchKernelGGL((ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, LOGI, KR, TRANS>), dim3(blocks), dim3(NT), lds, st, ev0, ev1,
@@ -36,15 +40,22 @@ void launch_variant(const Dims& dm, int64_t rows_per_wg, int blocks, size_t lds,
 
 #define LB_VARIANT_FULL(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, KR, TRANS)                                                \
     {dt, LOGI, TRANS, NT, (KCU) * (U), R, WGS,                                                                              \
-     (const void*)ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0, KR, (TRANS) != 0>,                               \
-     launch_variant<T, NT, KCU, U, R, NB, WPE, (LOGI) != 0, KR, (TRANS) != 0>, ring::lds_bytes<T, NT, (KCU) * (U), KR, R>}
+     (const void*)ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, LOGI, KR, (TRANS) != 0>,                                      \
+     launch_variant<T, NT, KCU, U, R, NB, WPE, LOGI, KR, (TRANS) != 0>, ring::lds_bytes<T, NT, (KCU) * (U), KR, R>, nullptr,   \
+     nullptr}
+#define LB_VARIANT_LOGI(dt, T, NT, KCU, U, R, NB, NBDIR, WPE, WGS)                                                           \
+    {dt, 1, 1, NT, (KCU) * (U), R, WGS, (const void*)ring::k_fused_ring<T, NT, KCU, U, R, NB, WPE, 1, 0, true>,                \
+     launch_variant<T, NT, KCU, U, R, NB, WPE, 1, 0, true>, ring::lds_bytes<T, NT, (KCU) * (U), 0, R>,                         \
+     (const void*)ring::k_fused_ring<T, NT, KCU, U, R, NBDIR, WPE, 2, 0, true>,                                              \
+     launch_variant<T, NT, KCU, U, R, NBDIR, WPE, 2, 0, true>}
 #define LB_VARIANT_KR(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, KR) LB_VARIANT_FULL(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, KR, 1)
 #define LB_VARIANT(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS) LB_VARIANT_FULL(dt, LOGI, T, NT, KCU, U, R, NB, WPE, WGS, 0, 1)
 #define LB_VARIANT_ROWS(dt, T, NT, KCU, U, R, NB, WPE, WGS) LB_VARIANT_FULL(dt, 0, T, NT, KCU, U, R, NB, WPE, WGS, 0, 0)
 
 // Ordered by capacity within a (matrix type, objective family) group: the first variant of the group
 // whose NT*KC*VEC columns cover a row and whose LDS need (v for every column) fits is used.  The
-// logistic kernels spend ~100 registers on exp/log1p/expm1, so their rings are shallower.
+// logistic evaluation kernels spend ~100 registers on exp/log1p, so their rings are shallower; the direction
+// pass of the logistic objective has its own instantiation with the deepest ring that does not spill.
 const Variant kVariants[] = {
     LB_VARIANT(LBFGSB_F64, 0, double, 256, 2, 1, 2, 4, 4, 4),    // cols <=  1024
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 5, 1, 2, 4, 2, 1),    // cols <=  5120
@@ -56,13 +67,14 @@ const Variant kVariants[] = {
     LB_VARIANT(LBFGSB_F32, 0, float, 256, 5, 1, 1, 2, 2, 2),     // cols <=  5120
     LB_VARIANT(LBFGSB_F32, 0, float, 512, 5, 1, 2, 4, 2, 1),     // cols <= 10240
     LB_VARIANT(LBFGSB_F32, 0, float, 512, 10, 1, 1, 2, 2, 1),    // cols <= 20480 (LDS: <= 20428)
-    LB_VARIANT(LBFGSB_F64, 1, double, 256, 2, 1, 4, 8, 2, 2),    // cols <=  1024
-    LB_VARIANT(LBFGSB_F64, 1, double, 512, 5, 1, 1, 2, 2, 1),    // cols <=  5120
-    LB_VARIANT(LBFGSB_F64, 1, double, 512, 10, 1, 1, 1, 2, 1),   // cols <= 10240
-    LB_VARIANT(LBFGSB_F32, 1, float, 256, 2, 1, 4, 8, 2, 2),     // cols <=  2048
-    LB_VARIANT(LBFGSB_F32, 1, float, 256, 5, 1, 1, 2, 2, 2),     // cols <=  5120
-    LB_VARIANT(LBFGSB_F32, 1, float, 512, 5, 1, 1, 2, 2, 1),     // cols <= 10240
-    LB_VARIANT(LBFGSB_F32, 1, float, 512, 10, 1, 1, 1, 2, 1),    // cols <= 20480 (LDS: <= 20428)
+    //              (…, R, ring depth of the evaluation kernel, of the direction kernel, …)
+    LB_VARIANT_LOGI(LBFGSB_F64, double, 256, 2, 1, 4, 8, 12, 2, 2),    // cols <=  1024
+    LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 5, 1, 1, 2, 4, 2, 1),     // cols <=  5120
+    LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 10, 1, 1, 1, 2, 2, 1),    // cols <= 10240
+    LB_VARIANT_LOGI(LBFGSB_F32, float, 256, 2, 1, 4, 8, 12, 2, 2),     // cols <=  2048
+    LB_VARIANT_LOGI(LBFGSB_F32, float, 256, 5, 1, 1, 2, 4, 2, 2),      // cols <=  5120
+    LB_VARIANT_LOGI(LBFGSB_F32, float, 512, 5, 1, 1, 2, 4, 2, 1),      // cols <= 10240
+    LB_VARIANT_LOGI(LBFGSB_F32, float, 512, 10, 1, 1, 1, 2, 2, 1),     // cols <= 20480 (LDS: <= 20428)
     // row products only: no accumulators of w, so the ring is deeper
     LB_VARIANT_ROWS(LBFGSB_F64, double, 256, 2, 1, 4, 8, 4, 4),  // cols <=  1024
     LB_VARIANT_ROWS(LBFGSB_F64, double, 512, 5, 1, 2, 8, 2, 1),  // cols <=  5120
@@ -130,13 +142,17 @@ hipError_t fused_prepare(const Dims& dm, const Geometry& ge) {
     const size_t cap = kLdsPerWorkgroup - 256;   // the kernels also hold a few bytes of static LDS
     if (most > cap) most = cap;
     if (v.lds(dm.cols) > most) most = v.lds(dm.cols);
-    return hipFuncSetAttribute(v.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
+    hipError_t e = hipFuncSetAttribute(v.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
+    if (e == hipSuccess && v.kernel_dir)
+        e = hipFuncSetAttribute(v.kernel_dir, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
+    return e;
 }
 
 void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
                   hipEvent_t ev0, hipEvent_t ev1) {
     const Variant& v = kVariants[ge.fused_variant];
-    v.launch(dm, rows_per_wg_for(dm, v), ge.fused_blocks, v.lds(dm.cols), bf, a, st, ev0, ev1);
+    auto launch = (a.mode == kRowLogiSpec && v.launch_dir) ? v.launch_dir : v.launch;
+    launch(dm, rows_per_wg_for(dm, v), ge.fused_blocks, v.lds(dm.cols), bf, a, st, ev0, ev1);
 }
 
 }  // namespace lb

@@ -55,12 +55,14 @@ constexpr int gcd_i(int a, int b) { return b == 0 ? a : gcd_i(b, a % b); }
 //   psi  : the row's weight in the transposed product,
 //   loss : the row's contribution to the loss partial,
 //   keep : the value stored for the row (into t for the direction modes, into row for the evaluations).
-// LOGI selects the family at compile time (the transcendental code of the logistic modes would
+// LOGI selects the family at compile time: 0 = quadratic objectives, 1 = logistic (evaluation and
+// direction pass), 2 = logistic direction pass only, whose chain is short enough to leave registers for
+// a deeper ring (the transcendental code of the logistic modes would
 // otherwise cost the quadratic kernels registers they need for the ring).
-template <bool LOGI>
+template <int LOGI>
 __device__ __forceinline__ void row_eval(int mode, double u, double b, double z, double alpha0, double invn,
                                          double& psi, double& loss, double& keep) {
-    if constexpr (!LOGI) {
+    if constexpr (LOGI == 0) {
         // z carries the row's weight here (1 when the objective has none); in the quadratic-form modes the
         // row's own entry of v (the row index is also a column index of the symmetric matrix)
         if (mode == kRowQpEval || mode == kRowQpDir) {
@@ -74,30 +76,21 @@ __device__ __forceinline__ void row_eval(int mode, double u, double b, double z,
         }
     } else {
         // one exponential serves sigma and softplus of the same argument
-        if (mode == kRowLogiEval) {         // margins z = X w; psi = -y sigma(-y z)/N
+        if (LOGI == 1 && mode == kRowLogiEval) {   // margins z = X w; psi = -y sigma(-y z)/N
             const double q = -b * u;
             const double e = exp(-fabs(q));
             psi = -b * ((q >= 0.0 ? 1.0 : e) / (1.0 + e)) * invn;
             loss = (fmax(q, 0.0) + log1p(e)) * invn;
             keep = u;
         } else {                            // kRowLogiSpec: t = X p, and the weights of the FIRST trial step alpha0
-            // With q = -y z, dq = -y alpha0 t, s = sigma(q), em = expm1(dq) and D = s*em:
-            //   softplus(q + dq) - softplus(q) = log1p(D)   (no cancellation for small steps),
-            //   sigma(q + dq) = s (1 + em) / (1 + D).
-            // The wave leaves this form for the plain definitions only if some row has |dq| >= 30.
-            const double q = -b * z, dq = -b * alpha0 * u;
+            // psi = -y sigma(-y (z + alpha0 t))/N: what the transposed product needs if alpha0 is accepted.
+            // Whether it is accepted is decided after this pass, from the margins (k_ls_logistic), so the
+            // chain every stage waits for is one exponential and one division.
+            const double q = -b * fma(alpha0, u, z);
             const double e = exp(-fabs(q));
-            const double sg = (q >= 0.0 ? 1.0 : e) / (1.0 + e);
+            psi = -b * ((q >= 0.0 ? 1.0 : e) / (1.0 + e)) * invn;
+            loss = 0.0;
             keep = u;
-            if (__builtin_amdgcn_ballot_w64(fabs(dq) >= 30.0) == 0ull) {
-                const double em = expm1(dq);
-                const double D = sg * em;
-                loss = log1p(D) * invn;
-                psi = -b * (sg * (1.0 + em) / (1.0 + D)) * invn;
-            } else {
-                psi = -b * sigmoid_d(q + dq) * invn;
-                loss = (fabs(dq) < 30.0 ? log1p(sg * expm1(dq)) : softplus_d(q + dq) - softplus_d(q)) * invn;
-            }
         }
     }
 }
@@ -113,7 +106,7 @@ __device__ __forceinline__ double lane_bcast(double v, int l) {
 // per stage, not once per row -- wave 0 stores the row's entry of t / row, and the weights psi are
 // handed to all lanes through scalar registers.  red: [R][NW] partial dot products of this stage;
 // bcur/zcur: the rows' entries of b and of the stored margins; row0: global index of the stage's first row.
-template <int R, int NW, bool LOGI>
+template <int R, int NW, int LOGI>
 __device__ __forceinline__ void stage_row_op(const double* red, int lane, int wave, int mode, const double (&bcur)[R],
                                              const double (&zcur)[R], int64_t row0, int64_t r_end, double alpha0,
                                              double invn, double* __restrict__ row, double* __restrict__ t,
@@ -145,36 +138,6 @@ __device__ __forceinline__ void stage_row_op(const double* red, int lane, int wa
     for (int r = 0; r < R; ++r) psi[r] = lane_bcast(psil, r);
 }
 
-// Speculative logistic pass: the partial columns are X^T psi for the first trial step alpha0 and the loss
-// partials are the terms of f(x + alpha0 p) - f(x).  The last workgroup to finish tests the Armijo
-// condition for alpha0; if it holds the iteration needs no second pass over X.  Called by all threads.
-template <int NT>
-__device__ __forceinline__ void spec_decide(Scal* __restrict__ scal, const APassArgs& a, double alpha0,
-                                            const double* __restrict__ losspart, double* red, int* last_flag) {
-    constexpr int NW = NT / 64;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (!arrive_is_last(&scal->counters[kCntSpec], last_flag)) return;
-    double tot = 0.0;
-    for (int k0 = tid; k0 < (int)gridDim.x; k0 += NT) tot += losspart[k0];
-    tot = wave_sum(tot);
-    if (lane == 0) red[wave] = tot;
-    __syncthreads();
-    if (tid == 0) {
-        tot = 0.0;
-#pragma unroll
-        for (int q = 0; q < NW; ++q) tot += red[q];
-        const double df = tot + a.mu * alpha0 * (scal->xp + 0.5 * alpha0 * scal->pp);
-        const int ok = isfinite(df) && df <= a.c1 * alpha0 * scal->gp;
-        scal->spec_ok = ok;
-        if (ok) {
-            scal->ls_ok = 1;
-            scal->backtracks = 0;
-            scal->fevals += 1;
-            scal->alpha = alpha0;
-        }
-    }
-}
-
 // dynamic LDS a launch needs: v for the columns held there (all of them unless the variant keeps the v of
 // its last KR chunks per thread in registers), one all-zero chunk, then the reduction scratch
 constexpr int kPad = 4;
@@ -190,7 +153,7 @@ inline size_t lds_bytes(int64_t cols) {
 
 // TRANS = false: the transposed accumulation is left out (quadratic form with a symmetric matrix: the row
 // products are all an iteration needs), and the registers it would take go to a deeper ring.
-template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, bool LOGI, int KR = 0, bool TRANS = true>
+template <typename T, int NT, int KCU, int U, int R, int NB, int WPE, int LOGI, int KR = 0, bool TRANS = true>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t cols, int64_t rows_per_wg, APassArgs a,
                   Scal* __restrict__ scal, double* __restrict__ row, double* __restrict__ t,
@@ -203,7 +166,6 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     constexpr int STAGES = NB / gcd_i(NB, SPS);              // stages after which the ring is back at slot 0
     static_assert(NB >= SPS, "the ring must hold at least one stage");
     static_assert(R <= 16, "one lane per row of a stage evaluates the row operation");
-    __shared__ int last_flag;
     extern __shared__ __align__(16) double lds[];
     // Rows too wide for v to fit in LDS: the v of each thread's last KR chunks stays in registers instead
     static_assert(KR == 0 || U == 1, "register-resident v is only combined with whole-row slots");
@@ -267,13 +229,13 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     // the vector loads of the ring, so waiting for one does not drain the rows in flight.
     typedef const double __attribute__((address_space(4))) * ConstD;
     const int mode = a.mode;
-    const bool need_b = mode != kRowDir && mode != kRowQpEval && mode != kRowQpDir, need_z = LOGI && mode == kRowLogiSpec;
+    const bool need_b = mode != kRowDir && mode != kRowQpEval && mode != kRowQpDir, need_z = LOGI != 0 && mode == kRowLogiSpec;
     auto read_rows = [&](double (&db)[R], double (&dz)[R], int64_t lr) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int64_t gr = r_begin + lr + r < r_end ? r_begin + lr + r : r_end - 1;
             db[r] = need_b ? *(ConstD)(uintptr_t)(a.b + gr) : 0.0;
-            if constexpr (LOGI) {
+            if constexpr (LOGI != 0) {
                 dz[r] = need_z ? *(ConstD)(uintptr_t)(row + gr) : 0.0;
             } else if (mode == kRowQpEval || mode == kRowQpDir) {
                 // (v is not written by this kernel: the scalar reads are safe)
@@ -386,7 +348,6 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     loss = wave_sum(loss);                                   // lanes 0..R-1 of a wave hold the row losses
     if (tid == 0) losspart[blockIdx.x] = loss;
 
-    if (LOGI && mode == kRowLogiSpec) spec_decide<NT>(scal, a, alpha0, losspart, red, &last_flag);
 }
 
 }  // namespace ring

@@ -464,60 +464,63 @@ void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, co
 //
 // With z = X w (kept in `row`) and t = X p:  f(x + a p) - f(x) = (1/N) sum_r [softplus(-y_r (z_r + a t_r))
 // - softplus(-y_r z_r)] + mu (a <x,p> + a^2/2 <p,p>).  The bracket is evaluated in the cancellation-free
-// form log1p(sigmoid(q) expm1(dq)), q = -y z, dq = -y a t.  kLsBatch step lengths are evaluated in one
-// sweep over the rows; if none is acceptable the last workgroup goes on alone, one length at a time.
+// form log1p(sigmoid(q) expm1(dq)), q = -y z, dq = -y a t.  Step lengths are evaluated NTRY at a time per sweep
+// over the rows: the first launch tries the first one alone (it is accepted in almost every quasi-Newton
+// iteration), a second launch, which returns at once when the first found the step, tries the next kLsBatch, and
+// if none of them is acceptable its last workgroup goes on alone, one length at a time.
 __device__ __forceinline__ double softplus_diff(double q, double sq, double dq) {
     return fabs(dq) < 30.0 ? log1p(sq * expm1(dq)) : softplus_d(q + dq) - softplus_d(q);
 }
 
-__global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, const double* __restrict__ yl,
-                                                        const double* __restrict__ z, const double* __restrict__ t,
-                                                        Scal* __restrict__ scal, double* __restrict__ lspart) {
-    __shared__ double red[kWaves * kLsBatch];
+template <int NTRY>
+__global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int first, int last_resort, int spec,
+                                                        const double* __restrict__ yl, const double* __restrict__ z,
+                                                        const double* __restrict__ t, Scal* __restrict__ scal,
+                                                        double* __restrict__ lspart) {
+    __shared__ double red[kWaves * NTRY];
     __shared__ int flag;
-    __shared__ double sh_alpha;
-    __shared__ int sh_done;
     if (scal->status != LBFGSB_RUNNING) return;
-    if (scal->spec_ok) return;   // the first trial step was accepted inside the speculative pass over X
+    if (first > 0 && scal->ls_ok) return;            // an earlier launch of this iteration found the step
     const int tid = threadIdx.x;
-    const double a0 = fmin(1.0, scal->alpha_ub);
-    double al[kLsBatch], s[kLsBatch];
+    double al[NTRY], s[NTRY];
     {
-        double a = a0;
+        double a = fmin(1.0, scal->alpha_ub);
+        for (int k = 0; k < first; ++k) a *= op.backtrack;
 #pragma unroll
-        for (int j = 0; j < kLsBatch; ++j) { al[j] = a; s[j] = 0.0; a *= op.backtrack; }
+        for (int j = 0; j < NTRY; ++j) { al[j] = a; s[j] = 0.0; a *= op.backtrack; }
     }
     for (int64_t r = (int64_t)blockIdx.x * kBlock + tid; r < dm.rows; r += (int64_t)gridDim.x * kBlock) {
         const double y = yl[r], q = -y * z[r], sq = sigmoid_d(q), ty = -y * t[r];
 #pragma unroll
-        for (int j = 0; j < kLsBatch; ++j) s[j] += softplus_diff(q, sq, al[j] * ty);
+        for (int j = 0; j < NTRY; ++j) s[j] += softplus_diff(q, sq, al[j] * ty);
     }
-    block_sum<kLsBatch, kWaves>(s, red);
+    block_sum<NTRY, kWaves>(s, red);
     if (tid == 0) {
 #pragma unroll
-        for (int j = 0; j < kLsBatch; ++j) lspart[(int64_t)blockIdx.x * kLsBatch + j] = s[j];
+        for (int j = 0; j < NTRY; ++j) lspart[(int64_t)blockIdx.x * NTRY + j] = s[j];
     }
     if (!arrive_is_last(&scal->counters[kCntLs], &flag)) return;
     const double gp = scal->gp, xp = scal->xp, pp = scal->pp;
     const double invn = 1.0 / (double)dm.rows;
     // totals of the batch
-    double tot[kLsBatch];
+    double tot[NTRY];
 #pragma unroll
-    for (int j = 0; j < kLsBatch; ++j) tot[j] = 0.0;
+    for (int j = 0; j < NTRY; ++j) tot[j] = 0.0;
     for (int b = tid; b < (int)gridDim.x; b += kBlock) {
 #pragma unroll
-        for (int j = 0; j < kLsBatch; ++j) tot[j] += lspart[(int64_t)b * kLsBatch + j];
+        for (int j = 0; j < NTRY; ++j) tot[j] += lspart[(int64_t)b * NTRY + j];
     }
-    block_sum<kLsBatch, kWaves>(tot, red);
+    block_sum<NTRY, kWaves>(tot, red);
     int found = -1;
     double a_acc = 0.0;
-    for (int j = 0; j < kLsBatch && j <= op.max_backtracks; ++j) {
+#pragma unroll
+    for (int j = 0; j < NTRY; ++j) {
         const double df = tot[j] * invn + dm.mu * al[j] * (xp + 0.5 * al[j] * pp);
-        if (isfinite(df) && df <= op.c1 * al[j] * gp) { found = j; a_acc = al[j]; break; }
+        if (found < 0 && first + j <= op.max_backtracks && isfinite(df) && df <= op.c1 * al[j] * gp) { found = first + j; a_acc = al[j]; }
     }
     // rare: continue one step length at a time (uniform control flow: every thread holds the same totals)
-    double a = al[kLsBatch - 1];
-    for (int k = kLsBatch; found < 0 && k <= op.max_backtracks; ++k) {
+    double a = al[NTRY - 1];
+    for (int k = first + NTRY; last_resort && found < 0 && k <= op.max_backtracks; ++k) {
         a *= op.backtrack;
         double sv[1] = {0.0};
         for (int64_t r = tid; r < dm.rows; r += kBlock) {
@@ -530,17 +533,21 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, const 
     }
     if (tid == 0) {
         scal->ls_ok = found >= 0;
-        scal->backtracks = found >= 0 ? found : op.max_backtracks + 1;
-        scal->fevals += found >= 0 ? found + 1 : op.max_backtracks + 1;
+        if (first == 0) scal->spec_ok = spec && found == 0;
+        if (found >= 0 || last_resort) {
+            scal->backtracks = found >= 0 ? found : op.max_backtracks + 1;
+            scal->fevals += found >= 0 ? found + 1 : op.max_backtracks + 1;
+        }
         if (found >= 0) scal->alpha = a_acc;
     }
-    (void)sh_alpha; (void)sh_done;
 }
 
 void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
-                        hipStream_t st) {
-    hipLaunchKernelGGL(k_ls_logistic, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, labels, bf.row, bf.t, bf.scal,
-                       bf.lspart);
+                        int spec, hipStream_t st) {
+    hipLaunchKernelGGL(k_ls_logistic<1>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 0, 0, spec, labels,
+                       (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
+    hipLaunchKernelGGL(k_ls_logistic<kLsBatch>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 1, 1, spec, labels,
+                       (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
 }
 
 // z += alpha t; psi = -y sigma(-y z)/N; loss partials of the new point (from the new margins).
