@@ -359,7 +359,8 @@ int set_x_impl(lbfgsb_solver* s, const double* x0, bool trusted) {
     }
     if (x0 != s->bf.x) HIP_TRY(hipMemcpyAsync(s->bf.x, x0, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream));
     fresh_scal(s);
-    HIP_TRY(write_scal(s));
+    // (no wait: the pinned block is next touched by the read below, which the stream orders after this upload)
+    HIP_TRY(hipMemcpyAsync(s->bf.scal, s->h_scal, sizeof(Scal), hipMemcpyHostToDevice, s->stream));
     enqueue_eval(s, 0);
     s->steps_since_refresh = 0;
     s->steps_since_set_x = 0;
@@ -1014,14 +1015,16 @@ int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info*
                        al->beta_c, al->omega_c);
     int rc = lbfgsb_set_x(s, x0);
     if (rc) return rc;
-    auto measure = [&](int update) -> hipError_t {
+    // constraint violation and penalty term at the current x (and the multiplier update); wait: whether to wait
+    // here or let a following read of the scalar block do it
+    auto measure = [&](int update, bool wait) -> hipError_t {
         hipLaunchKernelGGL(k_al_update, dim3(1), dim3(kBlock), 0, al->stream, al->n_eq, al->rho, update, al->res_c,
                            al->lambda, al->red);
         hipError_t e = hipMemcpyAsync(al->h_red, al->red, 16, hipMemcpyDeviceToHost, al->stream);
-        if (e != hipSuccess) return e;
+        if (e != hipSuccess || !wait) return e;
         return hipStreamSynchronize(al->stream);
     };
-    HIP_TRY(measure(0));
+    HIP_TRY(measure(0, true));
     double viol_prev = al->h_red[0];
     out.violation = viol_prev;
     for (int it = 0; it < al->ao.max_outer; ++it) {
@@ -1040,9 +1043,9 @@ int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info*
         out.pg2 = ii.pg2;
         if (ii.status == LBFGSB_LINESEARCH_FAILED) { out.status = ii.status; break; }
         HIP_TRY(al_fresh_eval(s));
-        HIP_TRY(read_scal(s));
+        HIP_TRY(measure(1, false));               // lambda += rho h(x); violation; penalty term
+        HIP_TRY(read_scal(s));                    // (one wait for both)
         out.L = s->h_scal->f;
-        HIP_TRY(measure(1));                      // lambda += rho h(x); violation; penalty term
         out.violation = al->h_red[0];
         out.f = out.L - al->h_red[1];
         if (out.violation <= al->ao.ctol && ii.status == LBFGSB_CONVERGED) { out.status = LBFGSB_CONVERGED; break; }
