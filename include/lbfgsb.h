@@ -274,8 +274,9 @@ void lbfgsb_auglag_destroy(lbfgsb_auglag* al);
  * and the bytes of A one launch requests from memory (rows*cols*sizeof(element): each such
  * kernel reads A exactly once).  The transport kinds have no such kernel: there the Gram kernel of the batched
  * two-loop recursion (the longest kernel of an iteration) is timed instead, from the m-th iteration after
- * lbfgsb_set_x on, when all m pairs are stored; the bytes are 41*n (x, g, l, u, the newest y, the mask) plus
- * 16*m per free variable (the pair vectors are not read where a variable is fixed). */
+ * lbfgsb_set_x on, when all m pairs are stored; the bytes are 41*n (x, g, l, u, the newest y, the mask; 25*n when
+ * all variables share the same bounds, which are then not streamed) plus 16*m per free variable (the pair vectors
+ * are not read where a variable is fixed). */
 int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable);
 int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count_host, double* total_ms_host, double* bytes_per_pass_host);
 /* Name of the A-pass organisation in use: "fused" or "two_pass" (host string). */

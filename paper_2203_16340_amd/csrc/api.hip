@@ -276,7 +276,7 @@ void enqueue_step(lbfgsb_solver* s) {
             TimedSlot ts(s, s->steps_since_set_x >= s->dm.m);
             launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream, ts.e0, ts.e1);
         }
-        launch_dir(s->dm, s->op, s->ge, s->bf, 0, s->stream);
+        launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream);
         const OtArgs oa = ot_args(s);
         launch_ot_sums(s->dm, s->ge, s->bf, oa, 0, 1, s->stream);
         if (quad) launch_ot_update_gauss(s->dm, s->op, s->ge, s->bf, oa, s->stream);
@@ -286,7 +286,7 @@ void enqueue_step(lbfgsb_solver* s) {
         return;
     }
     launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
-    launch_dir(s->dm, s->op, s->ge, s->bf, 0, s->stream);
+    launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream);
     APassArgs a = base_args(s);
     a.select_p = 1;
     a.check_status = 1;
@@ -419,7 +419,7 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
     if (!s) return fail(LBFGSB_E_INVALID_ARG, "out of host memory");
     s->dm = make_dims(n, m, obj);
     s->options = o;
-    s->op = Opts{o.eps, o.armijo_c1, o.backtrack, o.tol, o.max_backtracks, o.tol_relative, o.max_iter};
+    s->op = Opts{o.eps, o.armijo_c1, o.backtrack, o.tol, o.max_backtracks, o.tol_relative, o.max_iter, 0, 0.0, 0.0};
     s->obj = *obj;
     s->ge = make_geometry(s->dm, obj->A);
     s->stream = (hipStream_t)hip_stream;
@@ -483,6 +483,13 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
         if (!(hl[(size_t)i] <= hu[(size_t)i]))
             return bail(fail(LBFGSB_E_BOUNDS, "bounds cross or are NaN at index %lld (l = %g, u = %g)", (long long)i,
                              hl[(size_t)i], hu[(size_t)i]));
+    {
+        bool same = true;
+        for (int64_t i = 1; same && i < n; ++i) same = hl[(size_t)i] == hl[0] && hu[(size_t)i] == hu[0];
+        s->op.uniform_bounds = same ? 1 : 0;
+        s->op.lo = hl[0];
+        s->op.hi = hu[0];
+    }
     if (obj->kind == LBFGSB_OBJ_OT_ENTROPY)
         for (int64_t i = 0; i < n; ++i)
             if (!(hl[(size_t)i] > 0.0))
@@ -609,11 +616,12 @@ int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count, double* total_ms, doub
     *total_ms = tot;
     *bytes_per_pass = (double)s->dm.rows * (double)s->dm.cols * (s->dm.dtype == LBFGSB_F32 ? 4.0 : 8.0);
     // transport kinds: the timed kernel is the Gram kernel, timed in iterations m, m+1, ... after lbfgsb_set_x, when
-    // all m pairs are stored.  It reads x, g, l, u and the newest y in full and writes the one-byte free mask; the
-    // 2m pair vectors are read at the free variables only (count taken from the last status the host has seen)
+    // all m pairs are stored.  It reads x, g, the newest y (and l, u unless every variable has the same bounds) in
+    // full and writes the one-byte free mask; the 2m pair vectors are read at the free variables only (count taken
+    // from the last status the host has seen)
     if (is_transport(s->dm.kind)) {
         const double n_free = (double)(s->dm.n - s->h_scal->n_fixed);
-        *bytes_per_pass = (double)s->dm.n * 41.0 + n_free * 2.0 * s->dm.m * 8.0;
+        *bytes_per_pass = (double)s->dm.n * (s->op.uniform_bounds ? 25.0 : 41.0) + n_free * 2.0 * s->dm.m * 8.0;
     }
     return LBFGSB_OK;
 }
@@ -674,7 +682,7 @@ int lbfgsb_dbg_two_loop(lbfgsb_solver* s, const double* S, const double* Y, cons
     HIP_TRY(hipMemcpyAsync(s->bf.g, g, nb, hipMemcpyDeviceToDevice, s->stream));
     HIP_TRY(hipMemcpyAsync(s->bf.mask, mask, (size_t)s->dm.n, hipMemcpyDeviceToDevice, s->stream));
     launch_gram(s->dm, s->op, s->ge, s->bf, 1, 0, s->stream);
-    launch_dir(s->dm, s->op, s->ge, s->bf, 0, s->stream);
+    launch_dir(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
     HIP_TRY(hipMemcpyAsync(d, s->bf.d, nb, hipMemcpyDeviceToDevice, s->stream));
     HIP_TRY(read_scal(s));
     HIP_TRY(hipGetLastError());
@@ -692,7 +700,7 @@ int lbfgsb_dbg_project_direction(lbfgsb_solver* s, const double* x, const double
     HIP_TRY(hipMemcpyAsync(s->bf.d, d, nb, hipMemcpyDeviceToDevice, s->stream));
     fresh_scal(s);
     HIP_TRY(write_scal(s));
-    launch_dir(s->dm, s->op, s->ge, s->bf, 1, s->stream);
+    launch_dir(s->dm, s->op, s->ge, s->bf, 1, 1, s->stream);
     HIP_TRY(read_scal(s));
     HIP_TRY(hipGetLastError());
     const int br = s->h_scal->branch;

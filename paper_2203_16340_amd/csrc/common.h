@@ -78,6 +78,10 @@ __host__ __device__ inline int64_t row_entries(int kind, int64_t rows, int64_t c
 struct Opts {
     double eps, c1, backtrack, tol;
     int max_backtracks, tol_relative, max_iter;
+    // every variable has the same bounds (found when the bounds are validated): the long-vector kernels then take
+    // them from here instead of streaming l and u
+    int uniform_bounds;
+    double lo, hi;
 };
 
 // ---- reductions ---------------------------------------------------------------------------------
@@ -339,7 +343,9 @@ void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, c
 void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int dbg_inputs,
                  int evaluate_stop, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 void launch_commit(const Dims& dm, const Buffers& bf, hipStream_t st);
-void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st);
+// store_d: also keep d itself (the primitive-level hooks read it; an iteration only needs the two candidates)
+void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
+                hipStream_t st);
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
                              hipStream_t st);
 // extra rows: e_r.z for z = x (eval != 0: residuals against the targets) or the selected direction (eval == 0)

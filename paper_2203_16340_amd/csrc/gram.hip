@@ -713,8 +713,10 @@ __device__ __forceinline__ void wide_role(const WideCtx& w, const Opts& op, cons
     };
     bool in_next;
     int64_t ec_next = pair_index(blockIdx.x, in_next);
+    const bool ub_same = op.uniform_bounds != 0;       // same bounds everywhere: l and u are not streamed
     f64x2 xn = *reinterpret_cast<const f64x2*>(x + ec_next), gn = *reinterpret_cast<const f64x2*>(w.g + ec_next);
-    f64x2 ln = *reinterpret_cast<const f64x2*>(l + ec_next), un = *reinterpret_cast<const f64x2*>(u + ec_next);
+    f64x2 ln = f64x2{op.lo, op.lo}, un = f64x2{op.hi, op.hi};
+    if (!ub_same) { ln = *reinterpret_cast<const f64x2*>(l + ec_next); un = *reinterpret_cast<const f64x2*>(u + ec_next); }
     unsigned short mkn = dbg_inputs ? *reinterpret_cast<const unsigned short*>(mask + ec_next) : (unsigned short)0;
     for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
         const bool in = in_next;
@@ -723,7 +725,7 @@ __device__ __forceinline__ void wide_role(const WideCtx& w, const Opts& op, cons
         const unsigned short mk = mkn;
         ec_next = pair_index(ch + gridDim.x, in_next);
         xn = *reinterpret_cast<const f64x2*>(x + ec_next); gn = *reinterpret_cast<const f64x2*>(w.g + ec_next);
-        ln = *reinterpret_cast<const f64x2*>(l + ec_next); un = *reinterpret_cast<const f64x2*>(u + ec_next);
+        if (!ub_same) { ln = *reinterpret_cast<const f64x2*>(l + ec_next); un = *reinterpret_cast<const f64x2*>(u + ec_next); }
         if (dbg_inputs) mkn = *reinterpret_cast<const unsigned short*>(mask + ec_next);
         bool f0, f1;
         if (dbg_inputs) {

@@ -172,7 +172,8 @@ __global__ __launch_bounds__(kBlock) void k_ot_update_gauss(Dims dm, Opts op, Ot
                 const double cj = a.omega ? a.omega[dm.rows + j] * t[dm.rows + j] : 0.0;
                 const double y = alpha * fma(dm.lambda, p[e], ri + cj);
                 const double xi = x[e];
-                const double xn = clampd(fma(alpha, p[e], xi), l[e], u[e]);
+                const double xn = op.uniform_bounds ? clampd(fma(alpha, p[e], xi), op.lo, op.hi)
+                                                    : clampd(fma(alpha, p[e], xi), l[e], u[e]);
                 Sn[e] = xn - xi;
                 Yn[e] = y;
                 x[e] = xn;
@@ -279,7 +280,7 @@ __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int 
 }
 
 // x+ = P(x + a p); g+ = M + lambda (log x+ + 1) + K^T (omega . (res + a K p)); pair; f+ from scratch at x+.
-__global__ __launch_bounds__(kBlock) void k_ot_update_entropy(Dims dm, OtArgs a, const double* __restrict__ res,
+__global__ __launch_bounds__(kBlock) void k_ot_update_entropy(Dims dm, Opts op, OtArgs a, const double* __restrict__ res,
                                                               const double* __restrict__ t, const double* __restrict__ p1,
                                                               const double* __restrict__ p2, const double* __restrict__ l,
                                                               const double* __restrict__ u, double* __restrict__ x,
@@ -305,7 +306,8 @@ __global__ __launch_bounds__(kBlock) void k_ot_update_entropy(Dims dm, OtArgs a,
                 const double cj = a.omega ? a.omega[dm.rows + j] * fma(alpha, t[dm.rows + j], res[dm.rows + j]) : 0.0;
                 const double mij = m_at(a.M, dm.dtype, i * dm.ld + j);
                 const double xi = x[e];
-                const double xn = clampd(fma(alpha, p[e], xi), l[e], u[e]);
+                const double xn = op.uniform_bounds ? clampd(fma(alpha, p[e], xi), op.lo, op.hi)
+                                                    : clampd(fma(alpha, p[e], xi), l[e], u[e]);
                 const double lg = log(xn);
                 const double gn = mij + dm.lambda * (lg + 1.0) + (ri + cj);
                 Sn[e] = xn - xi;
@@ -404,7 +406,7 @@ void launch_ot_step_entropy(const Dims& dm, const Opts& op, const Geometry& ge, 
     hipLaunchKernelGGL(k_ot_ls_entropy<kLsTail>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
                        ge.ot_row_blocks + ge.ot_col_blocks, 2 + kLsBatch + kLsTail, 1, (const double*)bf.losspart,
                        (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
-    hipLaunchKernelGGL(k_ot_update_entropy, dim3(ge.ot_el_blocks), dim3(kBlock), 0, st, dm, a, (const double*)bf.row,
+    hipLaunchKernelGGL(k_ot_update_entropy, dim3(ge.ot_el_blocks), dim3(kBlock), 0, st, dm, op, a, (const double*)bf.row,
                        (const double*)bf.t, (const double*)bf.p1, (const double*)bf.p2, (const double*)bf.l,
                        (const double*)bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, bf.redpart);
     const int64_t count = dm.rows + dm.cols;

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
                                                 const double* __restrict__ S, const double* __restrict__ Y,
                                                 Scal* __restrict__ scal, double* __restrict__ d,
                                                 double* __restrict__ p1, double* __restrict__ p2,
-                                                double* __restrict__ redpart, int d_given) {
+                                                double* __restrict__ redpart, int d_given, int store_d) {
     __shared__ double delta_s[kMaxV + 8];
     __shared__ const double* vecp[kMaxV + 8];
     __shared__ double red[kWaves * 7];
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
                 }
                 de = -q;
             }
-            d[e] = de;
+            if (store_d) d[e] = de;
         }
         const double xe = x[e], ge = g[e], le = l[e], ue = u[e];
         const double a = clampd(xe + de, le, ue) - xe;
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
                                                       const double* __restrict__ S, const double* __restrict__ Y,
                                                       Scal* __restrict__ scal, double* __restrict__ d,
                                                       double* __restrict__ p1, double* __restrict__ p2,
-                                                      double* __restrict__ redpart, int d_given) {
+                                                      double* __restrict__ redpart, int d_given, int store_d) {
     __shared__ double delta_s[kMaxV + 24];
     __shared__ double red[kWaves * 7];
     __shared__ int flag;
@@ -181,8 +181,10 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
     };
     bool in_next;
     int64_t ec_next = pair_index(blockIdx.x, in_next);
+    const bool ub_same = op.uniform_bounds != 0;                 // same bounds everywhere: l and u are not streamed
     dir_f64x2 xn = *reinterpret_cast<const dir_f64x2*>(x + ec_next), gn = *reinterpret_cast<const dir_f64x2*>(g + ec_next);
-    dir_f64x2 ln = *reinterpret_cast<const dir_f64x2*>(l + ec_next), un = *reinterpret_cast<const dir_f64x2*>(u + ec_next);
+    dir_f64x2 ln = dir_f64x2{op.lo, op.lo}, un = dir_f64x2{op.hi, op.hi};
+    if (!ub_same) { ln = *reinterpret_cast<const dir_f64x2*>(l + ec_next); un = *reinterpret_cast<const dir_f64x2*>(u + ec_next); }
     unsigned short mkn = *reinterpret_cast<const unsigned short*>(mask + ec_next);
     for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
         const bool in = in_next;
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
         const unsigned short mk = in ? mkn : (unsigned short)0;
         ec_next = pair_index(ch + gridDim.x, in_next);
         xn = *reinterpret_cast<const dir_f64x2*>(x + ec_next); gn = *reinterpret_cast<const dir_f64x2*>(g + ec_next);
-        ln = *reinterpret_cast<const dir_f64x2*>(l + ec_next); un = *reinterpret_cast<const dir_f64x2*>(u + ec_next);
+        if (!ub_same) { ln = *reinterpret_cast<const dir_f64x2*>(l + ec_next); un = *reinterpret_cast<const dir_f64x2*>(u + ec_next); }
         mkn = *reinterpret_cast<const unsigned short*>(mask + ec_next);
         dir_f64x2 de;
         if (d_given) {
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
             }
             de.x = (mk & 0xffu) ? -q0 : 0.0;
             de.y = (mk >> 8) ? -q1 : 0.0;
-            if (in) *reinterpret_cast<dir_f64x2*>(d + e) = de;
+            if (in && store_d) *reinterpret_cast<dir_f64x2*>(d + e) = de;
         }
         if (in) {
             double a0, b0, a1, b1;
@@ -229,14 +231,15 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
     dir_finish(s, ub, op.eps, scal, redpart, red, &flag);
 }
 
-void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, hipStream_t st) {
+void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
+                hipStream_t st) {
     if (dm.n >= (1 << 17) && dm.n % 2 == 0) {
         hipLaunchKernelGGL(k_dir_pairs, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u,
-                           bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given);
+                           bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d);
         return;
     }
     hipLaunchKernelGGL(k_dir, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u, bf.mask,
-                       bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given);
+                       bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d);
 }
 
 // ---- after an evaluation pass: g and f ------------------------------------------------------------------
