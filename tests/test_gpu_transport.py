@@ -107,6 +107,27 @@ def test_box_solve_without_marginal_terms(kinds):
     np.testing.assert_allclose(x, closed, atol=1e-9)
 
 
+@pytest.mark.parametrize("kinds", KINDS, ids=KIND_IDS)
+def test_box_solve_with_a_different_box_per_entry(kinds):
+    """Bounds that differ from entry to entry (the kernels then stream l and u instead of taking one pair of
+    numbers from the argument block): the separable problem still has an entrywise closed form."""
+    kind, okind = kinds
+    rng = np.random.default_rng(10)
+    rows, cols, lam = 64, 310, 0.5
+    M = rng.standard_normal((rows, cols))
+    n = rows * cols
+    lo = 0.05 + 0.2 * rng.random(n)
+    hi = lo + 0.1 + rng.random(n)
+    s = _solver(kind, M, lo, hi, 6, lam, tol=1e-10)
+    s.set_x(to_dev(lo))
+    info = s.solve()
+    x = s.x().cpu().numpy()
+    s.close()
+    assert info.status == L.CONVERGED, info.as_dict()
+    free = -M.reshape(-1) / lam if kind == L.OBJ_OT_GAUSS else np.exp(-M.reshape(-1) / lam - 1.0)
+    np.testing.assert_allclose(x, np.clip(free, lo, hi), atol=1e-9)
+
+
 def _run_gpu(p, tol, ctol, max_outer=100, max_iter=20000, dtype=np.float64, eps=1e-10):
     al = L.AuglagMarginals(p.kind, to_dev(p.M.astype(dtype)), to_dev(np.concatenate([p.u, p.v])), to_dev(p.l), to_dev(p.ub),
                            p.m, lam=p.lam, options=L.default_options(tol=tol, max_iter=max_iter, eps=eps),
