@@ -260,6 +260,28 @@ def test_full_size_solve_properties(dataset):
     print(f"[transport] full size ds{dataset}: outer {info.outer}, inner {info.inner_iters}, violation {info.violation:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("kinds", KINDS, ids=KIND_IDS)
+def test_long_vector_runs_are_bit_reproducible(kinds):
+    """163840 variables: 512 workgroups of the Gram kernel, partials added in two levels by whichever workgroups
+    finish last -- the order of the additions must not depend on that."""
+    kind, _ = kinds
+    rng = np.random.default_rng(12)
+    rows, cols = 512, 320
+    M, u, v = _problem(rng, rows, cols)
+    n, lam, rho, lower = rows * cols, 0.5, 3.0, (0.0 if kind == L.OBJ_OT_GAUSS else 1e-30)
+    x0 = np.where(rng.random(n) < 0.5, lower, rng.random(n) / n)
+    outs = []
+    for _ in range(2):
+        s = _solver(kind, M, np.full(n, lower), np.full(n, np.inf), 10, lam, np.concatenate([u, v]), np.full(rows + cols, rho),
+                    tol=0.0)
+        s.set_x(to_dev(x0))
+        for _ in range(25):
+            s.step(want_info=False)
+        outs.append((s.x().clone(), s.g().clone(), s.info().f))
+        s.close()
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1]) and outs[0][2] == outs[1][2]
+
+
 def test_entropy_rejects_a_zero_lower_bound():
     M = np.zeros((4, 5))
     with pytest.raises(L.LbfgsbError) as e:
