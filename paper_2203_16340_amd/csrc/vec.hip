@@ -492,10 +492,26 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int fi
 #pragma unroll
         for (int j = 0; j < NTRY; ++j) { al[j] = a; s[j] = 0.0; a *= op.backtrack; }
     }
-    for (int64_t r = (int64_t)blockIdx.x * kBlock + tid; r < dm.rows; r += (int64_t)gridDim.x * kBlock) {
-        const double y = yl[r], q = -y * z[r], sq = sigmoid_d(q), ty = -y * t[r];
+    // four rows per trip: the transcendental chains of different rows are independent, and the few waves of this
+    // kernel are latency-bound, so interleaving them is what shortens it
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t r0 = (int64_t)blockIdx.x * kBlock + tid; r0 < dm.rows; r0 += 4 * stride) {
+        double q[4], sq[4], ty[4];
 #pragma unroll
-        for (int j = 0; j < NTRY; ++j) s[j] += softplus_diff(q, sq, al[j] * ty);
+        for (int k = 0; k < 4; ++k) {
+            const int64_t r = r0 + k * stride;
+            const bool in = r < dm.rows;
+            const double y = in ? yl[r] : 0.0;          // y = 0: q = ty = 0, the row contributes log1p(0.5 * expm1(0)) = 0
+            q[k] = -y * (in ? z[r] : 0.0);
+            ty[k] = -y * (in ? t[r] : 0.0);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) sq[k] = sigmoid_d(q[k]);
+#pragma unroll
+        for (int j = 0; j < NTRY; ++j) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) s[j] += softplus_diff(q[k], sq[k], al[j] * ty[k]);
+        }
     }
     block_sum<NTRY, kWaves>(s, red);
     if (tid == 0) {
