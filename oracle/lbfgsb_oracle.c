@@ -60,11 +60,18 @@
  *     ctol and the inner solve converged (or after max_outer iterations); every inner solve is
  *     warm-started at the previous x with an empty pair memory and run to the box solver's own
  *     tolerance; x^0 is the caller's (the listing's x^0 = 0 when that is feasible).
+ *   - Joint probability: the paper names the regularisers without formulas.  Taken here: Gaussian
+ *     r(P) = 0.5 sum P_ij^2, entropy r(P) = sum P_ij log P_ij (the negative entropy) with 0 log 0 = 0.
+ *     The entropy's gradient log P + 1 is -inf at P = 0, so callers give it a (tiny) positive lower bound
+ *     and start there; the oracle itself only evaluates what it is given.
  *
  * Parity pins (tests/test_oracle_*.py): KKT at the returned point, numpy lstsq when no
  * bound is active, brute-force active-set enumeration, scipy nnls / lsq_linear /
  * L-BFGS-B minimisers, dense BFGS-matrix construction for Algorithm 3, truth tables for
- * Eq. (ws) and Algorithm 2, finite differences for the gradients.  The individual
+ * Eq. (ws) and Algorithm 2, finite differences for the gradients; for the transport kinds the same
+ * objective written as the generic quadratic form with a dense 0/1 constraint matrix, entrywise closed
+ * forms, the closed-form couplings for zero cost, the dual structure of the solution and scipy's SLSQP
+ * (tests/test_oracle_transport.py).  The individual
  * trajectory (iterates, step lengths) is parity unpinned: the paper prints no worked
  * example and none of the constants above.
  */
