@@ -165,7 +165,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     if ((size_t)ge.upd_blocks * 2 > red) red = (size_t)ge.upd_blocks * 2;
     if (is_transport(dm.kind) && (size_t)ge.ot_el_blocks > red) red = (size_t)ge.ot_el_blocks;
     L.redpart = take(red * 8);
-    L.lspart = take((size_t)ge.ls_blocks * 32 * 8);   // up to 32 step lengths per sweep (entropy line search)
+    L.lspart = take((size_t)ge.ls_blocks * 64 * 8);   // up to 64 step lengths per sweep (entropy line search: 51)
     L.wextra = take(dm.n_extra > 0 ? (size_t)dm.n * 8 : 8);
     L.xres = take((size_t)(dm.n_extra + 1) * 8);
     L.total = off;

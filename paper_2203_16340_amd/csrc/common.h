@@ -292,7 +292,7 @@ struct Buffers {
     double *losspart;       // loss partials of the A pass
     double *grampart;       // gram_blocks x gram_entries
     double *redpart;        // partials of the direction / update / finish kernels
-    double *lspart;         // ls_blocks x kLsBatch
+    double *lspart;         // ls_blocks x (step lengths per sweep, at most 64)
     double *wextra;         // n: contribution of the extra rows to the columns of the gradient (or of its change)
     double *xres;           // n_extra residuals e_r.x - target_r of the last evaluation, then [n_extra] the loss term
 };

@@ -203,11 +203,13 @@ __device__ __forceinline__ double entropy_h(double r) {
     return (1.0 + r) * log1p(r) - r;
 }
 
-// NTRY step lengths a0 backtrack^first, ... per sweep over (x, p).  The first launch tries two; further launches,
-// which return at once when an earlier one found the step, try the next kLsBatch and then kLsTail at a time (a
-// long run of rejected steps happens at a start on the lower bound, where p/x is huge).  Only beyond those does the
-// last workgroup of the last launch go on alone, one length at a time.
-constexpr int kLsTail = 26;   // 2 + kLsBatch + 2 kLsTail = 62 step lengths cover the default limit of 60 backtracks
+// NTRY step lengths a0 backtrack^first, ... per sweep over (x, p).  The first launch tries two; two further
+// launches, which return at once when an earlier one found the step (such a launch still costs ~4.5 us: the scalar
+// block was just written, so its status word comes from memory), try the next kLsBatch and then kLsTail (a long run
+// of rejected steps happens at a start on the lower bound, where p/x is huge).  Together they cover the default
+// limit of 60 backtracks; only beyond those does the last workgroup of the last launch go on alone, one length at
+// a time.
+constexpr int kLsTail = 51;   // 2 + kLsBatch + kLsTail = 61 step lengths
 
 template <int NTRY>
 __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int loss_parts, int first, int last_resort,
@@ -221,17 +223,19 @@ __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int 
     if (first > 0 && scal->ls_ok) return;            // an earlier launch of this iteration found the step
     const int tid = threadIdx.x;
     const double* p = scal->branch == 1 ? p1 : p2;
-    double al[NTRY], s[NTRY];
-    {
-        double v = fmin(1.0, scal->alpha_ub);
-        for (int k = 0; k < first; ++k) v *= op.backtrack;
+    double s[NTRY];
+    double a_first = fmin(1.0, scal->alpha_ub);      // step lengths by repeated multiplication, the same everywhere
+    for (int k = 0; k < first; ++k) a_first *= op.backtrack;
 #pragma unroll
-        for (int k = 0; k < NTRY; ++k) { al[k] = v; s[k] = 0.0; v *= op.backtrack; }
-    }
+    for (int k = 0; k < NTRY; ++k) s[k] = 0.0;
     for (int64_t e = (int64_t)blockIdx.x * kBlock + tid; e < dm.n; e += (int64_t)gridDim.x * kBlock) {
         const double xe = x[e], ratio = p[e] / xe;
+        double a = a_first;
 #pragma unroll
-        for (int k = 0; k < NTRY; ++k) s[k] = fma(xe, entropy_h(al[k] * ratio), s[k]);
+        for (int k = 0; k < NTRY; ++k) {
+            s[k] = fma(xe, entropy_h(a * ratio), s[k]);
+            a *= op.backtrack;
+        }
     }
     block_sum<NTRY, kWaves>(s, red);
     if (tid == 0) {
@@ -250,14 +254,14 @@ __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int 
     }
     block_sum<NTRY, kWaves>(tot, red);
     int found = -1;
-    double a_acc = 0.0;
+    double a_acc = 0.0, av = a_first;
 #pragma unroll
     for (int k = 0; k < NTRY; ++k) {
-        const double df = al[k] * (gp + 0.5 * al[k] * tt) + dm.lambda * tot[k];
-        if (found < 0 && first + k <= op.max_backtracks && isfinite(df) && df <= op.c1 * al[k] * gp) { found = first + k; a_acc = al[k]; }
+        const double df = av * (gp + 0.5 * av * tt) + dm.lambda * tot[k];
+        if (found < 0 && first + k <= op.max_backtracks && isfinite(df) && df <= op.c1 * av * gp) { found = first + k; a_acc = av; }
+        if (k + 1 < NTRY) av *= op.backtrack;
     }
     // rare: continue one step length at a time (every thread holds the same totals: uniform control flow)
-    double av = al[NTRY - 1];
     for (int k = first + NTRY; last_resort && found < 0 && k <= op.max_backtracks; ++k) {
         av *= op.backtrack;
         double sv[1] = {0.0};
@@ -401,10 +405,7 @@ void launch_ot_step_entropy(const Dims& dm, const Opts& op, const Geometry& ge, 
                        ge.ot_row_blocks + ge.ot_col_blocks, 2, 0, (const double*)bf.losspart, (const double*)bf.x,
                        (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
     hipLaunchKernelGGL(k_ot_ls_entropy<kLsTail>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
-                       ge.ot_row_blocks + ge.ot_col_blocks, 2 + kLsBatch, 0, (const double*)bf.losspart,
-                       (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
-    hipLaunchKernelGGL(k_ot_ls_entropy<kLsTail>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
-                       ge.ot_row_blocks + ge.ot_col_blocks, 2 + kLsBatch + kLsTail, 1, (const double*)bf.losspart,
+                       ge.ot_row_blocks + ge.ot_col_blocks, 2 + kLsBatch, 1, (const double*)bf.losspart,
                        (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
     hipLaunchKernelGGL(k_ot_update_entropy, dim3(ge.ot_el_blocks), dim3(kBlock), 0, st, dm, op, a, (const double*)bf.row,
                        (const double*)bf.t, (const double*)bf.p1, (const double*)bf.p2, (const double*)bf.l,
