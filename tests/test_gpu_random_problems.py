@@ -1,0 +1,84 @@
+"""Whole solves of randomly drawn small problems against the CPU oracle: objective kind, shape (single rows and
+columns, sizes around the tile and wave widths), memory m, storage type, A-pass organisation and the kind of box
+(none, one-sided, two-sided, mixed with infinities, coinciding bounds) all vary together.  What the method fixes is
+compared: feasibility, that the reported f is the objective at the returned point (recomputed with numpy), and the
+final objective value when both sides converged (1e-6 relative for fp64-stored matrices at the relative
+stopping tolerance 1e-7 used here, 1e-4 for fp32-stored ones)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2203_16340_amd as L
+import workloads
+from gpu_helpers import DEV, host_gradient, host_objective
+
+pytestmark = pytest.mark.gpu
+
+SMALL = dict(rows=[1, 2, 7, 33, 64, 65, 130, 257, 400, 900], cols=[1, 2, 3, 8, 31, 64, 66, 128, 250, 513],
+             m=[1, 2, 3, 5, 10, 12, 17])
+LARGER = dict(rows=[5, 100, 511, 1025, 2300], cols=[4, 17, 100, 255, 1000, 1026, 2052], m=[1, 4, 10, 11, 20, 31])
+
+
+def draw(pool, case):
+    rng = np.random.default_rng(770000 + case)
+    kind = int(rng.choice([workloads.OBJ_LSQ, workloads.OBJ_LSQ_L1SPLIT, workloads.OBJ_LOGISTIC_L2]))
+    rows, cols, m = (int(rng.choice(pool[k])) for k in ("rows", "cols", "m"))
+    dtype = np.float64 if rng.random() < 0.6 else np.float32
+    a_pass = int(rng.choice([L.APASS_AUTO, L.APASS_TWO_PASS, L.APASS_FUSED]))
+    A = (rng.standard_normal((rows, cols)) / math.sqrt(rows)).astype(dtype)
+    n = 2 * cols if kind == workloads.OBJ_LSQ_L1SPLIT else cols
+    b = np.where(rng.random(rows) < 0.5, -1.0, 1.0) if kind == workloads.OBJ_LOGISTIC_L2 else rng.standard_normal(rows)
+    box = int(rng.integers(0, 5))
+    if kind == workloads.OBJ_LSQ_L1SPLIT or box == 0:
+        l, u = np.zeros(n), np.full(n, np.inf)
+    elif box == 1:
+        l, u = np.full(n, -np.inf), np.full(n, np.inf)
+    elif box == 2:
+        l, u = -rng.random(n), rng.random(n)
+    elif box == 3:
+        l = np.where(rng.random(n) < 0.5, -np.inf, -rng.random(n))
+        u = np.where(rng.random(n) < 0.5, np.inf, rng.random(n))
+    else:
+        l = 0.3 * rng.standard_normal(n)
+        u = l + np.where(rng.random(n) < 0.2, 0.0, rng.random(n))      # a fifth of the variables have l = u
+    x0 = np.clip(0.5 * rng.standard_normal(n), l, u)
+    prob = workloads.Problem("random", kind, np.ascontiguousarray(A), b, l, u, x0, m,
+                             lam=0.05 if kind == workloads.OBJ_LSQ_L1SPLIT else 0.0,
+                             mu=0.05 if kind == workloads.OBJ_LOGISTIC_L2 else 0.0,
+                             tol=1e-7, tol_relative=True, max_iter=1500)
+    return prob, a_pass
+
+
+@pytest.mark.parametrize("pool,case", [("small", c) for c in range(60)] + [("larger", c) for c in range(100, 116)])
+def test_random_problem_matches_the_oracle(pool, case):
+    prob, a_pass = draw(SMALL if pool == "small" else LARGER, case)
+    try:
+        s = L.solver_for_problem(prob, DEV, a_pass=a_pass)
+    except L.LbfgsbError as e:
+        if e.code != L.E_UNSUPPORTED:
+            raise
+        s = L.solver_for_problem(prob, DEV, a_pass=L.APASS_AUTO)   # the fused pass does not take this shape
+    info = s.solve()
+    x = s.x().cpu().numpy()
+    s.close()
+    ref = oracle.solve_problem(prob)
+    assert np.all(x >= prob.l) and np.all(x <= prob.u)
+    f_host = host_objective(prob, x)
+    assert abs(info.f - f_host) <= 1e-8 * abs(f_host) + 1e-14
+    tol = 1e-6 if prob.A.dtype == np.float64 else 1e-4
+    slack = tol * max(abs(ref.info.f), 1e-12) + 1e-12
+    if info.status != L.CONVERGED or ref.info.status != oracle.CONVERGED:
+        # the iteration limit (the method zigzags when many bounds become active one at a time, and the two sides
+        # do not follow the same trajectory): a side that converged is not above the one that did not
+        assert info.status in (L.CONVERGED, L.MAX_ITER) and ref.info.status in (oracle.CONVERGED, oracle.MAX_ITER)
+        if info.status == L.CONVERGED:
+            assert info.f <= ref.info.f + slack
+        if ref.info.status == oracle.CONVERGED:
+            assert ref.info.f <= info.f + slack
+        return
+    assert abs(info.f - ref.info.f) <= slack, (info.f, ref.info.f)
+    g = host_gradient(prob, x)
+    mask = oracle.free_mask(x, g, prob.l, prob.u, 1e-10).astype(bool)
+    assert np.linalg.norm(g[mask]) <= 1.5 * max(info.pg2, 1e-300) + 1e-9 * np.linalg.norm(g) + 1e-12
