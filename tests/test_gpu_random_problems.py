@@ -3,7 +3,8 @@ columns, sizes around the tile and wave widths), memory m, storage type, A-pass 
 (none, one-sided, two-sided, mixed with infinities, coinciding bounds) all vary together.  What the method fixes is
 compared: feasibility, that the reported f is the objective at the returned point (recomputed with numpy), and the
 final objective value when both sides converged (1e-6 relative for fp64-stored matrices at the relative
-stopping tolerance 1e-7 used here, 1e-4 for fp32-stored ones)."""
+stopping tolerance 1e-7 used here, 1e-4 for fp32-stored ones).  A second test draws strictly convex quadratic forms,
+with and without equality rows (Algorithm 4), where the minimiser is unique and is compared itself."""
 import math
 
 import numpy as np
@@ -82,3 +83,58 @@ def test_random_problem_matches_the_oracle(pool, case):
     g = host_gradient(prob, x)
     mask = oracle.free_mask(x, g, prob.l, prob.u, 1e-10).astype(bool)
     assert np.linalg.norm(g[mask]) <= 1.5 * max(info.pg2, 1e-300) + 1e-9 * np.linalg.norm(g) + 1e-12
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_quadratic_form_with_and_without_constraint_rows(case):
+    """Strictly convex quadratic forms (unique minimiser, so the points themselves are compared): box only, or with
+    one to three equality rows through Algorithm 4; sign vector or none, fp64 or fp32 matrix."""
+    from gpu_helpers import rel_err, to_dev
+    rng = np.random.default_rng(880000 + case)
+    n = int(rng.choice([1, 2, 5, 64, 65, 130, 257, 513, 1030]))
+    n_eq = int(rng.choice([0, 0, 1, 2, 3])) if n >= 5 else 0
+    dtype = np.float64 if rng.random() < 0.7 else np.float32
+    m = int(rng.choice([1, 3, 8, 12]))
+    B = rng.standard_normal((n, max(n, 2)))
+    K = (B @ B.T / n + 0.5 * np.eye(n)).astype(dtype)
+    K = np.ascontiguousarray(0.5 * (K + K.T))
+    b = 2.0 * rng.standard_normal(n)
+    sign = np.where(rng.random(n) < 0.5, -1.0, 1.0) if rng.random() < 0.6 else None
+    if rng.random() < 0.5:
+        l, u = np.zeros(n), np.ones(n)
+    else:
+        l = np.where(rng.random(n) < 0.3, -np.inf, -rng.random(n))
+        u = np.where(rng.random(n) < 0.3, np.inf, 1.0 + rng.random(n))
+    x0 = np.clip(np.zeros(n), l, u)
+    sd = to_dev(sign) if sign is not None else None
+    ftol = 1e-8 if dtype == np.float64 else 1e-4
+    if n_eq == 0:
+        obj = oracle.Objective(oracle.QP, K, b, sign=sign)
+        osol = oracle.Solver(obj, l, u, x0, m, oracle.default_options(tol=1e-9))
+        ref = osol.solve()
+        osol.close()
+        sol = L.Solver(L.OBJ_QP, to_dev(K), to_dev(b), to_dev(l), to_dev(u), m, sign=sd, options=L.default_options(tol=1e-9))
+        sol.set_x(to_dev(x0))
+        info = sol.solve()
+        x = sol.x().cpu().numpy()
+        sol.close()
+        assert ref.info.status == oracle.CONVERGED and info.status == L.CONVERGED, info.as_dict()
+        assert np.all(x >= l) and np.all(x <= u)
+        assert abs(info.f - ref.info.f) <= ftol * abs(ref.info.f) + 1e-12
+        assert rel_err(x, ref.x) <= (1e-6 if dtype == np.float64 else 1e-3) or np.linalg.norm(ref.x) < 1e-9
+        return
+    x_feas = np.clip(0.5 * rng.random(n), l, u)
+    Cm = rng.standard_normal((n_eq, n)) / math.sqrt(n)
+    d = Cm @ x_feas
+    obj = oracle.Objective(oracle.QP, K, b, sign=sign).set_constraints(Cm, d)
+    x_ref, lam_ref, _, iref = oracle.auglag_solve(obj, l, u, x0, m, oracle.default_options(tol=1e-9), ctol=1e-9, max_outer=200)
+    al = L.AuglagRows(L.OBJ_QP, to_dev(K), to_dev(b), to_dev(Cm), to_dev(d), to_dev(l), to_dev(u), m, sign=sd,
+                      options=L.default_options(tol=1e-9), ctol=1e-9, max_outer=200)
+    info = al.solve(to_dev(x0))
+    x, lam = al.x().cpu().numpy(), al.lam().cpu().numpy()
+    al.close()
+    assert iref.status == oracle.CONVERGED and info.status == L.CONVERGED, info.as_dict()
+    assert np.all(x >= l) and np.all(x <= u) and np.abs(Cm @ x - d).max() <= 1e-8
+    assert rel_err(x, x_ref) <= (1e-5 if dtype == np.float64 else 1e-3)
+    assert rel_err(lam, lam_ref) <= (1e-4 if dtype == np.float64 else 1e-2)
+    assert info.f == pytest.approx(iref.f, rel=10 * ftol, abs=1e-10)
