@@ -141,6 +141,36 @@ def test_async_steps_equal_synchronous_steps():
     a.close(); b.close()
 
 
+def test_solvers_on_their_own_streams_run_side_by_side():
+    """Two solvers created on two non-default streams (default priority), their steps enqueued alternately without
+    synchronising in between: each owns its workspace, scalar block and arrival counters, so both end bit-identical
+    to the same problems solved one after the other on the default stream."""
+    probs = [workloads.config("C2", scale=0.05), workloads.config("C4", scale=0.01)]
+    ref = []
+    for prob in probs:
+        s = L.solver_for_problem(prob, DEV, tol=0.0)
+        for _ in range(10):
+            s.step(want_info=False)
+        ref.append((s.x().clone(), s.info().f))
+        s.close()
+    streams = [torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)]
+    solvers = []
+    for prob, st in zip(probs, streams):
+        with torch.cuda.stream(st):
+            solvers.append(L.solver_for_problem(prob, DEV, tol=0.0))
+    for _ in range(10):
+        for s, st in zip(solvers, streams):
+            with torch.cuda.stream(st):
+                s.step(want_info=False)
+    for s, st, (x_ref, f_ref) in zip(solvers, streams, ref):
+        with torch.cuda.stream(st):
+            x, info = s.x().clone(), s.info()
+        st.synchronize()
+        assert info.iters == 10 and info.f == f_ref
+        assert torch.equal(x, x_ref)
+        s.close()
+
+
 def test_runs_are_bit_reproducible():
     prob = workloads.config("C3", scale=0.03)
     xs = []
