@@ -169,7 +169,11 @@ int lbfgsb_set_x(lbfgsb_solver* s, const double* x0);
 
 /* One iteration of Algorithm 1 (a no-op once the status is not RUNNING).  With
  * info_host == NULL the call only enqueues kernels and returns without synchronising; with a
- * non-NULL info_host it synchronises and fills it. */
+ * non-NULL info_host it synchronises and fills it.  The info_host == NULL form issues kernel launches
+ * only (no memset, copy or wait), so a run of such calls may be recorded into a HIP graph on the solver's
+ * stream; whether a step also recomputes residual and gradient (refresh_every) is decided on the host when
+ * the call is made, so a recorded run replays the pattern it was recorded with (use refresh_every = 0, or
+ * record a multiple of it).  Not while lbfgsb_enable_apass_timing is on: timed launches carry events. */
 int lbfgsb_step(lbfgsb_solver* s, lbfgsb_info* info_host);
 
 /* Iterates until the tolerance, max_iter or a line-search failure.  The device decides all

@@ -171,6 +171,36 @@ def test_solvers_on_their_own_streams_run_side_by_side():
         s.close()
 
 
+def test_steps_recorded_into_a_graph_replay_like_eager_steps():
+    """lbfgsb_step(info = NULL) launches kernels only, so a run of steps can be recorded into a HIP graph.  Every
+    replay (with eager work and a synchronisation in between) must leave exactly the state the same number of
+    eager steps leaves.  refresh_every = 0: the periodic recomputation is scheduled by the host when a step is
+    enqueued, and a recorded sequence would replay whatever pattern it was recorded with."""
+    K, REPLAYS = 6, 3
+    prob = workloads.config("C2", scale=0.05)
+    st = torch.cuda.Stream(device=DEV)
+    with torch.cuda.stream(st):
+        x0 = torch.from_numpy(prob.x0).to(DEV)
+        eager = L.solver_for_problem(prob, DEV, tol=0.0, refresh_every=0)
+        rec = L.solver_for_problem(prob, DEV, tol=0.0, refresh_every=0)
+        st.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            for _ in range(K):
+                rec.step(want_info=False)
+        rec.set_x(x0)                       # recording executes nothing: both start from x0
+        for r in range(REPLAYS):
+            graph.replay()
+            for _ in range(K):
+                eager.step(want_info=False)
+            gi, ei = rec.info(), eager.info()                # synchronises
+            assert gi.iters == ei.iters == K * (r + 1)
+            assert gi.f == ei.f
+            assert torch.equal(rec.x(), eager.x()) and torch.equal(rec.g(), eager.g())
+            st.synchronize()
+        eager.close(); rec.close()
+
+
 def test_runs_are_bit_reproducible():
     prob = workloads.config("C3", scale=0.03)
     xs = []
