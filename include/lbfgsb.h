@@ -207,7 +207,9 @@ void lbfgsb_destroy(lbfgsb_solver* s);
  *
  * The objective handed to lbfgsb_auglag_create is the STACKED problem: kind LSQ, A = [A; C] with
  * rows = data rows + n_eq, b = [b; d], row_weight NULL.  A and b are borrowed as before; the targets and
- * weights the algorithm rewrites live in the workspace.  info.status uses the LBFGSB_* termination codes
+ * weights the algorithm rewrites live in the workspace.  Between two inner solves only the constraint rows'
+ * targets and weights change; f and grad f at the unchanged x are brought up to date from those n_eq rows
+ * alone, not by another pass over the whole matrix.  info.status uses the LBFGSB_* termination codes
  * (LBFGSB_MAX_ITER: outer limit reached). */
 typedef struct lbfgsb_auglag lbfgsb_auglag;   /* opaque, host object */
 

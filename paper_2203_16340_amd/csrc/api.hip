@@ -735,6 +735,10 @@ struct lbfgsb_auglag {
     double* h_red;           // pinned host copy of red
     double rho;
     hipStream_t stream;
+    // stacked variant only: the constraint rows inside the caller's matrix, and n_eq doubles of scratch (the
+    // change of weight*residual per constraint row), for re-evaluating f and g after the targets changed
+    const void* c_rows = nullptr;
+    double* coef = nullptr;
 };
 
 namespace {
@@ -753,6 +757,42 @@ __global__ void k_al_prepare(int64_t n_eq, double rho, const double* __restrict_
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_eq; r += (int64_t)gridDim.x * blockDim.x) {
         beta[r] = d[r] - lambda[r] / rho;
         omega[r] = rho;
+    }
+}
+
+// Stacked variant, between two inner solves: only the targets beta and the weights omega of the constraint rows
+// change, so f and g at the unchanged x follow from the fresh residuals without another pass over the whole matrix:
+// with c_r . x = res_r + beta_r,  res_r' = c_r . x - beta_r',  f' = f + 0.5 sum (omega' res'^2 - omega res^2),
+// g' = g + C^T (omega' res' - omega res).  First kernel (one workgroup): new targets, weights and residuals, the
+// coefficients omega' res' - omega res, and f; second kernel: the n_eq x n product into g.
+__global__ __launch_bounds__(kBlock) void k_al_shift_rows(int64_t n_eq, double rho, const double* __restrict__ d,
+                                                          const double* __restrict__ lambda, double* __restrict__ beta,
+                                                          double* __restrict__ omega, double* __restrict__ res,
+                                                          double* __restrict__ coef, Scal* __restrict__ scal) {
+    __shared__ double lds[kWaves];
+    double df[1] = {0.0};
+    for (int64_t r = threadIdx.x; r < n_eq; r += kBlock) {
+        const double res_old = res[r], w_old = omega[r];
+        const double cx = res_old + beta[r];
+        const double b_new = d[r] - lambda[r] / rho;
+        const double res_new = cx - b_new;
+        coef[r] = rho * res_new - w_old * res_old;
+        df[0] += 0.5 * (rho * res_new * res_new - w_old * res_old * res_old);
+        beta[r] = b_new;
+        omega[r] = rho;
+        res[r] = res_new;
+    }
+    block_sum<1, kWaves>(df, lds);
+    if (threadIdx.x == 0) scal->f += df[0];
+}
+
+template <typename T>
+__global__ void k_al_shift_g(int64_t n_eq, int64_t cols, int64_t ld, const T* __restrict__ Crows,
+                             const double* __restrict__ coef, double* __restrict__ g) {
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < cols; j += (int64_t)gridDim.x * blockDim.x) {
+        double acc = 0.0;
+        for (int64_t r = 0; r < n_eq; ++r) acc = fma(coef[r], (double)Crows[r * ld + j], acc);
+        g[j] += acc;
     }
 }
 
@@ -786,7 +826,7 @@ __global__ __launch_bounds__(kBlock) void k_al_update(int64_t n_eq, double rho, 
 }
 
 size_t al_extra_bytes(int64_t rows, int64_t n_eq) {
-    return align_up((size_t)rows * 8) * 2 + align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8) + align_up(64);
+    return align_up((size_t)rows * 8) * 2 + 2 * align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8) + align_up(64);
 }
 
 int check_al(int64_t n, const lbfgsb_objective* o, int64_t n_eq) {
@@ -870,7 +910,9 @@ int lbfgsb_auglag_create(lbfgsb_auglag** out, int64_t n, int m, const double* l,
     double* omega = (double*)w; w += align_up((size_t)obj->rows * 8);
     al->beta_c = beta + rows_data; al->omega_c = omega + rows_data;
     al->lambda = (double*)w; w += align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8);
+    al->coef = (double*)w; w += align_up((size_t)(n_eq > 0 ? n_eq : 1) * 8);
     al->red = (double*)w;
+    al->c_rows = (const char*)obj->A + (size_t)rows_data * (size_t)obj->ld * (obj->dtype == LBFGSB_F64 ? 8 : 4);
     lbfgsb_objective inner_obj = *obj;
     inner_obj.b = beta;
     inner_obj.row_weight = omega;
@@ -1036,7 +1078,26 @@ int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info*
     double viol_prev = al->h_red[0];
     out.violation = viol_prev;
     for (int it = 0; it < al->ao.max_outer; ++it) {
-        if (it > 0) {
+        if (it > 0 && al->c_rows) {
+            // new targets/weights of the stacked constraint rows: the pair memory is cleared, and f and g at the
+            // unchanged x are shifted by the constraint rows' share (residuals and gradient are fresh at this point)
+            const double f_old = s->h_scal->f;
+            fresh_scal(s);
+            s->h_scal->f = f_old;
+            HIP_TRY(hipMemcpyAsync(s->bf.scal, s->h_scal, sizeof(Scal), hipMemcpyHostToDevice, s->stream));
+            hipLaunchKernelGGL(k_al_shift_rows, dim3(1), dim3(kBlock), 0, al->stream, al->n_eq, al->rho, al->d_c,
+                               (const double*)al->lambda, al->beta_c, al->omega_c, (double*)al->res_c, al->coef, s->bf.scal);
+            int gb = (int)((s->dm.cols + 255) / 256);
+            if (gb > 1024) gb = 1024;
+            if (s->dm.dtype == LBFGSB_F64)
+                hipLaunchKernelGGL(k_al_shift_g<double>, dim3(gb), dim3(256), 0, al->stream, al->n_eq, s->dm.cols, s->dm.ld,
+                                   (const double*)al->c_rows, (const double*)al->coef, s->bf.g);
+            else
+                hipLaunchKernelGGL(k_al_shift_g<float>, dim3(gb), dim3(256), 0, al->stream, al->n_eq, s->dm.cols, s->dm.ld,
+                                   (const float*)al->c_rows, (const double*)al->coef, s->bf.g);
+            s->steps_since_refresh = 0;
+            s->steps_since_set_x = 0;
+        } else if (it > 0) {
             // new targets/weights: the objective changed, so f and g are re-evaluated at x and the pair memory is cleared
             hipLaunchKernelGGL(k_al_prepare, dim3(pb), dim3(256), 0, al->stream, al->n_eq, al->rho, al->d_c, al->lambda,
                                al->beta_c, al->omega_c);

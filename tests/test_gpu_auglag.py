@@ -89,6 +89,34 @@ def test_equality_constraints_with_an_active_box(seed, rows, cols, n_eq):
     assert np.abs(x - np.clip(x - grad, cp.l, cp.u)).max() <= 1e-6
 
 
+@pytest.mark.parametrize("dtype,pad", [(np.float32, 0), (np.float64, 24), (np.float32, 8)], ids=["f32", "f64_ld", "f32_ld"])
+def test_stacked_rows_in_fp32_and_with_a_leading_dimension(dtype, pad):
+    """Between two inner solves f and g are shifted by the constraint rows' share, read from the caller's stacked
+    matrix: its element type and row stride must be honoured."""
+    cp = workloads.constrained_lsq(300, 96, 3, 0, seed=41, m=8)
+    A_s, b_s, n_eq, l_s, u_s, x0_s = cp.stacked()
+    A_s = A_s.astype(dtype)
+    rows = A_s.shape[0] - n_eq
+    A64 = A_s.astype(np.float64)
+    obj = oracle.Objective(oracle.LSQ, np.ascontiguousarray(A64[:rows]), cp.b).set_constraints(np.ascontiguousarray(A64[rows:]), cp.d)
+    x_ref, lam_ref, _, iref = oracle.auglag_solve(obj, cp.l, cp.u, cp.x0, cp.m, oracle.default_options(tol=1e-9), ctol=1e-9)
+    wide = torch.zeros((A_s.shape[0], A_s.shape[1] + pad), dtype=torch.from_numpy(A_s).dtype, device=DEV)
+    wide[:, :A_s.shape[1]] = to_dev(A_s)
+    if pad:
+        wide[:, A_s.shape[1]:] = 7.0                       # must never be read
+    al = L.Auglag(wide[:, :A_s.shape[1]], to_dev(b_s), n_eq, to_dev(l_s), to_dev(u_s), cp.m,
+                  options=L.default_options(tol=1e-9), ctol=1e-9)
+    info = al.solve(to_dev(x0_s))
+    x, lam = al.x().cpu().numpy(), al.lam().cpu().numpy()
+    al.close()
+    assert iref.status == oracle.CONVERGED and info.status == L.CONVERGED, info.as_dict()
+    assert info.outer > 2                                   # the shift between inner solves has run
+    assert rel_err(x, x_ref) <= 1e-6
+    assert rel_err(lam, lam_ref) <= 1e-5
+    assert info.f == pytest.approx(iref.f, rel=1e-7)
+    assert abs(info.outer - iref.outer) <= 1
+
+
 def test_inequality_rows_through_slack_columns_match_the_explicit_form():
     cp = workloads.constrained_lsq(200, 40, 1, 6, seed=31, m=6)
     x_ref, lam_ref, mu_ref, iref = _run_oracle(cp, 1e-10, 1e-9, max_outer=200)
