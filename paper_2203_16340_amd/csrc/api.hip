@@ -161,7 +161,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     if (is_transport(dm.kind) && ge.ot_row_blocks + ge.ot_col_blocks > lparts) lparts = ge.ot_row_blocks + ge.ot_col_blocks;
     L.losspart = take((size_t)lparts * 8);
     L.grampart = take(gram_partial_bytes(dm.n, dm.m));
-    size_t red = (size_t)ge.dir_blocks * 8;
+    size_t red = (size_t)ge.dir_blocks * (8 + 2 * kFoldMax);
     if ((size_t)ge.upd_blocks * 2 > red) red = (size_t)ge.upd_blocks * 2;
     if (is_transport(dm.kind) && (size_t)ge.ot_el_blocks > red) red = (size_t)ge.ot_el_blocks;
     L.redpart = take(red * 8);
@@ -286,11 +286,14 @@ void enqueue_step(lbfgsb_solver* s) {
         return;
     }
     launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
-    launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream);
+    // one or two extra rows ride along with the direction kernel; more get the kernel of their own
+    const bool fold = quad && dir_folds_extra_rows(s->dm);
+    const double* fold_rows = fold ? s->obj.extra_rows : nullptr;
+    launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream, fold_rows, s->obj.extra_weight);
     APassArgs a = base_args(s);
     a.select_p = 1;
     a.check_status = 1;
-    if (quad && s->dm.n_extra > 0)
+    if (quad && s->dm.n_extra > 0 && !fold)
         launch_extra_rows(s->dm, s->bf, s->obj.extra_rows, s->obj.extra_target, s->obj.extra_weight, 0, s->stream);
     if (s->dm.kind == LBFGSB_OBJ_QP) {
         a.mode = kRowQpDir;
@@ -299,7 +302,7 @@ void enqueue_step(lbfgsb_solver* s) {
             if (s->use_fused) launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
             else launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
         }
-        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->obj.sign, s->stream);
+        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->obj.sign, s->stream, fold_rows);
     } else if (quad) {
         a.mode = kRowDir;
         if (s->use_fused) {
@@ -309,7 +312,7 @@ void enqueue_step(lbfgsb_solver* s) {
             { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
             { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
         }
-        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, nullptr, s->stream);
+        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, nullptr, s->stream, fold_rows);
     } else if (s->use_fused) {
         // One read of X yields t = X p AND X^T psi for the first trial step min(1, alpha_ub).  The line
         // search over the margins then decides; only if it does not accept that first step does a second

@@ -14,6 +14,7 @@ constexpr int kMaxM = LBFGSB_MAX_M;
 constexpr int kMaxV = 64;          // 2*m + 1 <= 64 vectors enter the batched two-loop
 constexpr int kBlock = 256;        // threads per workgroup of every vector kernel (4 waves of 64)
 constexpr int kWaves = kBlock / 64;
+constexpr int kFoldMax = 2;       // extra dense rows the direction kernel handles itself (more: a kernel of their own)
 constexpr int kLsBatch = 8;        // step lengths the logistic line search evaluates per sweep over the rows
 
 // Which per-kernel arrival counter (Scal::counters) a kernel uses to find its last workgroup.
@@ -344,10 +345,12 @@ void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffe
                  int evaluate_stop, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 void launch_commit(const Dims& dm, const Buffers& bf, hipStream_t st);
 // store_d: also keep d itself (the primitive-level hooks read it; an iteration only needs the two candidates)
+bool dir_folds_extra_rows(const Dims& dm);
+// fold_rows / fold_weight: the objective's extra rows and their weights when they are to ride along (else NULL)
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
-                hipStream_t st);
+                hipStream_t st, const double* fold_rows = nullptr, const double* fold_weight = nullptr);
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
-                             hipStream_t st);
+                             hipStream_t st, const double* fold_rows = nullptr);
 // extra rows: e_r.z for z = x (eval != 0: residuals against the targets) or the selected direction (eval == 0)
 void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, const double* target, const double* weight,
                        int eval, hipStream_t st);

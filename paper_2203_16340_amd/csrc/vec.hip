@@ -28,13 +28,28 @@ void launch_set_status(const Buffers& bf, int status, hipStream_t st) {
 
 // ---- d = -B delta on the free set, then Algorithm 2 ------------------------------------------------------
 
-constexpr int kDirRed = 8;   // p1.g, p1.p1, x.p1, p2.g, p2.p2, x.p2, min step bound of p2, unused
+constexpr int kDirRed = 8 + 2 * kFoldMax;   // p1.g, p1.p1, x.p1, p2.g, p2.p2, x.p2, min step bound of p2, unused; then e_r.p1, e_r.p2 per folded extra row
+
+// Extra dense rows of the objective (at most kFoldMax of them) folded into the direction kernel: their products
+// with both candidate directions ride along with the other sums, the last workgroup turns the selected one into the
+// coefficient weight_r (e_r . p) of the row's contribution to the gradient change and into the curvature term
+// sum weight_r (e_r . p)^2, and the update kernel adds coef_r e_r on the fly.  (A kernel of its own for this, one
+// workgroup between the direction kernel and the pass over A, cost 9 us plus a launch gap per iteration.)
+struct FoldArgs {
+    int n_fold;              // 0: nothing folded
+    const double* E;         // n_fold x n, row-major
+    const double* weight;    // n_fold entries or NULL (= ones)
+    double* coef;            // out: n_fold coefficients
+    double* total;           // out: sum weight_r (e_r . p)^2
+};
 
 // Partial sums of the direction kernels -> Algorithm 2's choice between the two candidate directions (last workgroup).
 __device__ __forceinline__ void dir_finish(double (&s)[6], double ub, double eps, Scal* __restrict__ scal,
-                                           double* __restrict__ redpart, double* red, int* flag_p) {
+                                           double* __restrict__ redpart, double* red, int* flag_p,
+                                           double (&sx)[2 * kFoldMax], const FoldArgs& fold) {
     const int tid = threadIdx.x;
     block_sum<6, kWaves>(s, red);
+    if (fold.n_fold > 0) block_sum<2 * kFoldMax, kWaves>(sx, red);
     double mn = wave_min(ub);
     __syncthreads();
     if ((tid & 63) == 0) red[tid >> 6] = mn;
@@ -45,18 +60,27 @@ __device__ __forceinline__ void dir_finish(double (&s)[6], double ub, double eps
         double* part = redpart + (int64_t)blockIdx.x * kDirRed;
         for (int k = 0; k < 6; ++k) part[k] = s[k];
         part[6] = mn;
+        for (int k = 0; k < 2 * kFoldMax; ++k) part[8 + k] = sx[k];
     }
     if (!arrive_is_last(&scal->counters[kCntDir], flag_p)) return;
+    double tx[2 * kFoldMax];
     {
         // the workgroups' partials, strided over the threads in a fixed order, then the fixed-order reductions
         double t6[6] = {0, 0, 0, 0, 0, 0};
         double tmin = INFINITY;
+#pragma unroll
+        for (int k = 0; k < 2 * kFoldMax; ++k) tx[k] = 0.0;
         for (int b = tid; b < (int)gridDim.x; b += kBlock) {
 #pragma unroll
             for (int k = 0; k < 6; ++k) t6[k] += redpart[(int64_t)b * kDirRed + k];
             tmin = fmin(tmin, redpart[(int64_t)b * kDirRed + 6]);
+            if (fold.n_fold > 0) {
+#pragma unroll
+                for (int k = 0; k < 2 * kFoldMax; ++k) tx[k] += redpart[(int64_t)b * kDirRed + 8 + k];
+            }
         }
         block_sum<6, kWaves>(t6, red);
+        if (fold.n_fold > 0) block_sum<2 * kFoldMax, kWaves>(tx, red);
         tmin = wave_min(tmin);
         __syncthreads();
         if ((tid & 63) == 0) red[tid >> 6] = tmin;
@@ -74,10 +98,24 @@ __device__ __forceinline__ void dir_finish(double (&s)[6], double ub, double eps
     __syncthreads();
     if (tid == 0) {
         const double p1g = red[0], p1p1 = red[1];
-        if (p1g <= -eps * p1p1 && p1p1 >= eps) {
+        const int branch = (p1g <= -eps * p1p1 && p1p1 >= eps) ? 1 : 2;
+        if (branch == 1) {
             scal->branch = 1; scal->gp = p1g; scal->alpha_ub = 1.0; scal->pp = p1p1; scal->xp = red[2];
         } else {
             scal->branch = 2; scal->gp = red[3]; scal->alpha_ub = red[6]; scal->pp = red[4]; scal->xp = red[5];
+        }
+        if (fold.n_fold > 0) {
+            double total = 0.0;
+#pragma unroll
+            for (int r = 0; r < kFoldMax; ++r) {
+                if (r < fold.n_fold) {
+                    const double te = branch == 1 ? tx[2 * r] : tx[2 * r + 1];
+                    const double wr = fold.weight ? fold.weight[r] : 1.0;
+                    fold.coef[r] = wr * te;
+                    total += wr * te * te;
+                }
+            }
+            *fold.total = total;
         }
     }
 }
@@ -88,7 +126,7 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
                                                 const double* __restrict__ S, const double* __restrict__ Y,
                                                 Scal* __restrict__ scal, double* __restrict__ d,
                                                 double* __restrict__ p1, double* __restrict__ p2,
-                                                double* __restrict__ redpart, int d_given, int store_d) {
+                                                double* __restrict__ redpart, int d_given, int store_d, FoldArgs fold) {
     __shared__ double delta_s[kMaxV + 8];
     __shared__ const double* vecp[kMaxV + 8];
     __shared__ double red[kWaves * 7];
@@ -103,6 +141,9 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
     }
     __syncthreads();
     double s[6] = {0, 0, 0, 0, 0, 0};
+    double sx[2 * kFoldMax];
+#pragma unroll
+    for (int k = 0; k < 2 * kFoldMax; ++k) sx[k] = 0.0;
     double ub = INFINITY;
     for (int64_t e = (int64_t)blockIdx.x * kBlock + tid; e < n; e += (int64_t)gridDim.x * kBlock) {
         double de;
@@ -134,8 +175,16 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
         s[3] = fma(b, ge, s[3]); s[4] = fma(b, b, s[4]); s[5] = fma(xe, b, s[5]);
         if (b > 0.0) ub = fmin(ub, (ue - xe) / b);
         else if (b < 0.0) ub = fmin(ub, (le - xe) / b);
+#pragma unroll
+        for (int r = 0; r < kFoldMax; ++r) {
+            if (r < fold.n_fold) {
+                const double ev = fold.E[(int64_t)r * n + e];
+                sx[2 * r] = fma(ev, a, sx[2 * r]);
+                sx[2 * r + 1] = fma(ev, b, sx[2 * r + 1]);
+            }
+        }
     }
-    dir_finish(s, ub, op.eps, scal, redpart, red, &flag);
+    dir_finish(s, ub, op.eps, scal, redpart, red, &flag, sx, fold);
 }
 
 // The same for long vectors (n even, from 2^17 entries on): two elements per lane through 16-byte accesses; lanes
@@ -228,18 +277,28 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
             *reinterpret_cast<dir_f64x2*>(p2 + e) = dir_f64x2{b0, b1};
         }
     }
-    dir_finish(s, ub, op.eps, scal, redpart, red, &flag);
+    double sx[2 * kFoldMax];
+#pragma unroll
+    for (int k = 0; k < 2 * kFoldMax; ++k) sx[k] = 0.0;
+    dir_finish(s, ub, op.eps, scal, redpart, red, &flag, sx, FoldArgs{0, nullptr, nullptr, nullptr, nullptr});
+}
+
+// extra rows can ride along with the direction kernel for short vectors only
+bool dir_folds_extra_rows(const Dims& dm) {
+    return dm.n_extra > 0 && dm.n_extra <= kFoldMax && !(dm.n >= (1 << 17) && dm.n % 2 == 0);
 }
 
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
-                hipStream_t st) {
+                hipStream_t st, const double* fold_rows, const double* fold_weight) {
+    FoldArgs fold{0, nullptr, nullptr, nullptr, nullptr};
+    if (fold_rows && dir_folds_extra_rows(dm)) fold = FoldArgs{dm.n_extra, fold_rows, fold_weight, bf.wextra, bf.xres + dm.n_extra};
     if (dm.n >= (1 << 17) && dm.n % 2 == 0) {
         hipLaunchKernelGGL(k_dir_pairs, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u,
                            bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d);
         return;
     }
     hipLaunchKernelGGL(k_dir, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u, bf.mask,
-                       bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d);
+                       bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, fold);
 }
 
 // ---- after an evaluation pass: g and f ------------------------------------------------------------------
@@ -322,7 +381,8 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
                                                              double* __restrict__ S, double* __restrict__ Y,
                                                              Scal* __restrict__ scal, const double* __restrict__ sign,
                                                              const double* __restrict__ wextra,
-                                                             const double* __restrict__ xres) {
+                                                             const double* __restrict__ xres, int n_fold,
+                                                             const double* __restrict__ fold_rows) {
     __shared__ double lds[kBlock];
     __shared__ double red[kWaves];
     __shared__ double ls_alpha;
@@ -359,7 +419,11 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
                     const int64_t i = c + h * dm.cols;
                     double wi = h ? -w : w;
                     if (sign) wi *= sign[i];               // QP: the change of the gradient is s.(A (s.p))
-                    if (wextra) wi += wextra[i];
+                    if (n_fold > 0) {                       // folded extra rows: wextra[0 .. n_fold) holds their coefficients
+                        for (int r = 0; r < n_fold; ++r) wi = fma(wextra[r], fold_rows[(int64_t)r * dm.n + i], wi);
+                    } else if (wextra) {
+                        wi += wextra[i];
+                    }
                     const double y = alpha * wi;
                     const double xi = x[i];
                     const double xn = clampd(fma(alpha, p[i], xi), l[i], u[i]);
@@ -383,13 +447,14 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
 }
 
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
-                             hipStream_t st) {
+                             hipStream_t st, const double* fold_rows) {
+    const int n_fold = fold_rows && dir_folds_extra_rows(dm) ? dm.n_extra : 0;
     const bool qp = dm.kind == LBFGSB_OBJ_QP;   // its "partial columns" are the single vector t = A (s.p)
     hipLaunchKernelGGL(k_update_quadratic, dim3(ge.upd_blocks), dim3(kBlock), 0, st, dm, op, qp ? 1 : ge.w_parts,
                        ge.loss_parts, qp ? (const double*)bf.t : (const double*)bf.wpart, bf.losspart, bf.p1, bf.p2, bf.l,
                        bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, qp ? sign : nullptr,
                        dm.n_extra > 0 ? (const double*)bf.wextra : nullptr,
-                       dm.n_extra > 0 ? (const double*)bf.xres : nullptr);
+                       dm.n_extra > 0 ? (const double*)bf.xres : nullptr, n_fold, fold_rows);
 }
 
 // ---- extra dense rows ------------------------------------------------------------------------------------
