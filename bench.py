@@ -57,7 +57,7 @@ WORKLOADS = {
 # (scaled by the same counters read for a copy kernel of known size); filled in from the summaries
 # under profiles/ for the (config, a_pass) pairs that have been profiled, else null in the output.
 MEASURED_TRAFFIC_BYTES = {
-    ("C2", "fused"): 8.371e8,      # profiles/c2_nnls_20000x5000_f64_fused_a_pass.md      (algorithmic 8.0e8)
+    ("C2", "fused"): 8.369e8,      # profiles/c2_nnls_20000x5000_f64_fused_a_pass.md      (algorithmic 8.0e8)
     ("C3", "fused"): 1.682e9,      # profiles/c3_l1ls_10000x20000_f64_fused_a_pass.md     (algorithmic 1.6e9)
     ("C4", "fused"): 1.624e9,      # profiles/c4_logistic_200000x2000_f32_fused_a_pass.md (algorithmic 1.6e9)
     ("C5", "fused"): 8.099e9,      # profiles/c5_nnls_100000x20000_f32_fused_a_pass.md    (algorithmic 8.0e9)
