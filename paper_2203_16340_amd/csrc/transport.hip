@@ -47,25 +47,35 @@ __global__ __launch_bounds__(kBlock) void k_ot_sums(Dims dm, OtArgs a, int eval,
     double acc[RPW + 1];   // row sums, then the objective terms of these entries
 #pragma unroll
     for (int r = 0; r <= RPW; ++r) acc[r] = 0.0;
-    for (int64_t j0 = 0; j0 < dm.cols; j0 += kBlock) {
-        const int64_t j = j0 + tid;
-        const bool in = j < dm.cols;
-        double zv[RPW];
+    // several column tiles per round, all their loads issued before the first is used: the loop over the tiles is
+    // otherwise a chain of dependent trips to memory, and this kernel is nothing else
+    constexpr int JT = RPW <= 4 ? 4 : 2;
+    for (int64_t j0 = 0; j0 < dm.cols; j0 += JT * kBlock) {
+        double zv[JT][RPW];
 #pragma unroll
-        for (int r = 0; r < RPW; ++r) zv[r] = (in && r < nr) ? z[(r0 + r) * dm.cols + j] : 0.0;
-        double cs = 0.0;
+        for (int t = 0; t < JT; ++t) {
+            const int64_t j = j0 + t * kBlock + tid;
 #pragma unroll
-        for (int r = 0; r < RPW; ++r) { cs += zv[r]; acc[r] += zv[r]; }
-        if (eval) {
+            for (int r = 0; r < RPW; ++r) zv[t][r] = (j < dm.cols && r < nr) ? z[(r0 + r) * dm.cols + j] : 0.0;
+        }
 #pragma unroll
-            for (int r = 0; r < RPW; ++r) {
-                if (in && r < nr) {
-                    acc[RPW] = fma(m_at(a.M, dm.dtype, (r0 + r) * dm.ld + j), zv[r], acc[RPW]);
-                    acc[RPW] += reg_value(dm.kind, dm.lambda, zv[r]);
+        for (int t = 0; t < JT; ++t) {
+            const int64_t j = j0 + t * kBlock + tid;
+            const bool in = j < dm.cols;
+            double cs = 0.0;
+#pragma unroll
+            for (int r = 0; r < RPW; ++r) { cs += zv[t][r]; acc[r] += zv[t][r]; }
+            if (eval) {
+#pragma unroll
+                for (int r = 0; r < RPW; ++r) {
+                    if (in && r < nr) {
+                        acc[RPW] = fma(m_at(a.M, dm.dtype, (r0 + r) * dm.ld + j), zv[t][r], acc[RPW]);
+                        acc[RPW] += reg_value(dm.kind, dm.lambda, zv[t][r]);
+                    }
                 }
             }
+            if (in) wpart[(int64_t)blockIdx.x * dm.cols + j] = cs;
         }
-        if (in) wpart[(int64_t)blockIdx.x * dm.cols + j] = cs;
     }
     block_sum<RPW + 1, kWaves>(acc, red);
     if (tid == 0) {
