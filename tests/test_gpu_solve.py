@@ -311,3 +311,37 @@ def test_single_variable_and_single_row():
     info = s.solve()
     assert info.status == L.CONVERGED and s.x().item() == 0.25
     s.close()
+
+
+@pytest.mark.parametrize("a_pass,per_step", [(L.APASS_FUSED, 1), (L.APASS_TWO_PASS, 2)], ids=["fused", "two_pass"])
+def test_timing_of_the_passes_over_the_matrix(a_pass, per_step):
+    """The records behind the benchmark's roofline figure: one per launch that reads A (two per iteration when A is
+    read twice), the matrix's size as bytes per launch, durations that add up to less than the wall time of the same
+    steps, and the pause / resume / discard switch."""
+    import time
+    prob = workloads.config("C2", scale=0.1)
+    s = _gpu_solver(prob, a_pass, tol=0.0, refresh_every=0)
+    for _ in range(3):
+        s.step(want_info=False)                       # untimed
+    s.enable_apass_timing(2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        s.step(want_info=False)
+    torch.cuda.synchronize()
+    wall_ms = 1e3 * (time.perf_counter() - t0)
+    s.enable_apass_timing(0)                          # pause: the next steps are not recorded
+    for _ in range(4):
+        s.step(want_info=False)
+    count, total_ms, nbytes = s.apass_timing()
+    assert count == 10 * per_step
+    assert nbytes == prob.rows * prob.cols * prob.A.dtype.itemsize
+    assert 0.0 < total_ms < wall_ms
+    assert total_ms / count > 1e-3 * nbytes / 8e9     # no launch moves its bytes faster than the memory's peak
+    s.enable_apass_timing(1)                          # resume: records are kept and added to
+    for _ in range(2):
+        s.step(want_info=False)
+    assert s.apass_timing()[0] == 12 * per_step
+    s.enable_apass_timing(2)                          # discard
+    assert s.apass_timing()[0] == 0
+    s.close()
