@@ -287,3 +287,26 @@ def test_entropy_rejects_a_zero_lower_bound():
     with pytest.raises(L.LbfgsbError) as e:
         _solver(L.OBJ_OT_ENTROPY, M, np.zeros(20), np.full(20, np.inf), 3, 0.5)
     assert e.value.code == L.E_BOUNDS
+
+
+def test_timing_records_of_the_gram_kernel():
+    """Transport kinds have no pass over a matrix: the benchmark's roofline figure times the Gram kernel instead, from
+    the m-th iteration after lbfgsb_set_x on (pair memory full), and prices a launch at x, g, the newest y and the
+    mask in full (25 bytes per variable with uniform bounds) plus the 2m pair vectors at the free variables."""
+    rng = np.random.default_rng(77)
+    rows, cols, m, lam, rho = 300, 500, 4, 0.5, 5.0
+    M, u, v = _problem(rng, rows, cols)
+    n = rows * cols
+    s = _solver(L.OBJ_OT_GAUSS, M, np.zeros(n), np.full(n, np.inf), m, lam, np.concatenate([u, v]),
+                np.full(rows + cols, rho), tol=0.0)
+    s.set_x(to_dev(np.zeros(n)))
+    s.enable_apass_timing(2)
+    for _ in range(m + 6):
+        s.step(want_info=False)
+    info = s.info()
+    count, total_ms, nbytes = s.apass_timing()
+    assert count == 6
+    assert nbytes == 25.0 * n + 16.0 * m * (n - info.n_fixed)
+    assert 0 < info.n_fixed < n
+    assert total_ms / count > 1e-3 * nbytes / 8e9
+    s.close()
