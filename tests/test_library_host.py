@@ -180,3 +180,19 @@ def test_product_path_does_not_reach_the_oracle():
             if fn.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text.replace("no fallback", ""), f"{fn} mentions the oracle"
+
+
+def test_benchmark_refuses_more_than_one_gpu_and_a_machine_without_one():
+    """bench.py measures one GPU: --gpus N > 1 ends with a message that says so; without a GPU it ends with an
+    error instead of measuring anything else."""
+    import subprocess
+    import sys
+    import torch
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--config", "C1"], capture_output=True, text=True,
+                           timeout=300)
+        assert r.returncode != 0 and "no GPU" in (r.stdout + r.stderr)
+        assert '"metric"' not in r.stdout
