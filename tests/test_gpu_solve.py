@@ -345,3 +345,31 @@ def test_timing_of_the_passes_over_the_matrix(a_pass, per_step):
     s.enable_apass_timing(2)                          # discard
     assert s.apass_timing()[0] == 0
     s.close()
+
+
+def test_benchmark_line_has_the_agreed_fields():
+    """One run of bench.py on the smallest configuration in a process of its own: exactly one JSON line on stdout with
+    the fields the harness reads, the roofline object and the oracle timed beside it."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--config", "C1", "--steps", "10", "--warmup", "2",
+                        "--cpu-budget", "1"], capture_output=True, text=True, timeout=280)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 10 and d["warmup"] == 2 and d["higher_is_better"] is True
+    assert d["unit"] == "iterations/s" and d["data"] == "synthetic" and d["dtype"] == "f64" and d["vs_baseline"] is None
+    assert d["value"] > 0 and d["ms_per_step"] > 0 and d["value"] == pytest.approx(1e3 / d["ms_per_step"], rel=1e-6)
+    assert "workload" in d["config"] and "model" not in d["config"]
+    rf = d["roofline"]
+    assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
+    assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"]) and "traffic" in rf
+    cb = d["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["cores"] == 1 and cb["value"] > 0 and cb["unit"] == "iterations/s" and cb["sample"]
