@@ -122,6 +122,7 @@ Geometry make_geometry(const Dims& dm, const void* A) {
     ge.upd_blocks = ge.fin_blocks = (int)(ub > 2048 ? 2048 : ub);
     int64_t lb_ = (dm.rows + kBlock - 1) / kBlock;
     ge.ls_blocks = (int)(lb_ > 128 ? 128 : lb_);   // (the line search ends in a single-address arrival: few workgroups)
+    ge.lrows_blocks = (int)(lb_ > 512 ? 512 : lb_);   // the margins' update has no such ending: 512 measured faster than 128
     if (is_transport(dm.kind)) {
         int rpw = 1;
         while (rpw < kOtRpwMax && (dm.rows + rpw - 1) / rpw > 512) rpw *= 2;
@@ -158,6 +159,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     int lparts = ge.gemv_blocks;
     if (ge.fused_ok && ge.fused_blocks > lparts) lparts = ge.fused_blocks;
     if (ge.ls_blocks > lparts) lparts = ge.ls_blocks;
+    if (ge.lrows_blocks > lparts) lparts = ge.lrows_blocks;
     if (is_transport(dm.kind) && ge.ot_row_blocks + ge.ot_col_blocks > lparts) lparts = ge.ot_row_blocks + ge.ot_col_blocks;
     L.losspart = take((size_t)lparts * 8);
     L.grampart = take(gram_partial_bytes(dm.n, dm.m));
@@ -323,14 +325,14 @@ void enqueue_step(lbfgsb_solver* s) {
         launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, s->stream);
         launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
         launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 2, s->stream, nullptr, nullptr);
-        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.ls_blocks, s->stream);
+        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, s->stream);
     } else {
         a.mode = kRowLogiDir;
         { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
         launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 0, s->stream);
         launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
         { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
-        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.ls_blocks, s->stream);
+        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, s->stream);
     }
     s->steps_since_refresh++;
 }

@@ -271,7 +271,7 @@ struct Geometry {
     int fused_variant;      // index into the instantiation table
     int fused_blocks;       // workgroups = partial vectors per column and loss partials
     // vector kernels
-    int gram_blocks, dir_blocks, upd_blocks, fin_blocks, ls_blocks;
+    int gram_blocks, dir_blocks, upd_blocks, fin_blocks, ls_blocks, lrows_blocks;
     // transport kinds: workgroups of the marginal-sum kernel (each owns ot_rpw consecutive rows of P), of the
     // column-sum kernel, and of the entrywise kernels
     int ot_row_blocks, ot_rpw, ot_col_blocks, ot_el_blocks;

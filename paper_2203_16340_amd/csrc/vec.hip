@@ -657,7 +657,7 @@ __global__ __launch_bounds__(kBlock) void k_rows_logistic(Dims dm, const double*
 }
 
 void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* labels, hipStream_t st) {
-    hipLaunchKernelGGL(k_rows_logistic, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, labels, bf.t, bf.row, bf.psi, bf.scal,
+    hipLaunchKernelGGL(k_rows_logistic, dim3(ge.lrows_blocks), dim3(kBlock), 0, st, dm, labels, bf.t, bf.row, bf.psi, bf.scal,
                        bf.losspart);
 }
 
