@@ -71,7 +71,10 @@
  * Eq. (ws) and Algorithm 2, finite differences for the gradients; for the transport kinds the same
  * objective written as the generic quadratic form with a dense 0/1 constraint matrix, entrywise closed
  * forms, the closed-form couplings for zero cost, the dual structure of the solution and scipy's SLSQP
- * (tests/test_oracle_transport.py).  The individual
+ * (tests/test_oracle_transport.py).  The exhausted-line-search branch of orc_step (memory cleared, one
+ * retry from steepest descent, then ORC_LINESEARCH_FAILED) is pinned by hand-worked two-variable
+ * quadratics whose directions and Armijo decisions are re-derived in rational arithmetic from the dense
+ * BFGS matrix (tests/test_oracle_linesearch_exhausted.py).  The individual
  * trajectory (iterates, step lengths) is parity unpinned: the paper prints no worked
  * example and none of the constants above.
  */
