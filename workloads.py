@@ -143,19 +143,49 @@ def l1_split(rows: int, cols: int, *, seed: int, nnz_frac: float = 0.01, noise: 
 
 def logistic(rows: int, cols: int, *, seed: int, dtype=np.float32, label_noise: float = 0.5,
              mu: float = 1e-3, bound: float = 0.5, m: int = 10, name: str = "logistic",
-             tol: float = 1e-8, tol_relative: bool = False) -> Problem:
+             tol: float = 1e-8, tol_relative: bool = False, feature_scale: float = 1.0,
+             column_spread: float = 0.0, random_start: bool = False) -> Problem:
     """Box-constrained L2-regularised logistic regression:
     min (1/rows)*sum_i softplus(-y_i * X_i.w) + mu/2*||w||^2  s.t. -bound <= w <= bound.
-    X iid N(0,1); w* N(0,1); y = sign(X w* + label_noise*N(0,1)) in {-1,+1}."""
+    X iid N(0,1); w* N(0,1); y = sign(X w* + label_noise*N(0,1)) in {-1,+1}.
+
+    Badly scaled variants (for the line search: unit steps overshoot and have to be halved): after the labels
+    are fixed, column j of X is multiplied by feature_scale * 10^(column_spread * U(-1,1)); random_start
+    draws x0 uniformly in the box instead of 0.  With the defaults nothing more is drawn and X is untouched."""
     rng = np.random.default_rng(seed)
     X = _normal_matrix(rng, rows, cols, np.dtype(dtype))
     w_true = rng.standard_normal(cols)
     score = _matvec(X, w_true) + label_noise * rng.standard_normal(rows)
     y = np.where(score >= 0.0, 1.0, -1.0)
+    x0 = np.zeros(cols)
+    if feature_scale != 1.0 or column_spread != 0.0:
+        col_scale = feature_scale * 10.0 ** (column_spread * rng.uniform(-1.0, 1.0, cols))
+        X *= col_scale.astype(X.dtype)[None, :]
+    if random_start:
+        x0 = rng.uniform(-bound, bound, cols)
     return Problem(name=name, kind=OBJ_LOGISTIC_L2, A=X, b=y, l=np.full(cols, -bound),
-                   u=np.full(cols, bound), x0=np.zeros(cols), m=m, mu=mu, tol=tol,
+                   u=np.full(cols, bound), x0=x0, m=m, mu=mu, tol=tol,
                    tol_relative=tol_relative, x_true=w_true,
-                   meta=dict(seed=seed, label_noise=label_noise, bound=bound))
+                   meta=dict(seed=seed, label_noise=label_noise, bound=bound, feature_scale=feature_scale,
+                             column_spread=column_spread, random_start=random_start))
+
+
+def spectrum_lsq(rows: int, cols: int, *, seed: int, sigma_min: float, sigma_max: float, lower: float = -math.inf,
+                 m: int = 5, name: str = "spectrum_lsq") -> Problem:
+    """Least squares with a prescribed spectrum: A = U diag(sigma) V^T with U (rows x cols) and V (cols x cols)
+    orthonormal (QR of Gaussian matrices) and sigma log-uniform in [sigma_min, sigma_max]; b = 5*N(0,1).
+    With sigma_max^2 < 2 a unit steepest-descent step always satisfies the Armijo condition while unit
+    quasi-Newton steps sometimes do not, which is what the tests of an exhausted line search need.
+    Draw order: U's Gaussian, V's Gaussian, sigma, b."""
+    rng = np.random.default_rng(seed)
+    U, _ = np.linalg.qr(rng.standard_normal((rows, cols)))
+    V, _ = np.linalg.qr(rng.standard_normal((cols, cols)))
+    sigma = np.exp(rng.uniform(math.log(sigma_min), math.log(sigma_max), cols))
+    A = np.ascontiguousarray((U * sigma) @ V.T)
+    b = 5.0 * rng.standard_normal(rows)
+    return Problem(name=name, kind=OBJ_LSQ, A=A, b=b, l=np.full(cols, lower), u=np.full(cols, math.inf),
+                   x0=np.zeros(cols) if lower <= 0.0 else np.full(cols, lower), m=m, tol=1e-9,
+                   meta=dict(seed=seed, sigma_min=sigma_min, sigma_max=sigma_max))
 
 
 def paper_nnls_i(t: float, *, seed: int, m: int = 10) -> Problem:
