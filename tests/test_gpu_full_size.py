@@ -11,8 +11,17 @@ outputs it can compute one by one, each of them an exact output of the full-size
     entries K of the full problem (the GPU still multiplies with every column).
 End to end, the solve is checked through properties that hold at any size (feasibility, the
 stopping quantity and the epsilon-free KKT residual recomputed on the host with numpy, the reported
-objective, descent), and at C2 against a full oracle solve.
+objective, descent), and against FULL oracle solves of the same seeded problems: C2's runs inside the
+test (seconds), those of C3, C4 and C5 (minutes of one core each) are stored under tests/golden/ by
+tests/golden/make_full_size_goldens.py, which calls the oracle only.  By the corollary of Theorem 1 both
+implementations must reach the global optimum over the box, so the final objective agrees to 1e-8 (fp64
+storage) / 1e-4 (fp32 storage) relative and, where the minimiser is unique and well separated from the
+bounds (C4, C5), the set of active bounds is identical; C3's objective is convex but not strictly convex
+in [p; q], so there the set difference is reported and only bounded.
 """
+import json
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -38,6 +47,15 @@ def full(request):
     s.close()
     del s, prob
     torch.cuda.empty_cache()
+
+
+def _golden(name):
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"full_size_{name}.json")) as fh:
+        return json.load(fh)
+
+
+def _bitmap(hex_text, n):
+    return np.unpackbits(np.frombuffer(bytes.fromhex(hex_text), dtype=np.uint8))[:n].astype(bool)
 
 
 def _tol(prob):
@@ -128,17 +146,62 @@ def test_solve_properties_at_full_size(full):
           f"{np.linalg.norm(g[free]) / scale:.2e}, {int((~free).sum())} fixed", flush=True)
 
 
-def test_c2_full_size_against_a_full_oracle_solve():
-    prob = workloads.config("C2")
-    prob.tol, prob.tol_relative = 1e-10, True
-    ref = oracle.solve_problem(prob)
-    assert ref.info.status == oracle.CONVERGED
-    s = L.solver_for_problem(prob, DEV)
+def _solve_with_the_oracle_now(prob):
+    """The same record tests/golden/make_full_size_goldens.py stores, from an oracle solve run inside the test
+    (C2: about ten seconds of one core)."""
+    eps, tol = 1e-10, 1e-9
+    ref = oracle.solve_problem(prob, tol=tol, tol_relative=1, eps=eps)
+    active = active_set(prob, ref.x, eps=eps)
+    free_idx = np.flatnonzero(~active)
+    sample = free_idx[np.unique(np.linspace(0, free_idx.size - 1, min(128, free_idx.size)).astype(np.int64))]
+    return dict(rows=prob.rows, cols=prob.cols, n=prob.n, m=prob.m, seed=workloads.CONFIG_SEEDS[prob.name],
+                status=int(ref.info.status), iters=int(ref.info.iters), f=float(ref.info.f),
+                options=dict(tol=tol, tol_relative=1, eps=eps), n_active=int(active.sum()),
+                active_bitmap_hex=np.packbits(active).tobytes().hex(),
+                at_upper_bitmap_hex=np.packbits(ref.x >= prob.u - eps).tobytes().hex(),
+                x_sample_indices=[int(v) for v in sample], x_sample=[float(v) for v in ref.x[sample]],
+                x_norm2=float(np.linalg.norm(ref.x)))
+
+
+def test_full_size_result_against_a_full_oracle_solve(full):
+    """C2-C5 at full size, solved to 1e-9 relative like the oracle run (C2: run here; C3-C5: stored): final objective
+    within the benchmark spec's bound, identical active set where the minimiser is unique (C2, C4, C5), the minimiser itself
+    on a sample of free variables."""
+    name, prob, s0 = full
+    gold = _golden(name) if name != "C2" else _solve_with_the_oracle_now(prob)
+    assert (gold["rows"], gold["cols"], gold["n"], gold["m"], gold["seed"]) == \
+        (prob.rows, prob.cols, prob.n, prob.m, workloads.CONFIG_SEEDS[name])
+    assert gold["status"] == oracle.CONVERGED
+    opt = gold["options"]
+    # a second solver on the matrix already in device memory (the library borrows A and b)
+    s = L.Solver(prob.kind, s0._A, s0._b, torch.from_numpy(prob.l).to(DEV), torch.from_numpy(prob.u).to(DEV), prob.m,
+                 lam=prob.lam, mu=prob.mu,
+                 options=L.default_options(tol=opt["tol"], tol_relative=opt["tol_relative"], eps=opt["eps"], max_iter=1000))
+    s.set_x(torch.from_numpy(prob.x0).to(DEV))
     info = s.solve()
     x = s.x().cpu().numpy()
     s.close()
-    assert info.status == L.CONVERGED
-    assert abs(info.f - ref.info.f) <= 1e-8 * abs(ref.info.f), (info.f, ref.info.f)
-    assert np.array_equal(active_set(prob, x), active_set(prob, ref.x))
-    assert rel_err(x, ref.x) <= 1e-6
-    assert info.iters <= 2 * ref.info.iters + 20
+    assert info.status == L.CONVERGED, info.as_dict()
+    f_tol = 1e-8 if prob.A.dtype == np.float64 else 1e-4
+    assert abs(info.f - gold["f"]) <= f_tol * abs(gold["f"]), (info.f, gold["f"])
+    active = active_set(prob, x, eps=opt["eps"])
+    gold_active = _bitmap(gold["active_bitmap_hex"], prob.n)
+    assert int(gold_active.sum()) == gold["n_active"]
+    differ = np.flatnonzero(active != gold_active)
+    print(f"[full-size] {name}: {info.iters} iterations (oracle {gold['iters']}), f = {info.f!r} (oracle {gold['f']!r}), "
+          f"{int(active.sum())} active (oracle {gold['n_active']}), {differ.size} differ", flush=True)
+    idx = np.array(gold["x_sample_indices"])
+    x_ref = np.array(gold["x_sample"])
+    if name == "C3":
+        # convex, not strictly: the set difference is reported; the lasso solution p - q is still unique for a matrix
+        # in general position, so only entries whose value is within rounding of the bound may flip
+        assert differ.size <= 4, differ
+        assert np.all(np.abs(x[differ]) <= 1e-7)
+        assert rel_err(x[idx], x_ref) <= 1e-5
+    else:
+        assert differ.size == 0, (differ, x[differ])
+        upper = _bitmap(gold["at_upper_bitmap_hex"], prob.n)
+        assert np.array_equal(x >= prob.u - opt["eps"], upper)
+        assert rel_err(x[idx], x_ref) <= 1e-6
+        assert np.linalg.norm(x) == pytest.approx(gold["x_norm2"], rel=1e-7)
+    assert info.iters <= 2 * gold["iters"] + 20
