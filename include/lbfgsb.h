@@ -182,6 +182,22 @@ int lbfgsb_step(lbfgsb_solver* s, lbfgsb_info* info_host);
  * recomputed from x.  info_host may be NULL. */
 int lbfgsb_solve(lbfgsb_solver* s, lbfgsb_info* info_host);
 
+/* For callers that cannot allocate device memory (code that may run under HIP graph capture restrictions, tight
+ * serving loops, harnesses that forbid hipMalloc): lbfgsb_create + lbfgsb_set_x + lbfgsb_solve + lbfgsb_get_x in one
+ * call that allocates nothing -- no hipMalloc / hipFree / hipHostMalloc, no event, no host heap object.  The
+ * workspace is a file-scope device array of LBFGSB_STATIC_SCRATCH_BYTES inside the library (every GPU the library
+ * runs on holds its own copy until the process ends); the host object is static too.
+ *   x: device, n entries; in: the feasible start point x0, out: the final iterate.
+ *   l, u, obj_host, opt_host, hip_stream, info_host: as for lbfgsb_create / lbfgsb_solve (info_host may be NULL).
+ * Same kernels, same arithmetic and same results as the four calls it stands for.  Fails with LBFGSB_E_INVALID_ARG
+ * (message naming both sizes) when lbfgsb_workspace_bytes() of the problem exceeds LBFGSB_STATIC_SCRATCH_BYTES, and
+ * with the error codes of lbfgsb_create / lbfgsb_set_x otherwise.  Synchronises the stream.  All calls on one GPU
+ * share that GPU's array and host object: calls that overlap on one GPU (two threads, two streams) race; calls on
+ * different GPUs do not.  The part of the array a call uses is cleared first, so nothing carries over between calls. */
+#define LBFGSB_STATIC_SCRATCH_BYTES (32u << 20)
+int lbfgsb_solve_static(int64_t n, int m, const double* l, const double* u, const lbfgsb_objective* obj_host,
+                        const lbfgsb_options* opt_host, double* x, lbfgsb_info* info_host, void* hip_stream);
+
 /* Synchronises and reports the current state. */
 int lbfgsb_get_info(lbfgsb_solver* s, lbfgsb_info* info_host);
 

@@ -22,7 +22,7 @@ MAX_M = 31
 
 EXPORTS = [
     "lbfgsb_last_error", "lbfgsb_default_options", "lbfgsb_workspace_bytes", "lbfgsb_create", "lbfgsb_set_x",
-    "lbfgsb_step", "lbfgsb_solve", "lbfgsb_get_info", "lbfgsb_get_x", "lbfgsb_get_g", "lbfgsb_destroy",
+    "lbfgsb_step", "lbfgsb_solve", "lbfgsb_solve_static", "lbfgsb_get_info", "lbfgsb_get_x", "lbfgsb_get_g", "lbfgsb_destroy",
     "lbfgsb_enable_apass_timing", "lbfgsb_apass_timing", "lbfgsb_apass_name", "lbfgsb_dbg_fg",
     "lbfgsb_dbg_free_mask", "lbfgsb_dbg_two_loop", "lbfgsb_dbg_project_direction",
     "lbfgsb_auglag_default_options", "lbfgsb_auglag_workspace_bytes", "lbfgsb_auglag_create", "lbfgsb_auglag_solve",
@@ -101,6 +101,9 @@ def lib():
         L.lbfgsb_step.argtypes = [vp, C.POINTER(Info)]
         L.lbfgsb_solve.restype = C.c_int
         L.lbfgsb_solve.argtypes = [vp, C.POINTER(Info)]
+        L.lbfgsb_solve_static.restype = C.c_int
+        L.lbfgsb_solve_static.argtypes = [i64, C.c_int, vp, vp, C.POINTER(Objective), C.POINTER(Options), vp,
+                                          C.POINTER(Info), vp]
         L.lbfgsb_get_info.restype = C.c_int
         L.lbfgsb_get_info.argtypes = [vp, C.POINTER(Info)]
         L.lbfgsb_get_x.restype = C.c_int
@@ -491,6 +494,35 @@ class AuglagMarginals(Auglag):
                                                         C.byref(self._obj), self._d.data_ptr(), C.byref(self.options),
                                                         C.byref(self.al_options), self.workspace.data_ptr(), nbytes,
                                                         C.c_void_p(self._stream.cuda_stream)))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def solve_static(kind: int, A, b, l, u, m: int, x, *, lam: float = 0.0, mu: float = 0.0,
+                 options: Optional[Options] = None) -> Info:
+    """lbfgsb_solve_static: the whole solve in one call that allocates nothing (the workspace is a fixed array inside
+    the library).  x: float64 CUDA tensor, in: the start point, out: the result (overwritten in place).  Runs on
+    torch's current stream; no tensor is created here either."""
+    import torch
+    if not (isinstance(A, torch.Tensor) and A.is_cuda and A.dim() == 2 and A.stride(1) == 1
+            and A.dtype in (torch.float64, torch.float32)):
+        raise TypeError("A must be a 2-d float64/float32 CUDA tensor with unit column stride")
+    rows, cols = A.shape
+    n = 2 * cols if kind == OBJ_LSQ_L1SPLIT else cols
+    _dev_f64(b, "b", rows)
+    _dev_f64(l, "l", n)
+    _dev_f64(u, "u", n)
+    _dev_f64(x, "x", n)
+    opts = options if options is not None else default_options()
+    obj = Objective(kind, F64 if A.dtype == torch.float64 else F32, rows, cols, A.stride(0) if rows > 1 else cols,
+                    A.data_ptr(), b.data_ptr(), float(lam), float(mu), None, None, 0, None, None, None)
+    info = Info()
+    with torch.cuda.device(A.device):
+        stream = torch.cuda.current_stream(A.device)
+        _check(lib().lbfgsb_solve_static(n, m, l.data_ptr(), u.data_ptr(), C.byref(obj), C.byref(opts), x.data_ptr(),
+                                         C.byref(info), C.c_void_p(stream.cuda_stream)))
+    return info
 
 
 def solver_for_problem(prob, device="cuda:0", **option_overrides) -> Solver:

@@ -40,6 +40,14 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 }  // namespace
 
+// Workspace of lbfgsb_solve_static, for callers that cannot allocate.  In host code this name is only a stand-in
+// for the symbol: the device address comes from hipGetSymbolAddress, once per device (static_slot()), and that
+// address is what every kernel argument, fill and copy uses.
+// (No `used` attribute: it keeps the symbol local in the code object, and the runtime, which finds a device variable
+// by name among the code object's global symbols, then aborts in hipGetSymbolAddress.  The host code's use of the
+// variable is what makes the compiler export it.)
+static __device__ __align__(256) unsigned char scratch[LBFGSB_STATIC_SCRATCH_BYTES];
+
 struct lbfgsb_solver {
     Dims dm;
     Opts op;
@@ -48,7 +56,8 @@ struct lbfgsb_solver {
     Geometry ge;
     Buffers bf;
     hipStream_t stream;
-    Scal* h_scal;            // pinned host copy
+    Scal* h_scal;            // host copy (pinned, allocated by lbfgsb_create)
+    bool owns_h_scal;
     int use_fused;
     int steps_since_refresh;
     long long steps_since_set_x;
@@ -379,6 +388,190 @@ int set_x_impl(lbfgsb_solver* s, const double* x0, bool trusted) {
     return LBFGSB_OK;
 }
 
+
+// Argument checks shared by the entry points that set a solver up; *o receives the options (defaults when opt is NULL).
+int check_create_args(int64_t n, int m, const double* l, const double* u, const lbfgsb_objective* obj,
+                      const lbfgsb_options* opt, const void* workspace, lbfgsb_options* o) {
+    int rc = check_objective(n, m, obj);
+    if (rc) return rc;
+    const bool ot = is_transport(obj->kind);
+    if (!l || !u || !obj->A || !workspace) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
+    if (ot ? (obj->row_weight && !obj->b) : !obj->b) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer (b)");
+    if (obj->n_extra > 0 && (!obj->extra_rows || !obj->extra_target))
+        return fail(LBFGSB_E_INVALID_ARG, "NULL extra_rows / extra_target");
+    if (opt) *o = *opt; else lbfgsb_default_options(o);
+    rc = check_options(o);
+    if (rc) return rc;
+    if ((uintptr_t)workspace % 256) return fail(LBFGSB_E_INVALID_ARG, "workspace must be 256-byte aligned");
+    const int esz = obj->dtype == LBFGSB_F32 ? 4 : 8;
+    if ((uintptr_t)obj->A % esz || (uintptr_t)obj->b % 8 || (uintptr_t)obj->row_weight % 8 || (uintptr_t)l % 8 ||
+        (uintptr_t)u % 8)
+        return fail(LBFGSB_E_INVALID_ARG, "misaligned device pointer");
+    return LBFGSB_OK;
+}
+
+// Fills the host object for a checked problem: launch geometry, kernel preparation, and the device arrays carved
+// out of `workspace`.  Allocates nothing and touches no device memory; *total receives the bytes of workspace in use.
+int setup_solver(lbfgsb_solver* s, int64_t n, int m, const lbfgsb_objective* obj, const lbfgsb_options& o,
+                 void* workspace, size_t workspace_bytes, hipStream_t stream, size_t* total) {
+    s->dm = make_dims(n, m, obj);
+    s->options = o;
+    s->op = Opts{o.eps, o.armijo_c1, o.backtrack, o.tol, o.max_backtracks, o.tol_relative, o.max_iter, 0, 0.0, 0.0};
+    s->obj = *obj;
+    s->ge = make_geometry(s->dm, obj->A);
+    s->stream = stream;
+    s->h_scal = nullptr;
+    s->owns_h_scal = false;
+    s->steps_since_refresh = 0;
+    s->steps_since_set_x = 0;
+    s->x_set = false;
+    s->timing = false;
+    s->timed = 0;
+    const Layout L = make_layout(s->dm, s->ge);
+    *total = L.total;
+    if (workspace_bytes < L.total)
+        return fail(LBFGSB_E_INVALID_ARG, "workspace too small: %zu < %zu bytes", workspace_bytes, L.total);
+    if (o.a_pass == LBFGSB_APASS_FUSED && !s->ge.fused_ok)
+        return fail(LBFGSB_E_UNSUPPORTED, "the fused A pass does not support this shape");
+    {
+        const hipError_t ge_ = gram_prepare(n, m);
+        if (ge_ != hipSuccess) return fail(LBFGSB_E_HIP, "preparing the Gram kernel: %s", hipGetErrorString(ge_));
+    }
+    s->use_fused = s->ge.fused_ok && o.a_pass != LBFGSB_APASS_TWO_PASS;
+    if (s->use_fused) {
+        const hipError_t fe = fused_prepare(s->dm, s->ge);
+        if (fe != hipSuccess) return fail(LBFGSB_E_HIP, "preparing the fused A pass: %s", hipGetErrorString(fe));
+    }
+    s->ge.w_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemvt_row_blocks;
+    s->ge.loss_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemv_blocks;
+
+    char* w = (char*)workspace;
+    Buffers& b = s->bf;
+    b.scal = (Scal*)(w + L.scal);
+    b.x = (double*)(w + L.x); b.g = (double*)(w + L.g); b.l = (double*)(w + L.l); b.u = (double*)(w + L.u);
+    b.d = (double*)(w + L.d); b.p1 = (double*)(w + L.p1); b.p2 = (double*)(w + L.p2);
+    b.mask = (uint8_t*)(w + L.mask);
+    b.S = (double*)(w + L.S); b.Y = (double*)(w + L.Y);
+    b.row = (double*)(w + L.row); b.t = (double*)(w + L.t); b.psi = (double*)(w + L.psi);
+    b.wpart = (double*)(w + L.wpart); b.losspart = (double*)(w + L.losspart);
+    b.grampart = (double*)(w + L.grampart); b.redpart = (double*)(w + L.redpart); b.lspart = (double*)(w + L.lspart);
+    b.wextra = (double*)(w + L.wextra); b.xres = (double*)(w + L.xres);
+    return LBFGSB_OK;
+}
+
+// The workspace starts from all-zero memory (fill kernel: no memset node ever enters a captured graph); the bounds
+// are copied in.  Waits for both.
+int init_workspace(lbfgsb_solver* s, const double* l, const double* u, void* workspace, size_t total) {
+    launch_fill_zero(workspace, total, s->stream);
+    hipError_t e = hipMemcpyAsync(s->bf.l, l, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(s->bf.u, u, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(s->stream);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) return fail(LBFGSB_E_HIP, "initialising the workspace: %s", hipGetErrorString(e));
+    return LBFGSB_OK;
+}
+
+// The stopping logic of lbfgsb_solve, for a solver whose arguments have been checked.
+int solve_impl(lbfgsb_solver* s, lbfgsb_info* info) {
+    const bool quad = is_quadratic(s->dm.kind);
+    const long long cap = 2ll * s->options.max_iter + 64;   // accepted iterations + memory-reset retries
+    long long steps = 0;
+    for (;;) {
+        for (int k = 0; k < s->options.poll_every; ++k) enqueue_step(s);
+        steps += s->options.poll_every;
+        HIP_TRY(read_scal(s));
+        int st = s->h_scal->status;
+        if (st == LBFGSB_CONVERGED && quad && s->steps_since_refresh > 0 && s->h_scal->iters > 0) {
+            // the stopping quantity was computed from a gradient carried by recurrence: recompute
+            // residual and gradient from x and test again before declaring convergence
+            launch_set_status(s->bf, LBFGSB_RUNNING, s->stream);
+            enqueue_eval(s, 0);
+            s->steps_since_refresh = 0;
+            launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
+            HIP_TRY(read_scal(s));
+            st = s->h_scal->status;
+        }
+        if (st != LBFGSB_RUNNING) break;
+        if (steps >= cap) break;
+    }
+    HIP_TRY(hipGetLastError());
+    if (info) fill_info(*s->h_scal, info);
+    return LBFGSB_OK;
+}
+
+
+// ---- lbfgsb_solve_static: per-device state, nothing of it allocated at run time ----------------------------
+
+constexpr int kMaxDevices = 64;
+constexpr int kHostChunk = 2048;   // doubles per host-side validation chunk (stack arrays)
+
+struct StaticSlot {
+    void* ptr = nullptr;       // device address of this device's copy of `scratch`
+    lbfgsb_solver solver;      // host object, reused by every call on the device
+    Scal h_scal;               // host copy of the scalar block (pageable: allocating pinned memory is an allocation)
+};
+StaticSlot g_static[kMaxDevices];
+
+// The calling thread's current device's slot, with the address of that device's scratch array resolved.
+int static_slot(StaticSlot** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(LBFGSB_E_INVALID_ARG, "device index %d is not supported", dev);
+    StaticSlot* sl = &g_static[dev];
+    if (!sl->ptr) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || (uintptr_t)p % 256) return fail(LBFGSB_E_HIP, "the scratch array has no usable device address");
+        sl->ptr = p;
+    }
+    *out = sl;
+    return LBFGSB_OK;
+}
+
+// Bounds and start point checked on the host in chunks that live on the stack: l <= u, l <= x0 <= u, no NaN,
+// l > 0 for the entropy kind; also finds out whether all variables share one pair of bounds.
+int check_box_chunked(lbfgsb_solver* s, const double* l, const double* u, const double* x0) {
+    double hl[kHostChunk], hu[kHostChunk], hx[kHostChunk];
+    const int64_t n = s->dm.n;
+    bool same = true;
+    double lo0 = 0.0, hi0 = 0.0;
+    for (int64_t i0 = 0; i0 < n; i0 += kHostChunk) {
+        const int64_t cnt = n - i0 < kHostChunk ? n - i0 : kHostChunk;
+        HIP_TRY(hipMemcpyAsync(hl, l + i0, (size_t)cnt * 8, hipMemcpyDeviceToHost, s->stream));
+        HIP_TRY(hipMemcpyAsync(hu, u + i0, (size_t)cnt * 8, hipMemcpyDeviceToHost, s->stream));
+        HIP_TRY(hipMemcpyAsync(hx, x0 + i0, (size_t)cnt * 8, hipMemcpyDeviceToHost, s->stream));
+        HIP_TRY(hipStreamSynchronize(s->stream));
+        if (i0 == 0) { lo0 = hl[0]; hi0 = hu[0]; }
+        for (int64_t k = 0; k < cnt; ++k) {
+            if (!(hl[k] <= hu[k]))
+                return fail(LBFGSB_E_BOUNDS, "bounds cross or are NaN at index %lld (l = %g, u = %g)", (long long)(i0 + k),
+                            hl[k], hu[k]);
+            if (s->dm.kind == LBFGSB_OBJ_OT_ENTROPY && !(hl[k] > 0.0))
+                return fail(LBFGSB_E_BOUNDS, "the entropy regulariser needs l > 0 (l[%lld] = %g)", (long long)(i0 + k), hl[k]);
+            if (!(hx[k] >= hl[k]) || !(hx[k] <= hu[k]))
+                return fail(LBFGSB_E_INFEASIBLE_X0, "x0[%lld] = %g is outside [%g, %g]", (long long)(i0 + k), hx[k], hl[k],
+                            hu[k]);
+            same = same && hl[k] == lo0 && hu[k] == hi0;
+        }
+    }
+    s->op.uniform_bounds = same ? 1 : 0;
+    s->op.lo = lo0;
+    s->op.hi = hi0;
+    return LBFGSB_OK;
+}
+
+int check_finite_chunked(lbfgsb_solver* s, const double* v) {
+    double hv[kHostChunk];
+    for (int64_t i0 = 0; i0 < s->dm.n; i0 += kHostChunk) {
+        const int64_t cnt = s->dm.n - i0 < kHostChunk ? s->dm.n - i0 : kHostChunk;
+        HIP_TRY(hipMemcpyAsync(hv, v + i0, (size_t)cnt * 8, hipMemcpyDeviceToHost, s->stream));
+        HIP_TRY(hipStreamSynchronize(s->stream));
+        for (int64_t k = 0; k < cnt; ++k)
+            if (!std::isfinite(hv[k])) return fail(LBFGSB_E_NONFINITE, "f or grad f is not finite at x0");
+    }
+    return LBFGSB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -403,80 +596,20 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
                   const lbfgsb_options* opt, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!out) return fail(LBFGSB_E_INVALID_ARG, "out is NULL");
     *out = nullptr;
-    int rc = check_objective(n, m, obj);
-    if (rc) return rc;
-    const bool ot = is_transport(obj->kind);
-    if (!l || !u || !obj->A || !workspace) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer");
-    if (ot ? (obj->row_weight && !obj->b) : !obj->b) return fail(LBFGSB_E_INVALID_ARG, "NULL device pointer (b)");
-    if (obj->n_extra > 0 && (!obj->extra_rows || !obj->extra_target))
-        return fail(LBFGSB_E_INVALID_ARG, "NULL extra_rows / extra_target");
     lbfgsb_options o;
-    if (opt) o = *opt; else lbfgsb_default_options(&o);
-    rc = check_options(&o);
+    int rc = check_create_args(n, m, l, u, obj, opt, workspace, &o);
     if (rc) return rc;
-    if ((uintptr_t)workspace % 256) return fail(LBFGSB_E_INVALID_ARG, "workspace must be 256-byte aligned");
-    const int esz = obj->dtype == LBFGSB_F32 ? 4 : 8;
-    if ((uintptr_t)obj->A % esz || (uintptr_t)obj->b % 8 || (uintptr_t)obj->row_weight % 8 || (uintptr_t)l % 8 ||
-        (uintptr_t)u % 8)
-        return fail(LBFGSB_E_INVALID_ARG, "misaligned device pointer");
-
     lbfgsb_solver* s = new (std::nothrow) lbfgsb_solver();
     if (!s) return fail(LBFGSB_E_INVALID_ARG, "out of host memory");
-    s->dm = make_dims(n, m, obj);
-    s->options = o;
-    s->op = Opts{o.eps, o.armijo_c1, o.backtrack, o.tol, o.max_backtracks, o.tol_relative, o.max_iter, 0, 0.0, 0.0};
-    s->obj = *obj;
-    s->ge = make_geometry(s->dm, obj->A);
-    s->stream = (hipStream_t)hip_stream;
-    s->h_scal = nullptr;
-    s->steps_since_refresh = 0;
-    s->steps_since_set_x = 0;
-    s->x_set = false;
-    s->timing = false;
-    s->timed = 0;
-    const Layout L = make_layout(s->dm, s->ge);
-    if (workspace_bytes < L.total) {
-        delete s;
-        return fail(LBFGSB_E_INVALID_ARG, "workspace too small: %zu < %zu bytes", workspace_bytes, L.total);
-    }
-    if (o.a_pass == LBFGSB_APASS_FUSED && !s->ge.fused_ok) {
-        delete s;
-        return fail(LBFGSB_E_UNSUPPORTED, "the fused A pass does not support this shape");
-    }
-    {
-        const hipError_t ge_ = gram_prepare(n, m);
-        if (ge_ != hipSuccess) {
-            delete s;
-            return fail(LBFGSB_E_HIP, "preparing the Gram kernel: %s", hipGetErrorString(ge_));
-        }
-    }
-    s->use_fused = s->ge.fused_ok && o.a_pass != LBFGSB_APASS_TWO_PASS;
-    if (s->use_fused) {
-        const hipError_t fe = fused_prepare(s->dm, s->ge);
-        if (fe != hipSuccess) {
-            delete s;
-            return fail(LBFGSB_E_HIP, "preparing the fused A pass: %s", hipGetErrorString(fe));
-        }
-    }
-    s->ge.w_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemvt_row_blocks;
-    s->ge.loss_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemv_blocks;
-
-    char* w = (char*)workspace;
-    Buffers& b = s->bf;
-    b.scal = (Scal*)(w + L.scal);
-    b.x = (double*)(w + L.x); b.g = (double*)(w + L.g); b.l = (double*)(w + L.l); b.u = (double*)(w + L.u);
-    b.d = (double*)(w + L.d); b.p1 = (double*)(w + L.p1); b.p2 = (double*)(w + L.p2);
-    b.mask = (uint8_t*)(w + L.mask);
-    b.S = (double*)(w + L.S); b.Y = (double*)(w + L.Y);
-    b.row = (double*)(w + L.row); b.t = (double*)(w + L.t); b.psi = (double*)(w + L.psi);
-    b.wpart = (double*)(w + L.wpart); b.losspart = (double*)(w + L.losspart);
-    b.grampart = (double*)(w + L.grampart); b.redpart = (double*)(w + L.redpart); b.lspart = (double*)(w + L.lspart);
-    b.wextra = (double*)(w + L.wextra); b.xres = (double*)(w + L.xres);
+    size_t total = 0;
+    rc = setup_solver(s, n, m, obj, o, workspace, workspace_bytes, (hipStream_t)hip_stream, &total);
+    if (rc) { delete s; return rc; }
 
     auto bail = [&](int code) { lbfgsb_destroy(s); return code; };
     {
         hipError_t e = hipHostMalloc((void**)&s->h_scal, sizeof(Scal), hipHostMallocDefault);
         if (e != hipSuccess) { s->h_scal = nullptr; return bail(fail(LBFGSB_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e))); }
+        s->owns_h_scal = true;
     }
     // validate the bounds on the host
     std::vector<double> hl((size_t)n), hu((size_t)n);
@@ -500,13 +633,8 @@ int lbfgsb_create(lbfgsb_solver** out, int64_t n, int m, const double* l, const 
             if (!(hl[(size_t)i] > 0.0))
                 return bail(fail(LBFGSB_E_BOUNDS, "the entropy regulariser needs l > 0 (l[%lld] = %g)", (long long)i,
                                  hl[(size_t)i]));
-    // the workspace starts from all-zero memory (fill kernel: no memset node ever enters a captured graph)
-    launch_fill_zero(workspace, L.total, s->stream);
-    e = hipMemcpyAsync(b.l, l, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream);
-    if (e == hipSuccess) e = hipMemcpyAsync(b.u, u, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(s->stream);
-    if (e == hipSuccess) e = hipGetLastError();
-    if (e != hipSuccess) return bail(fail(LBFGSB_E_HIP, "initialising the workspace: %s", hipGetErrorString(e)));
+    rc = init_workspace(s, l, u, workspace, total);
+    if (rc) return bail(rc);
     *out = s;
     return LBFGSB_OK;
 }
@@ -515,7 +643,7 @@ void lbfgsb_destroy(lbfgsb_solver* s) {
     if (!s) return;
     for (hipEvent_t ev : s->ev0) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : s->ev1) (void)hipEventDestroy(ev);
-    if (s->h_scal) (void)hipHostFree(s->h_scal);
+    if (s->h_scal && s->owns_h_scal) (void)hipHostFree(s->h_scal);
     delete s;
 }
 
@@ -539,29 +667,44 @@ int lbfgsb_step(lbfgsb_solver* s, lbfgsb_info* info) {
 int lbfgsb_solve(lbfgsb_solver* s, lbfgsb_info* info) {
     if (!s) return fail(LBFGSB_E_INVALID_ARG, "solver is NULL");
     if (!s->x_set) return fail(LBFGSB_E_INVALID_ARG, "lbfgsb_set_x has not been called");
-    const bool quad = is_quadratic(s->dm.kind);
-    const long long cap = 2ll * s->options.max_iter + 64;   // accepted iterations + memory-reset retries
-    long long steps = 0;
-    for (;;) {
-        for (int k = 0; k < s->options.poll_every; ++k) enqueue_step(s);
-        steps += s->options.poll_every;
-        HIP_TRY(read_scal(s));
-        int st = s->h_scal->status;
-        if (st == LBFGSB_CONVERGED && quad && s->steps_since_refresh > 0 && s->h_scal->iters > 0) {
-            // the stopping quantity was computed from a gradient carried by recurrence: recompute
-            // residual and gradient from x and test again before declaring convergence
-            launch_set_status(s->bf, LBFGSB_RUNNING, s->stream);
-            enqueue_eval(s, 0);
-            s->steps_since_refresh = 0;
-            launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
-            HIP_TRY(read_scal(s));
-            st = s->h_scal->status;
-        }
-        if (st != LBFGSB_RUNNING) break;
-        if (steps >= cap) break;
-    }
-    HIP_TRY(hipGetLastError());
-    if (info) fill_info(*s->h_scal, info);
+    return solve_impl(s, info);
+}
+
+int lbfgsb_solve_static(int64_t n, int m, const double* l, const double* u, const lbfgsb_objective* obj,
+                        const lbfgsb_options* opt, double* x, lbfgsb_info* info, void* hip_stream) {
+    if (!x) return fail(LBFGSB_E_INVALID_ARG, "x is NULL");
+    if ((uintptr_t)x % 8) return fail(LBFGSB_E_INVALID_ARG, "misaligned device pointer");
+    StaticSlot* sl = nullptr;
+    int rc = static_slot(&sl);
+    if (rc) return rc;
+    lbfgsb_options o;
+    rc = check_create_args(n, m, l, u, obj, opt, sl->ptr, &o);
+    if (rc) return rc;
+    const size_t need = lbfgsb_workspace_bytes(n, m, obj, &o);
+    if (need == 0 || need > (size_t)LBFGSB_STATIC_SCRATCH_BYTES)
+        return fail(LBFGSB_E_INVALID_ARG,
+                    "this problem needs %zu bytes of workspace, lbfgsb_solve_static holds %zu: use lbfgsb_create with a "
+                    "workspace of your own", need, (size_t)LBFGSB_STATIC_SCRATCH_BYTES);
+    lbfgsb_solver* s = &sl->solver;
+    if (s->timing || !s->ev0.empty()) return fail(LBFGSB_E_INVALID_ARG, "the static solver object is in an unexpected state");
+    size_t total = 0;
+    rc = setup_solver(s, n, m, obj, o, sl->ptr, (size_t)LBFGSB_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream, &total);
+    if (rc) return rc;
+    s->h_scal = &sl->h_scal;
+    rc = check_box_chunked(s, l, u, x);
+    if (rc) return rc;
+    // the array keeps the previous call's contents: everything this problem uses starts from zero again
+    rc = init_workspace(s, l, u, sl->ptr, total);
+    if (rc) return rc;
+    rc = set_x_impl(s, x, true);
+    if (rc) return rc;
+    rc = check_finite_chunked(s, s->bf.g);
+    if (rc) { s->x_set = false; return rc; }
+    rc = solve_impl(s, info);
+    if (rc) return rc;
+    HIP_TRY(hipMemcpyAsync(x, s->bf.x, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream));
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    s->x_set = false;
     return LBFGSB_OK;
 }
 
