@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the modified L-BFGS-B hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--a-pass auto|two_pass|fused]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--a-pass auto|two_pass|fused]
 
 A "step" is one iteration of Algorithm 1 (one lbfgsb_step call: free set, batched two-loop,
 projectDirection, the pass(es) over A, line search, update) on a synthetic problem that is already
@@ -12,7 +12,11 @@ tolerance, so every timed step is a real iteration and none is a no-op after con
 
 Prints ONE JSON line: iterations/s (`value`), the time to reach the relative KKT tolerance 1e-6
 (`time_to_kkt_ms`), the achieved fraction of the HBM roofline of the dominant kernel
-(`roofline`), and the CPU oracle timed on this host on a bounded sample (`cpu_baseline`).
+(`roofline`), the whole iteration against the same roofline (`step_frac` = the matrix bytes one iteration
+requests / ms_per_step / peak), and the CPU oracle timed on this host on a bounded sample (`cpu_baseline`,
+with the host's core count and CPU model).  Without --config the line is the headline workload C2, and its
+`configs` object carries the same measurements for C1, C3, C4 and C5 (run one after the other, each at its
+full size); with --config only that workload runs.
 """
 from __future__ import annotations
 
@@ -56,15 +60,16 @@ WORKLOADS = {
 # HBM bytes per launch of the dominant kernel as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by the same counters read for a copy kernel of known size); filled in from the summaries
 # under profiles/ for the (config, a_pass) pairs that have been profiled, else null in the output.
-MEASURED_TRAFFIC_BYTES = {
-    ("C2", "fused"): 8.369e8,      # profiles/c2_nnls_20000x5000_f64_fused_a_pass.md      (algorithmic 8.0e8)
-    ("C3", "fused"): 1.682e9,      # profiles/c3_l1ls_10000x20000_f64_fused_a_pass.md     (algorithmic 1.6e9)
-    ("C4", "fused"): 1.624e9,      # profiles/c4_logistic_200000x2000_f32_fused_a_pass.md (algorithmic 1.6e9)
-    ("C5", "fused"): 8.099e9,      # profiles/c5_nnls_100000x20000_f32_fused_a_pass.md    (algorithmic 8.0e9)
-    ("AL2", "fused"): 8.372e8,     # profiles/al2_auglag_20001x5000_f64_fused_a_pass.md   (algorithmic 8.0004e8)
-    ("SVM", "fused"): 8.633e8,     # profiles/svm_dual_10000x10000_f64_row_products_pass.md (algorithmic 8.0e8)
-    ("JP1G", "gram"): 9.841e7,     # profiles/jp1g_joint_probability_1000x1000_f64_gram_kernel.md (algorithmic 0.83e8 at the final free set)
-    ("JP2G", "gram"): 6.023e7,     # profiles/jp2g_joint_probability_2000x1000_f64_gram_kernel.md (algorithmic 0.51e8)
+# (bytes per launch, where the figure comes from: summary file and the commit whose kernels it profiled)
+MEASURED_TRAFFIC = {
+    ("C2", "fused"): (8.369e8, "profiles/c2_nnls_20000x5000_f64_fused_a_pass.md @ efc89f7"),        # algorithmic 8.0e8
+    ("C3", "fused"): (1.682e9, "profiles/c3_l1ls_10000x20000_f64_fused_a_pass.md @ efc89f7"),       # algorithmic 1.6e9
+    ("C4", "fused"): (1.624e9, "profiles/c4_logistic_200000x2000_f32_fused_a_pass.md @ 865f136"),   # algorithmic 1.6e9
+    ("C5", "fused"): (8.099e9, "profiles/c5_nnls_100000x20000_f32_fused_a_pass.md @ efc89f7"),      # algorithmic 8.0e9
+    ("AL2", "fused"): (8.372e8, "profiles/al2_auglag_20001x5000_f64_fused_a_pass.md @ efc89f7"),    # algorithmic 8.0004e8
+    ("SVM", "fused"): (8.633e8, "profiles/svm_dual_10000x10000_f64_row_products_pass.md @ efc89f7"),   # algorithmic 8.0e8
+    ("JP1G", "gram"): (9.841e7, "profiles/jp1g_joint_probability_1000x1000_f64_gram_kernel.md @ efc89f7"),   # algorithmic 0.83e8 at the final free set
+    ("JP2G", "gram"): (6.023e7, "profiles/jp2g_joint_probability_2000x1000_f64_gram_kernel.md @ efc89f7"),   # algorithmic 0.51e8
 }
 
 
@@ -153,7 +158,8 @@ def bench_svm(args, L, workloads, np, torch, dev) -> int:
         "roofline": {"bound": "hbm", "kernel": "row-products-only instantiation of the ring kernel (t = K (y.p), one read of the symmetric matrix per iteration)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": apass_avg_ms, "launches_timed": n_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "fused"))},
+                     "traffic": (MEASURED_TRAFFIC.get((args.config, "fused")) or (None, None))[0],
+                     "traffic_source": (MEASURED_TRAFFIC.get((args.config, "fused")) or (None, None))[1]},
         "gen_seconds": t_gen,
     }
     al.close()
@@ -230,7 +236,8 @@ def bench_transport(args, L, workloads, np, torch, dev) -> int:
         "roofline": {"bound": "hbm", "kernel": "Gram kernel of the batched two-loop recursion (reads x, g, the newest y, and the 2m pair vectors at the free variables; evaluates the free set and writes the mask)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_ms, "launches_timed": n_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "gram"))},
+                     "traffic": (MEASURED_TRAFFIC.get((args.config, "gram")) or (None, None))[0],
+                     "traffic_source": (MEASURED_TRAFFIC.get((args.config, "gram")) or (None, None))[1]},
         "gen_seconds": t_gen,
     }
     al.close()
@@ -261,7 +268,7 @@ def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
     t_gen = time.perf_counter()
     cp = workloads.constrained_config(args.config, scale=args.scale)
     t_gen = time.perf_counter() - t_gen
-    A_s, b_s, n_eq, l_s, u_s, x0_s = cp.stacked()
+    A_s, b_s, n_eq, l_s, u_s, x0_s = L.stack_constraints(cp.A, cp.b, cp.C, cp.d, cp.E, cp.e, cp.l, cp.u, cp.x0)
     g0 = -(cp.b @ cp.A)                                     # gradient at x0 = 0
     free0 = ~((cp.x0 <= cp.l + 1e-10) & (g0 >= 0))
     tol = 1e-6 * max(1.0, float(np.linalg.norm(g0[free0])))
@@ -299,7 +306,8 @@ def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
         "roofline": {"bound": "hbm", "kernel": "fused A pass with per-row weights (data rows and the constraint rows in one read)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": apass_avg_ms, "launches_timed": n_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, "fused"))},
+                     "traffic": (MEASURED_TRAFFIC.get((args.config, "fused")) or (None, None))[0],
+                     "traffic_source": (MEASURED_TRAFFIC.get((args.config, "fused")) or (None, None))[1]},
         "gen_seconds": t_gen,
     }
     al.close()
@@ -318,40 +326,32 @@ def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C2", choices=sorted(WORKLOADS) + sorted(AL_WORKLOADS))
-    ap.add_argument("--a-pass", default="auto", choices=["auto", "two_pass", "fused"])
-    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
-    ap.add_argument("--scale", type=float, default=1.0, help="shrink both matrix dimensions (debugging only)")
-    ap.add_argument("--calibration-copy-mib", type=int, default=0,
-                    help="after the timed region, copy a device buffer of this many MiB three times (a plain copy of "
-                         "known size against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
-        return 2
+def host_cpu_description() -> dict:
+    """Core count and model string of the host the oracle is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"nproc": os.cpu_count(), "cpu_model": model}
 
-    import numpy as np
-    import torch
 
-    import paper_2203_16340_amd as L
-    import workloads
+# SURVEY's algorithmic bytes per iteration: one read of the matrix per iteration on the fused path (two on the
+# two-pass path: the kernels then request the matrix twice); the vector traffic is below 0.5 % and left out.
+def bytes_per_iteration(prob, apass_name: str) -> float:
+    passes = 1.0 if apass_name == "fused" else 2.0
+    return passes * float(prob.rows) * float(prob.cols) * prob.A.dtype.itemsize
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 3
-    dev = "cuda:0"
-    a_pass = {"auto": L.APASS_AUTO, "two_pass": L.APASS_TWO_PASS, "fused": L.APASS_FUSED}[args.a_pass]
 
-    if args.config in AL_WORKLOADS:
-        return bench_auglag(args, L, workloads, np, torch, dev, a_pass)
-
+def run_box_config(name, args, a_pass, L, workloads, np, torch, dev) -> tuple:
+    """One of C1..C5 / P1..P2b: time to the relative KKT tolerance 1e-6 from x0, then args.steps timed steps in episodes
+    from x0.  Returns (record, problem)."""
     t_gen = time.perf_counter()
-    prob = workloads.config(args.config, scale=args.scale)
+    prob = workloads.config(name, scale=args.scale)
     t_gen = time.perf_counter() - t_gen
     esz = prob.A.dtype.itemsize
 
@@ -366,7 +366,8 @@ def main() -> int:
         s_.set_x(x0)
         return s_
 
-    solver = new_solver(tol=1e-6, tol_relative=1, max_iter=int(prob.max_iter))
+    tol_opts = dict(tol=prob.tol, tol_relative=int(prob.tol_relative)) if name == "C1" else dict(tol=1e-6, tol_relative=1)
+    solver = new_solver(max_iter=int(prob.max_iter), **tol_opts)
     solver.solve()                                   # untimed first solve: loads code objects, warms caches
     solver.set_x(x0)
     torch.cuda.synchronize()
@@ -405,7 +406,9 @@ def main() -> int:
     g0_host = host_grad(prob.x0)
     free0 = ~(((prob.x0 <= prob.l + 1e-10) & (g0_host >= 0)) | ((prob.x0 >= prob.u - 1e-10) & (g0_host <= 0)))
     free = ~(((x <= prob.l + 1e-10) & (g_host >= 0)) | ((x >= prob.u - 1e-10) & (g_host <= 0)))
-    kkt_rel = float(np.linalg.norm(g_host[free]) / max(1.0, np.linalg.norm(g0_host[free0])))
+    pg_abs = float(np.linalg.norm(g_host[free]))
+    pg0_abs = float(np.linalg.norm(g0_host[free0]))
+    kkt_rel = pg_abs / max(1.0, pg0_abs)
     kkt_inf = float(np.abs(x - np.clip(x - g_host, prob.l, prob.u)).max())
     feasible = bool(np.all(x >= prob.l) and np.all(x <= prob.u))
 
@@ -439,6 +442,8 @@ def main() -> int:
     achieved = bytes_per_launch / (apass_avg_ms * 1e-3) / 1e9 if apass_avg_ms > 0 else 0.0
     launches_per_step = n_launch / max(1, args.steps)
     apass_name = timed.apass_name
+    traffic = MEASURED_TRAFFIC.get((name, apass_name)) if args.scale == 1.0 else None
+    latency_bound = name == "C1"            # 160 KB matrix: launch latency, not bandwidth, bounds it
 
     out = {
         "metric": METRIC,
@@ -454,7 +459,7 @@ def main() -> int:
         "dtype": "f64",
         "data": "synthetic",
         "config": {
-            "workload": f"{args.config}: {WORKLOADS[args.config]}" + (f" (scaled x{args.scale})" if args.scale != 1.0 else ""),
+            "workload": f"{name}: {WORKLOADS[name]}" + (f" (scaled x{args.scale})" if args.scale != 1.0 else ""),
             "rows": prob.rows, "cols": prob.cols, "n": prob.n, "m": prob.m,
             "matrix_dtype": "f64" if esz == 8 else "f32",
             "a_pass": apass_name, "a_pass_launches_per_step": launches_per_step,
@@ -462,7 +467,10 @@ def main() -> int:
         },
         "time_to_kkt_ms": 1e3 * t_kkt,
         "iters_to_kkt": iters_to_kkt,
-        "kkt": {"status": int(info.status), "rel_proj_grad_2norm_host": kkt_rel, "proj_grad_infnorm_host": kkt_inf,
+        # the stopping rule is RELATIVE: ||grad f[S]||_2 <= tol * max(1, its value at x0); both norms are given
+        "kkt": {"status": int(info.status), "tol": tol_opts["tol"], "tol_relative": bool(tol_opts["tol_relative"]),
+                "rel_proj_grad_2norm_host": kkt_rel, "proj_grad_2norm_host": pg_abs,
+                "proj_grad_2norm_at_x0_host": pg0_abs, "proj_grad_infnorm_host": kkt_inf,
                 "feasible": feasible, "f": info.f},
         "roofline": {
             "bound": "hbm",
@@ -477,17 +485,88 @@ def main() -> int:
             "bytes_per_launch": bytes_per_launch,
             "avg_launch_ms": apass_avg_ms,
             "launches_timed": n_launch,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, apass_name)),
+            "traffic": traffic[0] if traffic else None,
+            # rocprofv3 --pmc counters are not read by this run: the figure is the one of the named summary
+            "traffic_source": traffic[1] if traffic else None,
         },
+        # whole iteration against the roofline: algorithmic bytes of one iteration / ms_per_step / peak
+        "step_frac": (None if latency_bound else
+                      bytes_per_iteration(prob, apass_name) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS),
         "gen_seconds": t_gen,
     }
+    if latency_bound:
+        out["roofline"]["note"] = "160 KB matrix: the iteration is bound by kernel latency, not by HBM bandwidth"
     timed.close()
     solver.close()
+    del A_d, b_d, l_d, u_d, x0, timed, solver
+    torch.cuda.empty_cache()
+    return out, prob
+
+
+SWEEP = ["C1", "C3", "C4", "C5"]     # reported beside the headline workload by the default run
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default=None, choices=sorted(WORKLOADS) + sorted(AL_WORKLOADS),
+                    help="one workload only; default: the headline workload C2, with C1, C3, C4, C5 reported beside it "
+                         "in the `configs` object of the same JSON line")
+    ap.add_argument("--a-pass", default="auto", choices=["auto", "two_pass", "fused"])
+    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink both matrix dimensions (debugging only)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="after the timed region, copy a device buffer of this many MiB three times (a plain copy of "
+                         "known size against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2203_16340_amd as L
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    a_pass = {"auto": L.APASS_AUTO, "two_pass": L.APASS_TWO_PASS, "fused": L.APASS_FUSED}[args.a_pass]
+
+    sweep = args.config is None
+    if sweep:
+        args.config = "C2"
+    if args.config in AL_WORKLOADS:
+        return bench_auglag(args, L, workloads, np, torch, dev, a_pass)
+
+    out, prob = run_box_config(args.config, args, a_pass, L, workloads, np, torch, dev)
     calibration_copy(args, torch, dev, out)
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(prob, args.cpu_budget)
+        out["cpu_baseline"].update(host_cpu_description())
     else:
         out["cpu_baseline"] = None
+    del prob
+    if sweep:
+        # the other configurations, each with the same two measurements; a short record per configuration
+        out["configs"] = {}
+        for name in SWEEP:
+            try:
+                rec, p = run_box_config(name, args, a_pass, L, workloads, np, torch, dev)
+                del p
+                out["configs"][name] = {
+                    "workload": rec["config"]["workload"], "value": rec["value"], "unit": rec["unit"],
+                    "ms_per_step": rec["ms_per_step"], "steps": rec["steps"], "steps_valid": rec["config"]["steps_valid"],
+                    "a_pass": rec["config"]["a_pass"], "time_to_kkt_ms": rec["time_to_kkt_ms"],
+                    "iters_to_kkt": rec["iters_to_kkt"], "kkt": rec["kkt"], "roofline": rec["roofline"],
+                    "step_frac": rec["step_frac"], "gen_seconds": rec["gen_seconds"],
+                }
+            except Exception as exc:                              # one configuration must not cost the headline line
+                out["configs"][name] = {"error": f"{type(exc).__name__}: {exc}"}
     print(json.dumps(out), flush=True)
     return 0
 

@@ -419,6 +419,27 @@ class Auglag:
         return cnt.value, ms.value, by.value
 
 
+def stack_constraints(A, b, C_eq, d, E_in, e, l, u, x0):
+    """Host-side layout of a linearly constrained least-squares problem  min 0.5||A x - b||^2  s.t.  C x = d,
+    E x <= e, l <= x <= u  as lbfgsb_auglag_create takes it (numpy arrays in, numpy arrays out; no solver arithmetic):
+    equality rows appended to A, and one slack column s_r >= 0 per inequality row so that E x + s = e is an equality
+    too (minimising the augmented Lagrangian of Eq. (augLag) over s_r gives exactly its (.)_+ term).  Variables
+    [x; s], rows [A 0; C 0; E I], targets [b; d; e], bounds [l; 0] <= [x; s] <= [u; inf], start [x0; max(e - E x0, 0)].
+    Returns (A_stacked, b_stacked, n_eq_total, l, u, x0)."""
+    import math
+    import numpy as np
+    n, ne, ni = A.shape[1], C_eq.shape[0], E_in.shape[0]
+    top = np.hstack([A, np.zeros((A.shape[0], ni), dtype=A.dtype)])
+    mid = np.hstack([C_eq.astype(A.dtype), np.zeros((ne, ni), dtype=A.dtype)])
+    bot = np.hstack([E_in.astype(A.dtype), np.eye(ni, dtype=A.dtype)])
+    A_s = np.ascontiguousarray(np.vstack([top, mid, bot]))
+    b_s = np.concatenate([b, d, e])
+    l_s = np.concatenate([l, np.zeros(ni)])
+    u_s = np.concatenate([u, np.full(ni, math.inf)])
+    s0 = np.maximum(e - E_in @ x0, 0.0) if ni else np.zeros(0)
+    return A_s, b_s, ne + ni, l_s, u_s, np.concatenate([x0, s0])
+
+
 class AuglagRows(Auglag):
     """lbfgsb_auglag_create_rows: Algorithm 4 with the constraint rows C x = d passed separately, on top of a
     quadratic objective kind given as it is (e.g. OBJ_QP with the kernel matrix for the dual SVM)."""

@@ -40,7 +40,7 @@ def test_weighted_rows_evaluate_the_augmented_lagrangian(rows, cols, n_eq, a_pas
 
 
 def _run_gpu(cp, tol, ctol, max_outer=100, a_pass=L.APASS_AUTO):
-    A_s, b_s, n_eq, l_s, u_s, x0_s = cp.stacked()
+    A_s, b_s, n_eq, l_s, u_s, x0_s = L.stack_constraints(cp.A, cp.b, cp.C, cp.d, cp.E, cp.e, cp.l, cp.u, cp.x0)
     al = L.Auglag(to_dev(A_s), to_dev(b_s), n_eq, to_dev(l_s), to_dev(u_s), cp.m,
                   options=L.default_options(tol=tol, a_pass=a_pass), ctol=ctol, max_outer=max_outer)
     info = al.solve(to_dev(x0_s))
@@ -94,7 +94,7 @@ def test_stacked_rows_in_fp32_and_with_a_leading_dimension(dtype, pad):
     """Between two inner solves f and g are shifted by the constraint rows' share, read from the caller's stacked
     matrix: its element type and row stride must be honoured."""
     cp = workloads.constrained_lsq(300, 96, 3, 0, seed=41, m=8)
-    A_s, b_s, n_eq, l_s, u_s, x0_s = cp.stacked()
+    A_s, b_s, n_eq, l_s, u_s, x0_s = L.stack_constraints(cp.A, cp.b, cp.C, cp.d, cp.E, cp.e, cp.l, cp.u, cp.x0)
     A_s = A_s.astype(dtype)
     rows = A_s.shape[0] - n_eq
     A64 = A_s.astype(np.float64)

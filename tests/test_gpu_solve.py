@@ -371,5 +371,33 @@ def test_benchmark_line_has_the_agreed_fields():
     rf = d["roofline"]
     assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
     assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"]) and "traffic" in rf
+    assert "traffic_source" in rf and "step_frac" in d
+    assert d["kkt"]["proj_grad_2norm_host"] >= 0 and d["kkt"]["tol_relative"] is False      # C1: absolute 1e-8
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] == 1 and cb["value"] > 0 and cb["unit"] == "iterations/s" and cb["sample"]
+    assert cb["nproc"] >= 1 and isinstance(cb["cpu_model"], str)
+    assert "configs" not in d                               # a named --config runs that workload only
+
+
+def test_default_benchmark_line_reports_every_configuration():
+    """Without --config the line is the headline workload (C2) with C1, C3, C4, C5 beside it.  Run here at 2 % of the
+    sizes so that the test takes seconds; the records must still be complete."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "8", "--warmup", "2", "--cpu-budget", "1",
+                        "--scale", "0.02"], capture_output=True, text=True, timeout=280)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["config"]["workload"].startswith("C2:")
+    assert sorted(d["configs"]) == ["C1", "C3", "C4", "C5"]
+    for name, rec in d["configs"].items():
+        assert "error" not in rec, (name, rec)
+        assert rec["workload"].startswith(name + ":") and rec["value"] > 0 and rec["steps_valid"] is True
+        assert rec["kkt"]["status"] == L.CONVERGED and rec["kkt"]["feasible"] is True
+        assert rec["roofline"]["bound"] == "hbm" and "traffic_source" in rec["roofline"]
+        assert rec["step_frac"] is None or 0 < rec["step_frac"] < 1

@@ -289,21 +289,6 @@ class ConstrainedProblem:
     def cols(self) -> int:
         return self.A.shape[1]
 
-    def stacked(self):
-        """The same problem with equality rows appended to A and one slack column per inequality row:
-        variables [x; s], rows [A 0; C 0; E I], targets [b; d; e], bounds [l; 0] <= [x; s] <= [u; inf].
-        Returns (A_stacked, b_stacked, n_eq_total, l, u, x0)."""
-        n, ne, ni = self.cols, self.C.shape[0], self.E.shape[0]
-        top = np.hstack([self.A, np.zeros((self.rows, ni), dtype=self.A.dtype)])
-        mid = np.hstack([self.C.astype(self.A.dtype), np.zeros((ne, ni), dtype=self.A.dtype)])
-        bot = np.hstack([self.E.astype(self.A.dtype), np.eye(ni, dtype=self.A.dtype)])
-        A_s = np.ascontiguousarray(np.vstack([top, mid, bot]))
-        b_s = np.concatenate([self.b, self.d, self.e])
-        l_s = np.concatenate([self.l, np.zeros(ni)])
-        u_s = np.concatenate([self.u, np.full(ni, math.inf)])
-        s0 = np.maximum(self.e - self.E @ self.x0, 0.0) if ni else np.zeros(0)
-        return A_s, b_s, ne + ni, l_s, u_s, np.concatenate([self.x0, s0])
-
 
 def simplex_lsq(rows: int, cols: int, *, seed: int, dtype=np.float64, noise: float = 0.01, budget: float = 1.0,
                 m: int = 10) -> ConstrainedProblem:
