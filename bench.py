@@ -412,9 +412,11 @@ def run_box_config(name, args, a_pass, L, workloads, np, torch, dev) -> tuple:
     kkt_inf = float(np.abs(x - np.clip(x - g_host, prob.l, prob.u)).max())
     feasible = bool(np.all(x >= prob.l) and np.all(x <= prob.u))
 
-    # ---- K timed steps, in episodes from x0
-    timed = new_solver(tol=0.0, tol_relative=0, max_iter=10 ** 6)
+    # ---- K timed steps, in episodes from x0.  The resident organisation (small problems) runs a whole episode in
+    # one launch of lbfgsb_solve (the iteration limit ends it); the others take one lbfgsb_step call per iteration.
     episode = max(1, min(args.steps, iters_to_kkt if iters_to_kkt > 0 else args.steps))
+    resident = solver.apass_name == "resident"
+    timed = new_solver(tol=0.0, tol_relative=0, max_iter=episode if resident else 10 ** 6)
     for _ in range(args.warmup):
         timed.step(want_info=False)
     torch.cuda.synchronize()
@@ -423,17 +425,24 @@ def run_box_config(name, args, a_pass, L, workloads, np, torch, dev) -> tuple:
     done, total_s, valid = 0, 0.0, True
     while done < args.steps:
         k = min(episode, args.steps - done)
+        if resident and k != episode:        # (the iteration limit is fixed at creation: a last, shorter episode)
+            timed.close()
+            timed = new_solver(tol=0.0, tol_relative=0, max_iter=k)
         timed.set_x(x0)                      # untimed: back to x0, pair memory cleared
         timed.enable_apass_timing(1)         # HIP events around every A-pass launch of the timed steps
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(k):
-            timed.step(want_info=False)
-        torch.cuda.synchronize()
+        if resident:
+            st = timed.solve()               # synchronises
+        else:
+            for _ in range(k):
+                timed.step(want_info=False)
+            torch.cuda.synchronize()
         total_s += time.perf_counter() - t0
         timed.enable_apass_timing(0)
-        st = timed.info()
-        if st.iters != k or st.status != L.RUNNING:
+        if not resident:
+            st = timed.info()
+        if st.iters != k or st.status != (L.MAX_ITER if resident else L.RUNNING):
             valid = False
         done += k
     n_launch, apass_ms, bytes_per_launch = timed.apass_timing()
@@ -464,6 +473,7 @@ def run_box_config(name, args, a_pass, L, workloads, np, torch, dev) -> tuple:
             "matrix_dtype": "f64" if esz == 8 else "f32",
             "a_pass": apass_name, "a_pass_launches_per_step": launches_per_step,
             "episode_steps": episode, "steps_valid": valid,
+            "timed_through": "lbfgsb_solve, one launch per episode" if resident else "lbfgsb_step, one call per iteration",
         },
         "time_to_kkt_ms": 1e3 * t_kkt,
         "iters_to_kkt": iters_to_kkt,
@@ -474,7 +484,8 @@ def run_box_config(name, args, a_pass, L, workloads, np, torch, dev) -> tuple:
                 "feasible": feasible, "f": info.f},
         "roofline": {
             "bound": "hbm",
-            "kernel": ("two-pass A kernels (row-dot, then transposed), one read of A per launch" if apass_name != "fused"
+            "kernel": ("resident single-workgroup solver (matrix in registers: no pass over A in memory)" if resident
+                       else "two-pass A kernels (row-dot, then transposed), one read of A per launch" if apass_name != "fused"
                        else "fused A pass, logistic (t = X p, and X^T psi of the first trial step, in one read)"
                        if prob.kind == workloads.OBJ_LOGISTIC_L2
                        else "fused A pass (t = A p and w = A^T t in one read)"),

@@ -93,9 +93,18 @@ enum {
     LBFGSB_APASS_AUTO = 0,     /* fused single read of A when the shape allows it (16-byte aligned rows of at most
                                   20428 columns; 10240 for an fp64 logistic matrix), else two passes */
     LBFGSB_APASS_TWO_PASS = 1, /* t = A v, then w = A^T psi: A is read twice per evaluation and per iteration */
-    LBFGSB_APASS_FUSED = 2     /* force the fused kernel; lbfgsb_create fails if the shape does not fit.  For the
+    LBFGSB_APASS_FUSED = 2,    /* force the fused kernel; lbfgsb_create fails if the shape does not fit.  For the
                                   logistic objective an iteration's single read yields t = A p and A^T psi of the first
                                   trial step; a second (transposed) pass runs only if that step is rejected */
+    LBFGSB_APASS_RESIDENT = 3  /* small plain least-squares problems (kind LSQ without row weights or extra rows, at most
+                                  512 columns; up to 256 rows of at most 128 columns, or 64 rows of up to 512: at most 256 KB of fp64 matrix):
+                                  one workgroup keeps the matrix in registers and the vectors in LDS and runs whole
+                                  iterations without leaving its compute unit -- one launch per lbfgsb_step call, ONE
+                                  launch per lbfgsb_solve.  LBFGSB_APASS_AUTO picks it whenever the problem qualifies;
+                                  asking for it explicitly fails with LBFGSB_E_UNSUPPORTED when it does not.  Same
+                                  arithmetic as the other organisations with different summation orders (results agree
+                                  to rounding).  On this path a step that finds the stopping test met recomputes the
+                                  gradient from x and tests again before reporting LBFGSB_CONVERGED. */
 };
 
 typedef struct {
@@ -175,12 +184,18 @@ int lbfgsb_set_x(lbfgsb_solver* s, const double* x0);
  * the call is made, so a recorded run replays the pattern it was recorded with (use refresh_every = 0, or
  * record a multiple of it).  Not while lbfgsb_enable_apass_timing is on: timed launches carry events. */
 int lbfgsb_step(lbfgsb_solver* s, lbfgsb_info* info_host);
+/* (For the quadratic kinds the gradient is carried by recurrence between the periodic recomputations.  lbfgsb_solve
+ * and the resident organisation re-evaluate it from x before they report LBFGSB_CONVERGED; a loop of lbfgsb_step
+ * calls on the fused / two-pass organisations reports LBFGSB_CONVERGED from the carried gradient -- call
+ * lbfgsb_solve once at the end if the difference matters.) */
 
 /* Iterates until the tolerance, max_iter or a line-search failure.  The device decides all
  * data-dependent branches; the host only polls the status flag every poll_every iterations.
  * A least-squares solve is declared converged only with residual and gradient freshly
  * recomputed from x.  info_host may be NULL. */
 int lbfgsb_solve(lbfgsb_solver* s, lbfgsb_info* info_host);
+/* (Returns LBFGSB_OK with info.status == LBFGSB_RUNNING if 2*max_iter + 64 step launches -- accepted iterations plus
+ * retries after memory resets -- have not ended the solve.) */
 
 /* For callers that cannot allocate device memory (code that may run under HIP graph capture restrictions, tight
  * serving loops, harnesses that forbid hipMalloc): lbfgsb_create + lbfgsb_set_x + lbfgsb_solve + lbfgsb_get_x in one
@@ -301,7 +316,7 @@ void lbfgsb_auglag_destroy(lbfgsb_auglag* al);
  * are not read where a variable is fixed). */
 int lbfgsb_enable_apass_timing(lbfgsb_solver* s, int enable);
 int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count_host, double* total_ms_host, double* bytes_per_pass_host);
-/* Name of the A-pass organisation in use: "fused" or "two_pass" (host string). */
+/* Name of the A-pass organisation in use: "fused", "two_pass" or "resident" (host string). */
 const char* lbfgsb_apass_name(const lbfgsb_solver* s);
 
 /* ---- primitive-level hooks --------------------------------------------------------------------

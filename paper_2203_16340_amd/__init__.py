@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "liblbfgsb.so")
 
 F64, F32 = 0, 1
 OBJ_LSQ, OBJ_LSQ_L1SPLIT, OBJ_LOGISTIC_L2, OBJ_QP, OBJ_OT_GAUSS, OBJ_OT_ENTROPY = 0, 1, 2, 3, 4, 5
-APASS_AUTO, APASS_TWO_PASS, APASS_FUSED = 0, 1, 2
+APASS_AUTO, APASS_TWO_PASS, APASS_FUSED, APASS_RESIDENT = 0, 1, 2, 3
 RUNNING, CONVERGED, MAX_ITER, LINESEARCH_FAILED = 0, 1, 2, 3
 OK, E_INVALID_ARG, E_BOUNDS, E_INFEASIBLE_X0, E_NONFINITE, E_HIP, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 MAX_M = 31

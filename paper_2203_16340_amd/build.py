@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblbfgsb.so")
-SOURCES = ["api.hip", "apass.hip", "fused.hip", "gram.hip", "transport.hip", "vec.hip"]
+SOURCES = ["api.hip", "apass.hip", "fused.hip", "gram.hip", "resident.hip", "transport.hip", "vec.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
     # packed-fp32 instructions are kept out of the generated code on purpose

@@ -59,6 +59,7 @@ struct lbfgsb_solver {
     Scal* h_scal;            // host copy (pinned, allocated by lbfgsb_create)
     bool owns_h_scal;
     int use_fused;
+    int use_resident;        // small least squares: whole iterations in one resident workgroup
     int steps_since_refresh;
     long long steps_since_set_x;
     bool x_set;
@@ -102,7 +103,7 @@ int check_objective(int64_t n, int m, const lbfgsb_objective* o) {
 int check_options(const lbfgsb_options* o) {
     if (!(o->eps >= 0.0) || !(o->armijo_c1 > 0.0 && o->armijo_c1 < 1.0) || !(o->backtrack > 0.0 && o->backtrack < 1.0) ||
         o->max_backtracks < 0 || !(o->tol >= 0.0) || o->max_iter < 0 || o->refresh_every < 0 || o->poll_every < 1 ||
-        o->a_pass < LBFGSB_APASS_AUTO || o->a_pass > LBFGSB_APASS_FUSED)
+        o->a_pass < LBFGSB_APASS_AUTO || o->a_pass > LBFGSB_APASS_RESIDENT)
         return fail(LBFGSB_E_INVALID_ARG, "bad option value");
     return LBFGSB_OK;
 }
@@ -274,6 +275,11 @@ void enqueue_eval(lbfgsb_solver* s, int check_status) {
 
 // One iteration of Algorithm 1 as a fixed sequence of launches; nothing here waits for the device.
 void enqueue_step(lbfgsb_solver* s) {
+    if (s->use_resident) {
+        // (the periodic recomputation and the pending-update bookkeeping happen inside the kernel)
+        launch_resident(s->dm, s->op, s->bf, s->obj.A, s->obj.b, 1, s->options.refresh_every, s->stream);
+        return;
+    }
     const bool quad = is_quadratic(s->dm.kind);
     if (quad && s->options.refresh_every > 0 && s->steps_since_refresh >= s->options.refresh_every) {
         enqueue_eval(s, 1);
@@ -437,6 +443,14 @@ int setup_solver(lbfgsb_solver* s, int64_t n, int m, const lbfgsb_objective* obj
         const hipError_t ge_ = gram_prepare(n, m);
         if (ge_ != hipSuccess) return fail(LBFGSB_E_HIP, "preparing the Gram kernel: %s", hipGetErrorString(ge_));
     }
+    const bool resident_ok = resident_shape_ok(s->dm, obj->row_weight != nullptr);
+    if (o.a_pass == LBFGSB_APASS_RESIDENT && !resident_ok)
+        return fail(LBFGSB_E_UNSUPPORTED, "the resident solver does not take this problem (kind, shape or size)");
+    s->use_resident = resident_ok && (o.a_pass == LBFGSB_APASS_AUTO || o.a_pass == LBFGSB_APASS_RESIDENT);
+    if (s->use_resident) {
+        const hipError_t re = resident_prepare(s->dm);
+        if (re != hipSuccess) return fail(LBFGSB_E_HIP, "preparing the resident solver: %s", hipGetErrorString(re));
+    }
     s->use_fused = s->ge.fused_ok && o.a_pass != LBFGSB_APASS_TWO_PASS;
     if (s->use_fused) {
         const hipError_t fe = fused_prepare(s->dm, s->ge);
@@ -475,6 +489,16 @@ int init_workspace(lbfgsb_solver* s, const double* l, const double* u, void* wor
 int solve_impl(lbfgsb_solver* s, lbfgsb_info* info) {
     const bool quad = is_quadratic(s->dm.kind);
     const long long cap = 2ll * s->options.max_iter + 64;   // accepted iterations + memory-reset retries
+    if (s->use_resident) {
+        // one launch runs until the device-side status changes (it re-evaluates the gradient from x before it
+        // reports convergence) or the cap is reached
+        const int steps_cap = (int)(cap > 0x3fffffff ? 0x3fffffff : cap);
+        launch_resident(s->dm, s->op, s->bf, s->obj.A, s->obj.b, steps_cap, s->options.refresh_every, s->stream);
+        HIP_TRY(read_scal(s));
+        HIP_TRY(hipGetLastError());
+        if (info) fill_info(*s->h_scal, info);
+        return LBFGSB_OK;
+    }
     long long steps = 0;
     for (;;) {
         for (int k = 0; k < s->options.poll_every; ++k) enqueue_step(s);
@@ -775,7 +799,10 @@ int lbfgsb_apass_timing(lbfgsb_solver* s, int64_t* count, double* total_ms, doub
 }
 
 
-const char* lbfgsb_apass_name(const lbfgsb_solver* s) { return s && s->use_fused ? "fused" : "two_pass"; }
+const char* lbfgsb_apass_name(const lbfgsb_solver* s) {
+    if (s && s->use_resident) return "resident";
+    return s && s->use_fused ? "fused" : "two_pass";
+}
 
 // ---- primitive-level hooks ------------------------------------------------------------------------------
 

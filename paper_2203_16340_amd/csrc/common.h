@@ -57,6 +57,7 @@ struct Scal {
     double delta[kMaxV];        // coefficients of q = sum_j delta_j b_j in the batched two-loop
     unsigned counters[kCntCount];
     unsigned gram_cnt[kGramGroups + 1];   // two-level arrival of the large-n Gram kernel: one per group, then the top
+    int since_refresh;      // resident solver: iterations since residual and gradient were last computed from x
 };
 
 struct Dims {
@@ -102,6 +103,41 @@ __device__ __forceinline__ double wave_min(double v) {
     for (int o = 32; o > 0; o >>= 1) v = fmin(v, __shfl_xor(v, o));
     return v;
 }
+
+// The same reductions through the data-parallel-primitive lane permutations inside a row of 16 lanes (an operand
+// modifier of a move: a few cycles, where a shuffle goes through the LDS crossbar and costs ~130 cycles per dependent
+// step), then the four row totals through scalar registers.  Every lane gets the result; the order of the additions
+// is fixed: lane pairs, quads, halves of a row, rows 0..3.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i within each half row
+constexpr int kDppMirror = 0x140;       // lane i <-> 15 - i within each row
+__device__ __forceinline__ double lane_bcast(double v, int l) {   // l: compile-time lane index
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double wave_sum_dpp(double v) {
+    v += dpp_move<kDppXor1>(v);
+    v += dpp_move<kDppXor2>(v);
+    v += dpp_move<kDppHalfMirror>(v);
+    v += dpp_move<kDppMirror>(v);
+    return ((lane_bcast(v, 0) + lane_bcast(v, 16)) + lane_bcast(v, 32)) + lane_bcast(v, 48);
+}
+__device__ __forceinline__ double wave_min_dpp(double v) {
+    v = fmin(v, dpp_move<kDppXor1>(v));
+    v = fmin(v, dpp_move<kDppXor2>(v));
+    v = fmin(v, dpp_move<kDppHalfMirror>(v));
+    v = fmin(v, dpp_move<kDppMirror>(v));
+    return fmin(fmin(lane_bcast(v, 0), lane_bcast(v, 16)), fmin(lane_bcast(v, 32), lane_bcast(v, 48)));
+}
+__device__ __forceinline__ double wave_max_dpp(double v) { return -wave_min_dpp(-v); }
 
 // Sum of K values over a workgroup of NW waves; every thread gets the totals.  The order of the
 // additions is fixed (butterfly inside a wave, waves in index order), so results are bit-reproducible.
@@ -375,6 +411,12 @@ void launch_ot_update_gauss(const Dims& dm, const Opts& op, const Geometry& ge, 
                             hipStream_t st);
 void launch_ot_step_entropy(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const OtArgs& a,
                             hipStream_t st);
+
+// single-workgroup resident solver for small least-squares problems (resident.hip)
+bool resident_shape_ok(const Dims& dm, bool has_row_weight);
+hipError_t resident_prepare(const Dims& dm);   // once per solver, before the first launch_resident
+void launch_resident(const Dims& dm, const Opts& op, const Buffers& bf, const void* A, const double* b, int max_steps,
+                     int refresh_every, hipStream_t st);
 
 int gram_blocks_for(int64_t n, int m);
 size_t gram_partial_bytes(int64_t n, int m);   // Buffers::grampart

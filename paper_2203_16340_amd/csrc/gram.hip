@@ -21,6 +21,7 @@
 #include <cstddef>
 
 #include "common.h"
+#include "recursion.h"
 
 namespace lb {
 
@@ -47,97 +48,10 @@ size_t gram_lds_bytes(int m) {
     if (d < 1024) d = 1024;
     return d * 8;
 }
-// value of v in lane l (l uniform across the wave): a scalar-register read, not a trip through LDS
-__device__ __forceinline__ double lane_value(double v, int l) {
-    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
-    return __hiloint2double(hi, lo);
-}
-
 __device__ __forceinline__ void tile_of(int q, int T, int& ti, int& tj) {
     int a = 0;
     while (q >= T - a) { q -= T - a; ++a; }
     ti = a; tj = a + q;
-}
-
-// The recursion of Algorithm 3 on coefficients, by one wave of the last workgroup.  G: Vp x Vp (LDS), row-major,
-// vectors ordered s^0..s^{c-1}, y^0..y^{c-1}, g.  red[0] = sum g[S]^2, red[1] = max KKT residual, red[2] = #fixed,
-// red[3] = ||y_new||^2 (full vector).
-__device__ __forceinline__ void recursion_on_coefficients(const double* G, int Vp, int c, int head, int m, const Opts& op,
-                                                          Scal* __restrict__ scal, const double* red, double* alpha_s,
-                                                          int dbg_inputs, int evaluate_stop) {
-    const int tid = threadIdx.x, lane = tid & 63;
-    if (tid < 64) {
-        const int i = lane;   // lane i owns pair i (oldest = 0)
-        double rho = 1.0, yn = 1.0, inv = 0.0;
-        bool pass = false;
-        if (i < c) {
-            rho = G[i * Vp + (c + i)];
-            // the newest pair's norm was just summed (tid 0 also stored it for later iterations)
-            yn = (i == c - 1 && !dbg_inputs) ? red[3] : scal->ynorm2[(head - c + i + 2 * m) % m];
-            pass = rho > op.eps * yn;
-            inv = 1.0 / rho;
-        }
-        const unsigned long long pm = __ballot(pass);
-        // first loop: alpha_k, newest to oldest.  Steps of pairs that fail the gate run with alpha_k = 0;
-        // a lane's row is dead once its own alpha has been taken, so updating it further is harmless.
-        double part_s = i < c ? G[i * Vp + 2 * c] : 0.0;   // <s_i, g>
-        double alpha_i = 0.0;
-#pragma unroll 4
-        for (int k = c - 1; k >= 0; --k) {
-            const double gsy = i < c ? G[i * Vp + (c + k)] : 0.0;   // <s_i, y_k>
-            double ak = lane_value(part_s * inv, k);
-            if (!((pm >> k) & 1ull)) ak = 0.0;
-            if (i == k) alpha_i = ak;
-            part_s = fma(-ak, gsy, part_s);
-        }
-        if (i < c) alpha_s[i] = alpha_i;
-        double gamma = 1.0;
-        if (c > 0 && ((pm >> (c - 1)) & 1ull)) gamma = lane_value(rho / yn, c - 1);
-        // <y_i, gamma (g - sum_k alpha_k y_k)>
-        double by = 0.0;
-        {
-            double tsum = i < c ? G[(c + i) * Vp + 2 * c] : 0.0;
-#pragma unroll 4
-            for (int k = 0; k < c; ++k) {
-                const double gyy = i < c ? G[(c + i) * Vp + (c + k)] : 0.0;
-                tsum = fma(-alpha_s[k], gyy, tsum);
-            }
-            by = gamma * tsum;
-        }
-        // second loop: alpha_k - beta_k, oldest to newest
-        double coef_s = 0.0;
-#pragma unroll 4
-        for (int k = 0; k < c; ++k) {
-            const double gys = i < c ? G[(c + i) * Vp + k] : 0.0;   // <y_i, s_k>
-            double ck = lane_value(alpha_i - by * inv, k);
-            if (!((pm >> k) & 1ull)) ck = 0.0;
-            if (i == k) coef_s = ck;
-            if (i > k) by = fma(ck, gys, by);
-        }
-        if (i < c) {
-            scal->delta[i] = coef_s;
-            scal->delta[c + i] = -gamma * alpha_i;
-        }
-        if (lane == 0) {
-            scal->delta[2 * c] = gamma;
-            scal->pairs_used = __popcll(pm);
-            if (evaluate_stop) {
-                const double pgn = sqrt(red[0]);
-                scal->pg2 = pgn;
-                scal->pginf = red[1];
-                scal->n_fixed = (long long)red[2];
-                if (!scal->tol_resolved) {
-                    scal->tol_abs = op.tol_relative ? op.tol * fmax(1.0, pgn) : op.tol;
-                    scal->tol_resolved = 1;
-                }
-                if (scal->status == LBFGSB_RUNNING) {
-                    if (pgn <= scal->tol_abs) scal->status = LBFGSB_CONVERGED;
-                    else if (scal->iters >= op.max_iter) scal->status = LBFGSB_MAX_ITER;
-                }
-            }
-        }
-    }
 }
 
 __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts op, const double* __restrict__ x,
@@ -161,6 +75,7 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
         if (__shfl(hdr, offsetof(Scal, pend_ok) / 4)) { head = (head + 1) % m; c = c < m ? c + 1 : m; }
         else c = 0;
     }
+    const double yn_old = prefetch_ynorm2(scal, c, head, m);   // (used by the last workgroup's recursion, fetched now)
     const int V = 2 * c + 1;
     const int Vp = V + 1;
     const int T = Vp / 2;
@@ -344,7 +259,7 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
         }
     }
     __syncthreads();
-    recursion_on_coefficients(G, Vp, c, head, m, op, scal, red, alpha_s, dbg_inputs, evaluate_stop);
+    recursion_on_coefficients(G, Vp, c, head, m, op, scal, red[0], red[1], red[2], red[3], yn_old, alpha_s, dbg_inputs, evaluate_stop);
 }
 
 
@@ -472,6 +387,7 @@ __global__ __launch_bounds__(kBlock) void k_gram_mfma(int64_t n, int m, Opts op,
         if (__shfl(hdr, offsetof(Scal, pend_ok) / 4)) { head = (head + 1) % m; c = c < m ? c + 1 : m; }
         else c = 0;
     }
+    const double yn_old = prefetch_ynorm2(scal, c, head, m);   // (used by the last workgroup's recursion, fetched now)
     const int V = 2 * c + 1;
     const int Vp = V + 1;
     const int base_slot = c > 0 ? (head - c + 2 * m) % m : 0;   // ring slot of the oldest pair
@@ -610,7 +526,7 @@ __global__ __launch_bounds__(kBlock) void k_gram_mfma(int64_t n, int m, Opts op,
         if (c > 0 && !dbg_inputs) scal->ynorm2[(head - 1 + m) % m] = red[3];
     }
     __syncthreads();
-    recursion_on_coefficients(G, Vp, c, head, m, op, scal, red, alpha_s, dbg_inputs, evaluate_stop);
+    recursion_on_coefficients(G, Vp, c, head, m, op, scal, red[0], red[1], red[2], red[3], yn_old, alpha_s, dbg_inputs, evaluate_stop);
 }
 
 
@@ -828,6 +744,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         if (__shfl(hdr, offsetof(Scal, pend_ok) / 4)) { head = (head + 1) % m; c = c < m ? c + 1 : m; }
         else c = 0;
     }
+    const double yn_old = prefetch_ynorm2(scal, c, head, m);   // (used by the last workgroup's recursion, fetched now)
     const int V = 2 * c + 1, Vp = V + 1;
     WideCtx w;
     w.n = n; w.m = m; w.c = c; w.S = S; w.Y = Y; w.g = g;
@@ -875,7 +792,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         if (c > 0 && !dbg_inputs) scal->ynorm2[(head - 1 + m) % m] = red[3];
     }
     __syncthreads();
-    recursion_on_coefficients(Gs, Vp, c, head, m, op, scal, red, alpha_s, dbg_inputs, evaluate_stop);
+    recursion_on_coefficients(Gs, Vp, c, head, m, op, scal, red[0], red[1], red[2], red[3], yn_old, alpha_s, dbg_inputs, evaluate_stop);
 }
 
 // (any even n: below 2^17 entries the grid stays small enough for the one-level sum of the partials)
