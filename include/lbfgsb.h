@@ -96,8 +96,8 @@ enum {
     LBFGSB_APASS_FUSED = 2,    /* force the fused kernel; lbfgsb_create fails if the shape does not fit.  For the
                                   logistic objective an iteration's single read yields t = A p and A^T psi of the first
                                   trial step; a second (transposed) pass runs only if that step is rejected */
-    LBFGSB_APASS_RESIDENT = 3  /* small plain least-squares problems (kind LSQ without row weights or extra rows, at most
-                                  512 columns; up to 256 rows of at most 128 columns, or 64 rows of up to 512: at most 256 KB of fp64 matrix):
+    LBFGSB_APASS_RESIDENT = 3  /* small plain least-squares problems (kind LSQ without row weights or extra rows; up to
+                                  256 rows of at most 128 columns, or 128 rows of at most 256: at most 256 KB of fp64 matrix):
                                   one workgroup keeps the matrix in registers and the vectors in LDS and runs whole
                                   iterations without leaving its compute unit -- one launch per lbfgsb_step call, ONE
                                   launch per lbfgsb_solve.  LBFGSB_APASS_AUTO picks it whenever the problem qualifies;

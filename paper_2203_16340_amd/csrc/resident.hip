@@ -3,11 +3,12 @@
 // iteration of a 200 x 100 problem, i.e. it is bound by launch latency; here an iteration is a handful of
 // workgroup barriers.
 //
-//   * the matrix lives in REGISTERS for the whole launch: wave w of the 8 owns rows w, w + 8, w + 16, ..., lane l of a
-//     wave owns columns 2l, 2l + 1 of every 128-column chunk, so a lane holds up to 32 (row, chunk) tiles of two
-//     elements, loaded once at the start (fp32 storage is widened there).  One "pass over A" per iteration is then
-//     arithmetic and cross-lane sums only: t_r = a_r . p by a butterfly over the wave, and w = A^T t accumulated from
-//     the same registers, per wave, summed over the waves in wave order;
+//   * the matrix lives in REGISTERS for the whole launch: the 512 threads form 32 groups of 16 lanes (a row of the
+//     lane-permutation unit); group q owns rows q, q + 32, q + 64, ..., lane j of a group owns columns j, j + 16, ...
+//     of those rows, up to 64 elements per lane, loaded once at the start (fp32 storage is widened there).  One
+//     "pass over A" per iteration is then arithmetic only: t_r = a_r . p by four lane permutations inside the group,
+//     which leaves t_r in exactly the lanes that need it for w = A^T t, accumulated from the same registers; the 32
+//     groups' partial columns meet in LDS and are added in group order;
 //   * x, g, l, u, the pair memory and the Gram matrix live in LDS; the scalar block is an LDS copy of the device one;
 //   * every phase is the arithmetic of the corresponding kernel of the multi-kernel path (Eq. (ws), masked Gram matrix,
 //     Algorithm 3 on coefficients -- the same device function --, Algorithm 2 with both candidate directions, the
@@ -25,8 +26,7 @@ namespace {
 
 constexpr int kResThreads = 512;                // 8 waves, two per SIMD: 256 registers per lane, half of them hold the matrix
 constexpr int kResWaves = kResThreads / 64;
-constexpr int kResTiles = 32;                   // (row, chunk) tiles of two elements a lane holds, at most
-constexpr int kResBatch = 8;                    // rows whose cross-lane sums are in flight together
+constexpr int kResGroups = kResThreads / 16;    // 16-lane groups, each owning whole rows of the matrix
 constexpr size_t kResLdsLimit = 150 * 1024;
 
 struct ResArgs {
@@ -47,79 +47,83 @@ struct ResArgs {
 struct ResLayout {
     int x, g, l, u, p1, p2, msk, w, S, Y, G, wred, red, alpha, total;
 };
+// every n-vector has npad = n rounded up to 16 entries, the padding kept at zero, so that loops over elements in
+// steps of 16 need no bounds checks
+__host__ __device__ inline int res_npad(int n) { return (n + 15) & ~15; }
 __host__ __device__ inline ResLayout res_layout(int n, int m, int cpad) {
     ResLayout L;
+    const int np = res_npad(n);
     int off = 0;
     auto take = [&](int k) { int o = off; off += (k + 1) & ~1; return o; };
-    L.x = take(n); L.g = take(n); L.l = take(n); L.u = take(n); L.p1 = take(n); L.p2 = take(n); L.msk = take(n); L.w = take(n);
-    L.S = take(m * n); L.Y = take(m * n);
+    L.x = take(np); L.g = take(np); L.l = take(np); L.u = take(np); L.p1 = take(np); L.p2 = take(np); L.msk = take(np); L.w = take(np);
+    L.S = take(m * np); L.Y = take(m * np);
     L.G = take((2 * m + 2) * (2 * m + 2));
-    L.wred = take(kResWaves * cpad);
+    L.wred = take(kResGroups * cpad);
     L.red = take(96);               // per-phase exchange areas of the waves' partial results
     L.alpha = take(kMaxM + 1);
     L.total = off;
     return L;
 }
 
-// CH: 128-column chunks of a row; NT: tiles a lane holds (instantiated for a few sizes so that the matrix of a
-// problem smaller than the largest one leaves registers for everything else).
+// CPL: columns per lane (of each row its group owns); RG: rows per group (instantiated for a few sizes so that the
+// matrix of a problem smaller than the largest one leaves registers for everything else).
 //
 // What bounds an iteration here is the latency of dependent steps (an LDS access or a shuffle is ~130 cycles when
 // the next instruction waits for it), so: thread i owns element i of every n-vector (n <= 512 = threads) and keeps
 // x_i, g_i, l_i, u_i in registers; sums over a wave use the lane permutations of wave_sum_dpp; LDS loads that feed a
 // chain are issued in groups before they are used; reductions over the workgroup that can share a barrier do.
-template <int CH, int NT>
+template <int CPL, int RG>
 __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
     extern __shared__ __align__(16) double lds[];
     __shared__ Scal sc;
-    constexpr int RW = NT / CH;                 // rows a wave can own
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = tid >> 4, gj = tid & 15;    // this lane's group and its place in it
     const int n = (int)a.dm.cols, rows = (int)a.dm.rows, m = a.dm.m;
+    const int np = res_npad(n);
     const int64_t ld = a.dm.ld;
-    const ResLayout L = res_layout(n, m, CH * 128);
+    const ResLayout L = res_layout(n, m, CPL * 16);
     double *gs = lds + L.g, *p1s = lds + L.p1, *p2s = lds + L.p2, *xs = lds + L.x;
     double *msk = lds + L.msk, *Ss = lds + L.S, *Ys = lds + L.Y, *G = lds + L.G, *wred = lds + L.wred;
     double *red = lds + L.red, *alpha_s = lds + L.alpha;
     double *redA = red, *redD = red + 16, *redP = red + 16 + 56, *redU = red + 16 + 56 + 8;   // one region per phase
     const Opts op = a.op;
     const bool act = tid < n;                   // this thread owns element `tid`
+    const int nw = (n + 63) >> 6;               // waves that own elements; the others only help with Gram and pass
+    const bool wact = wave < nw;
 
     // ---- the scalar block; nothing to do when the solver has stopped
     for (int k = tid; k < (int)(sizeof(Scal) / 4); k += kResThreads)
         reinterpret_cast<int*>(&sc)[k] = reinterpret_cast<const int*>(a.scal)[k];
+    for (int k = tid; k < L.G; k += kResThreads) lds[k] = 0.0;   // the vectors, their padding included
     __syncthreads();
     if (sc.status != LBFGSB_RUNNING) return;
     if (tid == 0 && sc.pend_valid) apply_pending(&sc, m);   // (left by a step of the multi-kernel path; normally none)
 
     // ---- the matrix into registers, the vectors into LDS and registers
-    double at[NT][2];
+    double at[RG][CPL];
 #pragma unroll
-    for (int k = 0; k < NT; ++k) {
-        const int r = wave + kResWaves * (k / CH), c0 = (k % CH) * 128 + 2 * lane;
-        const int64_t o = (int64_t)r * ld + c0;
-        const bool in0 = r < rows && c0 < n, in1 = r < rows && c0 + 1 < n;
-        if (a.f32) {
-            const float* A = reinterpret_cast<const float*>(a.A);
-            at[k][0] = in0 ? (double)A[o] : 0.0;
-            at[k][1] = in1 ? (double)A[o + 1] : 0.0;
-        } else {
-            const double* A = reinterpret_cast<const double*>(a.A);
-            at[k][0] = in0 ? A[o] : 0.0;
-            at[k][1] = in1 ? A[o + 1] : 0.0;
+    for (int q = 0; q < RG; ++q) {
+        const int r = grp + kResGroups * q;
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            const int col = gj + 16 * k;
+            const int64_t o = (int64_t)r * ld + col;
+            const bool in = r < rows && col < n;
+            if (a.f32) at[q][k] = in ? (double)reinterpret_cast<const float*>(a.A)[o] : 0.0;
+            else at[q][k] = in ? reinterpret_cast<const double*>(a.A)[o] : 0.0;
         }
     }
     double xi = 0.0, gi = 0.0, li = 0.0, ui = 0.0, mi = 0.0;
     if (act) { xi = a.x[tid]; gi = a.g[tid]; li = a.l[tid]; ui = a.u[tid]; mi = a.mask[tid] ? 1.0 : 0.0; xs[tid] = xi; gs[tid] = gi; }
-    for (int i = tid; i < m * n; i += kResThreads) { Ss[i] = a.S[i]; Ys[i] = a.Y[i]; }
+    for (int i = tid; i < m * n; i += kResThreads) {
+        const int sl = i / n, e = i - sl * n;
+        Ss[sl * np + e] = a.S[i];
+        Ys[sl * np + e] = a.Y[i];
+    }
     __syncthreads();
+    // loop state every thread carries in registers (the same values in all of them)
+    int c = sc.count, head = sc.head, since = sc.since_refresh;
 
-#ifdef LBFGSB_RESIDENT_PROFILE
-    unsigned long long pt[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pt0 = 0;
-#define RES_MARK(k) do { if (tid == 0) { const unsigned long long now_ = wall_clock64(); pt[k] += now_ - pt0; pt0 = now_; } } while (0)
-    if (tid == 0) pt0 = wall_clock64();
-#else
-#define RES_MARK(k) do { } while (0)
-#endif
 
     // Every trip of the loop makes ONE product pass: either an evaluation from scratch (r = A x - b, f = 0.5 ||r||^2,
     // g = A^T r: the periodic recomputation, and the one before convergence is declared), or the pass of an iteration.
@@ -127,9 +131,8 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
     bool want_eval = false;
     for (;;) {
         if (!want_eval && steps >= a.max_steps) break;
-        if (!want_eval && a.refresh_every > 0 && sc.since_refresh >= a.refresh_every) want_eval = true;
+        if (!want_eval && a.refresh_every > 0 && since >= a.refresh_every) want_eval = true;
 
-        const int c = sc.count, head = sc.head;
         const int V = 2 * c + 1, Vp = V + 1;
         const int base_slot = c > 0 ? (head - c + 2 * m) % m : 0;
         auto vec = [&](int j) __attribute__((always_inline)) -> const double* {
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
             const bool is_y = j >= c;
             int sl = base_slot + (is_y ? j - c : j);
             if (sl >= m) sl -= m;
-            return (is_y ? Ys : Ss) + sl * n;
+            return (is_y ? Ys : Ss) + sl * np;
         };
         double s6[6] = {0, 0, 0, 0, 0, 0};
         double gp = 0.0, alpha_ub = 1.0, pa = 0.0, pb = 0.0;
@@ -146,7 +149,7 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
 
         if (!want_eval) {
             // ---- Eq. (ws): free set; the epsilon-free KKT residual and the number of fixed variables
-            {
+            if (wact) {
                 const bool fr = !(((xi <= li + op.eps) && (gi >= 0.0)) || ((xi >= ui - op.eps) && (gi <= 0.0)));
                 mi = (act && fr) ? 1.0 : 0.0;
                 if (act) msk[tid] = mi;
@@ -155,32 +158,25 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 if (lane == 0) { redA[wave] = nf; redA[kResWaves + wave] = pg; }
             }
             __syncthreads();                        // msk and the waves' partial statistics are in LDS
-            RES_MARK(0);
 
             // ---- masked Gram matrix of [s^0 .. s^{c-1}, y^0 .. y^{c-1}, g]: four lanes per entry, each taking every
             // fourth element; the loads of four elements are issued before their products
             {
                 const int E = V * (V + 1) / 2;
-                const int grp = tid >> 2, sub = tid & 3;
+                const int eg = tid >> 2, sub = tid & 3;
                 for (int e0 = 0; e0 < E; e0 += kResThreads / 4) {
-                    const int e = e0 + grp;
+                    const int e = e0 + eg;
                     int ra = 0, rb = 0;
                     double s = 0.0;
                     if (e < E) {
                         int q = e;
                         while (q >= V - ra) { q -= V - ra; ++ra; }
                         rb = ra + q;
-                        const double *va = vec(ra), *vb = vec(rb);
-                        for (int i0 = sub; i0 < n; i0 += 16) {
+                        const double *va = vec(ra) + sub, *vb = vec(rb) + sub, *vm = msk + sub;
+                        for (int i0 = 0; i0 < np; i0 += 16) {
                             double mv[4], av[4], bv[4];
 #pragma unroll
-                            for (int k = 0; k < 4; ++k) {
-                                const int i = i0 + 4 * k;
-                                const bool in = i < n;
-                                mv[k] = in ? msk[i] : 0.0;
-                                av[k] = in ? va[i] : 0.0;
-                                bv[k] = in ? vb[i] : 0.0;
-                            }
+                            for (int k = 0; k < 4; ++k) { mv[k] = vm[i0 + 4 * k]; av[k] = va[i0 + 4 * k]; bv[k] = vb[i0 + 4 * k]; }
 #pragma unroll
                             for (int k = 0; k < 4; ++k) s = fma(mv[k] * av[k], bv[k], s);
                         }
@@ -191,21 +187,18 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 }
             }
             __syncthreads();
-            RES_MARK(1);
             // ---- Algorithm 3 on coefficients (wave 0), the stopping test with it
             if (tid < 64) {
                 double nfix = 0.0, pginf = 0.0;
-#pragma unroll
-                for (int w = 0; w < kResWaves; ++w) { nfix += redA[w]; pginf = fmax(pginf, redA[kResWaves + w]); }
+                for (int w = 0; w < nw; ++w) { nfix += redA[w]; pginf = fmax(pginf, redA[kResWaves + w]); }
                 const double ynew = c > 0 ? sc.ynorm2[(head - 1 + m) % m] : 0.0;
                 const double yn_old = prefetch_ynorm2(&sc, c, head, m);
                 recursion_on_coefficients(G, Vp, c, head, m, op, &sc, G[(2 * c) * Vp + 2 * c], pginf, nfix, ynew, yn_old,
                                           alpha_s, 0, 1);
             }
             __syncthreads();
-            RES_MARK(2);
             const int st = sc.status;
-            const bool recheck = st == LBFGSB_CONVERGED && sc.since_refresh > 0 && sc.iters > 0;
+            const bool recheck = st == LBFGSB_CONVERGED && since > 0 && sc.iters > 0;
             if (recheck) {
                 // the stopping quantity came from a gradient carried by recurrence: recompute it from x, test again
                 __syncthreads();                    // every thread has read the status
@@ -217,7 +210,7 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
             ++steps;
 
             // ---- d = -B delta on the free set; both candidate directions of Algorithm 2 and their sums
-            {
+            if (wact) {
                 double de = 0.0;
                 if (mi != 0.0) {
                     double q = 0.0;
@@ -254,10 +247,11 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                     for (int k = 0; k < 6; ++k) redD[wave * 7 + k] = w6[k];
                     redD[wave * 7 + 6] = ub;
                 }
-                __syncthreads();                    // (also publishes p1s / p2s)
+            }
+            __syncthreads();                        // (also publishes p1s / p2s)
+            {
                 double ubt = INFINITY;
-#pragma unroll
-                for (int w = 0; w < kResWaves; ++w) {
+                for (int w = 0; w < nw; ++w) {
 #pragma unroll
                     for (int k = 0; k < 6; ++k) s6[k] += redD[w * 7 + k];
                     ubt = fmin(ubt, redD[w * 7 + 6]);
@@ -267,63 +261,62 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 alpha_ub = branch == 1 ? 1.0 : ubt;
                 ps = branch == 1 ? p1s : p2s;
             }
-            RES_MARK(3);
         }
 
-        // ---- the pass: u_r = a_r . v for this wave's rows, psi_r = u_r - (evaluation ? b_r : 0), w = A^T psi, sum psi^2
+        // ---- the pass: u_r = a_r . v for this group's rows, psi_r = u_r - (evaluation ? b_r : 0), w = A^T psi, sum psi^2
         double tt = 0.0, wi = 0.0;
         {
-            double pv[CH][2];
+            double pv[CPL], wl[CPL];
 #pragma unroll
-            for (int ch = 0; ch < CH; ++ch) {
-                const int c0 = ch * 128 + 2 * lane;
-                pv[ch][0] = c0 < n ? ps[c0] : 0.0;
-                pv[ch][1] = c0 + 1 < n ? ps[c0 + 1] : 0.0;
+            for (int k = 0; k < CPL; ++k) {
+                const int col = gj + 16 * k;
+                pv[k] = col < n ? ps[col] : 0.0;
+                wl[k] = 0.0;
             }
-            double wl[CH][2];
+            double ttg = 0.0;
 #pragma unroll
-            for (int ch = 0; ch < CH; ++ch) wl[ch][0] = wl[ch][1] = 0.0;
-            double ttw = 0.0;
-#pragma unroll
-            for (int q = 0; q < RW; ++q) {
+            for (int q = 0; q < RG; ++q) {
                 double s = 0.0;
 #pragma unroll
-                for (int ch = 0; ch < CH; ++ch) {
-                    s = fma(at[q * CH + ch][0], pv[ch][0], s);
-                    s = fma(at[q * CH + ch][1], pv[ch][1], s);
-                }
-                s = wave_sum_dpp(s);
-                const int r = wave + kResWaves * q;
+                for (int k = 0; k < CPL; ++k) s = fma(at[q][k], pv[k], s);
+                // the sum over the 16 lanes of the group; every lane of the group gets it
+                s += dpp_move<kDppXor1>(s);
+                s += dpp_move<kDppXor2>(s);
+                s += dpp_move<kDppHalfMirror>(s);
+                s += dpp_move<kDppMirror>(s);
+                const int r = grp + kResGroups * q;
                 double psi = r < rows ? s : 0.0;
                 if (want_eval && r < rows) psi -= a.b[r];      // (the targets are read in the rare evaluations only)
-                ttw = fma(psi, psi, ttw);
+                ttg = fma(psi, psi, ttg);
 #pragma unroll
-                for (int ch = 0; ch < CH; ++ch) {
-                    wl[ch][0] = fma(at[q * CH + ch][0], psi, wl[ch][0]);
-                    wl[ch][1] = fma(at[q * CH + ch][1], psi, wl[ch][1]);
-                }
+                for (int k = 0; k < CPL; ++k) wl[k] = fma(at[q][k], psi, wl[k]);
             }
 #pragma unroll
-            for (int ch = 0; ch < CH; ++ch) {
-                wred[wave * (CH * 128) + ch * 128 + 2 * lane] = wl[ch][0];
-                wred[wave * (CH * 128) + ch * 128 + 2 * lane + 1] = wl[ch][1];
-            }
+            for (int k = 0; k < CPL; ++k) wred[grp * (CPL * 16) + gj + 16 * k] = wl[k];
+            // the four groups of a wave in group order, then the waves in wave order
+            const double ttw = ((lane_bcast(ttg, 0) + lane_bcast(ttg, 16)) + lane_bcast(ttg, 32)) + lane_bcast(ttg, 48);
             if (lane == 0) redP[wave] = ttw;
             __syncthreads();
+            if (act) {
+                // four chains of eight groups each, so that the additions do not wait for one another
+                double w4[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int w = 0; w < kResWaves; ++w) {
-                wi += act ? wred[w * (CH * 128) + tid] : 0.0;
-                tt += redP[w];
+                for (int q = 0; q < kResGroups / 4; ++q) {
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) w4[h] += wred[(h * (kResGroups / 4) + q) * (CPL * 16) + tid];
+                }
+                wi = (w4[0] + w4[1]) + (w4[2] + w4[3]);
             }
+#pragma unroll
+            for (int w = 0; w < kResWaves; ++w) tt += redP[w];
         }
-        RES_MARK(4);
         if (want_eval) {
             gi = wi;
             if (act) { gs[tid] = gi; a.g[tid] = gi; }
             if (tid == 0) { sc.f = 0.5 * tt; sc.fevals += 1; sc.since_refresh = 0; }
-            __syncthreads();
+            since = 0;
             want_eval = false;
-            continue;
+            continue;                               // (the next trip's first barrier orders these writes before their readers)
         }
 
         // ---- closed-form Armijo search (every thread takes the same decisions)
@@ -338,31 +331,32 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
 
         // ---- update: x+, g+ = g + alpha w, the new pair into the ring (LDS and device memory)
         const int slot = head;
-        double ysq = 0.0;
-        if (ok && act) {
-            const double y = alpha * wi;
-            const double pi = branch == 1 ? pa : pb;
-            const double xn = clampd(fma(alpha, pi, xi), li, ui);
-            const double sn = xn - xi;
-            xi = xn;
-            gi += y;
-            Ss[slot * n + tid] = sn;
-            Ys[slot * n + tid] = y;
-            xs[tid] = xi;
-            gs[tid] = gi;
-            a.S[(int64_t)slot * n + tid] = sn;
-            a.Y[(int64_t)slot * n + tid] = y;
-            a.x[tid] = xi;
-            a.g[tid] = gi;
-            ysq = y * y;
+        if (wact) {
+            double ysq = 0.0;
+            if (ok && act) {
+                const double y = alpha * wi;
+                const double pi = branch == 1 ? pa : pb;
+                const double xn = clampd(fma(alpha, pi, xi), li, ui);
+                const double sn = xn - xi;
+                xi = xn;
+                gi += y;
+                Ss[slot * np + tid] = sn;
+                Ys[slot * np + tid] = y;
+                xs[tid] = xi;
+                gs[tid] = gi;
+                a.S[(int64_t)slot * n + tid] = sn;
+                a.Y[(int64_t)slot * n + tid] = y;
+                a.x[tid] = xi;
+                a.g[tid] = gi;
+                ysq = y * y;
+            }
+            ysq = wave_sum_dpp(ysq);
+            if (lane == 0) redU[wave] = ysq;
         }
-        ysq = wave_sum_dpp(ysq);
-        if (lane == 0) redU[wave] = ysq;
         __syncthreads();
         if (tid == 0) {
             double yn = 0.0;
-#pragma unroll
-            for (int w = 0; w < kResWaves; ++w) yn += redU[w];
+            for (int w = 0; w < nw; ++w) yn += redU[w];
             sc.branch = branch; sc.gp = gp; sc.alpha_ub = alpha_ub;
             sc.pp = branch == 1 ? s6[1] : s6[4];
             sc.xp = branch == 1 ? s6[2] : s6[5];
@@ -376,7 +370,7 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 sc.head = (slot + 1) % m;
                 sc.count = c < m ? c + 1 : m;
                 sc.iters += 1;
-                sc.since_refresh += 1;
+                sc.since_refresh = since + 1;
             } else if (c > 0) {
                 sc.count = 0;
                 sc.memory_resets += 1;
@@ -384,14 +378,11 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 sc.status = LBFGSB_LINESEARCH_FAILED;
             }
         }
-        __syncthreads();
-        RES_MARK(5);
+        // the same bookkeeping in every thread's registers; the next trip's first barrier orders thread 0's writes to
+        // the scalar block before the recursion reads them
+        if (ok) { head = (slot + 1) % m; c = c < m ? c + 1 : m; since += 1; }
+        else if (c > 0) c = 0;
     }
-#ifdef LBFGSB_RESIDENT_PROFILE
-    if (tid == 0 && steps > 8)
-        printf("resident: %d steps; per step (10 ns ticks): mask %llu gram %llu recursion %llu direction %llu pass %llu update %llu\n",
-               steps, pt[0] / steps, pt[1] / steps, pt[2] / steps, pt[3] / steps, pt[4] / steps, pt[5] / steps);
-#endif
 
     // ---- state the other entry points read: the scalar block and the free mask
     __syncthreads();
@@ -400,53 +391,44 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
         reinterpret_cast<int*>(a.scal)[k] = reinterpret_cast<const int*>(&sc)[k];
 }
 
-int resident_chunks(const Dims& dm) { return dm.cols <= 128 ? 1 : 4; }
-
-// tiles per lane of the instantiation that holds this problem (0: none does)
-int resident_tiles(const Dims& dm) {
-    const int ch = resident_chunks(dm);
-    const int64_t need = (dm.rows + kResWaves - 1) / kResWaves * ch;
-    if (ch == 1) return need <= 8 ? 8 : (need <= 16 ? 16 : (need <= 26 ? 26 : (need <= 32 ? 32 : 0)));
-    return need <= 16 ? 16 : (need <= 32 ? 32 : 0);
-}
-
+// The instantiations, smallest register footprint first: (columns per lane, rows per group) holds a matrix of up
+// to 32 * RG rows and 16 * CPL columns.  (7, 7) is the one the 200 x 100 benchmark configuration runs on: its 49
+// matrix elements per lane leave the rest of the iteration its registers, which (8, 8) does not.
 typedef void (*ResKernel)(ResArgs);
-ResKernel resident_kernel(const Dims& dm) {
-    const int nt = resident_tiles(dm);
-    if (resident_chunks(dm) == 1) {
-        switch (nt) {
-            case 8: return &k_resident<1, 8>;
-            case 16: return &k_resident<1, 16>;
-            case 26: return &k_resident<1, 26>;
-            default: return &k_resident<1, 32>;
-        }
-    }
-    return nt == 16 ? &k_resident<4, 16> : &k_resident<4, 32>;
+struct ResVariant { int cpl, rg; ResKernel kernel; };
+const ResVariant kResVariants[] = {
+    {8, 4, &k_resident<8, 4>}, {4, 8, &k_resident<4, 8>}, {7, 7, &k_resident<7, 7>},
+    {8, 8, &k_resident<8, 8>}, {16, 4, &k_resident<16, 4>},
+};
+const ResVariant* resident_variant(const Dims& dm) {
+    for (const ResVariant& v : kResVariants)
+        if (dm.cols <= 16 * v.cpl && dm.rows <= (int64_t)kResGroups * v.rg) return &v;
+    return nullptr;
 }
 
 }  // namespace
 
-// The resident solver takes plain least squares (no row weights, no extra rows) whose matrix fits the register tiles
-// of one workgroup and whose vectors fit its LDS.
+// The resident solver takes plain least squares (no row weights, no extra rows) whose matrix fits the registers of
+// one workgroup (up to 256 rows of at most 128 columns, or 128 rows of at most 256) and whose vectors fit its LDS.
 bool resident_shape_ok(const Dims& dm, bool has_row_weight) {
-    if (dm.kind != LBFGSB_OBJ_LSQ || has_row_weight || dm.n_extra > 0) return false;
-    if (dm.cols > 512 || dm.n != dm.cols) return false;
-    if (resident_tiles(dm) == 0) return false;
-    return (size_t)res_layout((int)dm.n, dm.m, resident_chunks(dm) * 128).total * 8 <= kResLdsLimit;
+    if (dm.kind != LBFGSB_OBJ_LSQ || has_row_weight || dm.n_extra > 0 || dm.n != dm.cols) return false;
+    const ResVariant* v = resident_variant(dm);
+    return v && (size_t)res_layout((int)dm.n, dm.m, v->cpl * 16).total * 8 <= kResLdsLimit;
 }
 
 hipError_t resident_prepare(const Dims& dm) {
-    const size_t bytes = (size_t)res_layout((int)dm.n, dm.m, resident_chunks(dm) * 128).total * 8;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(resident_kernel(dm)), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)bytes);
+    const ResVariant* v = resident_variant(dm);
+    const size_t bytes = (size_t)res_layout((int)dm.n, dm.m, v->cpl * 16).total * 8;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(v->kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
 void launch_resident(const Dims& dm, const Opts& op, const Buffers& bf, const void* A, const double* b, int max_steps,
                      int refresh_every, hipStream_t st) {
-    const size_t bytes = (size_t)res_layout((int)dm.n, dm.m, resident_chunks(dm) * 128).total * 8;
+    const ResVariant* v = resident_variant(dm);
+    const size_t bytes = (size_t)res_layout((int)dm.n, dm.m, v->cpl * 16).total * 8;
     ResArgs a{dm, op, A, b, bf.scal, bf.x, bf.g, bf.S, bf.Y, bf.l, bf.u, bf.mask, max_steps, refresh_every,
               dm.dtype == LBFGSB_F32 ? 1 : 0};
-    hipLaunchKernelGGL(resident_kernel(dm), dim3(1), dim3(kResThreads), bytes, st, a);
+    hipLaunchKernelGGL(v->kernel, dim3(1), dim3(kResThreads), bytes, st, a);
 }
 
 }  // namespace lb

@@ -13,10 +13,10 @@ from gpu_helpers import DEV, active_set, kkt_residual, rel_err, to_dev
 
 pytestmark = pytest.mark.gpu
 
-# rows x cols: one per instantiation (rows per wave 8 / 16 / 26 / 32 at up to 128 columns; 16 / 32 tiles at up to 512),
-# plus odd sizes, a single row, a single column
-SHAPES = [(60, 30), (64, 128), (120, 77), (200, 100), (208, 128), (250, 5), (256, 128), (30, 200), (32, 512), (61, 301),
-          (64, 500), (1, 40), (40, 1), (7, 3)]
+# rows x cols: every instantiation (columns per lane x rows per group: 8x4, 4x8, 7x7, 8x8, 16x4) at its limits and
+# inside them, odd sizes, a single row, a single column
+SHAPES = [(60, 30), (128, 128), (120, 77), (256, 64), (250, 5), (200, 100), (224, 112), (208, 128), (256, 128), (30, 200),
+          (128, 256), (61, 201), (1, 40), (40, 1), (7, 3)]
 
 
 def _problem(rows, cols, seed, dtype=np.float64, upper=np.inf, m=5):
@@ -135,7 +135,7 @@ def test_selection_and_refusal():
         s = _solver(small, a_pass=a_pass)
         assert s.apass_name == name
         s.close()
-    big = _problem(400, 100, seed=2)                # 50 rows per wave: does not fit the register tiles
+    big = _problem(400, 100, seed=2)                # 13 rows per group of lanes: does not fit the registers
     s = _solver(big)
     assert s.apass_name != "resident"
     s.close()
