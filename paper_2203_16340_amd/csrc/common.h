@@ -88,26 +88,11 @@ struct Opts {
 
 // ---- reductions ---------------------------------------------------------------------------------
 
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-__device__ __forceinline__ double wave_max(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
-    return v;
-}
-__device__ __forceinline__ double wave_min(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmin(v, __shfl_xor(v, o));
-    return v;
-}
-
-// The same reductions through the data-parallel-primitive lane permutations inside a row of 16 lanes (an operand
-// modifier of a move: a few cycles, where a shuffle goes through the LDS crossbar and costs ~130 cycles per dependent
-// step), then the four row totals through scalar registers.  Every lane gets the result; the order of the additions
-// is fixed: lane pairs, quads, halves of a row, rows 0..3.
+// Reductions over the 64 lanes of a wave: lane permutations of the data-parallel-primitive unit inside a row of 16
+// lanes (an operand modifier of a move: a few cycles, where a shuffle goes through the LDS crossbar and costs ~130
+// cycles per dependent step), then the four row totals through scalar registers.  Every lane gets the result; the
+// order of the operations is fixed: lane pairs, quads, halves of a row, rows 0..3.  ALL 64 lanes must be active
+// where these are called (a permutation reads zero from an inactive lane).
 template <int CTRL>
 __device__ __forceinline__ double dpp_move(double v) {
     const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
@@ -123,21 +108,21 @@ __device__ __forceinline__ double lane_bcast(double v, int l) {   // l: compile-
     const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
     return __hiloint2double(hi, lo);
 }
-__device__ __forceinline__ double wave_sum_dpp(double v) {
+__device__ __forceinline__ double wave_sum(double v) {
     v += dpp_move<kDppXor1>(v);
     v += dpp_move<kDppXor2>(v);
     v += dpp_move<kDppHalfMirror>(v);
     v += dpp_move<kDppMirror>(v);
     return ((lane_bcast(v, 0) + lane_bcast(v, 16)) + lane_bcast(v, 32)) + lane_bcast(v, 48);
 }
-__device__ __forceinline__ double wave_min_dpp(double v) {
+__device__ __forceinline__ double wave_min(double v) {
     v = fmin(v, dpp_move<kDppXor1>(v));
     v = fmin(v, dpp_move<kDppXor2>(v));
     v = fmin(v, dpp_move<kDppHalfMirror>(v));
     v = fmin(v, dpp_move<kDppMirror>(v));
     return fmin(fmin(lane_bcast(v, 0), lane_bcast(v, 16)), fmin(lane_bcast(v, 32), lane_bcast(v, 48)));
 }
-__device__ __forceinline__ double wave_max_dpp(double v) { return -wave_min_dpp(-v); }
+__device__ __forceinline__ double wave_max(double v) { return -wave_min(-v); }
 
 // Sum of K values over a workgroup of NW waves; every thread gets the totals.  The order of the
 // additions is fixed (butterfly inside a wave, waves in index order), so results are bit-reproducible.

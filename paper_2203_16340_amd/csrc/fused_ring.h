@@ -95,12 +95,6 @@ __device__ __forceinline__ void row_eval(int mode, double u, double b, double z,
     }
 }
 
-__device__ __forceinline__ double lane_bcast(double v, int l) {
-    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
-    return __hiloint2double(hi, lo);
-}
-
 // After the barrier of a stage: lane r (< R) of EVERY wave sums the partial dot products of row r of the
 // stage and evaluates its row operation -- the transcendental functions of the logistic modes run once
 // per stage, not once per row -- wave 0 stores the row's entry of t / row, and the weights psi are

@@ -70,7 +70,7 @@ __host__ __device__ inline ResLayout res_layout(int n, int m, int cpad) {
 //
 // What bounds an iteration here is the latency of dependent steps (an LDS access or a shuffle is ~130 cycles when
 // the next instruction waits for it), so: thread i owns element i of every n-vector (n <= 512 = threads) and keeps
-// x_i, g_i, l_i, u_i in registers; sums over a wave use the lane permutations of wave_sum_dpp; LDS loads that feed a
+// x_i, g_i, l_i, u_i in registers; sums over a wave use the lane permutations of wave_sum; LDS loads that feed a
 // chain are issued in groups before they are used; reductions over the workgroup that can share a barrier do.
 template <int CPL, int RG>
 __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
@@ -153,8 +153,8 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 const bool fr = !(((xi <= li + op.eps) && (gi >= 0.0)) || ((xi >= ui - op.eps) && (gi <= 0.0)));
                 mi = (act && fr) ? 1.0 : 0.0;
                 if (act) msk[tid] = mi;
-                const double nf = wave_sum_dpp((act && !fr) ? 1.0 : 0.0);
-                const double pg = wave_max_dpp(act ? fabs(xi - clampd(xi - gi, li, ui)) : 0.0);
+                const double nf = wave_sum((act && !fr) ? 1.0 : 0.0);
+                const double pg = wave_max(act ? fabs(xi - clampd(xi - gi, li, ui)) : 0.0);
                 if (lane == 0) { redA[wave] = nf; redA[kResWaves + wave] = pg; }
             }
             __syncthreads();                        // msk and the waves' partial statistics are in LDS
@@ -240,8 +240,8 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 }
                 double w6[6] = {pa * gi, pa * pa, xi * pa, pb * gi, pb * pb, xi * pb};
 #pragma unroll
-                for (int k = 0; k < 6; ++k) w6[k] = wave_sum_dpp(w6[k]);
-                ub = wave_min_dpp(ub);
+                for (int k = 0; k < 6; ++k) w6[k] = wave_sum(w6[k]);
+                ub = wave_min(ub);
                 if (lane == 0) {
 #pragma unroll
                     for (int k = 0; k < 6; ++k) redD[wave * 7 + k] = w6[k];
@@ -350,7 +350,7 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 a.g[tid] = gi;
                 ysq = y * y;
             }
-            ysq = wave_sum_dpp(ysq);
+            ysq = wave_sum(ysq);
             if (lane == 0) redU[wave] = ysq;
         }
         __syncthreads();
