@@ -346,8 +346,10 @@ double orc_fg(const orc_objective* o, const double* x, double* g, double* rowvec
 /* f(xt) - f(x) without cancellation.  row = residuals (least squares) or margins
  * (logistic) at x, as orc_fg produced them.  With dz = A (vt - v) computed from scratch:
  *   least squares:  0.5*(res+dz)^2 - 0.5*res^2 = dz*(res + 0.5*dz)
- *   logistic:       softplus(a+da) - softplus(a) = log1p(sigmoid(a)*expm1(da)),
- *                   a = -y*z, da = -y*dz
+ *   logistic:       softplus(a+da) - softplus(a) = log(1 + sigmoid(a)*expm1(da)),
+ *                   a = -y*z, da = -y*dz (evaluated as log1p(.) or, where sigmoid(a)*expm1(da) comes close
+ *                   to -1, as log(sigmoid(-a) + sigmoid(a)*exp(da)): no difference of nearly equal numbers
+ *                   in either regime)
  * plus the difference of the separable terms (lambda*sum x, mu/2*||x||^2). */
 double orc_delta_f(const orc_objective* o, const double* x, const double* xt, const double* row) {
     const int64_t rows = o->rows, cols = o->cols, n = orc_num_vars(o);
@@ -392,8 +394,15 @@ double orc_delta_f(const orc_objective* o, const double* x, const double* xt, co
         double dz = ns_val(&dacc);
         if (o->kind == ORC_LOGISTIC_L2) {
             double a = -o->b[r] * row[r], da = -o->b[r] * dz;
-            if (fabs(da) < 30.0) ns_add(&acc, log1p(sigmoid(a) * expm1(da)));
-            else ns_add(&acc, softplus(a + da) - softplus(a));
+            if (fabs(da) < 30.0) {
+                /* log(1 + sigmoid(a) (e^da - 1)): log1p of the product while that is not close to -1; otherwise
+                 * (a saturated margin that the step undoes: sigmoid(a) ~ 1, e^da ~ 0) the same number written as
+                 * log(sigmoid(-a) + sigmoid(a) e^da), a sum of two positive terms */
+                double u = sigmoid(a) * expm1(da);
+                ns_add(&acc, u > -0.5 ? log1p(u) : log(sigmoid(-a) + sigmoid(a) * exp(da)));
+            } else {
+                ns_add(&acc, softplus(a + da) - softplus(a));
+            }
         } else if (o->kind == ORC_QP) {
             /* 0.5 (v+dv)^T A (v+dv) - 0.5 v^T A v = dv^T (A v) + 0.5 dv^T (A dv) (A symmetric), plus b^T dx */
             ns_add_prod(&acc, dv[r], row[r] + 0.5 * dz);

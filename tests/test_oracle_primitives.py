@@ -239,6 +239,29 @@ def test_delta_f_equals_objective_difference(name, obj):
         assert oracle.delta_f(obj, x, xt, row) == pytest.approx(exact, rel=1e-6)
 
 
+def test_logistic_delta_f_where_the_margin_saturates():
+    """softplus(a + da) - softplus(a) for a single row with a large margin a and a step da that undoes most of it:
+    sigmoid(a) is 1 up to rounding and expm1(da) is nearly -1, so log1p(sigmoid(a) * expm1(da)) would take the
+    logarithm of a difference of two numbers that agree to nine digits.  Reference: 60-digit decimal arithmetic on
+    the definition log(1 + e^t)."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+
+    def softplus_exact(t):
+        return (Decimal(1) + Decimal(t).exp()).ln()
+
+    mu = 0.0
+    for a, da in [(20.0, -25.0), (25.0, -29.5), (12.0, -11.0), (30.0, -29.0), (18.0, -3.0), (-20.0, 25.0), (3.0, -2.0),
+                  (0.5, 1e-9), (40.0, -29.9), (35.0, -40.0)]:
+        # one row, one variable, label y = -1: the loss is softplus(-y * X w) = softplus(w) with X = [[1]]
+        obj = oracle.Objective(oracle.LOGISTIC_L2, np.array([[1.0]]), np.array([-1.0]), mu=mu)
+        x, xt = np.array([a]), np.array([a + da])
+        _, _, row = oracle.fg(obj, x, want_rowvec=True)
+        exact = float(softplus_exact(a + da) - softplus_exact(a))
+        got = oracle.delta_f(obj, x, xt, row)
+        assert got == pytest.approx(exact, rel=1e-13, abs=1e-300), (a, da)
+
+
 # ---- Algorithm 3 -----------------------------------------------------------------------------
 
 def _dense_reference(S, Y, ynorm2, g, mask, eps):
