@@ -217,7 +217,10 @@ int lbfgsb_solve_static(int64_t n, int m, const double* l, const double* u, cons
 int lbfgsb_get_info(lbfgsb_solver* s, lbfgsb_info* info_host);
 
 /* Device-to-device copies of the current iterate / gradient (n entries), enqueued on the
- * solver's stream. */
+ * solver's stream.  (Logistic objective on the fused pass: steps enqueued without an info struct use a short launch
+ * sequence that assumes the first trial step of the line search is accepted; when it is not, the iteration is
+ * finished, and the steps after it are redone, the next time the library looks at the device state.  These two calls
+ * do that first, which means they wait for the stream, whenever such steps have been enqueued since the last look.) */
 int lbfgsb_get_x(lbfgsb_solver* s, double* x_out);
 int lbfgsb_get_g(lbfgsb_solver* s, double* g_out);
 

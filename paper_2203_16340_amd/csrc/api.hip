@@ -60,6 +60,10 @@ struct lbfgsb_solver {
     bool owns_h_scal;
     int use_fused;
     int use_resident;        // small least squares: whole iterations in one resident workgroup
+    // logistic objective on the fused pass: steps still to be enqueued with the full launch sequence (after a
+    // rejected first trial step), and short-sequence steps enqueued since the host last looked at the scalar block
+    int logi_full_left;
+    int short_steps_unseen;
     int steps_since_refresh;
     long long steps_since_set_x;
     bool x_set;
@@ -192,12 +196,31 @@ Dims make_dims(int64_t n, int m, const lbfgsb_objective* o) {
     return dm;
 }
 
-// Reads the scalar block after applying any update the last step left pending.
+void enqueue_step(lbfgsb_solver* s);
+
+// Reads the scalar block after applying any update the last step left pending.  If the short logistic launch sequence
+// has parked the solver (first trial step rejected: kStatusBail), the iteration is finished here with the launches
+// that sequence leaves out, the steps that found the solver parked are enqueued again, and the block is read anew.
 hipError_t read_scal(lbfgsb_solver* s) {
-    launch_commit(s->dm, s->bf, s->stream);
-    hipError_t e = hipMemcpyAsync(s->h_scal, s->bf.scal, sizeof(Scal), hipMemcpyDeviceToHost, s->stream);
-    if (e != hipSuccess) return e;
-    return hipStreamSynchronize(s->stream);
+    for (;;) {
+        launch_commit(s->dm, s->bf, s->stream);
+        hipError_t e = hipMemcpyAsync(s->h_scal, s->bf.scal, sizeof(Scal), hipMemcpyDeviceToHost, s->stream);
+        if (e != hipSuccess) return e;
+        e = hipStreamSynchronize(s->stream);
+        if (e != hipSuccess) return e;
+        s->short_steps_unseen = 0;
+        if (s->h_scal->status != kStatusBail) return hipSuccess;
+        const int redo = s->h_scal->bail_skipped;
+        launch_clear_bail(s->bf, s->stream);
+        // the rest of the interrupted iteration: more step lengths, new margins and row weights, the transposed
+        // pass for the accepted step, the update
+        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, 2, s->stream);
+        launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
+        launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 2, s->stream, nullptr, nullptr);
+        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
+        s->logi_full_left = 8 + redo;   // a problem that backtracks once tends to do so again: full sequence for a while
+        for (int k = 0; k < redo; ++k) enqueue_step(s);
+    }
 }
 
 // Uploads a fresh scalar block (host template in h_scal) and waits for it.
@@ -337,17 +360,28 @@ void enqueue_step(lbfgsb_solver* s) {
         // among the timed launches: it reads A only in the iterations that backtrack.
         a.mode = kRowLogiSpec;
         { TimedSlot ts(s); launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
-        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, s->stream);
-        launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
-        launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 2, s->stream, nullptr, nullptr);
-        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, s->stream);
+        if (s->logi_full_left > 0) {
+            s->logi_full_left--;
+            launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, 3, s->stream);
+            launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
+            launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 2, s->stream, nullptr, nullptr);
+            launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
+        } else {
+            // Short sequence: the search on the margins tries the first step only, and the update of an accepted
+            // first step also moves the margins.  Three launches that almost never do work (eight more step
+            // lengths, new row weights, second transposed pass) are left out; should the first step be rejected,
+            // the solver parks itself and read_scal() supplies them.
+            launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, 1, s->stream);
+            launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, 1, s->stream);
+            s->short_steps_unseen++;
+        }
     } else {
         a.mode = kRowLogiDir;
         { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
-        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 0, s->stream);
+        launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 0, 3, s->stream);
         launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
         { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
-        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, s->stream);
+        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
     }
     s->steps_since_refresh++;
 }
@@ -384,6 +418,8 @@ int set_x_impl(lbfgsb_solver* s, const double* x0, bool trusted) {
     enqueue_eval(s, 0);
     s->steps_since_refresh = 0;
     s->steps_since_set_x = 0;
+    s->logi_full_left = 0;
+    s->short_steps_unseen = 0;
     if (!trusted) HIP_TRY(hipMemcpyAsync(hx.data(), s->bf.g, (size_t)n * 8, hipMemcpyDeviceToHost, s->stream));
     HIP_TRY(read_scal(s));
     HIP_TRY(hipGetLastError());
@@ -430,6 +466,8 @@ int setup_solver(lbfgsb_solver* s, int64_t n, int m, const lbfgsb_objective* obj
     s->owns_h_scal = false;
     s->steps_since_refresh = 0;
     s->steps_since_set_x = 0;
+    s->logi_full_left = 0;
+    s->short_steps_unseen = 0;
     s->x_set = false;
     s->timing = false;
     s->timed = 0;
@@ -741,12 +779,14 @@ int lbfgsb_get_info(lbfgsb_solver* s, lbfgsb_info* info) {
 
 int lbfgsb_get_x(lbfgsb_solver* s, double* x_out) {
     if (!s || !x_out) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    if (s->short_steps_unseen > 0) HIP_TRY(read_scal(s));   // a parked solver is brought up to date first (this waits)
     HIP_TRY(hipMemcpyAsync(x_out, s->bf.x, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
     return LBFGSB_OK;
 }
 
 int lbfgsb_get_g(lbfgsb_solver* s, double* g_out) {
     if (!s || !g_out) return fail(LBFGSB_E_INVALID_ARG, "NULL argument");
+    if (s->short_steps_unseen > 0) HIP_TRY(read_scal(s));
     HIP_TRY(hipMemcpyAsync(g_out, s->bf.g, (size_t)s->dm.n * 8, hipMemcpyDeviceToDevice, s->stream));
     return LBFGSB_OK;
 }

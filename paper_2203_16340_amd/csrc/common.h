@@ -58,7 +58,17 @@ struct Scal {
     unsigned counters[kCntCount];
     unsigned gram_cnt[kGramGroups + 1];   // two-level arrival of the large-n Gram kernel: one per group, then the top
     int since_refresh;      // resident solver: iterations since residual and gradient were last computed from x
+    // logistic objective, short launch sequence (see kStatusBail)
+    int bail_skipped;       // whole steps that found the status kStatusBail and did nothing
+    double ls_df;           // f(x + alpha p) - f(x) of the accepted first trial step
 };
+
+// Internal status of the short logistic launch sequence.  That sequence has no launches for the rare continuation of
+// the line search (more step lengths, a second transposed pass): when the first trial step is rejected, the search
+// kernel parks the solver in this state, every later kernel returns at once (as for any status other than RUNNING),
+// and the host finishes the iteration with the missing launches when it next looks at the scalar block.  Never
+// reported to the caller.
+constexpr int kStatusBail = 64;
 
 struct Dims {
     int64_t n, rows, cols, ld;
@@ -376,10 +386,15 @@ void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge,
 void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, const double* target, const double* weight,
                        int eval, hipStream_t st);
 // spec != 0: the A pass already holds X^T psi of the first trial step (recorded in Scal::spec_ok if that step is accepted)
+// stages: 1 = the first trial step only (short sequence: a rejected step parks the solver in kStatusBail),
+// 2 = the continuation only (eight more step lengths per sweep, then one at a time), 3 = both
 void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
-                        int spec, hipStream_t st);
+                        int spec, int stages, hipStream_t st);
 void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* labels, hipStream_t st);
-void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, hipStream_t st);
+// short != 0: the short sequence's update (accepted first trial step: margins z += alpha t here, f from Scal::ls_df)
+void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, int short_seq,
+                            hipStream_t st);
+void launch_clear_bail(const Buffers& bf, hipStream_t st);   // status kStatusBail -> RUNNING, bail_skipped -> 0
 
 // transport kinds (transport.hip).  M: cost matrix; beta/omega: targets and weights of the rows + cols marginal
 // terms (omega null = no such terms).  eval: z = x, residuals against beta -> Buffers::row; else z = the selected

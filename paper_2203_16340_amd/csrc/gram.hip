@@ -69,7 +69,12 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
     // update); readlanes hand the fields to every lane
     static_assert(offsetof(Scal, pend_ok) < 64, "header fields must sit in the first 16 ints");
     const int hdr = lane < 16 ? reinterpret_cast<const int*>(scal)[lane] : 0;
-    if (__shfl(hdr, offsetof(Scal, status) / 4) != LBFGSB_RUNNING) return;
+    if (__shfl(hdr, offsetof(Scal, status) / 4) != LBFGSB_RUNNING) {
+        // a step that finds the solver parked by the short logistic sequence is counted, so that the host can redo it
+        if (__shfl(hdr, offsetof(Scal, status) / 4) == kStatusBail && evaluate_stop && !dbg_inputs && blockIdx.x == 0 && tid == 0)
+            scal->bail_skipped += 1;
+        return;
+    }
     int head = __shfl(hdr, offsetof(Scal, head) / 4), c = __shfl(hdr, offsetof(Scal, count) / 4);
     if (__shfl(hdr, offsetof(Scal, pend_valid) / 4)) {          // same rule as effective_ring()
         if (__shfl(hdr, offsetof(Scal, pend_ok) / 4)) { head = (head + 1) % m; c = c < m ? c + 1 : m; }
@@ -381,7 +386,12 @@ __global__ __launch_bounds__(kBlock) void k_gram_mfma(int64_t n, int m, Opts op,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     static_assert(offsetof(Scal, pend_ok) < 64, "header fields must sit in the first 16 ints");
     const int hdr = lane < 16 ? reinterpret_cast<const int*>(scal)[lane] : 0;
-    if (__shfl(hdr, offsetof(Scal, status) / 4) != LBFGSB_RUNNING) return;
+    if (__shfl(hdr, offsetof(Scal, status) / 4) != LBFGSB_RUNNING) {
+        // a step that finds the solver parked by the short logistic sequence is counted, so that the host can redo it
+        if (__shfl(hdr, offsetof(Scal, status) / 4) == kStatusBail && evaluate_stop && !dbg_inputs && blockIdx.x == 0 && tid == 0)
+            scal->bail_skipped += 1;
+        return;
+    }
     int head = __shfl(hdr, offsetof(Scal, head) / 4), c = __shfl(hdr, offsetof(Scal, count) / 4);
     if (__shfl(hdr, offsetof(Scal, pend_valid) / 4)) {          // same rule as effective_ring()
         if (__shfl(hdr, offsetof(Scal, pend_ok) / 4)) { head = (head + 1) % m; c = c < m ? c + 1 : m; }
@@ -738,7 +748,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     static_assert(offsetof(Scal, pend_ok) < 64, "header fields must sit in the first 16 ints");
     const int hdr = lane < 16 ? reinterpret_cast<const int*>(scal)[lane] : 0;
-    if (__shfl(hdr, offsetof(Scal, status) / 4) != LBFGSB_RUNNING) return;
+    if (__shfl(hdr, offsetof(Scal, status) / 4) != LBFGSB_RUNNING) {
+        // a step that finds the solver parked by the short logistic sequence is counted, so that the host can redo it
+        if (__shfl(hdr, offsetof(Scal, status) / 4) == kStatusBail && evaluate_stop && !dbg_inputs && blockIdx.x == 0 && tid == 0)
+            scal->bail_skipped += 1;
+        return;
+    }
     int head = __shfl(hdr, offsetof(Scal, head) / 4), c = __shfl(hdr, offsetof(Scal, count) / 4);
     if (__shfl(hdr, offsetof(Scal, pend_valid) / 4)) {          // same rule as effective_ring()
         if (__shfl(hdr, offsetof(Scal, pend_ok) / 4)) { head = (head + 1) % m; c = c < m ? c + 1 : m; }

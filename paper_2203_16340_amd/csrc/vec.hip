@@ -26,6 +26,16 @@ void launch_set_status(const Buffers& bf, int status, hipStream_t st) {
     hipLaunchKernelGGL(k_set_status, dim3(1), dim3(64), 0, st, bf.scal, status);
 }
 
+__global__ void k_clear_bail(Scal* scal) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        if (scal->status == kStatusBail) scal->status = LBFGSB_RUNNING;
+        scal->bail_skipped = 0;
+    }
+}
+void launch_clear_bail(const Buffers& bf, hipStream_t st) {
+    hipLaunchKernelGGL(k_clear_bail, dim3(1), dim3(64), 0, st, bf.scal);
+}
+
 // ---- d = -B delta on the free set, then Algorithm 2 ------------------------------------------------------
 
 constexpr int kDirRed = 8 + 2 * kFoldMax;   // p1.g, p1.p1, x.p1, p2.g, p2.p2, x.p2, min step bound of p2, unused; then e_r.p1, e_r.p2 per folded extra row
@@ -532,16 +542,22 @@ void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, co
 //
 // With z = X w (kept in `row`) and t = X p:  f(x + a p) - f(x) = (1/N) sum_r [softplus(-y_r (z_r + a t_r))
 // - softplus(-y_r z_r)] + mu (a <x,p> + a^2/2 <p,p>).  The bracket is evaluated in the cancellation-free
-// form log1p(sigmoid(q) expm1(dq)), q = -y z, dq = -y a t.  Step lengths are evaluated NTRY at a time per sweep
+// form log(1 + sigmoid(q) expm1(dq)), q = -y z, dq = -y a t (softplus_diff).  Step lengths are evaluated NTRY at a time per sweep
 // over the rows: the first launch tries the first one alone (it is accepted in almost every quasi-Newton
 // iteration), a second launch, which returns at once when the first found the step, tries the next kLsBatch, and
 // if none of them is acceptable its last workgroup goes on alone, one length at a time.
 __device__ __forceinline__ double softplus_diff(double q, double sq, double dq) {
-    return fabs(dq) < 30.0 ? log1p(sq * expm1(dq)) : softplus_d(q + dq) - softplus_d(q);
+    if (fabs(dq) >= 30.0) return softplus_d(q + dq) - softplus_d(q);
+    // log(1 + sigmoid(q) (e^dq - 1)).  Where the product comes close to -1 (a saturated margin that the step undoes)
+    // log1p of it would itself take the logarithm of a difference of nearly equal numbers; there the same number is
+    // log(sigmoid(-q) + sigmoid(q) e^dq), a sum of two positive terms.
+    const double u = sq * expm1(dq);
+    if (u > -0.5) return log1p(u);
+    return log(sigmoid_d(-q) + sq * exp(dq));
 }
 
 template <int NTRY>
-__global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int first, int last_resort, int spec,
+__global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int first, int last_resort, int spec, int short_seq,
                                                         const double* __restrict__ yl, const double* __restrict__ z,
                                                         const double* __restrict__ t, Scal* __restrict__ scal,
                                                         double* __restrict__ lspart) {
@@ -596,11 +612,11 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int fi
     }
     block_sum<NTRY, kWaves>(tot, red);
     int found = -1;
-    double a_acc = 0.0;
+    double a_acc = 0.0, df_acc = 0.0;
 #pragma unroll
     for (int j = 0; j < NTRY; ++j) {
         const double df = tot[j] * invn + dm.mu * al[j] * (xp + 0.5 * al[j] * pp);
-        if (found < 0 && first + j <= op.max_backtracks && isfinite(df) && df <= op.c1 * al[j] * gp) { found = first + j; a_acc = al[j]; }
+        if (found < 0 && first + j <= op.max_backtracks && isfinite(df) && df <= op.c1 * al[j] * gp) { found = first + j; a_acc = al[j]; df_acc = df; }
     }
     // rare: continue one step length at a time (uniform control flow: every thread holds the same totals)
     double a = al[NTRY - 1];
@@ -618,6 +634,11 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int fi
     if (tid == 0) {
         scal->ls_ok = found >= 0;
         if (first == 0) scal->spec_ok = spec && found == 0;
+        if (short_seq) {
+            // the short sequence has nothing behind this launch but the update of an accepted first step
+            if (found == 0) scal->ls_df = df_acc;
+            else scal->status = kStatusBail;
+        }
         if (found >= 0 || last_resort) {
             scal->backtracks = found >= 0 ? found : op.max_backtracks + 1;
             scal->fevals += found >= 0 ? found + 1 : op.max_backtracks + 1;
@@ -627,11 +648,13 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int fi
 }
 
 void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
-                        int spec, hipStream_t st) {
-    hipLaunchKernelGGL(k_ls_logistic<1>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 0, 0, spec, labels,
-                       (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
-    hipLaunchKernelGGL(k_ls_logistic<kLsBatch>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 1, 1, spec, labels,
-                       (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
+                        int spec, int stages, hipStream_t st) {
+    if (stages & 1)
+        hipLaunchKernelGGL(k_ls_logistic<1>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 0, 0, spec, stages == 1 ? 1 : 0,
+                           labels, (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
+    if (stages & 2)
+        hipLaunchKernelGGL(k_ls_logistic<kLsBatch>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 1, 1, spec, 0, labels,
+                           (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
 }
 
 // z += alpha t; psi = -y sigma(-y z)/N; loss partials of the new point (from the new margins).
@@ -663,7 +686,8 @@ void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf,
 
 // x+ = P(x + alpha p), g+ = X^T psi + mu x+, pair (x+ - x, g+ - g), f+ from the new margins.
 __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts_two_pass, int w_parts_spec, int loss_parts,
-                                                            const double* __restrict__ wpart,
+                                                            int short_seq, const double* __restrict__ t,
+                                                            double* __restrict__ z, const double* __restrict__ wpart,
                                                             const double* __restrict__ losspart,
                                                             const double* __restrict__ p1, const double* __restrict__ p2,
                                                             const double* __restrict__ l, const double* __restrict__ u,
@@ -681,6 +705,12 @@ __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts
     const double* p = scal->branch == 1 ? p1 : p2;
     const int w_parts = scal->spec_ok ? w_parts_spec : w_parts_two_pass;   // which kernel wrote the partial columns
     double sums[2] = {0.0, 0.0};   // ||y||^2, ||x+||^2
+    if (ok && short_seq) {
+        // the margins of the new point (the full sequence has a kernel for this, which also recomputes the row weights:
+        // here the single-read pass already holds X^T psi of this step)
+        for (int64_t r = (int64_t)blockIdx.x * kBlock + tid; r < dm.rows; r += (int64_t)gridDim.x * kBlock)
+            z[r] = fma(alpha, t[r], z[r]);
+    }
     if (ok) {
         double* Sn = S + (int64_t)slot * dm.n;
         double* Yn = Y + (int64_t)slot * dm.n;
@@ -707,10 +737,11 @@ __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts
     double tot[2] = {0.0, 0.0};
     for (int b = tid; b < (int)gridDim.x; b += kBlock) { tot[0] += redpart[2 * b]; tot[1] += redpart[2 * b + 1]; }
     block_sum<2, kWaves>(tot, red);
-    const double loss = ok ? sum_all(losspart, loss_parts, red) : 0.0;
+    const double loss = (ok && !short_seq) ? sum_all(losspart, loss_parts, red) : 0.0;
     if (tid == 0) {
         if (ok) {
-            scal->f = loss + 0.5 * dm.mu * tot[1];
+            // full sequence: f from the new margins and the new iterate; short one: the line search's difference
+            scal->f = short_seq ? scal->f + scal->ls_df : loss + 0.5 * dm.mu * tot[1];
             scal->ynorm2[slot] = tot[0];
             scal->head = (slot + 1) % dm.m;
             scal->count = scal->count < dm.m ? scal->count + 1 : dm.m;
@@ -724,9 +755,10 @@ __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts
     }
 }
 
-void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, hipStream_t st) {
+void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, int short_seq,
+                            hipStream_t st) {
     hipLaunchKernelGGL(k_update_logistic, dim3(ge.upd_blocks), dim3(kBlock), 0, st, dm, ge.gemvt_row_blocks,
-                       ge.fused_blocks, loss_parts, bf.wpart,
+                       ge.fused_blocks, loss_parts, short_seq, (const double*)bf.t, bf.row, bf.wpart,
                        bf.losspart, bf.p1, bf.p2, bf.l, bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, bf.redpart);
 }
 
