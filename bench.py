@@ -42,8 +42,11 @@ AL_WORKLOADS = {
     "JP2G": "augmented Lagrangian: joint probability, data set 2 (uniform random marginals and costs), 2000x1000 fp64 (2*10^6 variables, 3000 constraints), Gaussian regulariser, m=10",
     "JP1E": "augmented Lagrangian: joint probability, data set 1, 1000x1000 fp64, entropy regulariser, m=10",
     "JP2E": "augmented Lagrangian: joint probability, data set 2, 2000x1000 fp64, entropy regulariser, m=10",
+    # the same problem as JP1G with 20 stored pairs: 41 vectors of 10^6 entries in the Gram matrix (matrix-core kernel)
+    "JP1G20": "augmented Lagrangian: joint probability, data set 1, 1000x1000 fp64, Gaussian regulariser, m=20",
 }
-TRANSPORT = {"JP1G": (1, "gauss"), "JP2G": (2, "gauss"), "JP1E": (1, "entropy"), "JP2E": (2, "entropy")}
+TRANSPORT = {"JP1G": (1, "gauss", 10), "JP2G": (2, "gauss", 10), "JP1E": (1, "entropy", 10), "JP2E": (2, "entropy", 10),
+             "JP1G20": (1, "gauss", 20)}
 
 WORKLOADS = {
     "C1": "NNLS 200x100 fp64, m=5",
@@ -183,10 +186,10 @@ def bench_transport(args, L, workloads, np, torch, dev) -> int:
     """Whole runs of Algorithm 4 on the joint-probability problem (matrix variable, marginal constraints): a "step"
     is one iteration of the box solver inside it.  There is no matrix-vector product: the iteration streams the
     L-BFGS pair memory, and the dominant kernel is the Gram kernel of the batched two-loop recursion."""
-    dataset, reg = TRANSPORT[args.config]
+    dataset, reg, m_pairs = TRANSPORT[args.config]
     size = max(8, int(round(1000 * args.scale)))
     t_gen = time.perf_counter()
-    p = workloads.joint_probability(size, dataset=dataset, reg=reg, seed=4001)
+    p = workloads.joint_probability(size, dataset=dataset, reg=reg, seed=4001, m=m_pairs)
     t_gen = time.perf_counter() - t_gen
     # Stopping rule.  Gaussian regulariser: ||grad L [S]|| <= 1e-6 max(1, its value at the inner solve's start), marginals
     # to 1e-6.  Entropy: 1e-4 for both, the accuracy the paper reports for this experiment (absolute errors of 1e-3 ..

@@ -276,17 +276,25 @@ class Solver:
         _check(lib().lbfgsb_get_info(self._h, C.byref(info)))
         return info
 
-    def x(self):
+    def _copy_out(self, getter, numel: int):
+        """A new tensor filled by a library copy that runs on the SOLVER's stream (the one current when it was
+        created).  The tensor is allocated under that stream, and a caller on another stream is made to wait for
+        the copy, so the result is safe to use wherever this returns."""
         import torch
-        out = torch.empty(self.n, dtype=torch.float64, device=self.device)
-        _check(lib().lbfgsb_get_x(self._h, out.data_ptr()))
+        with torch.cuda.stream(self._stream):
+            out = torch.empty(numel, dtype=torch.float64, device=self.device)
+            _check(getter(self._h, out.data_ptr()))
+        cur = torch.cuda.current_stream(self.device)
+        if cur != self._stream:
+            cur.wait_stream(self._stream)
+            out.record_stream(cur)
         return out
 
+    def x(self):
+        return self._copy_out(lib().lbfgsb_get_x, self.n)
+
     def g(self):
-        import torch
-        out = torch.empty(self.n, dtype=torch.float64, device=self.device)
-        _check(lib().lbfgsb_get_g(self._h, out.data_ptr()))
-        return out
+        return self._copy_out(lib().lbfgsb_get_g, self.n)
 
     # -- timing of the A pass
     def enable_apass_timing(self, mode: int = 2) -> None:
@@ -397,16 +405,10 @@ class Auglag:
         return info
 
     def x(self):
-        import torch
-        out = torch.empty(self.n, dtype=torch.float64, device=self.device)
-        _check(lib().lbfgsb_auglag_get_x(self._h, out.data_ptr()))
-        return out
+        return Solver._copy_out(self, lib().lbfgsb_auglag_get_x, self.n)
 
     def lam(self):
-        import torch
-        out = torch.empty(max(self.n_eq, 1), dtype=torch.float64, device=self.device)
-        _check(lib().lbfgsb_auglag_get_lambda(self._h, out.data_ptr()))
-        return out[:self.n_eq]
+        return Solver._copy_out(self, lib().lbfgsb_auglag_get_lambda, max(self.n_eq, 1))[:self.n_eq]
 
     def inner_apass_timing(self, mode: Optional[int] = None):
         """mode given: lbfgsb_enable_apass_timing on the inner solver; else its (launches, ms, bytes per launch)"""
