@@ -64,6 +64,7 @@ struct lbfgsb_solver {
     // rejected first trial step), and short-sequence steps enqueued since the host last looked at the scalar block
     int logi_full_left;
     int short_steps_unseen;
+    bool commit_needed;      // resident solver: a kernel of the multi-kernel path may have left an update pending
     int steps_since_refresh;
     long long steps_since_set_x;
     bool x_set;
@@ -203,7 +204,9 @@ void enqueue_step(lbfgsb_solver* s);
 // that sequence leaves out, the steps that found the solver parked are enqueued again, and the block is read anew.
 hipError_t read_scal(lbfgsb_solver* s) {
     for (;;) {
-        launch_commit(s->dm, s->bf, s->stream);
+        // (the resident solver applies its updates itself; only its evaluations by the multi-kernel path leave one pending)
+        if (!s->use_resident || s->commit_needed) launch_commit(s->dm, s->bf, s->stream);
+        s->commit_needed = false;
         hipError_t e = hipMemcpyAsync(s->h_scal, s->bf.scal, sizeof(Scal), hipMemcpyDeviceToHost, s->stream);
         if (e != hipSuccess) return e;
         e = hipStreamSynchronize(s->stream);
@@ -468,6 +471,7 @@ int setup_solver(lbfgsb_solver* s, int64_t n, int m, const lbfgsb_objective* obj
     s->steps_since_set_x = 0;
     s->logi_full_left = 0;
     s->short_steps_unseen = 0;
+    s->commit_needed = true;
     s->x_set = false;
     s->timing = false;
     s->timed = 0;

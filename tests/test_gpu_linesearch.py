@@ -118,6 +118,30 @@ def test_the_logistic_cases_cover_every_stage_of_the_search():
     assert seen == {"first", "batch", "continuation"}
 
 
+@pytest.mark.parametrize("case", [0, 1, 4])
+def test_steps_enqueued_without_waiting_survive_rejected_first_steps(case):
+    """lbfgsb_step(info = NULL) uses the short launch sequence of the logistic objective, which has no launches for a
+    rejected first trial step: the solver parks itself, later steps return at once, and the library finishes the
+    iteration and redoes the skipped steps when it next looks at the device state (here: in x()).  Sixteen such calls
+    must leave exactly the state sixteen synchronous calls leave, on problems that backtrack in the first iteration
+    (case 0: fourteen halvings) and several times later."""
+    prob = _logistic(LOGISTIC_CASES[case], np.float64)
+    a = L.solver_for_problem(prob, DEV, tol=0.0, a_pass=L.APASS_FUSED)
+    b = L.solver_for_problem(prob, DEV, tol=0.0, a_pass=L.APASS_FUSED)
+    for _ in range(16):
+        a.step(want_info=False)
+        b.step()
+    xa, xb = a.x(), b.x()                       # (x() brings a parked solver up to date first)
+    ia, ib = a.info(), b.info()
+    assert ia.iters == ib.iters == 16 and ia.status == ib.status == L.RUNNING
+    assert torch.equal(xa, xb) and torch.equal(a.g(), b.g())
+    assert ia.f == ib.f and ia.fevals == ib.fevals
+    # and lbfgsb_solve from here on agrees too
+    a2, b2 = a.solve(), b.solve()
+    assert (a2.status, a2.iters) == (b2.status, b2.iters) and torch.equal(a.x(), b.x())
+    a.close(); b.close()
+
+
 # ---- exhausted searches ---------------------------------------------------------------------------------------------
 
 def _hand_solver(a_diag, b, max_backtracks, a_pass):
