@@ -132,12 +132,13 @@ def bench_svm(args, L, workloads, np, torch, dev) -> int:
     al = L.AuglagRows(L.OBJ_QP, K_d, lin, y_d[None, :].contiguous(), torch.zeros(1, dtype=torch.float64, device=dev), zero,
                       upper, sp.m, sign=y_d, options=L.default_options(tol=tol, max_iter=5000), ctol=ctol, max_outer=200)
     al.solve(zero)                                          # untimed
-    al.inner_apass_timing(2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    info = al.solve(zero)
+    info = al.solve(zero)                                     # timed without events (they cost a few us per iteration)
     torch.cuda.synchronize()
     t_run = time.perf_counter() - t0
+    al.inner_apass_timing(2)                                # the same run once more, with HIP events on the dominant kernel
+    al.solve(zero)
     al.inner_apass_timing(0)
     n_launch, apass_ms, bytes_per_launch = al.inner_apass_timing()
     a = al.x().cpu().numpy()
@@ -204,12 +205,13 @@ def bench_transport(args, L, workloads, np, torch, dev) -> int:
     al = L.AuglagMarginals(p.kind, M_d, marg, l_d, u_d, p.m, lam=p.lam,
                            options=L.default_options(tol=tol, tol_relative=1, max_iter=5000, eps=eps), ctol=ctol, max_outer=100)
     al.solve(x0)                                            # untimed
-    al.inner_apass_timing(2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    info = al.solve(x0)
+    info = al.solve(x0)                                     # timed without events (they cost a few us per iteration)
     torch.cuda.synchronize()
     t_run = time.perf_counter() - t0
+    al.inner_apass_timing(2)                                # the same run once more, with HIP events on the dominant kernel
+    al.solve(x0)
     al.inner_apass_timing(0)
     n_launch, gram_ms, bytes_per_launch = al.inner_apass_timing()
     P = al.x().cpu().numpy().reshape(p.rows, p.cols)
@@ -280,12 +282,13 @@ def bench_auglag(args, L, workloads, np, torch, dev, a_pass) -> int:
     l_d, u_d, x0 = torch.from_numpy(l_s).to(dev), torch.from_numpy(u_s).to(dev), torch.from_numpy(x0_s).to(dev)
     al = L.Auglag(A_d, b_d, n_eq, l_d, u_d, cp.m, options=L.default_options(tol=tol, a_pass=a_pass), ctol=ctol)
     al.solve(x0)                                            # untimed
-    al.inner_apass_timing(2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    info = al.solve(x0)
+    info = al.solve(x0)                                     # timed without events (they cost a few us per iteration)
     torch.cuda.synchronize()
     t_run = time.perf_counter() - t0
+    al.inner_apass_timing(2)                                # the same run once more, with HIP events on the dominant kernel
+    al.solve(x0)
     al.inner_apass_timing(0)
     n_launch, apass_ms, bytes_per_launch = al.inner_apass_timing()
     x = al.x().cpu().numpy()
