@@ -2,7 +2,7 @@
 columns, sizes around the tile and wave widths), memory m, storage type, A-pass organisation and the kind of box
 (none, one-sided, two-sided, mixed with infinities, coinciding bounds) all vary together.  What the method fixes is
 compared: feasibility, that the reported f is the objective at the returned point (recomputed with numpy), and the
-final objective value when both sides converged (1e-6 relative for fp64-stored matrices at the relative
+final objective value (both sides must converge; 1e-8 relative for fp64-stored matrices at the relative
 stopping tolerance 1e-7 used here, 1e-4 for fp32-stored ones).  A second test draws strictly convex quadratic forms,
 with and without equality rows (Algorithm 4), where the minimiser is unique and is compared itself."""
 import math
@@ -52,15 +52,24 @@ def draw(pool, case):
     return prob, a_pass
 
 
+# Two draws zigzag for thousands of iterations (many bounds become active one at a time; with m = 1 the method is close
+# to projected steepest descent): the oracle needs over a minute (case 112: 4057 iterations) or does not converge within
+# 20000 iterations (case 103).  They keep a limit of 1500 iterations and a weaker comparison, stated below.
+SLOW = {("larger", 103), ("larger", 112)}
+
+
 @pytest.mark.parametrize("pool,case", [("small", c) for c in range(60)] + [("larger", c) for c in range(100, 116)])
 def test_random_problem_matches_the_oracle(pool, case):
     prob, a_pass = draw(SMALL if pool == "small" else LARGER, case)
+    slow = (pool, case) in SLOW
+    prob.max_iter = 1500 if slow else 5000
     try:
         s = L.solver_for_problem(prob, DEV, a_pass=a_pass)
     except L.LbfgsbError as e:
         if e.code != L.E_UNSUPPORTED:
             raise
         s = L.solver_for_problem(prob, DEV, a_pass=L.APASS_AUTO)   # the fused pass does not take this shape
+    f0 = s.info().f
     info = s.solve()
     x = s.x().cpu().numpy()
     s.close()
@@ -68,17 +77,20 @@ def test_random_problem_matches_the_oracle(pool, case):
     assert np.all(x >= prob.l) and np.all(x <= prob.u)
     f_host = host_objective(prob, x)
     assert abs(info.f - f_host) <= 1e-8 * abs(f_host) + 1e-14
-    tol = 1e-6 if prob.A.dtype == np.float64 else 1e-4
-    slack = tol * max(abs(ref.info.f), 1e-12) + 1e-12
-    if info.status != L.CONVERGED or ref.info.status != oracle.CONVERGED:
-        # the iteration limit (the method zigzags when many bounds become active one at a time, and the two sides
-        # do not follow the same trajectory): a side that converged is not above the one that did not
+    # the benchmark spec's bound on the final objective: 1e-8 relative for fp64-stored matrices, 1e-4 for fp32-stored ones
+    # (an objective that can be driven to zero -- more columns than rows -- is compared on the scale of its start value)
+    tol = 1e-8 if prob.A.dtype == np.float64 else 1e-4
+    slack = tol * max(abs(ref.info.f), 1e-10 * abs(f0))
+    if slow:
+        # both sides feasible, neither far from the other, and a side that converged is not above the one that did not
         assert info.status in (L.CONVERGED, L.MAX_ITER) and ref.info.status in (oracle.CONVERGED, oracle.MAX_ITER)
+        assert abs(info.f - ref.info.f) <= 1e-2 * abs(ref.info.f)
         if info.status == L.CONVERGED:
-            assert info.f <= ref.info.f + slack
+            assert info.f <= ref.info.f + 1e-6 * abs(ref.info.f)
         if ref.info.status == oracle.CONVERGED:
-            assert ref.info.f <= info.f + slack
+            assert ref.info.f <= info.f + 1e-6 * abs(ref.info.f)
         return
+    assert info.status == L.CONVERGED and ref.info.status == oracle.CONVERGED, (info.as_dict(), ref.info.status)
     assert abs(info.f - ref.info.f) <= slack, (info.f, ref.info.f)
     g = host_gradient(prob, x)
     mask = oracle.free_mask(x, g, prob.l, prob.u, 1e-10).astype(bool)
