@@ -213,6 +213,25 @@ int lbfgsb_solve(lbfgsb_solver* s, lbfgsb_info* info_host);
 int lbfgsb_solve_static(int64_t n, int m, const double* l, const double* u, const lbfgsb_objective* obj_host,
                         const lbfgsb_options* opt_host, double* x, lbfgsb_info* info_host, void* hip_stream);
 
+/* Per-iteration record, kept on the device in a ring of LBFGSB_HISTORY_CAPACITY entries (the solver's workspace holds
+ * it; nothing is read back while iterating).  One record per ACCEPTED iteration of Algorithm 1. */
+#define LBFGSB_HISTORY_CAPACITY 256
+typedef struct {          /* HOST struct (the device keeps the same layout) */
+    int64_t iter;         /* 1-based index of the iteration */
+    double f;             /* objective after it */
+    double pg2, pginf;    /* ||grad f[S]||_2 and ||x - P(x - grad f)||_inf at the iterate it started from */
+    int64_t n_fixed;      /* variables outside the free set there */
+    double alpha, alpha_ub, gp;   /* accepted step length, its bound, <grad f, p> */
+    int branch;           /* Algorithm 2: 1 = projected direction, 2 = masked quasi-Newton direction */
+    int backtracks;       /* rejected trial steps */
+    int pairs_used;       /* pairs that passed the curvature gate of Algorithm 3 */
+    int memory_resets;    /* resets of the pair memory so far */
+} lbfgsb_iter_record;
+/* Synchronises and copies the most recent records, oldest first, into records_host (room for `capacity` entries);
+ * *count_host receives how many were written (at most min(capacity, LBFGSB_HISTORY_CAPACITY, iterations since
+ * lbfgsb_set_x)).  lbfgsb_set_x clears the ring. */
+int lbfgsb_get_history(lbfgsb_solver* s, lbfgsb_iter_record* records_host, int capacity, int* count_host);
+
 /* Synchronises and reports the current state. */
 int lbfgsb_get_info(lbfgsb_solver* s, lbfgsb_info* info_host);
 

@@ -22,7 +22,7 @@ MAX_M = 31
 
 EXPORTS = [
     "lbfgsb_last_error", "lbfgsb_default_options", "lbfgsb_workspace_bytes", "lbfgsb_create", "lbfgsb_set_x",
-    "lbfgsb_step", "lbfgsb_solve", "lbfgsb_solve_static", "lbfgsb_get_info", "lbfgsb_get_x", "lbfgsb_get_g", "lbfgsb_destroy",
+    "lbfgsb_step", "lbfgsb_solve", "lbfgsb_solve_static", "lbfgsb_get_history", "lbfgsb_get_info", "lbfgsb_get_x", "lbfgsb_get_g", "lbfgsb_destroy",
     "lbfgsb_enable_apass_timing", "lbfgsb_apass_timing", "lbfgsb_apass_name", "lbfgsb_dbg_fg",
     "lbfgsb_dbg_free_mask", "lbfgsb_dbg_two_loop", "lbfgsb_dbg_project_direction",
     "lbfgsb_auglag_default_options", "lbfgsb_auglag_workspace_bytes", "lbfgsb_auglag_create", "lbfgsb_auglag_solve",
@@ -68,6 +68,18 @@ class Info(C.Structure):
         return {name: getattr(self, name) for name, _ in self._fields_}
 
 
+HISTORY_CAPACITY = 256
+
+
+class IterRecord(C.Structure):
+    _fields_ = [("iter", C.c_int64), ("f", C.c_double), ("pg2", C.c_double), ("pginf", C.c_double),
+                ("n_fixed", C.c_int64), ("alpha", C.c_double), ("alpha_ub", C.c_double), ("gp", C.c_double),
+                ("branch", C.c_int), ("backtracks", C.c_int), ("pairs_used", C.c_int), ("memory_resets", C.c_int)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
 class LbfgsbError(RuntimeError):
     def __init__(self, code: int, message: str):
         super().__init__(f"liblbfgsb error {code}: {message}")
@@ -106,6 +118,8 @@ def lib():
                                           C.POINTER(Info), vp]
         L.lbfgsb_get_info.restype = C.c_int
         L.lbfgsb_get_info.argtypes = [vp, C.POINTER(Info)]
+        L.lbfgsb_get_history.restype = C.c_int
+        L.lbfgsb_get_history.argtypes = [vp, C.POINTER(IterRecord), C.c_int, C.POINTER(C.c_int)]
         L.lbfgsb_get_x.restype = C.c_int
         L.lbfgsb_get_x.argtypes = [vp, vp]
         L.lbfgsb_get_g.restype = C.c_int
@@ -275,6 +289,13 @@ class Solver:
         info = Info()
         _check(lib().lbfgsb_get_info(self._h, C.byref(info)))
         return info
+
+    def history(self, capacity: int = HISTORY_CAPACITY):
+        """The most recent per-iteration records (oldest first), as a list of IterRecord."""
+        buf = (IterRecord * max(1, capacity))()
+        cnt = C.c_int(0)
+        _check(lib().lbfgsb_get_history(self._h, buf, int(capacity), C.byref(cnt)))
+        return [buf[k] for k in range(cnt.value)]
 
     def _copy_out(self, getter, numel: int):
         """A new tensor filled by a library copy that runs on the SOLVER's stream (the one current when it was

@@ -153,7 +153,7 @@ Geometry make_geometry(const Dims& dm, const void* A) {
 }
 
 struct Layout {
-    size_t scal, x, g, l, u, d, p1, p2, mask, S, Y, row, t, psi, wpart, losspart, grampart, redpart, lspart, wextra, xres, total;
+    size_t scal, x, g, l, u, d, p1, p2, mask, S, Y, row, t, psi, wpart, losspart, grampart, redpart, lspart, wextra, xres, hist, total;
 };
 
 Layout make_layout(const Dims& dm, const Geometry& ge) {
@@ -185,6 +185,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     L.lspart = take((size_t)ge.ls_blocks * 64 * 8);   // up to 64 step lengths per sweep (entropy line search: 51)
     L.wextra = take(dm.n_extra > 0 ? (size_t)dm.n * 8 : 8);
     L.xres = take((size_t)(dm.n_extra + 1) * 8);
+    L.hist = take((size_t)LBFGSB_HISTORY_CAPACITY * sizeof(lbfgsb_iter_record));
     L.total = off;
     return L;
 }
@@ -393,6 +394,7 @@ void fresh_scal(lbfgsb_solver* s) {
     std::memset(s->h_scal, 0, sizeof(Scal));
     s->h_scal->status = LBFGSB_RUNNING;
     s->h_scal->alpha_ub = 1.0;
+    s->h_scal->hist = s->bf.hist;
 }
 
 // trusted: x0 is the solver's own iterate (feasible by construction): only f is checked for finiteness and
@@ -512,6 +514,7 @@ int setup_solver(lbfgsb_solver* s, int64_t n, int m, const lbfgsb_objective* obj
     b.wpart = (double*)(w + L.wpart); b.losspart = (double*)(w + L.losspart);
     b.grampart = (double*)(w + L.grampart); b.redpart = (double*)(w + L.redpart); b.lspart = (double*)(w + L.lspart);
     b.wextra = (double*)(w + L.wextra); b.xres = (double*)(w + L.xres);
+    b.hist = (lbfgsb_iter_record*)(w + L.hist);
     return LBFGSB_OK;
 }
 
@@ -771,6 +774,23 @@ int lbfgsb_solve_static(int64_t n, int m, const double* l, const double* u, cons
     HIP_TRY(hipMemcpyAsync(x, s->bf.x, (size_t)n * 8, hipMemcpyDeviceToDevice, s->stream));
     HIP_TRY(hipStreamSynchronize(s->stream));
     s->x_set = false;
+    return LBFGSB_OK;
+}
+
+int lbfgsb_get_history(lbfgsb_solver* s, lbfgsb_iter_record* records, int capacity, int* count) {
+    if (!s || !records || !count || capacity < 0) return fail(LBFGSB_E_INVALID_ARG, "NULL argument or negative capacity");
+    *count = 0;
+    HIP_TRY(read_scal(s));
+    const long long written = s->h_scal->hist_count;
+    long long have = written < LBFGSB_HISTORY_CAPACITY ? written : LBFGSB_HISTORY_CAPACITY;
+    if (have > capacity) have = capacity;
+    // the `have` most recent records, oldest first: ring positions (written - have) .. (written - 1)
+    for (long long k = 0; k < have; ++k) {
+        const long long pos = (written - have + k) % LBFGSB_HISTORY_CAPACITY;
+        HIP_TRY(hipMemcpyAsync(records + k, s->bf.hist + pos, sizeof(lbfgsb_iter_record), hipMemcpyDeviceToHost, s->stream));
+    }
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    *count = (int)have;
     return LBFGSB_OK;
 }
 

@@ -61,6 +61,9 @@ struct Scal {
     // logistic objective, short launch sequence (see kStatusBail)
     int bail_skipped;       // whole steps that found the status kStatusBail and did nothing
     double ls_df;           // f(x + alpha p) - f(x) of the accepted first trial step
+    // per-iteration records (ring in the workspace; null: none kept)
+    lbfgsb_iter_record* hist;
+    long long hist_count;   // records written since lbfgsb_set_x
 };
 
 // Internal status of the short logistic launch sequence.  That sequence has no launches for the rare continuation of
@@ -208,6 +211,18 @@ __device__ __forceinline__ void effective_ring(const Scal* s, int m, int& head, 
     }
 }
 
+// One record per accepted iteration, written by the thread that has just completed the iteration's bookkeeping:
+// the scalar block then holds the stopping quantities of the iterate the iteration started from (the next free-set
+// pass has not run yet), the direction's branch and bound, and the accepted step.
+__device__ __forceinline__ void record_iteration(Scal* s) {
+    if (!s->hist) return;
+    lbfgsb_iter_record* r = s->hist + (s->hist_count % LBFGSB_HISTORY_CAPACITY);
+    r->iter = s->iters; r->f = s->f; r->pg2 = s->pg2; r->pginf = s->pginf; r->n_fixed = s->n_fixed;
+    r->alpha = s->alpha; r->alpha_ub = s->alpha_ub; r->gp = s->gp;
+    r->branch = s->branch; r->backtracks = s->backtracks; r->pairs_used = s->pairs_used; r->memory_resets = s->memory_resets;
+    s->hist_count += 1;
+}
+
 // Applies the pending update: accepted step (pair stored at slot `head`), or an exhausted line search
 // (clear the pair memory and retry once from the steepest-descent direction, else stop).
 __device__ __forceinline__ void apply_pending(Scal* s, int m) {
@@ -222,6 +237,7 @@ __device__ __forceinline__ void apply_pending(Scal* s, int m) {
         s->head = (s->head + 1) % m;
         s->count = s->count < m ? s->count + 1 : m;
         s->iters += 1;
+        record_iteration(s);
     } else if (s->count > 0) {
         s->count = 0;
         s->memory_resets += 1;
@@ -327,6 +343,7 @@ struct Buffers {
     double *lspart;         // ls_blocks x (step lengths per sweep, at most 64)
     double *wextra;         // n: contribution of the extra rows to the columns of the gradient (or of its change)
     double *xres;           // n_extra residuals e_r.x - target_r of the last evaluation, then [n_extra] the loss term
+    lbfgsb_iter_record* hist;   // LBFGSB_HISTORY_CAPACITY per-iteration records
 };
 
 // ---- launchers (defined in apass.hip / vec.hip) -------------------------------------------------------

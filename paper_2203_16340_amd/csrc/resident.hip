@@ -371,6 +371,7 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 sc.count = c < m ? c + 1 : m;
                 sc.iters += 1;
                 sc.since_refresh = since + 1;
+                record_iteration(&sc);
             } else if (c > 0) {
                 sc.count = 0;
                 sc.memory_resets += 1;

@@ -351,6 +351,7 @@ __global__ __launch_bounds__(kBlock) void k_ot_update_entropy(Dims dm, Opts op, 
             scal->head = (slot + 1) % dm.m;
             scal->count = scal->count < dm.m ? scal->count + 1 : dm.m;
             scal->iters += 1;
+            record_iteration(scal);
         } else if (scal->count > 0) {
             scal->count = 0;
             scal->memory_resets += 1;

@@ -112,6 +112,49 @@ def test_first_iterations_match_step_by_step(name, scale, a_pass):
     orc.close(); s.close()
 
 
+@pytest.mark.parametrize("name,scale,a_pass", [("C1", 1.0, L.APASS_AUTO), ("C2", 0.05, L.APASS_FUSED), ("C2", 0.05, L.APASS_TWO_PASS),
+                                               ("C3", 0.03, L.APASS_AUTO), ("C4", 0.01, L.APASS_FUSED), ("C4", 0.01, L.APASS_TWO_PASS)])
+def test_history_ring_holds_what_each_step_reported(name, scale, a_pass):
+    """The per-iteration records kept on the device while steps are enqueued without waiting equal what synchronous
+    steps report one by one (and, for the first iterations, what the oracle did)."""
+    prob = workloads.config(name, scale=scale)
+    a = _gpu_solver(prob, a_pass, tol=0.0)
+    b = _gpu_solver(prob, a_pass, tol=0.0)
+    infos = [a.step() for _ in range(12)]
+    for _ in range(12):
+        b.step(want_info=False)
+    hist = b.history()
+    assert [r.iter for r in hist] == list(range(1, 13))
+    for r, i in zip(hist, infos):
+        assert (r.f, r.alpha, r.alpha_ub, r.gp, r.pg2, r.pginf) == (i.f, i.alpha, i.alpha_ub, i.gp, i.pg2, i.pginf)
+        assert (r.branch, r.backtracks, r.pairs_used, r.n_fixed, r.memory_resets) == \
+            (i.branch, i.backtracks, i.pairs_used, i.n_fixed, i.memory_resets)
+    assert len(b.history(capacity=5)) == 5 and b.history(capacity=5)[-1].iter == 12 and b.history(capacity=5)[0].iter == 8
+    orc = oracle.Solver(oracle.Objective(prob.kind, prob.A, prob.b, prob.lam, prob.mu), prob.l, prob.u, prob.x0, prob.m,
+                        oracle.default_options(tol=0.0))
+    for r in hist[:3]:
+        orc.step()
+        oi = orc.info
+        assert (r.branch, r.backtracks, r.pairs_used, r.n_fixed) == (oi.branch, oi.backtracks, oi.pairs_used, oi.n_fixed)
+        assert r.alpha == pytest.approx(oi.alpha, rel=1e-12) and r.f == pytest.approx(oi.f, rel=1e-6)
+    b.set_x(torch.from_numpy(prob.x0).to(DEV))
+    assert b.history() == []                        # lbfgsb_set_x clears the ring
+    orc.close(); a.close(); b.close()
+
+
+def test_history_ring_keeps_the_most_recent_records():
+    prob = workloads.config("C2", scale=0.05)
+    s = L.solver_for_problem(prob, DEV, tol=0.0, max_iter=300, a_pass=L.APASS_FUSED)
+    info = s.solve()
+    assert info.status == L.MAX_ITER and info.iters == 300
+    hist = s.history()
+    assert len(hist) == L.HISTORY_CAPACITY
+    assert [r.iter for r in hist] == list(range(300 - L.HISTORY_CAPACITY + 1, 301))
+    # (with tol = 0 the iteration runs on at the rounding floor, where the periodic recomputation of f moves its last digits)
+    assert hist[-1].f == info.f and all(y.f <= x.f * (1 + 1e-12) for x, y in zip(hist, hist[1:]))
+    s.close()
+
+
 def test_iterates_stay_feasible_and_objective_decreases():
     prob = workloads.config("C5", scale=0.02)
     s = L.solver_for_problem(prob, DEV, tol=1e-10, tol_relative=1)

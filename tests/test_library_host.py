@@ -117,6 +117,20 @@ def test_transport_kinds_argument_checks():
     assert rc == L.E_INVALID_ARG and b"too small" in lib.lbfgsb_last_error()
 
 
+def test_history_record_layout_matches_the_header(tmp_path):
+    import subprocess
+    src = tmp_path / "sz3.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "lbfgsb.h"\n'
+                   'int main(void){printf("%zu %zu %zu %d\\n", sizeof(lbfgsb_iter_record), offsetof(lbfgsb_iter_record, alpha),'
+                   ' offsetof(lbfgsb_iter_record, memory_resets), LBFGSB_HISTORY_CAPACITY); return 0;}\n')
+    exe = tmp_path / "sz3"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    got = [int(t) for t in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [C.sizeof(L.IterRecord), L.IterRecord.alpha.offset, L.IterRecord.memory_resets.offset, L.HISTORY_CAPACITY]
+    cnt = C.c_int(7)
+    assert L.lib().lbfgsb_get_history(None, None, 0, C.byref(cnt)) == L.E_INVALID_ARG
+
+
 def test_default_options():
     o = L.default_options()
     assert (o.eps, o.armijo_c1, o.backtrack, o.max_backtracks) == (1e-10, 1e-4, 0.5, 60)
