@@ -239,7 +239,9 @@ int lbfgsb_get_info(lbfgsb_solver* s, lbfgsb_info* info_host);
  * solver's stream.  (Logistic objective on the fused pass: steps enqueued without an info struct use a short launch
  * sequence that assumes the first trial step of the line search is accepted; when it is not, the iteration is
  * finished, and the steps after it are redone, the next time the library looks at the device state.  These two calls
- * do that first, which means they wait for the stream, whenever such steps have been enqueued since the last look.) */
+ * do that first, which means they wait for the stream, whenever such steps have been enqueued since the last look.
+ * Steps replayed from a recorded HIP graph are not seen by that bookkeeping: call lbfgsb_get_info after a replay and
+ * before reading x or g.) */
 int lbfgsb_get_x(lbfgsb_solver* s, double* x_out);
 int lbfgsb_get_g(lbfgsb_solver* s, double* g_out);
 
