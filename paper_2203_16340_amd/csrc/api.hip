@@ -64,6 +64,7 @@ struct lbfgsb_solver {
     // rejected first trial step), and short-sequence steps enqueued since the host last looked at the scalar block
     int logi_full_left;
     int short_steps_unseen;
+    bool short_ok;           // the short sequence is available (the pass has the LDS for its per-row numbers)
     bool commit_needed;      // resident solver: a kernel of the multi-kernel path may have left an update pending
     int steps_since_refresh;
     long long steps_since_set_x;
@@ -138,6 +139,12 @@ Geometry make_geometry(const Dims& dm, const void* A) {
     int64_t lb_ = (dm.rows + kBlock - 1) / kBlock;
     ge.ls_blocks = (int)(lb_ > 128 ? 128 : lb_);   // (the line search ends in a single-address arrival: few workgroups)
     ge.lrows_blocks = (int)(lb_ > 512 ? 512 : lb_);   // the margins' update has no such ending: 512 measured faster than 128
+    {
+        // workgroups for the columns plus workgroups for the margins (four rows per thread), at most 512 in all
+        int64_t rb4 = (dm.rows + 4 * kBlock - 1) / (4 * kBlock);
+        int64_t tot = rb4 + ge.upd_blocks;
+        ge.updl_blocks = (int)(tot > 512 ? 512 : tot);
+    }
     if (is_transport(dm.kind)) {
         int rpw = 1;
         while (rpw < kOtRpwMax && (dm.rows + rpw - 1) / rpw > 512) rpw *= 2;
@@ -180,6 +187,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     L.grampart = take(gram_partial_bytes(dm.n, dm.m));
     size_t red = (size_t)ge.dir_blocks * (8 + 2 * kFoldMax);
     if ((size_t)ge.upd_blocks * 2 > red) red = (size_t)ge.upd_blocks * 2;
+    if ((size_t)ge.updl_blocks * 2 > red) red = (size_t)ge.updl_blocks * 2;
     if (is_transport(dm.kind) && (size_t)ge.ot_el_blocks > red) red = (size_t)ge.ot_el_blocks;
     L.redpart = take(red * 8);
     L.lspart = take((size_t)ge.ls_blocks * 64 * 8);   // up to 64 step lengths per sweep (entropy line search: 51)
@@ -221,7 +229,7 @@ hipError_t read_scal(lbfgsb_solver* s) {
         launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, 2, s->stream);
         launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
         launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 2, s->stream, nullptr, nullptr);
-        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
+        launch_update_logistic(s->dm, s->op, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
         s->logi_full_left = 8 + redo;   // a problem that backtracks once tends to do so again: full sequence for a while
         for (int k = 0; k < redo; ++k) enqueue_step(s);
     }
@@ -363,20 +371,22 @@ void enqueue_step(lbfgsb_solver* s) {
         // (transposed) pass over X run, otherwise that launch returns at once.  The transposed pass is not
         // among the timed launches: it reads A only in the iterations that backtrack.
         a.mode = kRowLogiSpec;
+        const bool full = s->logi_full_left > 0 || !s->short_ok;
+        a.ls_first = full ? 0 : 1;
         { TimedSlot ts(s); launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
-        if (s->logi_full_left > 0) {
-            s->logi_full_left--;
+        if (full) {
+            if (s->logi_full_left > 0) s->logi_full_left--;
             launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, 3, s->stream);
             launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
             launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 2, s->stream, nullptr, nullptr);
-            launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
+            launch_update_logistic(s->dm, s->op, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
         } else {
-            // Short sequence: the search on the margins tries the first step only, and the update of an accepted
-            // first step also moves the margins.  Three launches that almost never do work (eight more step
-            // lengths, new row weights, second transposed pass) are left out; should the first step be rejected,
-            // the solver parks itself and read_scal() supplies them.
-            launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 1, 1, s->stream);
-            launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, 1, s->stream);
+            // Short sequence: the pass itself sums the loss differences of the first trial step over each workgroup's
+            // rows, and the update kernel takes the Armijo decision from those partials; the update of an accepted
+            // first step also moves the margins.  The search kernels, the recomputation of the row weights and the
+            // second transposed pass -- launches that almost never do work -- are left out; should the first step be
+            // rejected, the solver parks itself and read_scal() supplies them.
+            launch_update_logistic(s->dm, s->op, s->ge, s->bf, s->ge.fused_blocks, 1, s->stream);
             s->short_steps_unseen++;
         }
     } else {
@@ -385,7 +395,7 @@ void enqueue_step(lbfgsb_solver* s) {
         launch_ls_logistic(s->dm, s->op, s->ge, s->bf, s->obj.b, 0, 3, s->stream);
         launch_rows_logistic(s->dm, s->ge, s->bf, s->obj.b, s->stream);
         { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
-        launch_update_logistic(s->dm, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
+        launch_update_logistic(s->dm, s->op, s->ge, s->bf, s->ge.lrows_blocks, 0, s->stream);
     }
     s->steps_since_refresh++;
 }
@@ -500,6 +510,7 @@ int setup_solver(lbfgsb_solver* s, int64_t n, int m, const lbfgsb_objective* obj
         const hipError_t fe = fused_prepare(s->dm, s->ge);
         if (fe != hipSuccess) return fail(LBFGSB_E_HIP, "preparing the fused A pass: %s", hipGetErrorString(fe));
     }
+    s->short_ok = s->use_fused && s->dm.kind == LBFGSB_OBJ_LOGISTIC_L2 && fused_ls_first_ok(s->dm, s->ge);
     s->ge.w_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemvt_row_blocks;
     s->ge.loss_parts = s->use_fused ? s->ge.fused_blocks : s->ge.gemv_blocks;
 

@@ -60,7 +60,6 @@ struct Scal {
     int since_refresh;      // resident solver: iterations since residual and gradient were last computed from x
     // logistic objective, short launch sequence (see kStatusBail)
     int bail_skipped;       // whole steps that found the status kStatusBail and did nothing
-    double ls_df;           // f(x + alpha p) - f(x) of the accepted first trial step
     // per-iteration records (ring in the workspace; null: none kept)
     lbfgsb_iter_record* hist;
     long long hist_count;   // records written since lbfgsb_set_x
@@ -257,6 +256,17 @@ __device__ __forceinline__ double sigmoid_d(double t) {
     return e / (1.0 + e);
 }
 
+// softplus(q + dq) - softplus(q) without differencing two rounded values; sq = sigmoid(q).
+__device__ __forceinline__ double softplus_diff(double q, double sq, double dq) {
+    if (fabs(dq) >= 30.0) return softplus_d(q + dq) - softplus_d(q);
+    // log(1 + sigmoid(q) (e^dq - 1)).  Where the product comes close to -1 (a saturated margin that the step undoes)
+    // log1p of it would itself take the logarithm of a difference of nearly equal numbers; there the same number is
+    // log(sigmoid(-q) + sigmoid(q) e^dq), a sum of two positive terms.
+    const double u = sq * expm1(dq);
+    if (u > -0.5) return log1p(u);
+    return log(sigmoid_d(-q) + sq * exp(dq));
+}
+
 // ---- helpers shared by the column-wise consumers of the A pass ---------------------------------------------
 
 constexpr int kCX = 16;             // columns per workgroup
@@ -319,6 +329,7 @@ struct Geometry {
     int fused_blocks;       // workgroups = partial vectors per column and loss partials
     // vector kernels
     int gram_blocks, dir_blocks, upd_blocks, fin_blocks, ls_blocks, lrows_blocks;
+    int updl_blocks;        // logistic update of the short sequence (it also moves the margins: rows / 1024 workgroups, at most 512)
     // transport kinds: workgroups of the marginal-sum kernel (each owns ot_rpw consecutive rows of P), of the
     // column-sum kernel, and of the entrywise kernels
     int ot_row_blocks, ot_rpw, ot_col_blocks, ot_el_blocks;
@@ -371,6 +382,10 @@ struct APassArgs {
     int split;              // L1SPLIT: vb = va + cols
     int mode;               // RowMode
     int check_status;       // skip all work unless Scal::status == RUNNING
+    // kRowLogiSpec only: every workgroup also sums, over its own rows, the loss differences of the first trial step
+    // (softplus(-y (z + alpha0 t)) - softplus(-y z)) into its loss partial, so that the update kernel can take the
+    // Armijo decision on that step without a sweep over the margins in a kernel of its own
+    int ls_first;
 };
 
 // ev0/ev1 (both or neither): HIP events attached to the dispatch itself, so that their difference is
@@ -381,6 +396,7 @@ void launch_gemv(const Dims& dm, const Geometry& ge, const Buffers& bf, const AP
 void launch_gemvt_from(const Dims& dm, const Geometry& ge, const Buffers& bf, const void* A, const double* psi_src,
                        int check_status, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 bool fused_shape_ok(const Dims& dm, const void* A, int* variant, int* blocks);
+bool fused_ls_first_ok(const Dims& dm, const Geometry& ge);   // APassArgs::ls_first may be set (its LDS fits)
 hipError_t fused_prepare(const Dims& dm, const Geometry& ge);   // once per solver, before the first launch_fused
 void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
                   hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
@@ -403,14 +419,17 @@ void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge,
 void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, const double* target, const double* weight,
                        int eval, hipStream_t st);
 // spec != 0: the A pass already holds X^T psi of the first trial step (recorded in Scal::spec_ok if that step is accepted)
-// stages: 1 = the first trial step only (short sequence: a rejected step parks the solver in kStatusBail),
-// 2 = the continuation only (eight more step lengths per sweep, then one at a time), 3 = both
+// stages: 2 = the continuation only (eight more step lengths per sweep, then one at a time: what the host supplies
+// after the short sequence has rejected the first trial step), 3 = the first trial step in a sweep of its own, then
+// the continuation
 void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
                         int spec, int stages, hipStream_t st);
 void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* labels, hipStream_t st);
-// short != 0: the short sequence's update (accepted first trial step: margins z += alpha t here, f from Scal::ls_df)
-void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, int short_seq,
-                            hipStream_t st);
+// short != 0: the short sequence's update.  The pass over X has left the loss differences of the first trial step in
+// its loss partials; every workgroup adds them up and takes the Armijo decision itself.  Accepted: margins z += alpha t
+// here, f from that difference.  Rejected: the solver is parked in kStatusBail and nothing is updated.
+void launch_update_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int loss_parts,
+                            int short_seq, hipStream_t st);
 void launch_clear_bail(const Buffers& bf, hipStream_t st);   // status kStatusBail -> RUNNING, bail_skipped -> 0
 
 // transport kinds (transport.hip).  M: cost matrix; beta/omega: targets and weights of the rows + cols marginal

@@ -143,16 +143,26 @@ hipError_t fused_prepare(const Dims& dm, const Geometry& ge) {
     if (most > cap) most = cap;
     if (v.lds(dm.cols) > most) most = v.lds(dm.cols);
     hipError_t e = hipFuncSetAttribute(v.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
-    if (e == hipSuccess && v.kernel_dir)
-        e = hipFuncSetAttribute(v.kernel_dir, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
+    if (e == hipSuccess && v.kernel_dir)   // (may also hold two numbers per row of a workgroup: whatever fits)
+        e = hipFuncSetAttribute(v.kernel_dir, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cap);
     return e;
+}
+
+// LDS the logistic direction pass needs on top when it also sums the loss differences of the first trial step:
+// two numbers per row of a workgroup
+static size_t ls_first_lds(const Dims& dm, const Variant& v) { return (size_t)rows_per_wg_for(dm, v) * 16; }
+
+bool fused_ls_first_ok(const Dims& dm, const Geometry& ge) {
+    const Variant& v = kVariants[ge.fused_variant];
+    return v.launch_dir && v.lds(dm.cols) + ls_first_lds(dm, v) <= kLdsPerWorkgroup - 256;
 }
 
 void launch_fused(const Dims& dm, const Geometry& ge, const Buffers& bf, const APassArgs& a, hipStream_t st,
                   hipEvent_t ev0, hipEvent_t ev1) {
     const Variant& v = kVariants[ge.fused_variant];
     auto launch = (a.mode == kRowLogiSpec && v.launch_dir) ? v.launch_dir : v.launch;
-    launch(dm, rows_per_wg_for(dm, v), ge.fused_blocks, v.lds(dm.cols), bf, a, st, ev0, ev1);
+    const size_t extra = a.mode == kRowLogiSpec && a.ls_first ? ls_first_lds(dm, v) : 0;
+    launch(dm, rows_per_wg_for(dm, v), ge.fused_blocks, v.lds(dm.cols) + extra, bf, a, st, ev0, ev1);
 }
 
 }  // namespace lb

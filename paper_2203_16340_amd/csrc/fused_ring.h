@@ -104,7 +104,7 @@ template <int R, int NW, int LOGI>
 __device__ __forceinline__ void stage_row_op(const double* red, int lane, int wave, int mode, const double (&bcur)[R],
                                              const double (&zcur)[R], int64_t row0, int64_t r_end, double alpha0,
                                              double invn, double* __restrict__ row, double* __restrict__ t,
-                                             double& loss, double (&psi)[R]) {
+                                             double& loss, double (&psi)[R], double* lsq = nullptr, int64_t r_begin = 0) {
     const int rl = lane < R ? lane : 0;
     double u = 0.0;
 #pragma unroll
@@ -127,6 +127,14 @@ __device__ __forceinline__ void stage_row_op(const double* red, int lane, int wa
     loss += lossl;
     if (valid && wave == 0) {
         if (mode == kRowDir || mode == kRowLogiSpec || mode == kRowQpDir) t[grow] = keep; else row[grow] = keep;
+        if constexpr (LOGI == 2) {
+            // what the first trial step's loss difference of this row needs (summed after the row loop): q = -y z and
+            // dq = -y alpha0 t, kept in LDS at the row's local index
+            if (lsq) {
+                lsq[2 * (grow - r_begin)] = -bl * zl;
+                lsq[2 * (grow - r_begin) + 1] = -bl * alpha0 * u;
+            }
+        }
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) psi[r] = lane_bcast(psil, r);
@@ -167,6 +175,8 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     const int lcols = KR > 0 && cols > (int64_t)KL * NT * VEC ? KL * NT * VEC : (int)cols;
     double* vs = lds;                                        // v, `lcols` entries, then kPad zeros
     double* red = lds + lcols + kPad;                        // [2][R][NW]
+    // logistic direction pass that also sums the first trial step's loss differences: (q, dq) per row of this workgroup
+    double* lsq = (LOGI == 2 && a.ls_first) ? red + 2 * R * NW : nullptr;
     if (a.check_status && scal->status != LBFGSB_RUNNING) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const double *va, *vb;
@@ -313,7 +323,7 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             read_rows(bnext, znext, lr0 + R);
             double psi[R];
             stage_row_op<R, NW, LOGI>(red + par * R * NW, lane, wave, mode, bcur, zcur, r_begin + lr0, r_end, alpha0,
-                                      invn, row, t, loss, psi);
+                                      invn, row, t, loss, psi, lsq, r_begin);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 bcur[r] = bnext[r];
@@ -344,6 +354,30 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             par ^= 1;
         }
     }
+    if constexpr (LOGI == 2) {
+        // First trial step of the line search: this workgroup's share of sum_r softplus(-y (z + alpha0 t)) - softplus(-y z)
+        // over its own rows, from the (q, dq) the row loop left in LDS.  Done here, after the row loop, where nothing
+        // waits for it and no trip to memory is needed, so that the Armijo decision on that step takes no sweep over
+        // the margins in a kernel of its own.
+        if (lsq) {
+            __syncthreads();
+            const int nloc = (int)(r_end - r_begin);
+            double s2[2] = {0.0, 0.0};
+            for (int i0 = tid; i0 < nloc; i0 += 2 * NT) {
+                double q[2], dq[2];
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const int i = i0 + k * NT;
+                    q[k] = i < nloc ? lsq[2 * i] : 0.0;      // q = dq = 0: the row contributes log1p(0.5 * expm1(0)) = 0
+                    dq[k] = i < nloc ? lsq[2 * i + 1] : 0.0;
+                }
+#pragma unroll
+                for (int k = 0; k < 2; ++k) s2[k] += softplus_diff(q[k], sigmoid_d(q[k]), dq[k]);
+            }
+            loss = wave_sum(s2[0] + s2[1]);
+            if (lane == 0) red[wave] = loss;
+        }
+    }
     if constexpr (TRANS) {
         double* out = wpart + (int64_t)blockIdx.x * cols + c0;
 #pragma unroll
@@ -352,6 +386,18 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) out[k * kStride + j] = w[k][j];
             }
+        }
+    }
+    if constexpr (LOGI == 2) {
+        if (lsq) {
+            __syncthreads();
+            if (tid == 0) {
+                double tot = 0.0;
+#pragma unroll
+                for (int q = 0; q < NW; ++q) tot += red[q];
+                losspart[blockIdx.x] = tot;
+            }
+            return;
         }
     }
     loss = wave_sum(loss);                                   // lanes 0..R-1 of a wave hold the row losses

@@ -544,20 +544,11 @@ void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, co
 // - softplus(-y_r z_r)] + mu (a <x,p> + a^2/2 <p,p>).  The bracket is evaluated in the cancellation-free
 // form log(1 + sigmoid(q) expm1(dq)), q = -y z, dq = -y a t (softplus_diff).  Step lengths are evaluated NTRY at a time per sweep
 // over the rows: the first launch tries the first one alone (it is accepted in almost every quasi-Newton
-// iteration), a second launch, which returns at once when the first found the step, tries the next kLsBatch, and
+// iteration; the short launch sequence has the pass over X form that sum itself and the update kernel decide,
+// see k_update_logistic), a second launch, which returns at once when the first found the step, tries the next kLsBatch, and
 // if none of them is acceptable its last workgroup goes on alone, one length at a time.
-__device__ __forceinline__ double softplus_diff(double q, double sq, double dq) {
-    if (fabs(dq) >= 30.0) return softplus_d(q + dq) - softplus_d(q);
-    // log(1 + sigmoid(q) (e^dq - 1)).  Where the product comes close to -1 (a saturated margin that the step undoes)
-    // log1p of it would itself take the logarithm of a difference of nearly equal numbers; there the same number is
-    // log(sigmoid(-q) + sigmoid(q) e^dq), a sum of two positive terms.
-    const double u = sq * expm1(dq);
-    if (u > -0.5) return log1p(u);
-    return log(sigmoid_d(-q) + sq * exp(dq));
-}
-
 template <int NTRY>
-__global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int first, int last_resort, int spec, int short_seq,
+__global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int first, int last_resort, int spec,
                                                         const double* __restrict__ yl, const double* __restrict__ z,
                                                         const double* __restrict__ t, Scal* __restrict__ scal,
                                                         double* __restrict__ lspart) {
@@ -612,11 +603,11 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int fi
     }
     block_sum<NTRY, kWaves>(tot, red);
     int found = -1;
-    double a_acc = 0.0, df_acc = 0.0;
+    double a_acc = 0.0;
 #pragma unroll
     for (int j = 0; j < NTRY; ++j) {
         const double df = tot[j] * invn + dm.mu * al[j] * (xp + 0.5 * al[j] * pp);
-        if (found < 0 && first + j <= op.max_backtracks && isfinite(df) && df <= op.c1 * al[j] * gp) { found = first + j; a_acc = al[j]; df_acc = df; }
+        if (found < 0 && first + j <= op.max_backtracks && isfinite(df) && df <= op.c1 * al[j] * gp) { found = first + j; a_acc = al[j]; }
     }
     // rare: continue one step length at a time (uniform control flow: every thread holds the same totals)
     double a = al[NTRY - 1];
@@ -634,11 +625,6 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int fi
     if (tid == 0) {
         scal->ls_ok = found >= 0;
         if (first == 0) scal->spec_ok = spec && found == 0;
-        if (short_seq) {
-            // the short sequence has nothing behind this launch but the update of an accepted first step
-            if (found == 0) scal->ls_df = df_acc;
-            else scal->status = kStatusBail;
-        }
         if (found >= 0 || last_resort) {
             scal->backtracks = found >= 0 ? found : op.max_backtracks + 1;
             scal->fevals += found >= 0 ? found + 1 : op.max_backtracks + 1;
@@ -650,10 +636,9 @@ __global__ __launch_bounds__(kBlock) void k_ls_logistic(Dims dm, Opts op, int fi
 void launch_ls_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* labels,
                         int spec, int stages, hipStream_t st) {
     if (stages & 1)
-        hipLaunchKernelGGL(k_ls_logistic<1>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 0, 0, spec, stages == 1 ? 1 : 0,
-                           labels, (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
+        hipLaunchKernelGGL(k_ls_logistic<1>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 0, 0, spec, labels, (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
     if (stages & 2)
-        hipLaunchKernelGGL(k_ls_logistic<kLsBatch>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 1, 1, spec, 0, labels,
+        hipLaunchKernelGGL(k_ls_logistic<kLsBatch>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op, 1, 1, spec, labels,
                            (const double*)bf.row, (const double*)bf.t, bf.scal, bf.lspart);
 }
 
@@ -685,8 +670,12 @@ void launch_rows_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf,
 }
 
 // x+ = P(x + alpha p), g+ = X^T psi + mu x+, pair (x+ - x, g+ - g), f+ from the new margins.
-__global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts_two_pass, int w_parts_spec, int loss_parts,
-                                                            int short_seq, const double* __restrict__ t,
+// short_seq: the pass over X has left, in its loss partials, the sums over its workgroups' rows of
+// softplus(-y (z + a0 t)) - softplus(-y z) for the first trial step a0 = min(1, alpha_ub).  Every workgroup adds
+// them in the same order and takes the same Armijo decision; an accepted step is applied here (the margins move
+// too), a rejected one parks the solver (kStatusBail) with nothing changed and no arrival counted.
+__global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, double c1, int w_parts_two_pass, int w_parts_spec,
+                                                            int loss_parts, int short_seq, const double* __restrict__ t,
                                                             double* __restrict__ z, const double* __restrict__ wpart,
                                                             const double* __restrict__ losspart,
                                                             const double* __restrict__ p1, const double* __restrict__ p2,
@@ -699,22 +688,69 @@ __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts
     __shared__ int flag;
     if (scal->status != LBFGSB_RUNNING) return;
     const int tid = threadIdx.x;
-    const int ok = scal->ls_ok;
-    const double alpha = scal->alpha;
+    int ok = scal->ls_ok;
+    double alpha = scal->alpha;
     const int slot = scal->head;
     const double* p = scal->branch == 1 ? p1 : p2;
-    const int w_parts = scal->spec_ok ? w_parts_spec : w_parts_two_pass;   // which kernel wrote the partial columns
+    int w_parts = scal->spec_ok ? w_parts_spec : w_parts_two_pass;   // which kernel wrote the partial columns
+    double df = 0.0, f_old = 0.0;
+    if (short_seq) {
+        const double gp = scal->gp, xp = scal->xp, pp = scal->pp;
+        f_old = scal->f;
+        alpha = fmin(1.0, scal->alpha_ub);
+        df = sum_all(losspart, loss_parts, red) / (double)dm.rows + dm.mu * alpha * (xp + 0.5 * alpha * pp);
+        ok = isfinite(df) && df <= c1 * alpha * gp;
+        w_parts = w_parts_spec;
+        if (!ok) {
+            // (a workgroup that starts after this store finds the solver parked and returns at once: same outcome)
+            if (blockIdx.x == 0 && tid == 0) {
+                scal->ls_ok = 0;
+                scal->spec_ok = 0;
+                scal->status = kStatusBail;
+            }
+            return;
+        }
+    }
     double sums[2] = {0.0, 0.0};   // ||y||^2, ||x+||^2
+    // short sequence: the first `col_blocks` workgroups take the columns, the others the margins (side by side, not
+    // one after the other: a workgroup's trips to memory are dependent and nothing else runs on its compute unit);
+    // a grid of one workgroup does both
+    int col_first = 0, col_stride = (int)gridDim.x;
     if (ok && short_seq) {
         // the margins of the new point (the full sequence has a kernel for this, which also recomputes the row weights:
         // here the single-read pass already holds X^T psi of this step)
-        for (int64_t r = (int64_t)blockIdx.x * kBlock + tid; r < dm.rows; r += (int64_t)gridDim.x * kBlock)
-            z[r] = fma(alpha, t[r], z[r]);
+        const int want = (int)((dm.cols + kCX - 1) / kCX);
+        const int col_blocks = want < (int)gridDim.x / 2 ? want : (int)gridDim.x / 2;
+        int rb = (int)blockIdx.x, nrb = (int)gridDim.x;
+        if (col_blocks > 0) {
+            col_stride = col_blocks;
+            if ((int)blockIdx.x >= col_blocks) col_first = -1;   // this workgroup takes no columns
+            rb = (int)blockIdx.x - col_blocks;                   // (negative: no rows)
+            nrb = (int)gridDim.x - col_blocks;
+        }
+        if (rb >= 0) {
+            // (four rows per trip with their loads issued together)
+            const int64_t stride = (int64_t)nrb * kBlock;
+            for (int64_t r0 = (int64_t)rb * kBlock + tid; r0 < dm.rows; r0 += 4 * stride) {
+                double tv[4], zv[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int64_t r = r0 + k * stride;
+                    tv[k] = r < dm.rows ? t[r] : 0.0;
+                    zv[k] = r < dm.rows ? z[r] : 0.0;
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int64_t r = r0 + k * stride;
+                    if (r < dm.rows) z[r] = fma(alpha, tv[k], zv[k]);
+                }
+            }
+        }
     }
-    if (ok) {
+    if (ok && col_first >= 0) {
         double* Sn = S + (int64_t)slot * dm.n;
         double* Yn = Y + (int64_t)slot * dm.n;
-        for (int64_t c0 = (int64_t)blockIdx.x * kCX; c0 < dm.cols; c0 += (int64_t)gridDim.x * kCX) {
+        for (int64_t c0 = (int64_t)blockIdx.x * kCX; c0 < dm.cols; c0 += (int64_t)col_stride * kCX) {
             const int64_t c = c0 + tid % kCX;
             const double w = column_sum(wpart, w_parts, dm.cols, c, lds);
             if (tid < kCX && c < dm.cols) {
@@ -731,17 +767,32 @@ __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts
             }
         }
     }
+    if (short_seq) {
+        // Nothing is left to add up: f moves by the line search's difference, and the new pair's ||y||^2 comes from
+        // the next free-set pass (as for the quadratic kinds).  No workgroup of this kernel reads the pend_* fields,
+        // so one thread may write them while others are still running; the next Gram kernel (or k_commit) turns
+        // them into head/count/iters/f.  Without an arrival at one address the grid need not stay small.
+        if (blockIdx.x == 0 && tid == 0) {
+            scal->spec_ok = 1;
+            scal->pend_ok = 1;
+            scal->pend_bt = 0;
+            scal->pend_alpha = alpha;
+            scal->pend_f = f_old + df;
+            scal->pend_valid = 1;
+        }
+        return;
+    }
     block_sum<2, kWaves>(sums, red);
     if (tid == 0) { redpart[2 * blockIdx.x] = sums[0]; redpart[2 * blockIdx.x + 1] = sums[1]; }
     if (!arrive_is_last(&scal->counters[kCntUpdate], &flag)) return;
     double tot[2] = {0.0, 0.0};
     for (int b = tid; b < (int)gridDim.x; b += kBlock) { tot[0] += redpart[2 * b]; tot[1] += redpart[2 * b + 1]; }
     block_sum<2, kWaves>(tot, red);
-    const double loss = (ok && !short_seq) ? sum_all(losspart, loss_parts, red) : 0.0;
+    const double loss = ok ? sum_all(losspart, loss_parts, red) : 0.0;
     if (tid == 0) {
         if (ok) {
-            // full sequence: f from the new margins and the new iterate; short one: the line search's difference
-            scal->f = short_seq ? scal->f + scal->ls_df : loss + 0.5 * dm.mu * tot[1];
+            // f from the new margins and the new iterate
+            scal->f = loss + 0.5 * dm.mu * tot[1];
             scal->ynorm2[slot] = tot[0];
             scal->head = (slot + 1) % dm.m;
             scal->count = scal->count < dm.m ? scal->count + 1 : dm.m;
@@ -756,9 +807,9 @@ __global__ __launch_bounds__(kBlock) void k_update_logistic(Dims dm, int w_parts
     }
 }
 
-void launch_update_logistic(const Dims& dm, const Geometry& ge, const Buffers& bf, int loss_parts, int short_seq,
-                            hipStream_t st) {
-    hipLaunchKernelGGL(k_update_logistic, dim3(ge.upd_blocks), dim3(kBlock), 0, st, dm, ge.gemvt_row_blocks,
+void launch_update_logistic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int loss_parts,
+                            int short_seq, hipStream_t st) {
+    hipLaunchKernelGGL(k_update_logistic, dim3(short_seq ? ge.updl_blocks : ge.upd_blocks), dim3(kBlock), 0, st, dm, op.c1, ge.gemvt_row_blocks,
                        ge.fused_blocks, loss_parts, short_seq, (const double*)bf.t, bf.row, bf.wpart,
                        bf.losspart, bf.p1, bf.p2, bf.l, bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, bf.redpart);
 }

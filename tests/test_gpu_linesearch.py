@@ -135,7 +135,10 @@ def test_steps_enqueued_without_waiting_survive_rejected_first_steps(case):
     ia, ib = a.info(), b.info()
     assert ia.iters == ib.iters == 16 and ia.status == ib.status == L.RUNNING
     assert torch.equal(xa, xb) and torch.equal(a.g(), b.g())
-    assert ia.f == ib.f and ia.fevals == ib.fevals
+    # f is a reported scalar that no decision reads (the Armijo test uses the difference): the short sequence carries it
+    # as f + [f(x + a p) - f(x)], the full one evaluates it from the new margins, and which iterations run which
+    # sequence differs between the two ways of stepping -- equal to rounding, not bit for bit
+    assert ia.f == pytest.approx(ib.f, rel=1e-14) and ia.fevals == ib.fevals
     # and lbfgsb_solve from here on agrees too
     a2, b2 = a.solve(), b.solve()
     assert (a2.status, a2.iters) == (b2.status, b2.iters) and torch.equal(a.x(), b.x())
