@@ -140,6 +140,32 @@ __device__ __forceinline__ void stage_row_op(const double* red, int lane, int wa
     for (int r = 0; r < R; ++r) psi[r] = lane_bcast(psil, r);
 }
 
+// v[c] = (va[c] - vb[c]) * sc[c] (difference and scaling optional) for c < lcols into LDS: E entries per thread
+// and round, every load of a round issued before the first value is used (a round is one trip to memory).
+template <int NT, int E, bool HAS_VB, bool HAS_VS>
+__device__ __forceinline__ void stage_v(const double* __restrict__ va, const double* __restrict__ vb,
+                                        const double* __restrict__ sc, double* vs, int lcols, int tid) {
+    for (int c0 = tid; c0 < lcols; c0 += NT * E) {
+        double v8[E], b8[E], s8[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const int c = c0 + k * NT;
+            const int cc = c < lcols ? c : lcols - 1;
+            v8[k] = va[cc];
+            if (HAS_VB) b8[k] = vb[cc];
+            if (HAS_VS) s8[k] = sc[cc];
+        }
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const int c = c0 + k * NT;
+            double v = v8[k];
+            if (HAS_VB) v -= b8[k];
+            if (HAS_VS) v *= s8[k];
+            if (c < lcols) vs[c] = v;
+        }
+    }
+}
+
 // dynamic LDS a launch needs: v for the columns held there (all of them unless the variant keeps the v of
 // its last KR chunks per thread in registers), one all-zero chunk, then the reduction scratch
 constexpr int kPad = 4;
@@ -177,38 +203,7 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     double* red = lds + lcols + kPad;                        // [2][R][NW]
     // logistic direction pass that also sums the first trial step's loss differences: (q, dq) per row of this workgroup
     double* lsq = (LOGI == 2 && a.ls_first) ? red + 2 * R * NW : nullptr;
-    if (a.check_status && scal->status != LBFGSB_RUNNING) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const double *va, *vb;
-    resolve_v(a, scal, cols, va, vb);
-
-    // v into LDS, eight entries per thread and round with all their loads issued before the first is used (one
-    // entry at a time this loop was a chain of dependent trips to memory: 3.5 us at 5000 columns)
-    for (int c0 = tid; c0 < lcols; c0 += NT * 8) {
-        double v8[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int c = c0 + k * NT;
-            const int cc = c < lcols ? c : lcols - 1;
-            v8[k] = (vb ? va[cc] - vb[cc] : va[cc]) * (a.vs ? a.vs[cc] : 1.0);
-        }
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int c = c0 + k * NT;
-            if (c < lcols) vs[c] = v8[k];
-        }
-    }
-    if (tid < kPad) vs[lcols + tid] = 0.0;
-    double vreg[KR > 0 ? KR : 1][VEC];
-#pragma unroll
-    for (int k = 0; k < KR; ++k) {
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) {
-            const int64_t c = (int64_t)((KL + k) * NT + tid) * VEC + j;
-            vreg[k][j] = c < cols ? (vb ? va[c] - vb[c] : va[c]) * (a.vs ? a.vs[c] : 1.0) : 0.0;
-        }
-    }
-
     // chunk k of this thread starts at column (k*NT + tid)*VEC.  A chunk at or past `cols` does not
     // exist: its loads are redirected to the last chunk of the row (valid memory) and its v to the
     // zero pad, so it adds nothing to a dot product, and its w is never stored.  No load is predicated.
@@ -242,6 +237,35 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             dst[k] = __builtin_nontemporal_load(reinterpret_cast<const RawT*>(rp + c * (unsigned)sizeof(T)));
         }
     };
+    // The ring is primed before anything else: the first rows of A depend on nothing, so their trip to memory
+    // overlaps with the reads of the status word and of v (which otherwise precede it, one after the other, while
+    // the memory system idles).  A launch that finds the solver stopped has fetched a few rows for nothing.
+#pragma unroll
+    for (int s = 0; s < NB; ++s) fetch(raw[s], (s / SPS) * R + (s % SPS) / U, (s % SPS) % U);
+    if (a.check_status && scal->status != LBFGSB_RUNNING) return;
+    const double *va, *vb;
+    resolve_v(a, scal, cols, va, vb);
+
+    // v into LDS, eight entries per thread and round with all their loads issued before the first is used (one
+    // entry at a time this loop was a chain of dependent trips to memory: 3.5 us at 5000 columns).  The optional
+    // difference and scaling are decided outside the loop, whose body then has no branch for a load to wait at.
+    constexpr int VE = 8;                                    // entries per thread and round (16 measured slower at 20000 columns)
+    if (vb) {
+        if (a.vs) stage_v<NT, VE, true, true>(va, vb, a.vs, vs, lcols, tid); else stage_v<NT, VE, true, false>(va, vb, a.vs, vs, lcols, tid);
+    } else {
+        if (a.vs) stage_v<NT, VE, false, true>(va, vb, a.vs, vs, lcols, tid); else stage_v<NT, VE, false, false>(va, vb, a.vs, vs, lcols, tid);
+    }
+    if (tid < kPad) vs[lcols + tid] = 0.0;
+    double vreg[KR > 0 ? KR : 1][VEC];
+#pragma unroll
+    for (int k = 0; k < KR; ++k) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const int64_t c = (int64_t)((KL + k) * NT + tid) * VEC + j;
+            vreg[k][j] = c < cols ? (vb ? va[c] - vb[c] : va[c]) * (a.vs ? a.vs[c] : 1.0) : 0.0;
+        }
+    }
+
     // The row's entries of b (targets or labels) and of the row weights (quadratic kinds) or, for the
     // speculative logistic pass, of the stored margins are read one stage ahead through the scalar unit (the row index is uniform and neither
     // vector is written by this kernel in the modes that read it): scalar loads are not ordered with
@@ -271,8 +295,6 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     const double invn = 1.0 / (double)rows;
     double bcur[R], zcur[R];
     read_rows(bcur, zcur, 0);
-#pragma unroll
-    for (int s = 0; s < NB; ++s) fetch(raw[s], (s / SPS) * R + (s % SPS) / U, (s % SPS) % U);
     __syncthreads();                                         // v is in LDS
 
     double loss = 0.0;
