@@ -117,7 +117,8 @@ typedef struct {
     int max_iter;          /* default 1000 */
     int refresh_every;     /* least-squares kinds carry residual and gradient by recurrence; every this many
                               iterations they are recomputed from x (default 32, 0 = never) */
-    int poll_every;        /* lbfgsb_solve reads the device status flag every this many iterations (default 8) */
+    int poll_every;        /* lbfgsb_solve reads the device status flag every this many iterations (default 8); in a long
+                              run the interval doubles each time eight intervals have gone by, up to 64 */
     int a_pass;            /* LBFGSB_APASS_* */
 } lbfgsb_options;
 
@@ -190,7 +191,7 @@ int lbfgsb_step(lbfgsb_solver* s, lbfgsb_info* info_host);
  * lbfgsb_solve once at the end if the difference matters.) */
 
 /* Iterates until the tolerance, max_iter or a line-search failure.  The device decides all
- * data-dependent branches; the host only polls the status flag every poll_every iterations.
+ * data-dependent branches; the host only polls the status flag every poll_every iterations (less often in long runs).
  * A least-squares solve is declared converged only with residual and gradient freshly
  * recomputed from x.  info_host may be NULL. */
 int lbfgsb_solve(lbfgsb_solver* s, lbfgsb_info* info_host);

@@ -541,6 +541,8 @@ int init_workspace(lbfgsb_solver* s, const double* l, const double* u, void* wor
     return LBFGSB_OK;
 }
 
+constexpr int kPollMax = 64;   // steps between two looks at the device status, at most
+
 // The stopping logic of lbfgsb_solve, for a solver whose arguments have been checked.
 int solve_impl(lbfgsb_solver* s, lbfgsb_info* info) {
     const bool quad = is_quadratic(s->dm.kind);
@@ -556,9 +558,14 @@ int solve_impl(lbfgsb_solver* s, lbfgsb_info* info) {
         return LBFGSB_OK;
     }
     long long steps = 0;
+    // A poll leaves the device idle for about 30 us (commit, copy of the scalar block, the host's wake-up and the next
+    // launches), a step enqueued after the solver has stopped costs about 6.  Long runs are therefore polled less
+    // often: the interval doubles whenever eight intervals' worth of steps have gone by, up to 64.
+    int batch = s->options.poll_every;
     for (;;) {
-        for (int k = 0; k < s->options.poll_every; ++k) enqueue_step(s);
-        steps += s->options.poll_every;
+        for (int k = 0; k < batch; ++k) enqueue_step(s);
+        steps += batch;
+        if (batch < kPollMax && steps >= 8ll * batch) batch = 2 * batch > kPollMax ? kPollMax : 2 * batch;
         HIP_TRY(read_scal(s));
         int st = s->h_scal->status;
         if (st == LBFGSB_CONVERGED && quad && s->steps_since_refresh > 0 && s->h_scal->iters > 0) {

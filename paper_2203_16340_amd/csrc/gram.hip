@@ -561,50 +561,54 @@ __global__ __launch_bounds__(kBlock) void k_gram_mfma(int64_t n, int m, Opts op,
 }
 
 
-// ---- large n, at most 10 pairs: one element pair per lane, the entries of G divided among the waves ------------
+// ---- at most 10 pairs: one element pair per lane, the entries of G divided among the waves -------------------
 //
 // The fp64 matrix cores of this chip run at the vector rate, and the 16-wide blocks above compute three times
 // the entries a 21-vector Gram matrix has.  For m <= 10 the plain vector unit does better: lane l of every wave
 // holds elements e0 + 2l, e0 + 2l + 1 of a 128-element chunk (16-byte loads, each instruction a contiguous
 // kilobyte of one vector), and the 231 entries of the 21 x 21 matrix over the STATIC slots
 //     S ring slots 0..9 | Y ring slots 10..19 | g 20
-// are divided among the four waves of a workgroup, each keeping its share as per-lane accumulators:
-//     wave 0: slots 0..10 among themselves (66)      wave 1: slots 11..20 among themselves (55), full ||y_new||^2
-//     wave 2: slots 0..10 x slots 11..15 (55)        wave 3: slots 0..10 x slots 16..20 (55)
-// The four waves read the same chunk, so the vectors come from memory once and from the cache after that.  Only one
-// operand of a product is masked (the mask is 0 or 1).  Ring slots not in use contribute zeros; the last
-// workgroup maps ring slots to the oldest-first order of the recursion.
+// are divided among three waves of a workgroup.  With the slots in three groups of seven, a = 0..6, b = 7..13,
+// c = 14..20, wave r takes group r among itself and group r times group r + 1 (cyclically):
+//     wave 0: a x a (28) + a x b (49)     wave 1: b x b + b x c     wave 2: c x c + c x a
+// -- 77 per-lane accumulators and 14 vector loads per chunk each, so the three finish together (an earlier split
+// into 66/55/55/55 entries had two waves load 16 vectors and two 10-11, and the workgroup waited 6-9 us for the
+// slow pair).  The fourth wave writes the free-set mask and sums the statistics (KKT residual, number of fixed
+// variables, full ||y_new||^2).  The waves read the same chunk, so the vectors come from memory once and from the
+// cache after that.  Only one operand of a product is masked (the mask is 0 or 1).  Ring slots not in use
+// contribute zeros; the last workgroup maps ring slots to the oldest-first order of the recursion.
 
 constexpr int kWideM = 10;
 constexpr int kWideT = 2 * kWideM + 1;
-constexpr int kWideH = 11;                                   // slots 0..10 | 11..20
-constexpr int kWideEntries = kWideT * (kWideT + 1) / 2;      // 231
+constexpr int kWideG = 7;                                    // slots per group
+constexpr int kWideDiag = kWideG * (kWideG + 1) / 2;         // 28
+constexpr int kWideRole = kWideDiag + kWideG * kWideG;       // 77 entries per wave
+constexpr int kWideEntries = kWideT * (kWideT + 1) / 2;      // 231 = 3 * 77
 constexpr int kWideNE = kHdr + kWideEntries;
-constexpr int kWideOff1 = 66, kWideOff2 = 121, kWideOff3 = 176;
+static_assert(3 * kWideG == kWideT && 3 * kWideRole == kWideEntries, "three groups of seven slots");
 
-// entry index -> static slots (a <= b)
+// entry index -> static slots (a, b)
 __device__ __forceinline__ void wide_entry_slots(int idx, int& a, int& b) {
-    if (idx < kWideOff2) {
-        const bool second = idx >= kWideOff1;
-        int q = second ? idx - kWideOff1 : idx;
-        const int T = second ? kWideT - kWideH : kWideH;
-        int r = 0;
-        while (q >= T - r) { q -= T - r; ++r; }
-        a = (second ? kWideH : 0) + r;
-        b = a + q;
+    const int r = idx / kWideRole;
+    int q = idx % kWideRole;
+    const int p0 = kWideG * r, q0 = kWideG * ((r + 1) % 3);
+    if (q < kWideDiag) {
+        int i = 0;
+        while (q >= kWideG - i) { q -= kWideG - i; ++i; }
+        a = p0 + i;
+        b = p0 + i + q;
     } else {
-        const bool second = idx >= kWideOff3;
-        const int q = idx - (second ? kWideOff3 : kWideOff2);
-        a = q / 5;
-        b = (second ? 16 : 11) + q % 5;
+        q -= kWideDiag;
+        a = p0 + q / kWideG;
+        b = q0 + q % kWideG;
     }
 }
 
 // Sums 64 per-lane values over the 64 lanes of a wave all at once: on return lane j holds the total of a[j].
 // Each step halves the number of values a lane carries (the half it gives away goes to the lane 32, 16, ... 1
 // away), so 63 exchanges do what 64 separate butterfly sums would need 384 for.  Fixed order of additions.
-template <int D>
-__device__ __forceinline__ void transpose_sum_step(double (&a)[64], int lane) {
+template <int D, int N>
+__device__ __forceinline__ void transpose_sum_step(double (&a)[N], int lane) {
     const bool upper = (lane & D) != 0;
 #pragma unroll
     for (int k = 0; k < D; ++k) {
@@ -624,6 +628,19 @@ __device__ __forceinline__ double transpose_sum64(double (&a)[64]) {
     return a[0];
 }
 
+// The same for 16 values: on return every lane l holds the total of a[l % 16].
+__device__ __forceinline__ double transpose_sum16(double (&a)[16]) {
+    const int lane = threadIdx.x & 63;
+    transpose_sum_step<8>(a, lane);
+    transpose_sum_step<4>(a, lane);
+    transpose_sum_step<2>(a, lane);
+    transpose_sum_step<1>(a, lane);
+    double t = a[0];                      // total over this row of 16 lanes
+    t += __shfl_xor(t, 16);
+    t += __shfl_xor(t, 32);
+    return t;
+}
+
 struct WideCtx {
     int64_t n;
     int m, c, base_slot;
@@ -637,13 +654,15 @@ __device__ __forceinline__ const double* wide_ptr(const WideCtx& w, int slot) {
     return w.g;
 }
 
-// One wave's share.  DIAG: the NA slots from A0 among themselves; else the NA slots from A0 times the NB slots from B0.
-template <int A0, int NA, int B0, int NBS, bool DIAG, int ROLE>
+// One wave's share.  ROLE 0..2: the seven slots from P0 among themselves and times the seven from Q0; ROLE 3: the
+// free-set mask and the statistics.  Chunks ch0, ch0 + chs, ... of 128 elements.
+template <int P0, int Q0, int ROLE, bool UB>
 __device__ __forceinline__ void wide_role(const WideCtx& w, const Opts& op, const double* __restrict__ x,
                                           const double* __restrict__ l, const double* __restrict__ u,
                                           uint8_t* __restrict__ mask, int dbg_inputs, double* __restrict__ part,
                                           int offset) {
-    constexpr int NACC = DIAG ? NA * (NA + 1) / 2 : NA * NBS;
+    constexpr bool STATS = ROLE == 3;
+    constexpr int NACC = STATS ? 1 : kWideRole;
     const int lane = threadIdx.x & 63;
     double acc[NACC];
 #pragma unroll
@@ -660,19 +679,20 @@ __device__ __forceinline__ void wide_role(const WideCtx& w, const Opts& op, cons
     };
     bool in_next;
     int64_t ec_next = pair_index(blockIdx.x, in_next);
-    const bool ub_same = op.uniform_bounds != 0;       // same bounds everywhere: l and u are not streamed
+    // UB: same bounds everywhere, l and u are not streamed (and take no registers)
     f64x2 xn = *reinterpret_cast<const f64x2*>(x + ec_next), gn = *reinterpret_cast<const f64x2*>(w.g + ec_next);
     f64x2 ln = f64x2{op.lo, op.lo}, un = f64x2{op.hi, op.hi};
-    if (!ub_same) { ln = *reinterpret_cast<const f64x2*>(l + ec_next); un = *reinterpret_cast<const f64x2*>(u + ec_next); }
+    if constexpr (!UB) { ln = *reinterpret_cast<const f64x2*>(l + ec_next); un = *reinterpret_cast<const f64x2*>(u + ec_next); }
     unsigned short mkn = dbg_inputs ? *reinterpret_cast<const unsigned short*>(mask + ec_next) : (unsigned short)0;
     for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
         const bool in = in_next;
         const int64_t ec = ec_next, e = ec_next;
-        const f64x2 xe = xn, ge = gn, le = ln, ue = un;
+        const f64x2 xe = xn, ge = gn;
+        const f64x2 le = UB ? f64x2{op.lo, op.lo} : ln, ue = UB ? f64x2{op.hi, op.hi} : un;
         const unsigned short mk = mkn;
         ec_next = pair_index(ch + gridDim.x, in_next);
         xn = *reinterpret_cast<const f64x2*>(x + ec_next); gn = *reinterpret_cast<const f64x2*>(w.g + ec_next);
-        if (!ub_same) { ln = *reinterpret_cast<const f64x2*>(l + ec_next); un = *reinterpret_cast<const f64x2*>(u + ec_next); }
+        if constexpr (!UB) { ln = *reinterpret_cast<const f64x2*>(l + ec_next); un = *reinterpret_cast<const f64x2*>(u + ec_next); }
         if (dbg_inputs) mkn = *reinterpret_cast<const unsigned short*>(mask + ec_next);
         bool f0, f1;
         if (dbg_inputs) {
@@ -682,79 +702,76 @@ __device__ __forceinline__ void wide_role(const WideCtx& w, const Opts& op, cons
             f0 = !(((xe.x <= le.x + op.eps) && (ge.x >= 0.0)) || ((xe.x >= ue.x - op.eps) && (ge.x <= 0.0)));
             f1 = !(((xe.y <= le.y + op.eps) && (ge.y >= 0.0)) || ((xe.y >= ue.y - op.eps) && (ge.y <= 0.0)));
         }
-        if (ROLE == 0 && in) {
-            if (!dbg_inputs)
-                *reinterpret_cast<unsigned short*>(mask + e) = (unsigned short)((f0 ? 1u : 0u) | (f1 ? 0x100u : 0u));
-            pginf = fmax(pginf, fmax(fabs(xe.x - clampd(xe.x - ge.x, le.x, ue.x)), fabs(xe.y - clampd(xe.y - ge.y, le.y, ue.y))));
-            nfixed += (f0 ? 0.0 : 1.0) + (f1 ? 0.0 : 1.0);
-        }
-        if (ROLE == 1 && in && w.c > 0) {
-            const f64x2 yv = *reinterpret_cast<const f64x2*>(yn_ptr + ec);
-            ynew = fma(yv.x, yv.x, ynew);
-            ynew = fma(yv.y, yv.y, ynew);
-        }
-        const double m0 = (in && f0) ? 1.0 : 0.0, m1 = (in && f1) ? 1.0 : 0.0;
-        // fixed variables contribute nothing: lanes whose two elements are both fixed (or past the end) load no vector
-        if (m0 != 0.0 || m1 != 0.0) {
-            f64x2 va[NA], vb[DIAG ? 1 : NBS];
-#pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                va[i] = f64x2{0.0, 0.0};
-                if ((w.active >> (A0 + i)) & 1u) va[i] = *reinterpret_cast<const f64x2*>(wide_ptr(w, A0 + i) + ec);
-            }
-            if (!DIAG) {
-#pragma unroll
-                for (int j = 0; j < NBS; ++j) {
-                    vb[j] = f64x2{0.0, 0.0};
-                    if ((w.active >> (B0 + j)) & 1u) vb[j] = *reinterpret_cast<const f64x2*>(wide_ptr(w, B0 + j) + ec);
+        if constexpr (STATS) {
+            if (in) {
+                if (!dbg_inputs)
+                    *reinterpret_cast<unsigned short*>(mask + e) = (unsigned short)((f0 ? 1u : 0u) | (f1 ? 0x100u : 0u));
+                pginf = fmax(pginf, fmax(fabs(xe.x - clampd(xe.x - ge.x, le.x, ue.x)), fabs(xe.y - clampd(xe.y - ge.y, le.y, ue.y))));
+                nfixed += (f0 ? 0.0 : 1.0) + (f1 ? 0.0 : 1.0);
+                if (w.c > 0) {
+                    const f64x2 yv = *reinterpret_cast<const f64x2*>(yn_ptr + ec);
+                    ynew = fma(yv.x, yv.x, ynew);
+                    ynew = fma(yv.y, yv.y, ynew);
                 }
             }
+        } else {
+            const double m0 = (in && f0) ? 1.0 : 0.0, m1 = (in && f1) ? 1.0 : 0.0;
+            // fixed variables contribute nothing: lanes whose two elements are both fixed (or past the end) load no vector
+            if (m0 != 0.0 || m1 != 0.0) {
+                f64x2 vp[kWideG], vq[kWideG];
 #pragma unroll
-            for (int i = 0; i < NA; ++i) { va[i].x *= m0; va[i].y *= m1; }
-            int k = 0;
-            if (DIAG) {
+                for (int i = 0; i < kWideG; ++i) {
+                    vp[i] = f64x2{0.0, 0.0};
+                    if ((w.active >> (P0 + i)) & 1u) vp[i] = *reinterpret_cast<const f64x2*>(wide_ptr(w, P0 + i) + ec);
+                }
 #pragma unroll
-                for (int a = 0; a < NA; ++a) {
+                for (int j = 0; j < kWideG; ++j) {
+                    vq[j] = f64x2{0.0, 0.0};
+                    if ((w.active >> (Q0 + j)) & 1u) vq[j] = *reinterpret_cast<const f64x2*>(wide_ptr(w, Q0 + j) + ec);
+                }
 #pragma unroll
-                    for (int b = a; b < NA; ++b, ++k) {
-                        acc[k] = fma(va[a].x, va[b].x, acc[k]);
-                        acc[k] = fma(va[a].y, va[b].y, acc[k]);
+                for (int i = 0; i < kWideG; ++i) { vp[i].x *= m0; vp[i].y *= m1; }
+                int k = 0;
+#pragma unroll
+                for (int a = 0; a < kWideG; ++a) {
+#pragma unroll
+                    for (int b = a; b < kWideG; ++b, ++k) {
+                        acc[k] = fma(vp[a].x, vp[b].x, acc[k]);
+                        acc[k] = fma(vp[a].y, vp[b].y, acc[k]);
                     }
                 }
-            } else {
 #pragma unroll
-                for (int a = 0; a < NA; ++a) {
+                for (int a = 0; a < kWideG; ++a) {
 #pragma unroll
-                    for (int b = 0; b < NBS; ++b, ++k) {
-                        acc[k] = fma(va[a].x, vb[b].x, acc[k]);
-                        acc[k] = fma(va[a].y, vb[b].y, acc[k]);
+                    for (int b = 0; b < kWideG; ++b, ++k) {
+                        acc[k] = fma(vp[a].x, vq[b].x, acc[k]);
+                        acc[k] = fma(vp[a].y, vq[b].y, acc[k]);
                     }
                 }
             }
         }
     }
-    // sums over the lanes: 64 accumulators at once (lane j ends up with the total of accumulator j), the rest one by one
-    double first[64];
-#pragma unroll
-    for (int k = 0; k < 64; ++k) first[k] = k < NACC ? acc[k] : 0.0;
-    const double mine = transpose_sum64(first);
-    if (lane < NACC) part[kHdr + offset + lane] = mine;
-#pragma unroll
-    for (int k = 64; k < NACC; ++k) {
-        const double t = wave_sum(acc[k]);
-        if (lane == 0) part[kHdr + offset + k] = t;
-    }
-    if (ROLE == 0) {
+    if constexpr (STATS) {
         pginf = wave_max(pginf);
         nfixed = wave_sum(nfixed);
-        if (lane == 0) { part[0] = 0.0; part[1] = pginf; part[2] = nfixed; }
-    }
-    if (ROLE == 1) {
         ynew = wave_sum(ynew);
-        if (lane == 0) part[3] = ynew;
+        if (lane == 0) { part[0] = 0.0; part[1] = pginf; part[2] = nfixed; part[3] = ynew; }
+    } else {
+        // sums over the lanes: 64 accumulators at once (lane j ends up with the total of accumulator j), then the other 13
+        double first[64];
+#pragma unroll
+        for (int k = 0; k < 64; ++k) first[k] = acc[k];
+        const double mine = transpose_sum64(first);
+        part[kHdr + offset + lane] = mine;
+        double rest[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) rest[k] = 64 + k < NACC ? acc[64 + k] : 0.0;
+        const double mine2 = transpose_sum16(rest);
+        if (lane < NACC - 64) part[kHdr + offset + 64 + lane] = mine2;
     }
 }
 
+template <bool UB>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gram_wide(int64_t n, int m, Opts op, const double* __restrict__ x,
                                                       const double* __restrict__ g, const double* __restrict__ l,
                                                       const double* __restrict__ u, const double* __restrict__ S,
@@ -792,10 +809,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
     double* part = grampart + (int64_t)blockIdx.x * kWideNE;
     switch (wave) {
-        case 0: wide_role<0, kWideH, 0, 0, true, 0>(w, op, x, l, u, mask, dbg_inputs, part, 0); break;
-        case 1: wide_role<kWideH, kWideT - kWideH, 0, 0, true, 1>(w, op, x, l, u, mask, dbg_inputs, part, kWideOff1); break;
-        case 2: wide_role<0, kWideH, 11, 5, false, 2>(w, op, x, l, u, mask, dbg_inputs, part, kWideOff2); break;
-        default: wide_role<0, kWideH, 16, 5, false, 3>(w, op, x, l, u, mask, dbg_inputs, part, kWideOff3); break;
+        case 0: wide_role<0, kWideG, 0, UB>(w, op, x, l, u, mask, dbg_inputs, part, 0); break;
+        case 1: wide_role<kWideG, 2 * kWideG, 1, UB>(w, op, x, l, u, mask, dbg_inputs, part, kWideRole); break;
+        case 2: wide_role<2 * kWideG, 0, 2, UB>(w, op, x, l, u, mask, dbg_inputs, part, 2 * kWideRole); break;
+        default: wide_role<0, 0, 3, UB>(w, op, x, l, u, mask, dbg_inputs, part, 0); break;
     }
     if (!reduce_partials(grampart, kWideNE, scal, &flag, tot)) return;
     // static slots -> the recursion's order (s oldest..newest, y oldest..newest, g)
@@ -883,8 +900,12 @@ void launch_gram_mfma(const Dims& dm, const Opts& op, const Geometry& ge, const 
 void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int dbg_inputs,
                  int evaluate_stop, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     if (gram_uses_wide(dm.n, dm.m)) {
-        hipExtLaunchKernelGGL(k_gram_wide, dim3(ge.gram_blocks), dim3(kBlock), 0, st, ev0, ev1, 0, dm.n, dm.m, op, bf.x, bf.g,
-                              bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart, dbg_inputs, evaluate_stop);
+        if (op.uniform_bounds)
+            hipExtLaunchKernelGGL(k_gram_wide<true>, dim3(ge.gram_blocks), dim3(kBlock), 0, st, ev0, ev1, 0, dm.n, dm.m, op, bf.x,
+                                  bf.g, bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart, dbg_inputs, evaluate_stop);
+        else
+            hipExtLaunchKernelGGL(k_gram_wide<false>, dim3(ge.gram_blocks), dim3(kBlock), 0, st, ev0, ev1, 0, dm.n, dm.m, op, bf.x,
+                                  bf.g, bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart, dbg_inputs, evaluate_stop);
         return;
     }
     if (gram_uses_mfma(dm.n, dm.m)) {
