@@ -28,12 +28,13 @@ struct Loader<T, 1> {
 };
 
 // Resolves the vector A multiplies: either fixed pointers, or the direction Algorithm 2 selected.
+// branch: Algorithm 2's choice when the caller has made it itself (0: read it from the scalar block)
 __device__ __forceinline__ void resolve_v(const APassArgs& a, const Scal* scal, int64_t cols, const double*& va,
-                                          const double*& vb) {
+                                          const double*& vb, int branch = 0) {
     va = a.va;
     vb = a.vb;
     if (a.select_p) {
-        va = scal->branch == 1 ? a.p1 : a.p2;
+        va = (branch ? branch : scal->branch) == 1 ? a.p1 : a.p2;
         vb = a.split ? va + cols : nullptr;
     }
 }

@@ -341,10 +341,14 @@ void enqueue_step(lbfgsb_solver* s) {
     // one or two extra rows ride along with the direction kernel; more get the kernel of their own
     const bool fold = quad && dir_folds_extra_rows(s->dm);
     const double* fold_rows = fold ? s->obj.extra_rows : nullptr;
-    launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream, fold_rows, s->obj.extra_weight);
+    // The single-read pass can make Algorithm 2's choice itself from the direction kernel's partial sums, which then
+    // needs no closing step (not with extra rows: their kernels read the choice from the scalar block)
+    const bool defer = s->use_fused && s->dm.n_extra == 0;
+    launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream, fold_rows, s->obj.extra_weight, defer ? 1 : 0);
     APassArgs a = base_args(s);
     a.select_p = 1;
     a.check_status = 1;
+    if (defer) { a.dir_part = s->bf.redpart; a.dir_blocks = s->ge.dir_blocks; a.eps = s->op.eps; }
     if (quad && s->dm.n_extra > 0 && !fold)
         launch_extra_rows(s->dm, s->bf, s->obj.extra_rows, s->obj.extra_target, s->obj.extra_weight, 0, s->stream);
     if (s->dm.kind == LBFGSB_OBJ_QP) {

@@ -267,6 +267,58 @@ __device__ __forceinline__ double softplus_diff(double q, double sq, double dq) 
     return log(sigmoid_d(-q) + sq * exp(dq));
 }
 
+// ---- Algorithm 2's choice between the two candidate directions, from the direction kernel's partial sums ----------
+//
+// Per workgroup of the direction kernel one record of kDirRed doubles: p1.g, p1.p1, x.p1, p2.g, p2.p2, x.p2, the
+// smallest step bound of p2, one unused; then e_r.p1, e_r.p2 per folded extra row.
+constexpr int kDirRed = 8 + 2 * kFoldMax;
+
+struct DirChoice {
+    int branch;              // 1: p = P(x + d) - x, step bound 1;  2: p = d with outward components zeroed
+    double gp, alpha_ub, pp, xp;
+};
+
+// The choice, computed by ONE FULL WAVE from the records of `nblocks` workgroups: lane l adds records l, l + 64, ...
+// in that order, then the fixed-order wave reductions.  Every wave that calls this on the same records gets the same
+// bits, whatever its workgroup's size, so a kernel that needs the choice can make it itself instead of waiting for a
+// last workgroup of the direction kernel to publish it (that closing step -- fences, an atomic on one address, a
+// dependent round of loads -- is about half of that kernel's duration).
+__device__ __forceinline__ DirChoice dir_choice_from_partials(const double* __restrict__ redpart, int nblocks, double eps) {
+    const int lane = threadIdx.x & 63;
+    double t6[6] = {0, 0, 0, 0, 0, 0};
+    double tmin = INFINITY;
+    for (int b0 = 0; b0 < nblocks; b0 += 2 * 64) {          // two records per lane and trip, their loads issued together
+        double v[2][7];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int b = b0 + 64 * j + lane;
+            const bool in = b < nblocks;
+            const double* r = redpart + (int64_t)(in ? b : 0) * kDirRed;
+#pragma unroll
+            for (int k = 0; k < 7; ++k) v[j][k] = r[k];
+            if (!in) {
+#pragma unroll
+                for (int k = 0; k < 6; ++k) v[j][k] = 0.0;
+                v[j][6] = INFINITY;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int k = 0; k < 6; ++k) t6[k] += v[j][k];
+            tmin = fmin(tmin, v[j][6]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 6; ++k) t6[k] = wave_sum(t6[k]);
+    tmin = wave_min(tmin);
+    DirChoice c;
+    c.branch = (t6[0] <= -eps * t6[1] && t6[1] >= eps) ? 1 : 2;
+    if (c.branch == 1) { c.gp = t6[0]; c.alpha_ub = 1.0; c.pp = t6[1]; c.xp = t6[2]; }
+    else { c.gp = t6[3]; c.alpha_ub = tmin; c.pp = t6[4]; c.xp = t6[5]; }
+    return c;
+}
+
 // ---- helpers shared by the column-wise consumers of the A pass ---------------------------------------------
 
 constexpr int kCX = 16;             // columns per workgroup
@@ -386,6 +438,12 @@ struct APassArgs {
     // (softplus(-y (z + alpha0 t)) - softplus(-y z)) into its loss partial, so that the update kernel can take the
     // Armijo decision on that step without a sweep over the margins in a kernel of its own
     int ls_first;
+    // select_p with dir_blocks > 0: the direction kernel has left its partial sums in dir_part without choosing; every
+    // workgroup of the pass makes Algorithm 2's choice itself (dir_choice_from_partials) and workgroup 0 records it in
+    // the scalar block.  dir_blocks == 0: the choice is read from the scalar block.
+    const double* dir_part;
+    int dir_blocks;
+    double eps;
 };
 
 // ev0/ev1 (both or neither): HIP events attached to the dispatch itself, so that their difference is
@@ -411,8 +469,11 @@ void launch_commit(const Dims& dm, const Buffers& bf, hipStream_t st);
 // store_d: also keep d itself (the primitive-level hooks read it; an iteration only needs the two candidates)
 bool dir_folds_extra_rows(const Dims& dm);
 // fold_rows / fold_weight: the objective's extra rows and their weights when they are to ride along (else NULL)
+// defer_choice: the kernel stops after its partial sums (no last workgroup, nothing written to the scalar block): the
+// consumer of the direction makes Algorithm 2's choice from them (APassArgs::dir_part); not with folded rows
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
-                hipStream_t st, const double* fold_rows = nullptr, const double* fold_weight = nullptr);
+                hipStream_t st, const double* fold_rows = nullptr, const double* fold_weight = nullptr,
+                int defer_choice = 0);
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
                              hipStream_t st, const double* fold_rows = nullptr);
 // extra rows: e_r.z for z = x (eval != 0: residuals against the targets) or the selected direction (eval == 0)

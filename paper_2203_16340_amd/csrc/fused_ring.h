@@ -242,9 +242,27 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     // the memory system idles).  A launch that finds the solver stopped has fetched a few rows for nothing.
 #pragma unroll
     for (int s = 0; s < NB; ++s) fetch(raw[s], (s / SPS) * R + (s % SPS) / U, (s % SPS) % U);
-    if (a.check_status && scal->status != LBFGSB_RUNNING) return;
+    // Algorithm 2's choice between the candidate directions: from the scalar block, or made here from the direction
+    // kernel's partial sums (every wave of every workgroup gets the same bits; workgroup 0 records them).  The status
+    // word is requested first and looked at afterwards, so that its trip to memory and the records' are one.
+    const int status = a.check_status ? scal->status : LBFGSB_RUNNING;
+    int branch = 0;
+    double alpha_ub = 1.0;
+    DirChoice ch{};
+    const bool own_choice = a.select_p && a.dir_blocks > 0;
+    if (own_choice) ch = dir_choice_from_partials(a.dir_part, a.dir_blocks, a.eps);
+    if (status != LBFGSB_RUNNING) return;
+    if (own_choice) {
+        branch = ch.branch;
+        alpha_ub = ch.alpha_ub;
+        if (blockIdx.x == 0 && tid == 0) {
+            scal->branch = ch.branch; scal->gp = ch.gp; scal->alpha_ub = ch.alpha_ub; scal->pp = ch.pp; scal->xp = ch.xp;
+        }
+    } else if (LOGI != 0 && a.mode == kRowLogiSpec) {
+        alpha_ub = scal->alpha_ub;
+    }
     const double *va, *vb;
-    resolve_v(a, scal, cols, va, vb);
+    resolve_v(a, scal, cols, va, vb, branch);
 
     // v into LDS, eight entries per thread and round with all their loads issued before the first is used (one
     // entry at a time this loop was a chain of dependent trips to memory: 3.5 us at 5000 columns).  The optional
@@ -291,7 +309,7 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             }
         }
     };
-    const double alpha0 = need_z ? fmin(1.0, scal->alpha_ub) : 0.0;   // first trial step of the line search
+    const double alpha0 = need_z ? fmin(1.0, alpha_ub) : 0.0;   // first trial step of the line search
     const double invn = 1.0 / (double)rows;
     double bcur[R], zcur[R];
     read_rows(bcur, zcur, 0);

@@ -38,8 +38,6 @@ void launch_clear_bail(const Buffers& bf, hipStream_t st) {
 
 // ---- d = -B delta on the free set, then Algorithm 2 ------------------------------------------------------
 
-constexpr int kDirRed = 8 + 2 * kFoldMax;   // p1.g, p1.p1, x.p1, p2.g, p2.p2, x.p2, min step bound of p2, unused; then e_r.p1, e_r.p2 per folded extra row
-
 // Extra dense rows of the objective (at most kFoldMax of them) folded into the direction kernel: their products
 // with both candidate directions ride along with the other sums, the last workgroup turns the selected one into the
 // coefficient weight_r (e_r . p) of the row's contribution to the gradient change and into the curvature term
@@ -56,7 +54,7 @@ struct FoldArgs {
 // Partial sums of the direction kernels -> Algorithm 2's choice between the two candidate directions (last workgroup).
 __device__ __forceinline__ void dir_finish(double (&s)[6], double ub, double eps, Scal* __restrict__ scal,
                                            double* __restrict__ redpart, double* red, int* flag_p,
-                                           double (&sx)[2 * kFoldMax], const FoldArgs& fold) {
+                                           double (&sx)[2 * kFoldMax], const FoldArgs& fold, int defer_choice = 0) {
     const int tid = threadIdx.x;
     block_sum<6, kWaves>(s, red);
     if (fold.n_fold > 0) block_sum<2 * kFoldMax, kWaves>(sx, red);
@@ -72,6 +70,7 @@ __device__ __forceinline__ void dir_finish(double (&s)[6], double ub, double eps
         part[6] = mn;
         for (int k = 0; k < 2 * kFoldMax; ++k) part[8 + k] = sx[k];
     }
+    if (defer_choice) return;   // the consumer of the direction chooses between the candidates from the records
     if (!arrive_is_last(&scal->counters[kCntDir], flag_p)) return;
     double tx[2 * kFoldMax];
     {
@@ -136,7 +135,8 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
                                                 const double* __restrict__ S, const double* __restrict__ Y,
                                                 Scal* __restrict__ scal, double* __restrict__ d,
                                                 double* __restrict__ p1, double* __restrict__ p2,
-                                                double* __restrict__ redpart, int d_given, int store_d, FoldArgs fold) {
+                                                double* __restrict__ redpart, int d_given, int store_d, FoldArgs fold,
+                                                int defer_choice) {
     __shared__ double delta_s[kMaxV + 8];
     __shared__ const double* vecp[kMaxV + 8];
     __shared__ double red[kWaves * 7];
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
             }
         }
     }
-    dir_finish(s, ub, op.eps, scal, redpart, red, &flag, sx, fold);
+    dir_finish(s, ub, op.eps, scal, redpart, red, &flag, sx, fold, defer_choice);
 }
 
 // The same for long vectors (n even, from 2^17 entries on): two elements per lane through 16-byte accesses; lanes
@@ -219,7 +219,8 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
                                                       const double* __restrict__ S, const double* __restrict__ Y,
                                                       Scal* __restrict__ scal, double* __restrict__ d,
                                                       double* __restrict__ p1, double* __restrict__ p2,
-                                                      double* __restrict__ redpart, int d_given, int store_d) {
+                                                      double* __restrict__ redpart, int d_given, int store_d,
+                                                      int defer_choice) {
     __shared__ double delta_s[kMaxV + 24];
     __shared__ double red[kWaves * 7];
     __shared__ int flag;
@@ -290,7 +291,7 @@ __global__ __launch_bounds__(kBlock) void k_dir_pairs(int64_t n, int m, Opts op,
     double sx[2 * kFoldMax];
 #pragma unroll
     for (int k = 0; k < 2 * kFoldMax; ++k) sx[k] = 0.0;
-    dir_finish(s, ub, op.eps, scal, redpart, red, &flag, sx, FoldArgs{0, nullptr, nullptr, nullptr, nullptr});
+    dir_finish(s, ub, op.eps, scal, redpart, red, &flag, sx, FoldArgs{0, nullptr, nullptr, nullptr, nullptr}, defer_choice);
 }
 
 // extra rows can ride along with the direction kernel for short vectors only
@@ -299,16 +300,17 @@ bool dir_folds_extra_rows(const Dims& dm) {
 }
 
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
-                hipStream_t st, const double* fold_rows, const double* fold_weight) {
+                hipStream_t st, const double* fold_rows, const double* fold_weight, int defer_choice) {
     FoldArgs fold{0, nullptr, nullptr, nullptr, nullptr};
     if (fold_rows && dir_folds_extra_rows(dm)) fold = FoldArgs{dm.n_extra, fold_rows, fold_weight, bf.wextra, bf.xres + dm.n_extra};
+    if (fold.n_fold > 0) defer_choice = 0;   // (the folded rows' coefficients are the last workgroup's work)
     if (dm.n >= (1 << 17) && dm.n % 2 == 0) {
         hipLaunchKernelGGL(k_dir_pairs, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u,
-                           bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d);
+                           bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, defer_choice);
         return;
     }
     hipLaunchKernelGGL(k_dir, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u, bf.mask,
-                       bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, fold);
+                       bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, fold, defer_choice);
 }
 
 // ---- after an evaluation pass: g and f ------------------------------------------------------------------
