@@ -394,11 +394,22 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             par ^= 1;
         }
     }
+    if constexpr (TRANS) {
+        double* out = wpart + (int64_t)blockIdx.x * cols + c0;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            if (c0 + k * kStride < icols) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) out[k * kStride + j] = w[k][j];
+            }
+        }
+    }
     if constexpr (LOGI == 2) {
         // First trial step of the line search: this workgroup's share of sum_r softplus(-y (z + alpha0 t)) - softplus(-y z)
         // over its own rows, from the (q, dq) the row loop left in LDS.  Done here, after the row loop, where nothing
         // waits for it and no trip to memory is needed, so that the Armijo decision on that step takes no sweep over
-        // the margins in a kernel of its own.
+        // the margins in a kernel of its own.  (The partial columns are already on their way: their stores were
+        // issued above and drain meanwhile.)
         if (lsq) {
             __syncthreads();
             const int nloc = (int)(r_end - r_begin);
@@ -416,16 +427,6 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             }
             loss = wave_sum(s2[0] + s2[1]);
             if (lane == 0) red[wave] = loss;
-        }
-    }
-    if constexpr (TRANS) {
-        double* out = wpart + (int64_t)blockIdx.x * cols + c0;
-#pragma unroll
-        for (int k = 0; k < KC; ++k) {
-            if (c0 + k * kStride < icols) {
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) out[k * kStride + j] = w[k][j];
-            }
         }
     }
     if constexpr (LOGI == 2) {
