@@ -287,37 +287,20 @@ __device__ __forceinline__ bool reduce_partials(double* __restrict__ grampart, i
     if (nwg <= kGramOneLevelMax) {
         // few workgroups: one level, the last one to finish adds all partials in index order
         if (!arrive_is_last(&scal->gram_cnt[kGramGroups], flag, (unsigned)nwg)) return false;
-        if (nwg <= 2 * kGramGroupMax) {
-            // up to 64 partials: every load of an entry is issued before the first is used (one trip to memory)
-            for (int idx = tid; idx < NE; idx += kBlock) {
+        // 64 partials of an entry at a time, every load of a batch issued before the first is used (one trip to
+        // memory per batch; the accumulators' registers are free by now)
+        for (int idx = tid; idx < NE; idx += kBlock) {
+            double t = idx == 1 ? -INFINITY : 0.0;
+            for (int k0 = 0; k0 < nwg; k0 += 2 * kGramGroupMax) {
                 double v[2 * kGramGroupMax];
 #pragma unroll
-                for (int k = 0; k < 2 * kGramGroupMax; ++k) v[k] = k < nwg ? grampart[(int64_t)k * NE + idx] : (idx == 1 ? -INFINITY : 0.0);
-                double t = idx == 1 ? -INFINITY : 0.0;
+                for (int k = 0; k < 2 * kGramGroupMax; ++k) v[k] = k0 + k < nwg ? grampart[(int64_t)(k0 + k) * NE + idx] : (idx == 1 ? -INFINITY : 0.0);
                 if (idx == 1) {
 #pragma unroll
                     for (int k = 0; k < 2 * kGramGroupMax; ++k) t = fmax(t, v[k]);
                 } else {
 #pragma unroll
                     for (int k = 0; k < 2 * kGramGroupMax; ++k) t += v[k];
-                }
-                tot[idx] = t;
-            }
-            __syncthreads();
-            return true;
-        }
-        for (int idx = tid; idx < NE; idx += kBlock) {
-            double t = idx == 1 ? -INFINITY : 0.0;
-            for (int k0 = 0; k0 < nwg; k0 += kGramGroupMax) {
-                double v[kGramGroupMax];
-#pragma unroll
-                for (int k = 0; k < kGramGroupMax; ++k) v[k] = k0 + k < nwg ? grampart[(int64_t)(k0 + k) * NE + idx] : (idx == 1 ? -INFINITY : 0.0);
-                if (idx == 1) {
-#pragma unroll
-                    for (int k = 0; k < kGramGroupMax; ++k) t = fmax(t, v[k]);
-                } else {
-#pragma unroll
-                    for (int k = 0; k < kGramGroupMax; ++k) t += v[k];
                 }
             }
             tot[idx] = t;

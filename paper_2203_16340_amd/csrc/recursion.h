@@ -32,6 +32,14 @@ __device__ __forceinline__ void recursion_on_coefficients(const double* G, int V
     const int tid = threadIdx.x, lane = tid & 63;
     if (tid < 64) {
         const int i = lane;   // lane i owns pair i (oldest = 0)
+        // what the stopping test at the end reads from the scalar block, requested now: behind the recursion these
+        // were three dependent trips (each read sits under a test of the one before)
+        int tol_resolved = 1, status0 = LBFGSB_RUNNING;
+        double tol_abs0 = 0.0;
+        long long iters0 = 0;
+        if (lane == 0 && evaluate_stop) {
+            tol_resolved = scal->tol_resolved; status0 = scal->status; tol_abs0 = scal->tol_abs; iters0 = scal->iters;
+        }
         double rho = 1.0, yn = 1.0, inv = 0.0;
         bool pass = false;
         if (i < c) {
@@ -126,13 +134,14 @@ __device__ __forceinline__ void recursion_on_coefficients(const double* G, int V
                 scal->pg2 = pgn;
                 scal->pginf = pginf;
                 scal->n_fixed = (long long)nfixed;
-                if (!scal->tol_resolved) {
-                    scal->tol_abs = op.tol_relative ? op.tol * fmax(1.0, pgn) : op.tol;
+                if (!tol_resolved) {
+                    tol_abs0 = op.tol_relative ? op.tol * fmax(1.0, pgn) : op.tol;
+                    scal->tol_abs = tol_abs0;
                     scal->tol_resolved = 1;
                 }
-                if (scal->status == LBFGSB_RUNNING) {
-                    if (pgn <= scal->tol_abs) scal->status = LBFGSB_CONVERGED;
-                    else if (scal->iters >= op.max_iter) scal->status = LBFGSB_MAX_ITER;
+                if (status0 == LBFGSB_RUNNING) {
+                    if (pgn <= tol_abs0) scal->status = LBFGSB_CONVERGED;
+                    else if (iters0 >= op.max_iter) scal->status = LBFGSB_MAX_ITER;
                 }
             }
         }
