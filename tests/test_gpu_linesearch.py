@@ -145,6 +145,29 @@ def test_steps_enqueued_without_waiting_survive_rejected_first_steps(case):
     a.close(); b.close()
 
 
+def test_a_very_tall_matrix_takes_the_full_logistic_sequence():
+    """The short launch sequence keeps two numbers per row of a workgroup in LDS; with more than about ten thousand
+    rows per workgroup (here 5.3 million rows of 8 columns: 512 workgroups) they do not fit, and the library has to
+    fall back to the full sequence instead of asking for more LDS than a workgroup can have.  Steps enqueued without
+    waiting, steps with an info struct and the oracle must agree."""
+    prob = workloads.logistic(rows=5_300_000, cols=8, seed=11, dtype=np.float32, label_noise=0.5, mu=1e-3, bound=0.5, m=5)
+    a = L.solver_for_problem(prob, DEV, tol=0.0, a_pass=L.APASS_FUSED)
+    b = L.solver_for_problem(prob, DEV, tol=0.0, a_pass=L.APASS_FUSED)
+    assert a.apass_name == "fused"
+    for _ in range(4):
+        a.step(want_info=False)
+        b.step()
+    ia, ib = a.info(), b.info()
+    assert ia.iters == ib.iters == 4 and ia.status == ib.status == L.RUNNING
+    assert torch.equal(a.x(), b.x()) and torch.equal(a.g(), b.g())
+    orc = _oracle_solver(prob, tol=0.0)
+    for _ in range(4):
+        orc.step()
+    assert rel_err(a.x().cpu().numpy(), orc.x) <= 1e-6
+    assert ia.f == pytest.approx(orc.info.f, rel=1e-6)
+    orc.close(); a.close(); b.close()
+
+
 # ---- exhausted searches ---------------------------------------------------------------------------------------------
 
 def _hand_solver(a_diag, b, max_backtracks, a_pass):
