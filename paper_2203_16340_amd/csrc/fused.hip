@@ -58,19 +58,25 @@ void launch_variant(const Dims& dm, int64_t rows_per_wg, int blocks, size_t lds,
 // pass of the logistic objective has its own instantiation with the deepest ring that does not spill.
 const Variant kVariants[] = {
     LB_VARIANT(LBFGSB_F64, 0, double, 256, 2, 1, 2, 4, 4, 4),    // cols <=  1024
+    LB_VARIANT(LBFGSB_F64, 0, double, 512, 2, 1, 4, 8, 2, 1),    // cols <=  2048
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 5, 1, 2, 4, 2, 1),    // cols <=  5120
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 10, 1, 1, 2, 2, 1),   // cols <= 10240
     LB_VARIANT(LBFGSB_F64, 0, double, 512, 20, 1, 1, 1, 2, 1),   // cols <= 20480 (LDS: <= 20428)
     LB_VARIANT_KR(LBFGSB_F64, 0, double, 512, 22, 1, 1, 1, 2, 1, 3),   // cols <= 22528, v of the last 3 chunks in registers
     LB_VARIANT_KR(LBFGSB_F64, 0, double, 512, 24, 1, 1, 1, 2, 1, 5),   // cols <= 24576, v of the last 5 chunks in registers
+    LB_VARIANT(LBFGSB_F32, 0, float, 128, 1, 1, 2, 4, 4, 8),     // cols <=   512
     LB_VARIANT(LBFGSB_F32, 0, float, 256, 1, 1, 2, 4, 4, 4),     // cols <=  1024
+    LB_VARIANT(LBFGSB_F32, 0, float, 256, 2, 1, 4, 12, 2, 2),    // cols <=  2048 (the geometry of the logistic direction pass)
     LB_VARIANT(LBFGSB_F32, 0, float, 256, 5, 1, 1, 2, 2, 2),     // cols <=  5120
     LB_VARIANT(LBFGSB_F32, 0, float, 512, 5, 1, 2, 4, 2, 1),     // cols <= 10240
     LB_VARIANT(LBFGSB_F32, 0, float, 512, 10, 1, 1, 2, 2, 1),    // cols <= 20480 (LDS: <= 20428)
     //              (…, R, ring depth of the evaluation kernel, of the direction kernel, …)
     LB_VARIANT_LOGI(LBFGSB_F64, double, 256, 2, 1, 4, 8, 12, 2, 2),    // cols <=  1024
+    LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 2, 1, 4, 4, 8, 2, 1),     // cols <=  2048
     LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 5, 1, 1, 2, 4, 2, 1),     // cols <=  5120
     LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 10, 1, 1, 1, 2, 2, 1),    // cols <= 10240
+    LB_VARIANT_LOGI(LBFGSB_F32, float, 128, 1, 1, 2, 4, 8, 4, 8),      // cols <=   512
+    LB_VARIANT_LOGI(LBFGSB_F32, float, 256, 1, 1, 2, 4, 8, 4, 4),      // cols <=  1024
     LB_VARIANT_LOGI(LBFGSB_F32, float, 256, 2, 1, 4, 8, 12, 2, 2),     // cols <=  2048
     LB_VARIANT_LOGI(LBFGSB_F32, float, 256, 5, 1, 1, 2, 4, 2, 2),      // cols <=  5120
     LB_VARIANT_LOGI(LBFGSB_F32, float, 512, 5, 1, 1, 2, 4, 2, 1),      // cols <= 10240
