@@ -213,12 +213,14 @@ __device__ __forceinline__ void effective_ring(const Scal* s, int m, int& head, 
 // One record per accepted iteration, written by the thread that has just completed the iteration's bookkeeping:
 // the scalar block then holds the stopping quantities of the iterate the iteration started from (the next free-set
 // pass has not run yet), the direction's branch and bound, and the accepted step.
-__device__ __forceinline__ void record_iteration(Scal* s) {
-    if (!s->hist) return;
-    lbfgsb_iter_record* r = s->hist + (s->hist_count % LBFGSB_HISTORY_CAPACITY);
+__device__ __forceinline__ void fill_record(const Scal* s, lbfgsb_iter_record* r) {
     r->iter = s->iters; r->f = s->f; r->pg2 = s->pg2; r->pginf = s->pginf; r->n_fixed = s->n_fixed;
     r->alpha = s->alpha; r->alpha_ub = s->alpha_ub; r->gp = s->gp;
     r->branch = s->branch; r->backtracks = s->backtracks; r->pairs_used = s->pairs_used; r->memory_resets = s->memory_resets;
+}
+__device__ __forceinline__ void record_iteration(Scal* s) {
+    if (!s->hist) return;
+    fill_record(s, s->hist + (s->hist_count % LBFGSB_HISTORY_CAPACITY));
     s->hist_count += 1;
 }
 

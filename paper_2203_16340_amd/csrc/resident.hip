@@ -13,8 +13,9 @@
 //   * every phase is the arithmetic of the corresponding kernel of the multi-kernel path (Eq. (ws), masked Gram matrix,
 //     Algorithm 3 on coefficients -- the same device function --, Algorithm 2 with both candidate directions, the
 //     closed-form Armijo search of the quadratic objectives, update and pair storage), with its own fixed summation
-//     orders; iterate, gradient and new pair are also written through to device memory every iteration, the scalar
-//     block and the free mask when the launch ends, so the other entry points find the state they expect.
+//     orders; iterate, gradient, pair memory, free mask and the scalar block go to device memory when the launch
+//     ends, so the other entry points find the state they expect (the per-iteration records are written as they arise:
+//     keeping them in LDS until the end measured slower).
 // The gradient is carried by recurrence as on the multi-kernel path; it is recomputed from x every refresh_every
 // iterations and before convergence is declared.
 #include "common.h"
@@ -312,7 +313,7 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
         }
         if (want_eval) {
             gi = wi;
-            if (act) { gs[tid] = gi; a.g[tid] = gi; }
+            if (act) gs[tid] = gi;
             if (tid == 0) { sc.f = 0.5 * tt; sc.fevals += 1; sc.since_refresh = 0; }
             since = 0;
             want_eval = false;
@@ -344,10 +345,6 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
                 Ys[slot * np + tid] = y;
                 xs[tid] = xi;
                 gs[tid] = gi;
-                a.S[(int64_t)slot * n + tid] = sn;
-                a.Y[(int64_t)slot * n + tid] = y;
-                a.x[tid] = xi;
-                a.g[tid] = gi;
                 ysq = y * y;
             }
             ysq = wave_sum(ysq);
@@ -385,9 +382,17 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
         else if (c > 0) c = 0;
     }
 
-    // ---- state the other entry points read: the scalar block and the free mask
+    // ---- state the other entry points read: iterate, gradient, pair memory, free mask and the scalar block.  Written
+    // once, here: a store to device memory inside the loop is waited for at the next barrier (the barrier orders
+    // memory for the workgroup), which costs every iteration a trip to memory for values nobody reads before the
+    // launch has ended.
     __syncthreads();
-    if (act) a.mask[tid] = mi != 0.0 ? 1 : 0;
+    if (act) { a.x[tid] = xi; a.g[tid] = gi; a.mask[tid] = mi != 0.0 ? 1 : 0; }
+    for (int i = tid; i < m * n; i += kResThreads) {
+        const int sl = i / n, e = i - sl * n;
+        a.S[i] = Ss[sl * np + e];
+        a.Y[i] = Ys[sl * np + e];
+    }
     for (int k = tid; k < (int)(sizeof(Scal) / 4); k += kResThreads)
         reinterpret_cast<int*>(a.scal)[k] = reinterpret_cast<const int*>(&sc)[k];
 }
