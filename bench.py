@@ -346,7 +346,7 @@ def host_cpu_description() -> dict:
     return {"nproc": os.cpu_count(), "cpu_model": model}
 
 
-# SURVEY's algorithmic bytes per iteration: one read of the matrix per iteration on the fused path (two on the
+# Algorithmic bytes per iteration: one read of the matrix per iteration on the fused path (two on the
 # two-pass path: the kernels then request the matrix twice); the vector traffic is below 0.5 % and left out.
 def bytes_per_iteration(prob, apass_name: str) -> float:
     passes = 1.0 if apass_name == "fused" else 2.0
