@@ -112,6 +112,48 @@ def test_first_iterations_match_step_by_step(name, scale, a_pass):
     orc.close(); s.close()
 
 
+def _width_case(case):
+    kind, dtype, rows, cols = case
+    if kind == "nnls":
+        return workloads.nnls(rows, cols, seed=900 + cols, dtype=dtype, zero_frac=0.6, nonzero="uniform", m=6)
+    if kind == "l1":
+        return workloads.l1_split(rows, cols, seed=900 + cols, m=6)
+    return workloads.logistic(rows, cols, seed=900 + cols, dtype=dtype, mu=1e-3, bound=0.5, m=6)
+
+
+@pytest.mark.parametrize("case", [
+    # widths between the tuned configurations: each takes a variant of the single-read pass of its own
+    ("nnls", np.float64, 2300, 1500),      # fp64, 1025..2048 columns: 512-thread workgroups, two chunks per thread
+    ("l1", np.float64, 900, 1800),         # the same variant with v = p - q
+    ("nnls", np.float32, 1500, 300),       # fp32 up to 512 columns: 128-thread workgroups
+    ("nnls", np.float32, 2500, 1800),      # fp32, 1025..2048 columns
+    ("logistic", np.float64, 2500, 1200),  # logistic, fp64, 1025..2048 columns
+    ("logistic", np.float32, 3000, 400),   # logistic, fp32 up to 512 columns
+    ("logistic", np.float32, 3000, 900),   # logistic, fp32 up to 1024 columns
+], ids=lambda c: f"{c[0]}-{np.dtype(c[1]).name}-{c[2]}x{c[3]}")
+def test_first_iterations_on_the_widths_between_the_tuned_ones(case):
+    """Iterations 1-4 against the oracle on the single-read pass (direction passes, deferred choice of Algorithm 2's
+    branch, the short logistic sequence), each width on the pass's variant for it."""
+    prob = _width_case(case)
+    obj = oracle.Objective(prob.kind, prob.A, prob.b, prob.lam, prob.mu)
+    orc = oracle.Solver(obj, prob.l, prob.u, prob.x0, prob.m, oracle.default_options(tol=0.0))
+    s = _gpu_solver(prob, L.APASS_FUSED, tol=0.0)
+    assert s.apass_name == "fused"
+    tol = 1e-10 if prob.A.dtype == np.float64 else 1e-6
+    for k in range(4):
+        assert orc.step() == oracle.RUNNING
+        info = s.step()
+        oi = orc.info
+        assert info.status == L.RUNNING and info.iters == k + 1
+        assert (info.branch, info.backtracks, info.pairs_used) == (oi.branch, oi.backtracks, oi.pairs_used)
+        assert info.alpha == pytest.approx(oi.alpha, rel=1e-12)
+        assert info.gp == pytest.approx(oi.gp, rel=tol)
+        assert info.f == pytest.approx(oi.f, rel=tol)
+        assert rel_err(s.x().cpu().numpy(), orc.x) <= tol
+        assert rel_err(s.g().cpu().numpy(), orc.g) <= tol * 10
+    orc.close(); s.close()
+
+
 @pytest.mark.parametrize("name,scale,a_pass", [("C1", 1.0, L.APASS_AUTO), ("C2", 0.05, L.APASS_FUSED), ("C2", 0.05, L.APASS_TWO_PASS),
                                                ("C3", 0.03, L.APASS_AUTO), ("C4", 0.01, L.APASS_FUSED), ("C4", 0.01, L.APASS_TWO_PASS)])
 def test_history_ring_holds_what_each_step_reported(name, scale, a_pass):
