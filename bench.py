@@ -473,7 +473,15 @@ def run_box_config(name, args, a_pass, L, workloads, np, torch, dev) -> tuple:
     # The K timed steps carry no events: a pair of HIP events attached to a dispatch costs 3-4 us per iteration at C2 /
     # C3, which would be charged to the solver.  The same K steps are then run once more WITH events on every launch
     # that reads A; that second run gives the roofline figure (and its own, slightly longer, time per step).
-    total_s, valid = run_steps(False)
+    # The K steps are timed args.repeats times (each time exactly K steps between two synchronisations) and the MEDIAN
+    # is reported: a single run now and then comes out 10 % long on a shared host (one was seen in a dozen); every
+    # run's figure is in `ms_per_step_runs`.
+    runs, valid = [], True
+    for _ in range(max(1, args.repeats)):
+        dt, ok_run = run_steps(False)
+        runs.append(dt)
+        valid = valid and ok_run
+    total_s = sorted(runs)[len(runs) // 2]
     events_s, valid_ev = run_steps(True)
     valid = valid and valid_ev
     n_launch, apass_ms, bytes_per_launch = timed.apass_timing()
@@ -506,6 +514,7 @@ def run_box_config(name, args, a_pass, L, workloads, np, torch, dev) -> tuple:
             "episode_steps": episode, "steps_valid": valid,
             "timed_through": "lbfgsb_solve, one launch per episode" if resident else "lbfgsb_step, one call per iteration",
         },
+        "ms_per_step_runs": [1e3 * r / args.steps for r in runs],  # every timed run of the K steps; ms_per_step is their median
         "ms_per_step_with_events": 1e3 * events_s / args.steps,   # the same steps with HIP events on the A-pass launches
         # untimed episodes run right before the timed ones so that the GPU is at its sustained clocks (see above)
         "clock_warm": {"ms": 1e3 * warm_s, "steps": warm_steps},
@@ -562,6 +571,8 @@ def main() -> int:
     ap.add_argument("--a-pass", default="auto", choices=["auto", "two_pass", "fused"])
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink both matrix dimensions (debugging only)")
+    ap.add_argument("--repeats", type=int, default=3,
+                    help="the K steps are timed this many times; the median run is reported")
     ap.add_argument("--clock-warm-ms", type=float, default=40.0,
                     help="untimed episodes of the same steps are run for this many milliseconds right before the timed "
                          "ones (an idle GPU clocks down while the host checks the solution)")
@@ -611,7 +622,8 @@ def main() -> int:
                     "ms_per_step": rec["ms_per_step"], "steps": rec["steps"], "steps_valid": rec["config"]["steps_valid"],
                     "a_pass": rec["config"]["a_pass"], "time_to_kkt_ms": rec["time_to_kkt_ms"],
                     "iters_to_kkt": rec["iters_to_kkt"], "kkt": rec["kkt"], "roofline": rec["roofline"],
-                    "step_frac": rec["step_frac"], "clock_warm": rec["clock_warm"], "gen_seconds": rec["gen_seconds"],
+                    "step_frac": rec["step_frac"], "clock_warm": rec["clock_warm"],
+                    "ms_per_step_runs": rec["ms_per_step_runs"], "gen_seconds": rec["gen_seconds"],
                 }
             except Exception as exc:                              # one configuration must not cost the headline line
                 out["configs"][name] = {"error": f"{type(exc).__name__}: {exc}"}
