@@ -75,6 +75,7 @@ const Variant kVariants[] = {
     LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 2, 1, 4, 4, 8, 2, 1),     // cols <=  2048
     LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 5, 1, 1, 2, 4, 2, 1),     // cols <=  5120
     LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 10, 1, 1, 1, 2, 2, 1),    // cols <= 10240
+    LB_VARIANT_LOGI(LBFGSB_F64, double, 512, 20, 1, 1, 1, 1, 2, 1),    // cols <= 20480 (LDS: <= 20428)
     LB_VARIANT_LOGI(LBFGSB_F32, float, 128, 1, 1, 2, 4, 8, 4, 8),      // cols <=   512
     LB_VARIANT_LOGI(LBFGSB_F32, float, 256, 1, 1, 2, 4, 8, 4, 4),      // cols <=  1024
     LB_VARIANT_LOGI(LBFGSB_F32, float, 256, 2, 1, 4, 8, 12, 2, 2),     // cols <=  2048
