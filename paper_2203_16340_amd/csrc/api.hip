@@ -328,9 +328,11 @@ void enqueue_step(lbfgsb_solver* s) {
             TimedSlot ts(s, s->steps_since_set_x >= s->dm.m);
             launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream, ts.e0, ts.e1);
         }
-        launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream);
+        // (the direction kernel ends without its closing step: the row-sum kernel, the first to need Algorithm 2's
+        // choice, makes it from the per-workgroup sums)
+        launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream, nullptr, nullptr, 1);
         const OtArgs oa = ot_args(s);
-        launch_ot_sums(s->dm, s->ge, s->bf, oa, 0, 1, s->stream);
+        launch_ot_sums(s->dm, s->ge, s->bf, oa, 0, 1, s->stream, s->ge.dir_blocks, s->op.eps);
         if (quad) launch_ot_update_gauss(s->dm, s->op, s->ge, s->bf, oa, s->stream);
         else launch_ot_step_entropy(s->dm, s->op, s->ge, s->bf, oa, s->stream);
         s->steps_since_refresh++;

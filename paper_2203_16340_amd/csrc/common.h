@@ -321,6 +321,50 @@ __device__ __forceinline__ DirChoice dir_choice_from_partials(const double* __re
     return c;
 }
 
+// The same choice made by a whole workgroup of kBlock threads: thread t adds records t, t + kBlock, ... (their loads
+// issued together), then the fixed-order sums over the workgroup; every thread gets the result.  lds: kWaves * 7 doubles.
+__device__ __forceinline__ DirChoice dir_choice_block(const double* __restrict__ redpart, int nblocks, double eps,
+                                                      double* lds) {
+    const int tid = threadIdx.x;
+    double t6[6] = {0, 0, 0, 0, 0, 0};
+    double tmin = INFINITY;
+    for (int b0 = 0; b0 < nblocks; b0 += 2 * kBlock) {
+        double v[2][7];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int b = b0 + kBlock * j + tid;
+            const bool in = b < nblocks;
+            const double* r = redpart + (int64_t)(in ? b : 0) * kDirRed;
+#pragma unroll
+            for (int k = 0; k < 7; ++k) v[j][k] = r[k];
+            if (!in) {
+#pragma unroll
+                for (int k = 0; k < 6; ++k) v[j][k] = 0.0;
+                v[j][6] = INFINITY;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int k = 0; k < 6; ++k) t6[k] += v[j][k];
+            tmin = fmin(tmin, v[j][6]);
+        }
+    }
+    block_sum<6, kWaves>(t6, lds);
+    tmin = wave_min(tmin);
+    __syncthreads();
+    if ((tid & 63) == 0) lds[tid >> 6] = tmin;
+    __syncthreads();
+    tmin = lds[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) tmin = fmin(tmin, lds[w]);
+    DirChoice c;
+    c.branch = (t6[0] <= -eps * t6[1] && t6[1] >= eps) ? 1 : 2;
+    if (c.branch == 1) { c.gp = t6[0]; c.alpha_ub = 1.0; c.pp = t6[1]; c.xp = t6[2]; }
+    else { c.gp = t6[3]; c.alpha_ub = tmin; c.pp = t6[4]; c.xp = t6[5]; }
+    return c;
+}
+
 // ---- helpers shared by the column-wise consumers of the A pass ---------------------------------------------
 
 constexpr int kCX = 16;             // columns per workgroup
@@ -503,8 +547,10 @@ struct OtArgs {
     const double* beta;
     const double* omega;
 };
+// dir_blocks > 0 (direction sums only): the direction kernel has left its partial sums in Buffers::redpart without
+// choosing between Algorithm 2's candidates; the row-sum kernel makes the choice and records it in the scalar block
 void launch_ot_sums(const Dims& dm, const Geometry& ge, const Buffers& bf, const OtArgs& a, int eval, int check_status,
-                    hipStream_t st);
+                    hipStream_t st, int dir_blocks = 0, double eps = 0.0);
 void launch_ot_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, const OtArgs& a, hipStream_t st);
 void launch_ot_update_gauss(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const OtArgs& a,
                             hipStream_t st);

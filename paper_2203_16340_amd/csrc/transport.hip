@@ -35,13 +35,27 @@ __device__ __forceinline__ double reg_slope(int kind, double lambda, double p) {
 template <int RPW>
 __global__ __launch_bounds__(kBlock) void k_ot_sums(Dims dm, OtArgs a, int eval, int check_status,
                                                     const double* __restrict__ x, const double* __restrict__ p1,
-                                                    const double* __restrict__ p2, const Scal* __restrict__ scal,
+                                                    const double* __restrict__ p2, Scal* __restrict__ scal,
                                                     double* __restrict__ out, double* __restrict__ wpart,
-                                                    double* __restrict__ losspart) {
-    __shared__ double red[kWaves * (RPW + 1)];
-    if (check_status && scal->status != LBFGSB_RUNNING) return;
-    const double* z = eval ? x : (scal->branch == 1 ? p1 : p2);
+                                                    double* __restrict__ losspart, const double* __restrict__ dir_part,
+                                                    int dir_blocks, double eps) {
+    __shared__ double red[kWaves * (RPW + 1 > 7 ? RPW + 1 : 7)];
     const int tid = threadIdx.x;
+    const int status = check_status ? scal->status : LBFGSB_RUNNING;
+    const double* z = x;
+    if (!eval && dir_blocks > 0) {
+        // Algorithm 2's choice from the direction kernel's per-workgroup sums (requested together with the status
+        // word); workgroup 0 records it for the kernels that follow
+        const DirChoice ch = dir_choice_block(dir_part, dir_blocks, eps, red);
+        if (status != LBFGSB_RUNNING) return;
+        if (blockIdx.x == 0 && tid == 0) {
+            scal->branch = ch.branch; scal->gp = ch.gp; scal->alpha_ub = ch.alpha_ub; scal->pp = ch.pp; scal->xp = ch.xp;
+        }
+        z = ch.branch == 1 ? p1 : p2;
+    } else {
+        if (status != LBFGSB_RUNNING) return;
+        if (!eval) z = scal->branch == 1 ? p1 : p2;
+    }
     const int64_t r0 = (int64_t)blockIdx.x * RPW;
     const int nr = dm.rows - r0 < RPW ? (int)(dm.rows - r0) : RPW;
     double acc[RPW + 1];   // row sums, then the objective terms of these entries
@@ -372,22 +386,22 @@ __global__ void k_ot_res_axpy(int64_t count, const double* __restrict__ t, doubl
 
 template <int RPW>
 void launch_sums_t(const Dims& dm, const Geometry& ge, const Buffers& bf, const OtArgs& a, int eval, int check_status,
-                   hipStream_t st) {
+                   hipStream_t st, int dir_blocks, double eps) {
     hipLaunchKernelGGL(k_ot_sums<RPW>, dim3(ge.ot_row_blocks), dim3(kBlock), 0, st, dm, a, eval, check_status,
-                       (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, (const Scal*)bf.scal,
-                       eval ? bf.row : bf.t, bf.wpart, bf.losspart);
+                       (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, bf.scal, eval ? bf.row : bf.t,
+                       bf.wpart, bf.losspart, (const double*)bf.redpart, eval ? 0 : dir_blocks, eps);
 }
 
 }  // namespace
 
 void launch_ot_sums(const Dims& dm, const Geometry& ge, const Buffers& bf, const OtArgs& a, int eval, int check_status,
-                    hipStream_t st) {
+                    hipStream_t st, int dir_blocks, double eps) {
     switch (ge.ot_rpw) {
-        case 1: launch_sums_t<1>(dm, ge, bf, a, eval, check_status, st); break;
-        case 2: launch_sums_t<2>(dm, ge, bf, a, eval, check_status, st); break;
-        case 4: launch_sums_t<4>(dm, ge, bf, a, eval, check_status, st); break;
-        case 8: launch_sums_t<8>(dm, ge, bf, a, eval, check_status, st); break;
-        default: launch_sums_t<kOtRpwMax>(dm, ge, bf, a, eval, check_status, st); break;
+        case 1: launch_sums_t<1>(dm, ge, bf, a, eval, check_status, st, dir_blocks, eps); break;
+        case 2: launch_sums_t<2>(dm, ge, bf, a, eval, check_status, st, dir_blocks, eps); break;
+        case 4: launch_sums_t<4>(dm, ge, bf, a, eval, check_status, st, dir_blocks, eps); break;
+        case 8: launch_sums_t<8>(dm, ge, bf, a, eval, check_status, st, dir_blocks, eps); break;
+        default: launch_sums_t<kOtRpwMax>(dm, ge, bf, a, eval, check_status, st, dir_blocks, eps); break;
     }
     hipLaunchKernelGGL(k_ot_cols, dim3(ge.ot_col_blocks), dim3(kBlock), 0, st, dm, a, eval, check_status, ge.ot_row_blocks,
                        (const double*)bf.wpart, (const Scal*)bf.scal, eval ? bf.row : bf.t, bf.losspart + ge.ot_row_blocks);
