@@ -344,13 +344,17 @@ void enqueue_step(lbfgsb_solver* s) {
     const bool fold = quad && dir_folds_extra_rows(s->dm);
     const double* fold_rows = fold ? s->obj.extra_rows : nullptr;
     // The single-read pass can make Algorithm 2's choice itself from the direction kernel's partial sums, which then
-    // needs no closing step (not with extra rows: their kernels read the choice from the scalar block)
-    const bool defer = s->use_fused && s->dm.n_extra == 0;
+    // needs no closing step (not with extra rows that have a kernel of their own, which reads the choice from the
+    // scalar block; rows folded into the direction kernel get their coefficients in the update kernel)
+    const bool defer = s->use_fused && (s->dm.n_extra == 0 || fold);
     launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream, fold_rows, s->obj.extra_weight, defer ? 1 : 0);
     APassArgs a = base_args(s);
     a.select_p = 1;
     a.check_status = 1;
-    if (defer) { a.dir_part = s->bf.redpart; a.dir_blocks = s->ge.dir_blocks; a.eps = s->op.eps; }
+    if (defer) {
+        a.dir_part = s->bf.redpart; a.dir_blocks = s->ge.dir_blocks; a.eps = s->op.eps;
+    }
+    const int fold_blocks = defer && fold ? s->ge.dir_blocks : 0;   // the update kernel forms the folded rows' coefficients
     if (quad && s->dm.n_extra > 0 && !fold)
         launch_extra_rows(s->dm, s->bf, s->obj.extra_rows, s->obj.extra_target, s->obj.extra_weight, 0, s->stream);
     if (s->dm.kind == LBFGSB_OBJ_QP) {
@@ -360,7 +364,7 @@ void enqueue_step(lbfgsb_solver* s) {
             if (s->use_fused) launch_fused(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
             else launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1);
         }
-        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->obj.sign, s->stream, fold_rows);
+        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, s->obj.sign, s->stream, fold_rows, s->obj.extra_weight, fold_blocks);
     } else if (quad) {
         a.mode = kRowDir;
         if (s->use_fused) {
@@ -370,7 +374,7 @@ void enqueue_step(lbfgsb_solver* s) {
             { TimedSlot ts(s); launch_gemv(s->dm, s->ge, s->bf, a, s->stream, ts.e0, ts.e1); }
             { TimedSlot ts(s); launch_gemvt_from(s->dm, s->ge, s->bf, s->obj.A, s->bf.psi, 1, s->stream, ts.e0, ts.e1); }
         }
-        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, nullptr, s->stream, fold_rows);
+        launch_update_quadratic(s->dm, s->op, s->ge, s->bf, nullptr, s->stream, fold_rows, s->obj.extra_weight, fold_blocks);
     } else if (s->use_fused) {
         // One read of X yields t = X p AND X^T psi for the first trial step min(1, alpha_ub).  The line
         // search over the margins then decides; only if it does not accept that first step does a second

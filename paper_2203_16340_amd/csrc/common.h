@@ -321,6 +321,37 @@ __device__ __forceinline__ DirChoice dir_choice_from_partials(const double* __re
     return c;
 }
 
+// Sums, over the same records, of the folded extra rows' products with both candidates (one full wave; lane l adds
+// records l, l + 64, ...): tx[2r] with the first candidate, tx[2r+1] with the second.
+__device__ __forceinline__ void dir_fold_from_partials(const double* __restrict__ redpart, int nblocks,
+                                                       double (&tx)[2 * kFoldMax]) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 0; k < 2 * kFoldMax; ++k) tx[k] = 0.0;
+    for (int b0 = 0; b0 < nblocks; b0 += 2 * 64) {
+        double v[2][2 * kFoldMax];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int b = b0 + 64 * j + lane;
+            const bool in = b < nblocks;
+            const double* r = redpart + (int64_t)(in ? b : 0) * kDirRed + 8;
+#pragma unroll
+            for (int k = 0; k < 2 * kFoldMax; ++k) v[j][k] = r[k];
+            if (!in) {
+#pragma unroll
+                for (int k = 0; k < 2 * kFoldMax; ++k) v[j][k] = 0.0;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int k = 0; k < 2 * kFoldMax; ++k) tx[k] += v[j][k];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 2 * kFoldMax; ++k) tx[k] = wave_sum(tx[k]);
+}
+
 // The same choice made by a whole workgroup of kBlock threads: thread t adds records t, t + kBlock, ... (their loads
 // issued together), then the fixed-order sums over the workgroup; every thread gets the result.  lds: kWaves * 7 doubles.
 __device__ __forceinline__ DirChoice dir_choice_block(const double* __restrict__ redpart, int nblocks, double eps,
@@ -520,8 +551,11 @@ bool dir_folds_extra_rows(const Dims& dm);
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
                 hipStream_t st, const double* fold_rows = nullptr, const double* fold_weight = nullptr,
                 int defer_choice = 0);
+// fold_weight, dir_blocks > 0: the direction kernel ended without its closing step; the update kernel forms the folded
+// rows' coefficients itself from that kernel's per-workgroup sums (Buffers::redpart)
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
-                             hipStream_t st, const double* fold_rows = nullptr);
+                             hipStream_t st, const double* fold_rows = nullptr, const double* fold_weight = nullptr,
+                             int dir_blocks = 0);
 // extra rows: e_r.z for z = x (eval != 0: residuals against the targets) or the selected direction (eval == 0)
 void launch_extra_rows(const Dims& dm, const Buffers& bf, const double* rows, const double* target, const double* weight,
                        int eval, hipStream_t st);

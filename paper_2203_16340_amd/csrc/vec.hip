@@ -303,7 +303,6 @@ void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffer
                 hipStream_t st, const double* fold_rows, const double* fold_weight, int defer_choice) {
     FoldArgs fold{0, nullptr, nullptr, nullptr, nullptr};
     if (fold_rows && dir_folds_extra_rows(dm)) fold = FoldArgs{dm.n_extra, fold_rows, fold_weight, bf.wextra, bf.xres + dm.n_extra};
-    if (fold.n_fold > 0) defer_choice = 0;   // (the folded rows' coefficients are the last workgroup's work)
     if (dm.n >= (1 << 17) && dm.n % 2 == 0) {
         hipLaunchKernelGGL(k_dir_pairs, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u,
                            bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, defer_choice);
@@ -394,18 +393,47 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
                                                              Scal* __restrict__ scal, const double* __restrict__ sign,
                                                              const double* __restrict__ wextra,
                                                              const double* __restrict__ xres, int n_fold,
-                                                             const double* __restrict__ fold_rows) {
+                                                             const double* __restrict__ fold_rows,
+                                                             const double* __restrict__ fold_weight,
+                                                             const double* __restrict__ dir_part, int dir_blocks) {
     __shared__ double lds[kBlock];
     __shared__ double red[kWaves];
     __shared__ double ls_alpha;
     __shared__ int ls_ok, ls_bt;
+    __shared__ double fold_s[kFoldMax + 1];   // folded rows: coefficients weight_r (e_r . p), then sum weight_r (e_r . p)^2
     if (scal->status != LBFGSB_RUNNING) return;
     const int tid = threadIdx.x;
     const double gp = scal->gp, alpha_ub = scal->alpha_ub, f_old = scal->f;
     const int slot = scal->head;
-    const double* p = scal->branch == 1 ? p1 : p2;
+    const int branch = scal->branch;
+    const double* p = branch == 1 ? p1 : p2;
+    const bool own_fold = n_fold > 0 && dir_blocks > 0;
+    if (own_fold) {
+        // the direction kernel left only its per-workgroup sums: the first wave adds the folded rows' products with
+        // the chosen candidate (every workgroup the same bits)
+        if (tid < 64) {
+            double tx[2 * kFoldMax];
+            dir_fold_from_partials(dir_part, dir_blocks, tx);
+            if (tid == 0) {
+                double total = 0.0;
+#pragma unroll
+                for (int r = 0; r < kFoldMax; ++r) {
+                    double cr = 0.0;
+                    if (r < n_fold) {
+                        const double te = branch == 1 ? tx[2 * r] : tx[2 * r + 1];
+                        const double wr = fold_weight ? fold_weight[r] : 1.0;
+                        cr = wr * te;
+                        total += wr * te * te;
+                    }
+                    fold_s[r] = cr;
+                }
+                fold_s[kFoldMax] = total;
+            }
+        }
+        __syncthreads();
+    }
     // curvature along p: ||t||^2 (weighted) from the A pass, plus the extra rows' sum weight (e_r.p)^2
-    const double tt = sum_all(losspart, loss_parts, red) + (xres ? xres[dm.n_extra] : 0.0);
+    const double tt = sum_all(losspart, loss_parts, red) + (own_fold ? fold_s[kFoldMax] : (xres ? xres[dm.n_extra] : 0.0));
     if (tid == 0) {
         double a = fmin(1.0, alpha_ub);
         int ok = 0, bt = 0;
@@ -432,7 +460,7 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
                     double wi = h ? -w : w;
                     if (sign) wi *= sign[i];               // QP: the change of the gradient is s.(A (s.p))
                     if (n_fold > 0) {                       // folded extra rows: wextra[0 .. n_fold) holds their coefficients
-                        for (int r = 0; r < n_fold; ++r) wi = fma(wextra[r], fold_rows[(int64_t)r * dm.n + i], wi);
+                        for (int r = 0; r < n_fold; ++r) wi = fma(own_fold ? fold_s[r] : wextra[r], fold_rows[(int64_t)r * dm.n + i], wi);
                     } else if (wextra) {
                         wi += wextra[i];
                     }
@@ -459,14 +487,15 @@ __global__ __launch_bounds__(kBlock) void k_update_quadratic(Dims dm, Opts op, i
 }
 
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,
-                             hipStream_t st, const double* fold_rows) {
+                             hipStream_t st, const double* fold_rows, const double* fold_weight, int dir_blocks) {
     const int n_fold = fold_rows && dir_folds_extra_rows(dm) ? dm.n_extra : 0;
     const bool qp = dm.kind == LBFGSB_OBJ_QP;   // its "partial columns" are the single vector t = A (s.p)
     hipLaunchKernelGGL(k_update_quadratic, dim3(ge.upd_blocks), dim3(kBlock), 0, st, dm, op, qp ? 1 : ge.w_parts,
                        ge.loss_parts, qp ? (const double*)bf.t : (const double*)bf.wpart, bf.losspart, bf.p1, bf.p2, bf.l,
                        bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, qp ? sign : nullptr,
                        dm.n_extra > 0 ? (const double*)bf.wextra : nullptr,
-                       dm.n_extra > 0 ? (const double*)bf.xres : nullptr, n_fold, fold_rows);
+                       dm.n_extra > 0 ? (const double*)bf.xres : nullptr, n_fold, fold_rows, fold_weight,
+                       (const double*)bf.redpart, n_fold > 0 ? dir_blocks : 0);
 }
 
 // ---- extra dense rows ------------------------------------------------------------------------------------
