@@ -9,7 +9,7 @@
 //   k_ot_sums + k_ot_cols   K z for z = x (evaluation) or the selected direction p, the loss partials
 //   k_ot_eval_finish        gradient M + lambda phi'(P) + K^T (omega . residual), objective value
 //   k_ot_update_gauss       closed-form Armijo search (the objective is quadratic along p) and the update
-//   k_ot_ls_entropy / k_ot_update_entropy / k_ot_res_axpy   the same for the entropy, whose line search
+//   k_ot_ls_entropy / k_ot_update_entropy   the same for the entropy, whose line search
 //                           needs one pass over (x, p) per batch of trial steps
 #include "common.h"
 
@@ -154,6 +154,8 @@ __global__ __launch_bounds__(kBlock) void k_ot_eval_finish(Dims dm, OtArgs a, in
     }
 }
 
+constexpr int kOtTiles = 4;   // column tiles of a row whose loads the Gaussian update kernel keeps in flight together
+
 // Gaussian regulariser: along p the objective is the quadratic  a <g,p> + a^2/2 (lambda <p,p> + sum omega (K p)^2),
 // so the Armijo search is the closed form of the least-squares kinds; the change of the gradient is
 // y = a (lambda p + K^T (omega . K p)).
@@ -189,19 +191,35 @@ __global__ __launch_bounds__(kBlock) void k_ot_update_gauss(Dims dm, Opts op, Ot
     if (ok) {
         double* Sn = S + (int64_t)slot * dm.n;
         double* Yn = Y + (int64_t)slot * dm.n;
+        // kOtTiles column tiles of a row per round, all their loads issued before the first is used (one tile at a
+        // time the row is a chain of dependent trips to memory)
         for (int64_t i = blockIdx.x; i < dm.rows; i += gridDim.x) {
             const double ri = a.omega ? a.omega[i] * t[i] : 0.0;
-            for (int64_t j = tid; j < dm.cols; j += kBlock) {
-                const int64_t e = i * dm.cols + j;
-                const double cj = a.omega ? a.omega[dm.rows + j] * t[dm.rows + j] : 0.0;
-                const double y = alpha * fma(dm.lambda, p[e], ri + cj);
-                const double xi = x[e];
-                const double xn = op.uniform_bounds ? clampd(fma(alpha, p[e], xi), op.lo, op.hi)
-                                                    : clampd(fma(alpha, p[e], xi), l[e], u[e]);
-                Sn[e] = xn - xi;
-                Yn[e] = y;
-                x[e] = xn;
-                g[e] += y;
+            for (int64_t j0 = 0; j0 < dm.cols; j0 += kOtTiles * kBlock) {
+                double pv[kOtTiles], xv[kOtTiles], gv[kOtTiles], cv[kOtTiles], lv[kOtTiles], uv[kOtTiles];
+#pragma unroll
+                for (int k = 0; k < kOtTiles; ++k) {
+                    const int64_t j = j0 + k * kBlock + tid;
+                    const bool in = j < dm.cols;
+                    const int64_t e = i * dm.cols + (in ? j : 0);
+                    pv[k] = p[e]; xv[k] = x[e]; gv[k] = g[e];
+                    cv[k] = (a.omega && in) ? a.omega[dm.rows + j] * t[dm.rows + j] : 0.0;
+                    lv[k] = op.uniform_bounds ? op.lo : l[e];
+                    uv[k] = op.uniform_bounds ? op.hi : u[e];
+                }
+#pragma unroll
+                for (int k = 0; k < kOtTiles; ++k) {
+                    const int64_t j = j0 + k * kBlock + tid;
+                    if (j < dm.cols) {
+                        const int64_t e = i * dm.cols + j;
+                        const double y = alpha * fma(dm.lambda, pv[k], ri + cv[k]);
+                        const double xn = clampd(fma(alpha, pv[k], xv[k]), lv[k], uv[k]);
+                        Sn[e] = xn - xv[k];
+                        Yn[e] = y;
+                        x[e] = xn;
+                        g[e] = gv[k] + y;
+                    }
+                }
             }
         }
     }
@@ -235,20 +253,69 @@ __device__ __forceinline__ double entropy_h(double r) {
 // a time.
 constexpr int kLsTail = 51;   // 2 + kLsBatch + kLsTail = 61 step lengths
 
+// Armijo test of NTRY step lengths a_first, a_first * backtrack, ... (indices first, first + 1, ...) given their sums
+// tot[k] = sum_e x_e h(a_k p_e / x_e): the first acceptable one, or found = -1.
 template <int NTRY>
+__device__ __forceinline__ void entropy_decide(const double (&tot)[NTRY], int first, double a_first, double gp, double tt,
+                                               double lambda, const Opts& op, int& found, double& a_acc, double& a_last) {
+    found = -1;
+    a_acc = 0.0;
+    double av = a_first;
+#pragma unroll
+    for (int k = 0; k < NTRY; ++k) {
+        const double df = av * (gp + 0.5 * av * tt) + lambda * tot[k];
+        if (found < 0 && first + k <= op.max_backtracks && isfinite(df) && df <= op.c1 * av * gp) { found = first + k; a_acc = av; }
+        if (k + 1 < NTRY) av *= op.backtrack;
+    }
+    a_last = av;
+}
+
+// NPREV > 0: the launch before this one (NPREV step lengths from index first - NPREV on) ended without deciding;
+// every workgroup of this launch adds that launch's partial sums (prev) and takes its decision, and only if none of
+// those step lengths was acceptable goes on with its own.  NPREV == 0 with defer != 0: this launch leaves its decision
+// to the next one (no closing arrival).
+template <int NTRY, int NPREV>
 __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int loss_parts, int first, int last_resort,
-                                                          const double* __restrict__ losspart,
+                                                          int defer, const double* __restrict__ losspart,
                                                           const double* __restrict__ x, const double* __restrict__ p1,
                                                           const double* __restrict__ p2, Scal* __restrict__ scal,
-                                                          double* __restrict__ lspart) {
-    __shared__ double red[kWaves * NTRY];
+                                                          const double* __restrict__ prev, double* __restrict__ lspart) {
+    __shared__ double red[kWaves * (NTRY > NPREV ? NTRY : NPREV)];
     __shared__ int flag;
     if (scal->status != LBFGSB_RUNNING) return;
-    if (first > 0 && scal->ls_ok) return;            // an earlier launch of this iteration found the step
+    if (NPREV == 0 && first > 0 && scal->ls_ok) return;   // an earlier launch of this iteration found the step
     const int tid = threadIdx.x;
     const double* p = scal->branch == 1 ? p1 : p2;
+    const double a0 = fmin(1.0, scal->alpha_ub);     // step lengths by repeated multiplication, the same everywhere
+    if constexpr (NPREV > 0) {
+        const double gp = scal->gp;
+        double tp[NPREV];
+#pragma unroll
+        for (int k = 0; k < NPREV; ++k) tp[k] = 0.0;
+        for (int b = tid; b < (int)gridDim.x; b += kBlock) {
+#pragma unroll
+            for (int k = 0; k < NPREV; ++k) tp[k] += prev[(int64_t)b * NPREV + k];
+        }
+        const double tt = sum_all(losspart, loss_parts, red);
+        block_sum<NPREV, kWaves>(tp, red);
+        double a_prev = a0;
+        for (int k = 0; k < first - NPREV; ++k) a_prev *= op.backtrack;
+        int found;
+        double a_acc, a_last;
+        entropy_decide<NPREV>(tp, first - NPREV, a_prev, gp, tt, dm.lambda, op, found, a_acc, a_last);
+        if (found >= 0) {
+            if (blockIdx.x == 0 && tid == 0) {
+                scal->ls_ok = 1;
+                scal->backtracks = found;
+                scal->fevals += found + 1;
+                scal->alpha = a_acc;
+            }
+            return;
+        }
+        __syncthreads();   // (red is used again below)
+    }
     double s[NTRY];
-    double a_first = fmin(1.0, scal->alpha_ub);      // step lengths by repeated multiplication, the same everywhere
+    double a_first = a0;
     for (int k = 0; k < first; ++k) a_first *= op.backtrack;
 #pragma unroll
     for (int k = 0; k < NTRY; ++k) s[k] = 0.0;
@@ -266,6 +333,7 @@ __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int 
 #pragma unroll
         for (int k = 0; k < NTRY; ++k) lspart[(int64_t)blockIdx.x * NTRY + k] = s[k];
     }
+    if (NPREV == 0 && defer) return;
     if (!arrive_is_last(&scal->counters[kCntLs], &flag)) return;
     const double gp = scal->gp;
     const double tt = sum_all(losspart, loss_parts, red);
@@ -277,14 +345,9 @@ __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int 
         for (int k = 0; k < NTRY; ++k) tot[k] += lspart[(int64_t)b * NTRY + k];
     }
     block_sum<NTRY, kWaves>(tot, red);
-    int found = -1;
-    double a_acc = 0.0, av = a_first;
-#pragma unroll
-    for (int k = 0; k < NTRY; ++k) {
-        const double df = av * (gp + 0.5 * av * tt) + dm.lambda * tot[k];
-        if (found < 0 && first + k <= op.max_backtracks && isfinite(df) && df <= op.c1 * av * gp) { found = first + k; a_acc = av; }
-        if (k + 1 < NTRY) av *= op.backtrack;
-    }
+    int found;
+    double a_acc, av;
+    entropy_decide<NTRY>(tot, first, a_first, gp, tt, dm.lambda, op, found, a_acc, av);
     // rare: continue one step length at a time (every thread holds the same totals: uniform control flow)
     for (int k = first + NTRY; last_resort && found < 0 && k <= op.max_backtracks; ++k) {
         av *= op.backtrack;
@@ -308,7 +371,7 @@ __global__ __launch_bounds__(kBlock) void k_ot_ls_entropy(Dims dm, Opts op, int 
 }
 
 // x+ = P(x + a p); g+ = M + lambda (log x+ + 1) + K^T (omega . (res + a K p)); pair; f+ from scratch at x+.
-__global__ __launch_bounds__(kBlock) void k_ot_update_entropy(Dims dm, Opts op, OtArgs a, const double* __restrict__ res,
+__global__ __launch_bounds__(kBlock) void k_ot_update_entropy(Dims dm, Opts op, OtArgs a, double* res,
                                                               const double* __restrict__ t, const double* __restrict__ p1,
                                                               const double* __restrict__ p2, const double* __restrict__ l,
                                                               const double* __restrict__ u, double* __restrict__ x,
@@ -352,10 +415,13 @@ __global__ __launch_bounds__(kBlock) void k_ot_update_entropy(Dims dm, Opts op, 
     if (!arrive_is_last(&scal->counters[kCntUpdate], &flag)) return;
     double tot[1] = {0.0};
     for (int b = tid; b < (int)gridDim.x; b += kBlock) tot[0] += redpart[b];
-    if (ok && a.omega) {
+    if (ok) {
+        // the residuals of the marginal terms move to the new point here, res += a K p: every other workgroup has
+        // finished reading them (it has arrived)
         for (int64_t k = tid; k < dm.rows + dm.cols; k += kBlock) {
             const double rn = fma(alpha, t[k], res[k]);
-            tot[0] = fma(0.5 * a.omega[k] * rn, rn, tot[0]);
+            res[k] = rn;
+            if (a.omega) tot[0] = fma(0.5 * a.omega[k] * rn, rn, tot[0]);
         }
     }
     block_sum<1, kWaves>(tot, red);
@@ -373,15 +439,6 @@ __global__ __launch_bounds__(kBlock) void k_ot_update_entropy(Dims dm, Opts op, 
             scal->status = LBFGSB_LINESEARCH_FAILED;
         }
     }
-}
-
-// residuals of the marginal terms at the new point: res += a K p
-__global__ void k_ot_res_axpy(int64_t count, const double* __restrict__ t, double* __restrict__ res,
-                              const Scal* __restrict__ scal) {
-    if (scal->status != LBFGSB_RUNNING || !scal->ls_ok) return;
-    const double alpha = scal->alpha;
-    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < count; k += (int64_t)gridDim.x * blockDim.x)
-        res[k] = fma(alpha, t[k], res[k]);
 }
 
 template <int RPW>
@@ -415,7 +472,8 @@ void launch_ot_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf
 
 void launch_ot_update_gauss(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const OtArgs& a,
                             hipStream_t st) {
-    hipLaunchKernelGGL(k_ot_update_gauss, dim3(ge.ot_el_blocks), dim3(kBlock), 0, st, dm, op, a,
+    // (no closing arrival in this kernel: one workgroup per row)
+    hipLaunchKernelGGL(k_ot_update_gauss, dim3((unsigned)(dm.rows > 2048 ? 2048 : dm.rows)), dim3(kBlock), 0, st, dm, op, a,
                        ge.ot_row_blocks + ge.ot_col_blocks, (const double*)bf.losspart, (const double*)bf.t,
                        (const double*)bf.p1, (const double*)bf.p2, (const double*)bf.l, (const double*)bf.u, bf.x, bf.g,
                        bf.S, bf.Y, bf.scal);
@@ -423,23 +481,25 @@ void launch_ot_update_gauss(const Dims& dm, const Opts& op, const Geometry& ge, 
 
 void launch_ot_step_entropy(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const OtArgs& a,
                             hipStream_t st) {
-    hipLaunchKernelGGL(k_ot_ls_entropy<2>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
-                       ge.ot_row_blocks + ge.ot_col_blocks, 0, 0, (const double*)bf.losspart, (const double*)bf.x,
-                       (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
-    hipLaunchKernelGGL(k_ot_ls_entropy<kLsBatch>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
-                       ge.ot_row_blocks + ge.ot_col_blocks, 2, 0, (const double*)bf.losspart, (const double*)bf.x,
-                       (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
-    hipLaunchKernelGGL(k_ot_ls_entropy<kLsTail>, dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
-                       ge.ot_row_blocks + ge.ot_col_blocks, 2 + kLsBatch, 1, (const double*)bf.losspart,
-                       (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, bf.scal, bf.lspart);
-    hipLaunchKernelGGL(k_ot_update_entropy, dim3(ge.ot_el_blocks), dim3(kBlock), 0, st, dm, op, a, (const double*)bf.row,
+    // three launches, each with a region of lspart of its own: the first (two step lengths) only leaves its partial
+    // sums, the second takes the first's decision before anything else
+    double* part0 = bf.lspart;
+    double* part1 = part0 + (size_t)ge.ls_blocks * 2;
+    double* part2 = part1 + (size_t)ge.ls_blocks * kLsBatch;
+    static_assert(2 + kLsBatch + kLsTail <= 64, "lspart holds 64 step lengths per workgroup");
+    hipLaunchKernelGGL((k_ot_ls_entropy<2, 0>), dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
+                       ge.ot_row_blocks + ge.ot_col_blocks, 0, 0, 1, (const double*)bf.losspart, (const double*)bf.x,
+                       (const double*)bf.p1, (const double*)bf.p2, bf.scal, (const double*)nullptr, part0);
+    hipLaunchKernelGGL((k_ot_ls_entropy<kLsBatch, 2>), dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
+                       ge.ot_row_blocks + ge.ot_col_blocks, 2, 0, 0, (const double*)bf.losspart, (const double*)bf.x,
+                       (const double*)bf.p1, (const double*)bf.p2, bf.scal, (const double*)part0, part1);
+    hipLaunchKernelGGL((k_ot_ls_entropy<kLsTail, 0>), dim3(ge.ls_blocks), dim3(kBlock), 0, st, dm, op,
+                       ge.ot_row_blocks + ge.ot_col_blocks, 2 + kLsBatch, 1, 0, (const double*)bf.losspart,
+                       (const double*)bf.x, (const double*)bf.p1, (const double*)bf.p2, bf.scal, (const double*)nullptr,
+                       part2);
+    hipLaunchKernelGGL(k_ot_update_entropy, dim3(ge.ot_el_blocks), dim3(kBlock), 0, st, dm, op, a, bf.row,
                        (const double*)bf.t, (const double*)bf.p1, (const double*)bf.p2, (const double*)bf.l,
                        (const double*)bf.u, bf.x, bf.g, bf.S, bf.Y, bf.scal, bf.redpart);
-    const int64_t count = dm.rows + dm.cols;
-    int blocks = (int)((count + 255) / 256);
-    if (blocks > 64) blocks = 64;
-    hipLaunchKernelGGL(k_ot_res_axpy, dim3(blocks), dim3(256), 0, st, count, (const double*)bf.t, bf.row,
-                       (const Scal*)bf.scal);
 }
 
 }  // namespace lb
