@@ -561,8 +561,15 @@ int solve_impl(lbfgsb_solver* s, lbfgsb_info* info) {
         // one launch runs until the device-side status changes (it re-evaluates the gradient from x before it
         // reports convergence) or the cap is reached
         const int steps_cap = (int)(cap > 0x3fffffff ? 0x3fffffff : cap);
-        launch_resident(s->dm, s->op, s->bf, s->obj.A, s->obj.b, steps_cap, s->options.refresh_every, s->stream);
-        HIP_TRY(read_scal(s));
+        if (s->owns_h_scal) {
+            // (pinned host copy: the kernel writes the scalar block there itself, with every pending update applied)
+            launch_resident(s->dm, s->op, s->bf, s->obj.A, s->obj.b, steps_cap, s->options.refresh_every, s->stream, s->h_scal);
+            s->commit_needed = false;
+            HIP_TRY(hipStreamSynchronize(s->stream));
+        } else {
+            launch_resident(s->dm, s->op, s->bf, s->obj.A, s->obj.b, steps_cap, s->options.refresh_every, s->stream);
+            HIP_TRY(read_scal(s));
+        }
         HIP_TRY(hipGetLastError());
         if (info) fill_info(*s->h_scal, info);
         return LBFGSB_OK;

@@ -594,8 +594,9 @@ void launch_ot_step_entropy(const Dims& dm, const Opts& op, const Geometry& ge, 
 // single-workgroup resident solver for small least-squares problems (resident.hip)
 bool resident_shape_ok(const Dims& dm, bool has_row_weight);
 hipError_t resident_prepare(const Dims& dm);   // once per solver, before the first launch_resident
+// host_scal: pinned host memory that receives the scalar block as well when the launch ends (null: device copy only)
 void launch_resident(const Dims& dm, const Opts& op, const Buffers& bf, const void* A, const double* b, int max_steps,
-                     int refresh_every, hipStream_t st);
+                     int refresh_every, hipStream_t st, Scal* host_scal = nullptr);
 
 int gram_blocks_for(int64_t n, int m);
 size_t gram_partial_bytes(int64_t n, int m);   // Buffers::grampart

@@ -42,6 +42,7 @@ struct ResArgs {
     int max_steps;         // iterations this launch may take
     int refresh_every;
     int f32;               // storage type of the matrix (it is widened when it is loaded into the registers)
+    Scal* host_scal;       // pinned host memory that also receives the scalar block when the launch ends (or null)
 };
 
 // LDS layout in doubles
@@ -97,7 +98,13 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
         reinterpret_cast<int*>(&sc)[k] = reinterpret_cast<const int*>(a.scal)[k];
     for (int k = tid; k < L.G; k += kResThreads) lds[k] = 0.0;   // the vectors, their padding included
     __syncthreads();
-    if (sc.status != LBFGSB_RUNNING) return;
+    if (sc.status != LBFGSB_RUNNING) {
+        if (a.host_scal) {
+            for (int k = tid; k < (int)(sizeof(Scal) / 4); k += kResThreads)
+                reinterpret_cast<int*>(a.host_scal)[k] = reinterpret_cast<const int*>(&sc)[k];
+        }
+        return;
+    }
     if (tid == 0 && sc.pend_valid) apply_pending(&sc, m);   // (left by a step of the multi-kernel path; normally none)
 
     // ---- the matrix into registers, the vectors into LDS and registers
@@ -395,6 +402,12 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
     }
     for (int k = tid; k < (int)(sizeof(Scal) / 4); k += kResThreads)
         reinterpret_cast<int*>(a.scal)[k] = reinterpret_cast<const int*>(&sc)[k];
+    // the host's copy directly (pinned memory is visible to the device): the caller then only waits for the launch,
+    // where a copy command behind it costs several microseconds more
+    if (a.host_scal) {
+        for (int k = tid; k < (int)(sizeof(Scal) / 4); k += kResThreads)
+            reinterpret_cast<int*>(a.host_scal)[k] = reinterpret_cast<const int*>(&sc)[k];
+    }
 }
 
 // The instantiations, smallest register footprint first: (columns per lane, rows per group) holds a matrix of up
@@ -429,11 +442,11 @@ hipError_t resident_prepare(const Dims& dm) {
 }
 
 void launch_resident(const Dims& dm, const Opts& op, const Buffers& bf, const void* A, const double* b, int max_steps,
-                     int refresh_every, hipStream_t st) {
+                     int refresh_every, hipStream_t st, Scal* host_scal) {
     const ResVariant* v = resident_variant(dm);
     const size_t bytes = (size_t)res_layout((int)dm.n, dm.m, v->cpl * 16).total * 8;
     ResArgs a{dm, op, A, b, bf.scal, bf.x, bf.g, bf.S, bf.Y, bf.l, bf.u, bf.mask, max_steps, refresh_every,
-              dm.dtype == LBFGSB_F32 ? 1 : 0};
+              dm.dtype == LBFGSB_F32 ? 1 : 0, host_scal};
     hipLaunchKernelGGL(v->kernel, dim3(1), dim3(kResThreads), bytes, st, a);
 }
 
