@@ -93,6 +93,21 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
     const int nw = (n + 63) >> 6;               // waves that own elements; the others only help with Gram and pass
     const bool wact = wave < nw;
 
+    // ---- the matrix into registers (requested before the scalar block is looked at: it depends on nothing)
+    double at[RG][CPL];
+#pragma unroll
+    for (int q = 0; q < RG; ++q) {
+        const int r = grp + kResGroups * q;
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            const int col = gj + 16 * k;
+            const int64_t o = (int64_t)r * ld + col;
+            const bool in = r < rows && col < n;
+            if (a.f32) at[q][k] = in ? (double)reinterpret_cast<const float*>(a.A)[o] : 0.0;
+            else at[q][k] = in ? reinterpret_cast<const double*>(a.A)[o] : 0.0;
+        }
+    }
+
     // ---- the scalar block; nothing to do when the solver has stopped
     for (int k = tid; k < (int)(sizeof(Scal) / 4); k += kResThreads)
         reinterpret_cast<int*>(&sc)[k] = reinterpret_cast<const int*>(a.scal)[k];
@@ -107,20 +122,7 @@ __global__ __launch_bounds__(kResThreads) void k_resident(ResArgs a) {
     }
     if (tid == 0 && sc.pend_valid) apply_pending(&sc, m);   // (left by a step of the multi-kernel path; normally none)
 
-    // ---- the matrix into registers, the vectors into LDS and registers
-    double at[RG][CPL];
-#pragma unroll
-    for (int q = 0; q < RG; ++q) {
-        const int r = grp + kResGroups * q;
-#pragma unroll
-        for (int k = 0; k < CPL; ++k) {
-            const int col = gj + 16 * k;
-            const int64_t o = (int64_t)r * ld + col;
-            const bool in = r < rows && col < n;
-            if (a.f32) at[q][k] = in ? (double)reinterpret_cast<const float*>(a.A)[o] : 0.0;
-            else at[q][k] = in ? reinterpret_cast<const double*>(a.A)[o] : 0.0;
-        }
-    }
+    // ---- the vectors into LDS and registers
     double xi = 0.0, gi = 0.0, li = 0.0, ui = 0.0, mi = 0.0;
     if (act) { xi = a.x[tid]; gi = a.g[tid]; li = a.l[tid]; ui = a.u[tid]; mi = a.mask[tid] ? 1.0 : 0.0; xs[tid] = xi; gs[tid] = gi; }
     for (int i = tid; i < m * n; i += kResThreads) {
