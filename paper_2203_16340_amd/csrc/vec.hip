@@ -141,13 +141,21 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
     __shared__ const double* vecp[kMaxV + 8];
     __shared__ double red[kWaves * 7];
     __shared__ int flag;
-    if (scal->status != LBFGSB_RUNNING) return;
     const int tid = threadIdx.x;
+    // What depends on nothing the scalar block says is requested together with it: the coefficients (masked by the
+    // number of vectors afterwards) and the first element's x, g, l, u and mask -- otherwise three dependent trips.
+    const int64_t e_first = (int64_t)blockIdx.x * kBlock + tid;
+    const int64_t e_safe = e_first < n ? e_first : n - 1;
+    const int status = scal->status;
+    const double delta_raw = tid < kMaxV ? scal->delta[tid] : 0.0;
+    double xn = x[e_safe], gn = g[e_safe], ln = l[e_safe], un = u[e_safe];
+    uint8_t mkn = mask[e_safe];
+    if (status != LBFGSB_RUNNING) return;
     const int c = scal->count, head = scal->head;
     const int V = 2 * c + 1;
     if (tid < kMaxV + 8) {
         vecp[tid] = tid < V ? ring_vec(tid, c, head, m, n, S, Y, g) : g;
-        delta_s[tid] = tid < V ? scal->delta[tid] : 0.0;
+        delta_s[tid] = tid < V ? delta_raw : 0.0;
     }
     __syncthreads();
     double s[6] = {0, 0, 0, 0, 0, 0};
@@ -155,13 +163,21 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
 #pragma unroll
     for (int k = 0; k < 2 * kFoldMax; ++k) sx[k] = 0.0;
     double ub = INFINITY;
-    for (int64_t e = (int64_t)blockIdx.x * kBlock + tid; e < n; e += (int64_t)gridDim.x * kBlock) {
+    for (int64_t e = e_first; e < n; e += (int64_t)gridDim.x * kBlock) {
+        const double xe = xn, ge = gn, le = ln, ue = un;
+        const uint8_t mk = mkn;
+        {
+            // the next element's, one trip ahead
+            const int64_t e2 = e + (int64_t)gridDim.x * kBlock;
+            const int64_t e2s = e2 < n ? e2 : n - 1;
+            xn = x[e2s]; gn = g[e2s]; ln = l[e2s]; un = u[e2s]; mkn = mask[e2s];
+        }
         double de;
         if (d_given) {
             de = d[e];
         } else {
             de = 0.0;
-            if (mask[e]) {
+            if (mk) {
                 double q = 0.0;
                 for (int j0 = 0; j0 < V; j0 += 8) {
                     double v[8];
@@ -174,7 +190,6 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
             }
             if (store_d) d[e] = de;
         }
-        const double xe = x[e], ge = g[e], le = l[e], ue = u[e];
         const double a = clampd(xe + de, le, ue) - xe;
         double b = de;
         if (de < 0.0 && xe <= le + op.eps) b = 0.0;
