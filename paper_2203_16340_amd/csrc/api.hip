@@ -160,7 +160,7 @@ Geometry make_geometry(const Dims& dm, const void* A) {
 }
 
 struct Layout {
-    size_t scal, x, g, l, u, d, p1, p2, mask, S, Y, row, t, psi, wpart, losspart, grampart, redpart, lspart, wextra, xres, hist, total;
+    size_t scal, scal_next, x, g, l, u, d, p1, p2, mask, S, Y, row, t, psi, wpart, losspart, grampart, redpart, lspart, wextra, xres, hist, total;
 };
 
 Layout make_layout(const Dims& dm, const Geometry& ge) {
@@ -170,6 +170,7 @@ Layout make_layout(const Dims& dm, const Geometry& ge) {
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     const size_t nb = (size_t)dm.n * 8, rb = (size_t)row_entries(dm.kind, dm.rows, dm.cols) * 8;
     L.scal = take(sizeof(Scal));
+    L.scal_next = take(sizeof(Scal));
     L.x = take(nb); L.g = take(nb); L.l = take(nb); L.u = take(nb); L.d = take(nb); L.p1 = take(nb); L.p2 = take(nb);
     L.mask = take((size_t)dm.n);
     L.S = take(nb * dm.m); L.Y = take(nb * dm.m);
@@ -339,7 +340,6 @@ void enqueue_step(lbfgsb_solver* s) {
         s->steps_since_set_x++;
         return;
     }
-    launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
     // one or two extra rows ride along with the direction kernel; more get the kernel of their own
     const bool fold = quad && dir_folds_extra_rows(s->dm);
     const double* fold_rows = fold ? s->obj.extra_rows : nullptr;
@@ -347,12 +347,19 @@ void enqueue_step(lbfgsb_solver* s) {
     // needs no closing step (not with extra rows that have a kernel of their own, which reads the choice from the
     // scalar block; rows folded into the direction kernel get their coefficients in the update kernel)
     const bool defer = s->use_fused && (s->dm.n_extra == 0 || fold);
-    launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream, fold_rows, s->obj.extra_weight, defer ? 1 : 0);
+    // ... and then the Gram kernel needs no closing step either, where its grid is small enough for the direction
+    // kernel's workgroups to add its partial sums themselves: they finish its work on private copies of the scalar
+    // block, and the pass moves workgroup 0's copy into place (Buffers::scal_next)
+    const bool open_gram = defer && gram_can_skip_close(s->dm, s->ge);
+    launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream, nullptr, nullptr, open_gram ? 1 : 0);
+    launch_dir(s->dm, s->op, s->ge, s->bf, 0, 0, s->stream, fold_rows, s->obj.extra_weight, defer ? 1 : 0,
+               open_gram ? s->ge.gram_blocks : 0);
     APassArgs a = base_args(s);
     a.select_p = 1;
     a.check_status = 1;
     if (defer) {
         a.dir_part = s->bf.redpart; a.dir_blocks = s->ge.dir_blocks; a.eps = s->op.eps;
+        if (open_gram) a.scal_next = s->bf.scal_next;
     }
     const int fold_blocks = defer && fold ? s->ge.dir_blocks : 0;   // the update kernel forms the folded rows' coefficients
     if (quad && s->dm.n_extra > 0 && !fold)
@@ -527,6 +534,7 @@ int setup_solver(lbfgsb_solver* s, int64_t n, int m, const lbfgsb_objective* obj
     char* w = (char*)workspace;
     Buffers& b = s->bf;
     b.scal = (Scal*)(w + L.scal);
+    b.scal_next = (Scal*)(w + L.scal_next);
     b.x = (double*)(w + L.x); b.g = (double*)(w + L.g); b.l = (double*)(w + L.l); b.u = (double*)(w + L.u);
     b.d = (double*)(w + L.d); b.p1 = (double*)(w + L.p1); b.p2 = (double*)(w + L.p2);
     b.mask = (uint8_t*)(w + L.mask);

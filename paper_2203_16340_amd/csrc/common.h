@@ -57,6 +57,9 @@ struct Scal {
     double delta[kMaxV];        // coefficients of q = sum_j delta_j b_j in the batched two-loop
     unsigned counters[kCntCount];
     unsigned gram_cnt[kGramGroups + 1];   // two-level arrival of the large-n Gram kernel: one per group, then the top
+    // Only in the copy the direction kernel hands to the pass (Buffers::scal_next): this copy holds a state the scalar
+    // block itself does not have yet
+    int fresh;
     int since_refresh;      // resident solver: iterations since residual and gradient were last computed from x
     // logistic objective, short launch sequence (see kStatusBail)
     int bail_skipped;       // whole steps that found the status kStatusBail and did nothing
@@ -226,7 +229,8 @@ __device__ __forceinline__ void record_iteration(Scal* s) {
 
 // Applies the pending update: accepted step (pair stored at slot `head`), or an exhausted line search
 // (clear the pair memory and retry once from the steepest-descent direction, else stop).
-__device__ __forceinline__ void apply_pending(Scal* s, int m) {
+// record: also write the per-iteration record (false where several workgroups apply the same update to private copies)
+__device__ __forceinline__ void apply_pending(Scal* s, int m, bool record = true) {
     if (!s->pend_valid) return;
     s->pend_valid = 0;
     s->ls_ok = s->pend_ok;
@@ -238,7 +242,8 @@ __device__ __forceinline__ void apply_pending(Scal* s, int m) {
         s->head = (s->head + 1) % m;
         s->count = s->count < m ? s->count + 1 : m;
         s->iters += 1;
-        record_iteration(s);
+        if (record) record_iteration(s);
+        else if (s->hist) s->hist_count += 1;
     } else if (s->count > 0) {
         s->count = 0;
         s->memory_resets += 1;
@@ -470,6 +475,11 @@ struct Geometry {
 // Device arrays carved out of the caller's workspace.
 struct Buffers {
     Scal* scal;
+    // Second scalar block for the sequence in which the Gram kernel has no closing step: every workgroup of the
+    // direction kernel works the closing step out on a private copy, workgroup 0 leaves its copy here (nothing in that
+    // kernel reads it), and workgroup 0 of the pass, whose other workgroups read only the status word of this copy,
+    // moves it into `scal`.
+    Scal* scal_next;
     double *x, *g, *l, *u, *d, *p1, *p2;
     uint8_t* mask;
     double *S, *Y;          // m x n rings
@@ -521,6 +531,9 @@ struct APassArgs {
     const double* dir_part;
     int dir_blocks;
     double eps;
+    // non-null: the status word is read from this copy of the scalar block, and workgroup 0 first moves the copy into the
+    // scalar block itself if the direction kernel marked it fresh (see Buffers::scal_next)
+    Scal* scal_next;
 };
 
 // ev0/ev1 (both or neither): HIP events attached to the dispatch itself, so that their difference is
@@ -540,17 +553,23 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 void launch_set_status(const Buffers& bf, int status, hipStream_t st);
 void launch_eval_finish(const Dims& dm, const Geometry& ge, const Buffers& bf, const double* lin, const double* sign,
                         hipStream_t st);   // lin, sign: QP only (linear term b, sign vector)
+// no_close (wide kernel with a one-level grid only, see gram_can_skip_close): the kernel ends when its workgroups'
+// partial sums are written; the direction kernel does the rest (launch_dir with gram_blocks > 0)
 void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int dbg_inputs,
-                 int evaluate_stop, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+                 int evaluate_stop, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, int no_close = 0);
+bool gram_can_skip_close(const Dims& dm, const Geometry& ge);
 void launch_commit(const Dims& dm, const Buffers& bf, hipStream_t st);
 // store_d: also keep d itself (the primitive-level hooks read it; an iteration only needs the two candidates)
 bool dir_folds_extra_rows(const Dims& dm);
 // fold_rows / fold_weight: the objective's extra rows and their weights when they are to ride along (else NULL)
 // defer_choice: the kernel stops after its partial sums (no last workgroup, nothing written to the scalar block): the
 // consumer of the direction makes Algorithm 2's choice from them (APassArgs::dir_part); not with folded rows
+// gram_blocks > 0 (short vectors only): the Gram kernel left its workgroups' partial sums without a closing step; every
+// workgroup of the direction kernel adds them, applies the pending update and runs the recursion on a private copy of
+// the scalar block, and workgroup 0 leaves its copy in Buffers::scal_next
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
                 hipStream_t st, const double* fold_rows = nullptr, const double* fold_weight = nullptr,
-                int defer_choice = 0);
+                int defer_choice = 0, int gram_blocks = 0);
 // fold_weight, dir_blocks > 0: the direction kernel ended without its closing step; the update kernel forms the folded
 // rows' coefficients itself from that kernel's per-workgroup sums (Buffers::redpart)
 void launch_update_quadratic(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, const double* sign,

@@ -245,17 +245,55 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     // Algorithm 2's choice between the candidate directions: from the scalar block, or made here from the direction
     // kernel's partial sums (every wave of every workgroup gets the same bits; workgroup 0 records them).  The status
     // word is requested first and looked at afterwards, so that its trip to memory and the records' are one.
-    const int status = a.check_status ? scal->status : LBFGSB_RUNNING;
+    // With a.scal_next the status word comes from the copy of the scalar block the direction kernel's workgroup 0 left
+    // there, and the first wave of workgroup 0 moves that copy into the scalar block itself (no other workgroup of this
+    // kernel reads the scalar block then), with the choice just made written into it on the way.
+    const Scal* st_src = a.scal_next ? a.scal_next : scal;
+    const int status = a.check_status ? st_src->status : LBFGSB_RUNNING;
+    constexpr int kScalWords = (int)(sizeof(Scal) / 4), kScalPerLane = (kScalWords + 63) / 64;
+    const bool mover = a.scal_next && blockIdx.x == 0 && tid < 64;
+    int moved[kScalPerLane];
+    int fresh = 0;
+    if (mover) {
+        fresh = a.scal_next->fresh;
+#pragma unroll
+        for (int j = 0; j < kScalPerLane; ++j) {
+            const int idx = tid + 64 * j;
+            moved[j] = idx < kScalWords ? reinterpret_cast<const int*>(a.scal_next)[idx] : 0;
+        }
+    }
     int branch = 0;
     double alpha_ub = 1.0;
     DirChoice ch{};
     const bool own_choice = a.select_p && a.dir_blocks > 0;
     if (own_choice) ch = dir_choice_from_partials(a.dir_part, a.dir_blocks, a.eps);
+    if (mover && fresh) {
+        const bool with_choice = own_choice && status == LBFGSB_RUNNING;
+#pragma unroll
+        for (int j = 0; j < kScalPerLane; ++j) {
+            const int idx = tid + 64 * j;
+            int v = moved[j];
+            auto put_double = [&](size_t off, double val) {
+                if (idx == (int)(off / 4)) v = __double2loint(val);
+                if (idx == (int)(off / 4) + 1) v = __double2hiint(val);
+            };
+            if (with_choice) {
+                if (idx == (int)(offsetof(Scal, branch) / 4)) v = ch.branch;
+                put_double(offsetof(Scal, gp), ch.gp);
+                put_double(offsetof(Scal, alpha_ub), ch.alpha_ub);
+                put_double(offsetof(Scal, pp), ch.pp);
+                put_double(offsetof(Scal, xp), ch.xp);
+            }
+            if (idx == (int)(offsetof(Scal, fresh) / 4)) v = 0;
+            if (idx < kScalWords) reinterpret_cast<int*>(scal)[idx] = v;
+        }
+        if (tid == 0) a.scal_next->fresh = 0;
+    }
     if (status != LBFGSB_RUNNING) return;
     if (own_choice) {
         branch = ch.branch;
         alpha_ub = ch.alpha_ub;
-        if (blockIdx.x == 0 && tid == 0) {
+        if (blockIdx.x == 0 && tid == 0 && !(a.scal_next && fresh)) {
             scal->branch = ch.branch; scal->gp = ch.gp; scal->alpha_ub = ch.alpha_ub; scal->pp = ch.pp; scal->xp = ch.xp;
         }
     } else if (LOGI != 0 && a.mode == kRowLogiSpec) {

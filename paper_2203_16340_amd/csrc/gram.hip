@@ -22,12 +22,13 @@
 
 #include "common.h"
 #include "recursion.h"
+#include "wide_close.h"
 
 namespace lb {
 
 namespace {
 constexpr int kStageMax = 32;   // vectors one thread stages per chunk
-constexpr int kHdr = 8;         // per-workgroup partial: [0] sum g[S]^2, [1] max KKT residual, [2] #fixed, [3] ||y_new||^2
+constexpr int kHdr = kGramHdr;   // per-workgroup partial: [0] sum g[S]^2, [1] max KKT residual, [2] #fixed, [3] ||y_new||^2
 constexpr int kTPT = 3;         // tiles per thread when there are more 2x2 tiles than threads (<= 528)
 
 __host__ __device__ inline int gram_tiles(int V) {
@@ -278,7 +279,6 @@ __global__ __launch_bounds__(kBlock) void k_gram(int64_t n, int m, int E, Opts o
 // and the order of the additions does not depend on which workgroup finishes last.  Grids of at most
 // kGramOneLevelMax workgroups skip the first level (each level costs two fences, an atomic and a dependent round of
 // loads: 6-7 us).
-constexpr int kGramOneLevelMax = 128;   // grids up to this size add their partials in one level
 constexpr int kGramGroupMax = 32;   // workgroups per group at most: grids of up to kGramGroups * kGramGroupMax
 
 __device__ __forceinline__ bool reduce_partials(double* __restrict__ grampart, int NE, Scal* __restrict__ scal, int* flag,
@@ -289,22 +289,7 @@ __device__ __forceinline__ bool reduce_partials(double* __restrict__ grampart, i
         if (!arrive_is_last(&scal->gram_cnt[kGramGroups], flag, (unsigned)nwg)) return false;
         // 64 partials of an entry at a time, every load of a batch issued before the first is used (one trip to
         // memory per batch; the accumulators' registers are free by now)
-        for (int idx = tid; idx < NE; idx += kBlock) {
-            double t = idx == 1 ? -INFINITY : 0.0;
-            for (int k0 = 0; k0 < nwg; k0 += 2 * kGramGroupMax) {
-                double v[2 * kGramGroupMax];
-#pragma unroll
-                for (int k = 0; k < 2 * kGramGroupMax; ++k) v[k] = k0 + k < nwg ? grampart[(int64_t)(k0 + k) * NE + idx] : (idx == 1 ? -INFINITY : 0.0);
-                if (idx == 1) {
-#pragma unroll
-                    for (int k = 0; k < 2 * kGramGroupMax; ++k) t = fmax(t, v[k]);
-                } else {
-#pragma unroll
-                    for (int k = 0; k < 2 * kGramGroupMax; ++k) t += v[k];
-                }
-            }
-            tot[idx] = t;
-        }
+        gram_sum_partials_flat(grampart, NE, nwg, tot);
         __syncthreads();
         return true;
     }
@@ -561,32 +546,6 @@ __global__ __launch_bounds__(kBlock) void k_gram_mfma(int64_t n, int m, Opts op,
 // cache after that.  Only one operand of a product is masked (the mask is 0 or 1).  Ring slots not in use
 // contribute zeros; the last workgroup maps ring slots to the oldest-first order of the recursion.
 
-constexpr int kWideM = 10;
-constexpr int kWideT = 2 * kWideM + 1;
-constexpr int kWideG = 7;                                    // slots per group
-constexpr int kWideDiag = kWideG * (kWideG + 1) / 2;         // 28
-constexpr int kWideRole = kWideDiag + kWideG * kWideG;       // 77 entries per wave
-constexpr int kWideEntries = kWideT * (kWideT + 1) / 2;      // 231 = 3 * 77
-constexpr int kWideNE = kHdr + kWideEntries;
-static_assert(3 * kWideG == kWideT && 3 * kWideRole == kWideEntries, "three groups of seven slots");
-
-// entry index -> static slots (a, b)
-__device__ __forceinline__ void wide_entry_slots(int idx, int& a, int& b) {
-    const int r = idx / kWideRole;
-    int q = idx % kWideRole;
-    const int p0 = kWideG * r, q0 = kWideG * ((r + 1) % 3);
-    if (q < kWideDiag) {
-        int i = 0;
-        while (q >= kWideG - i) { q -= kWideG - i; ++i; }
-        a = p0 + i;
-        b = p0 + i + q;
-    } else {
-        q -= kWideDiag;
-        a = p0 + q / kWideG;
-        b = q0 + q % kWideG;
-    }
-}
-
 // Sums 64 per-lane values over the 64 lanes of a wave all at once: on return lane j holds the total of a[j].
 // Each step halves the number of values a lane carries (the half it gives away goes to the lane 32, 16, ... 1
 // away), so 63 exchanges do what 64 separate butterfly sums would need 384 for.  Fixed order of additions.
@@ -760,10 +719,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                                                       const double* __restrict__ u, const double* __restrict__ S,
                                                       const double* __restrict__ Y, uint8_t* __restrict__ mask,
                                                       Scal* __restrict__ scal, double* __restrict__ grampart,
-                                                      int dbg_inputs, int evaluate_stop) {
+                                                      int dbg_inputs, int evaluate_stop, int no_close) {
     __shared__ double Gs[(2 * kWideM + 2) * (2 * kWideM + 2)];
     __shared__ double tot[kWideNE];
-    __shared__ double red[kWaves * 4];
     __shared__ double alpha_s[kMaxM + 1];
     __shared__ int flag;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -781,7 +739,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         else c = 0;
     }
     const double yn_old = prefetch_ynorm2(scal, c, head, m);   // (used by the last workgroup's recursion, fetched now)
-    const int V = 2 * c + 1, Vp = V + 1;
     WideCtx w;
     w.n = n; w.m = m; w.c = c; w.S = S; w.Y = Y; w.g = g;
     w.base_slot = c > 0 ? (head - c + 2 * m) % m : 0;           // ring slot of the oldest pair
@@ -797,38 +754,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         case 2: wide_role<2 * kWideG, 0, 2, UB>(w, op, x, l, u, mask, dbg_inputs, part, 2 * kWideRole); break;
         default: wide_role<0, 0, 3, UB>(w, op, x, l, u, mask, dbg_inputs, part, 0); break;
     }
+    if (no_close) return;   // the direction kernel adds the partial sums and does the rest
     if (!reduce_partials(grampart, kWideNE, scal, &flag, tot)) return;
-    // static slots -> the recursion's order (s oldest..newest, y oldest..newest, g)
-    for (int idx = tid; idx < kWideEntries; idx += kBlock) {
-        int a, b;
-        wide_entry_slots(idx, a, b);
-        auto logical = [&](int slot) -> int {
-            if (slot == 2 * kWideM) return 2 * c;
-            const int ring = slot < kWideM ? slot : slot - kWideM;
-            if (ring >= m) return -1;
-            const int j = (ring - w.base_slot + m) % m;
-            if (j >= c) return -1;
-            return slot < kWideM ? j : c + j;
-        };
-        const int row = logical(a), col = logical(b);
-        if (row >= 0 && col >= 0) {
-            const double t = tot[kHdr + idx];
-            Gs[row * Vp + col] = t;
-            Gs[col * Vp + row] = t;
-        }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        red[0] = Gs[(2 * c) * Vp + 2 * c];    // sum over the free set of g^2
-        red[1] = tot[1];
-        red[2] = tot[2];
-        red[3] = tot[3];                      // ||y_new||^2 over the full vector
-        // apply the update the previous kernel left pending, then record the newest pair's norm
-        apply_pending(scal, m);
-        if (c > 0 && !dbg_inputs) scal->ynorm2[(head - 1 + m) % m] = red[3];
-    }
-    __syncthreads();
-    recursion_on_coefficients(Gs, Vp, c, head, m, op, scal, red[0], red[1], red[2], red[3], yn_old, alpha_s, dbg_inputs, evaluate_stop);
+    wide_finish(tot, Gs, alpha_s, scal, m, c, head, w.base_slot, op, yn_old, dbg_inputs, evaluate_stop, true);
 }
 
 // (any even n: below 2^17 entries the grid stays small enough for the one-level sum of the partials)
@@ -880,15 +808,20 @@ void launch_gram_mfma(const Dims& dm, const Opts& op, const Geometry& ge, const 
                           evaluate_stop);
 }
 
+bool gram_can_skip_close(const Dims& dm, const Geometry& ge) {
+    return gram_uses_wide(dm.n, dm.m) && ge.gram_blocks <= kGramOneLevelMax;
+}
+
 void launch_gram(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int dbg_inputs,
-                 int evaluate_stop, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+                 int evaluate_stop, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1, int no_close) {
     if (gram_uses_wide(dm.n, dm.m)) {
+        if (no_close && !gram_can_skip_close(dm, ge)) no_close = 0;
         if (op.uniform_bounds)
             hipExtLaunchKernelGGL(k_gram_wide<true>, dim3(ge.gram_blocks), dim3(kBlock), 0, st, ev0, ev1, 0, dm.n, dm.m, op, bf.x,
-                                  bf.g, bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart, dbg_inputs, evaluate_stop);
+                                  bf.g, bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart, dbg_inputs, evaluate_stop, no_close);
         else
             hipExtLaunchKernelGGL(k_gram_wide<false>, dim3(ge.gram_blocks), dim3(kBlock), 0, st, ev0, ev1, 0, dm.n, dm.m, op, bf.x,
-                                  bf.g, bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart, dbg_inputs, evaluate_stop);
+                                  bf.g, bf.l, bf.u, bf.S, bf.Y, bf.mask, bf.scal, bf.grampart, dbg_inputs, evaluate_stop, no_close);
         return;
     }
     if (gram_uses_mfma(dm.n, dm.m)) {

@@ -4,6 +4,7 @@
 // device by the last workgroup of the kernel that produces the numbers it depends on.
 // (The free set, the Gram matrix and the recursion of Algorithm 3 are in gram.hip.)
 #include "common.h"
+#include "wide_close.h"
 
 namespace lb {
 
@@ -129,6 +130,14 @@ __device__ __forceinline__ void dir_finish(double (&s)[6], double ub, double eps
     }
 }
 
+// CLOSE: the wide Gram kernel before this one ended without its closing step (gram_blocks workgroups' partial sums in
+// grampart).  Every workgroup here then does that step on a private copy of the scalar block: adds the partial sums in
+// workgroup order, applies the pending update, runs Algorithm 3 on coefficients and the stopping test -- the same
+// functions in the same order as the Gram kernel's last workgroup, so the same bits -- and takes the coefficients from
+// its copy.  Workgroup 0 leaves its copy in scal_next for the pass (nothing in this kernel reads that); the scalar
+// block itself is only read here.  What this saves is the Gram kernel's arrival (a fence, an atomic, a dependent round
+// of loads) and this kernel's own dependent reads of the status word and the coefficients.
+template <bool CLOSE>
 __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const double* __restrict__ x,
                                                 const double* __restrict__ g, const double* __restrict__ l,
                                                 const double* __restrict__ u, const uint8_t* __restrict__ mask,
@@ -136,7 +145,8 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
                                                 Scal* __restrict__ scal, double* __restrict__ d,
                                                 double* __restrict__ p1, double* __restrict__ p2,
                                                 double* __restrict__ redpart, int d_given, int store_d, FoldArgs fold,
-                                                int defer_choice) {
+                                                int defer_choice, const double* __restrict__ grampart, int gram_blocks,
+                                                Scal* __restrict__ scal_next) {
     __shared__ double delta_s[kMaxV + 8];
     __shared__ const double* vecp[kMaxV + 8];
     __shared__ double red[kWaves * 7];
@@ -146,17 +156,69 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
     // number of vectors afterwards) and the first element's x, g, l, u and mask -- otherwise three dependent trips.
     const int64_t e_first = (int64_t)blockIdx.x * kBlock + tid;
     const int64_t e_safe = e_first < n ? e_first : n - 1;
-    const int status = scal->status;
-    const double delta_raw = tid < kMaxV ? scal->delta[tid] : 0.0;
     double xn = x[e_safe], gn = g[e_safe], ln = l[e_safe], un = u[e_safe];
     uint8_t mkn = mask[e_safe];
-    if (status != LBFGSB_RUNNING) return;
-    const int c = scal->count, head = scal->head;
-    const int V = 2 * c + 1;
-    if (tid < kMaxV + 8) {
-        vecp[tid] = tid < V ? ring_vec(tid, c, head, m, n, S, Y, g) : g;
-        delta_s[tid] = tid < V ? delta_raw : 0.0;
+    int c, head;
+    constexpr int kDirPre = CLOSE ? 2 * kWideM + 1 : 1;      // (the wide Gram kernel takes at most kWideM pairs)
+    double vpre[kDirPre];
+#pragma unroll
+    for (int j = 0; j < kDirPre; ++j) vpre[j] = 0.0;
+    if constexpr (CLOSE) {
+        __shared__ Scal sc;
+        __shared__ double Gs[(2 * kWideM + 2) * (2 * kWideM + 2)];
+        __shared__ double tot[kWideNE];
+        __shared__ double alpha_s[kMaxM + 1];
+        constexpr int kScalWords = (int)(sizeof(Scal) / 4);
+        for (int k = tid; k < kScalWords; k += kBlock)
+            reinterpret_cast<int*>(&sc)[k] = reinterpret_cast<const int*>(scal)[k];
+        gram_sum_partials_flat(grampart, kWideNE, gram_blocks, tot);
+        __syncthreads();
+        if (sc.status != LBFGSB_RUNNING) {
+            // (the pass reads its status word from scal_next: it must not find an older one there)
+            if (blockIdx.x == 0 && tid == 0) { scal_next->status = sc.status; scal_next->fresh = 0; }
+            return;
+        }
+        head = sc.head; c = sc.count;
+        if (sc.pend_valid) {                                       // same rule as effective_ring()
+            if (sc.pend_ok) { head = (head + 1) % m; c = c < m ? c + 1 : m; }
+            else c = 0;
+        }
+        const int base_slot = c > 0 ? (head - c + 2 * m) % m : 0;
+        const double yn_old = prefetch_ynorm2(&sc, c, head, m);
+        // the first element's vectors are requested now (which ring slots hold them is known), so that their trip to
+        // memory runs under the closing step instead of behind it
+        if (tid < kMaxV + 8) vecp[tid] = tid < 2 * c + 1 ? ring_vec(tid, c, head, m, n, S, Y, g) : g;
+        __syncthreads();
+        if (!d_given && mkn && e_first < n) {
+#pragma unroll
+            for (int j = 0; j < kDirPre; ++j) vpre[j] = j < 2 * c + 1 ? vecp[j][e_first] : 0.0;
+        }
+        __syncthreads();                                           // every thread has read the ring before it changes
+        wide_finish(tot, Gs, alpha_s, &sc, m, c, head, base_slot, op, yn_old, 0, 1, blockIdx.x == 0);
+        __syncthreads();                                           // the first wave's results are in the copy
+        if (blockIdx.x == 0) {
+            for (int k = tid; k < kScalWords; k += kBlock) {
+                int v = reinterpret_cast<const int*>(&sc)[k];
+                if (k == (int)(offsetof(Scal, fresh) / 4)) v = 1;
+                reinterpret_cast<int*>(scal_next)[k] = v;
+            }
+        }
+        if (sc.status != LBFGSB_RUNNING) return;
+        c = sc.count; head = sc.head;                              // (as computed above: the update has been applied)
+        const int V = 2 * c + 1;
+        if (tid < kMaxV + 8) delta_s[tid] = tid < V ? sc.delta[tid] : 0.0;
+    } else {
+        const int status = scal->status;
+        const double delta_raw = tid < kMaxV ? scal->delta[tid] : 0.0;
+        if (status != LBFGSB_RUNNING) return;
+        c = scal->count; head = scal->head;
+        const int V = 2 * c + 1;
+        if (tid < kMaxV + 8) {
+            vecp[tid] = tid < V ? ring_vec(tid, c, head, m, n, S, Y, g) : g;
+            delta_s[tid] = tid < V ? delta_raw : 0.0;
+        }
     }
+    const int V = 2 * c + 1;
     __syncthreads();
     double s[6] = {0, 0, 0, 0, 0, 0};
     double sx[2 * kFoldMax];
@@ -179,12 +241,18 @@ __global__ __launch_bounds__(kBlock) void k_dir(int64_t n, int m, Opts op, const
             de = 0.0;
             if (mk) {
                 double q = 0.0;
-                for (int j0 = 0; j0 < V; j0 += 8) {
-                    double v[8];
+                if (CLOSE && e == e_first) {
+                    // (same order of additions as below; entries past the last vector are zero times zero)
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) v[k] = j0 + k < V ? vecp[j0 + k][e] : 0.0;
+                    for (int j = 0; j < kDirPre; ++j) q = fma(delta_s[j], vpre[j], q);
+                } else {
+                    for (int j0 = 0; j0 < V; j0 += 8) {
+                        double v[8];
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) q = fma(delta_s[j0 + k], v[k], q);
+                        for (int k = 0; k < 8; ++k) v[k] = j0 + k < V ? vecp[j0 + k][e] : 0.0;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) q = fma(delta_s[j0 + k], v[k], q);
+                    }
                 }
                 de = -q;
             }
@@ -315,7 +383,7 @@ bool dir_folds_extra_rows(const Dims& dm) {
 }
 
 void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffers& bf, int d_given, int store_d,
-                hipStream_t st, const double* fold_rows, const double* fold_weight, int defer_choice) {
+                hipStream_t st, const double* fold_rows, const double* fold_weight, int defer_choice, int gram_blocks) {
     FoldArgs fold{0, nullptr, nullptr, nullptr, nullptr};
     if (fold_rows && dir_folds_extra_rows(dm)) fold = FoldArgs{dm.n_extra, fold_rows, fold_weight, bf.wextra, bf.xres + dm.n_extra};
     if (dm.n >= (1 << 17) && dm.n % 2 == 0) {
@@ -323,8 +391,15 @@ void launch_dir(const Dims& dm, const Opts& op, const Geometry& ge, const Buffer
                            bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, defer_choice);
         return;
     }
-    hipLaunchKernelGGL(k_dir, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u, bf.mask,
-                       bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, fold, defer_choice);
+    if (gram_blocks > 0) {
+        hipLaunchKernelGGL(k_dir<true>, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u,
+                           bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, fold, defer_choice,
+                           (const double*)bf.grampart, gram_blocks, bf.scal_next);
+        return;
+    }
+    hipLaunchKernelGGL(k_dir<false>, dim3(ge.dir_blocks), dim3(kBlock), 0, st, dm.n, dm.m, op, bf.x, bf.g, bf.l, bf.u,
+                       bf.mask, bf.S, bf.Y, bf.scal, bf.d, bf.p1, bf.p2, bf.redpart, d_given, store_d, fold, defer_choice,
+                       (const double*)nullptr, 0, (Scal*)nullptr);
 }
 
 // ---- after an evaluation pass: g and f ------------------------------------------------------------------
