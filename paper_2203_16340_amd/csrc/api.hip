@@ -66,6 +66,16 @@ struct lbfgsb_solver {
     int short_steps_unseen;
     bool short_ok;           // the short sequence is available (the pass has the LDS for its per-row numbers)
     bool commit_needed;      // resident solver: a kernel of the multi-kernel path may have left an update pending
+    // Called by lbfgsb_solve after it has enqueued the re-evaluation that confirms convergence and before it waits for
+    // the result: work that is only wanted if convergence is confirmed can ride on the same wait (the augmented
+    // Lagrangian's multiplier update, whose kernel looks at the status word itself).
+    void (*after_retest)(void*) = nullptr;
+    void* after_retest_ctx = nullptr;
+    bool last_read_was_retest = false;   // the scalar block was last read behind such a call
+    // lbfgsb_solve looks at the status after this many steps the first time (0: after poll_every, as always later).
+    // A warm-started solve that may be over at once (the augmented Lagrangian's later inner solves) sets 1: every step
+    // enqueued behind the one that converged is four launches that return at once.
+    int first_batch = 0;
     int steps_since_refresh;
     long long steps_since_set_x;
     bool x_set;
@@ -583,15 +593,19 @@ int solve_impl(lbfgsb_solver* s, lbfgsb_info* info) {
         return LBFGSB_OK;
     }
     long long steps = 0;
+    s->last_read_was_retest = false;
     // A poll leaves the device idle for about 30 us (commit, copy of the scalar block, the host's wake-up and the next
     // launches), a step enqueued after the solver has stopped costs about 6.  Long runs are therefore polled less
     // often: the interval doubles whenever eight intervals' worth of steps have gone by, up to 64.
-    int batch = s->options.poll_every;
+    int batch = s->first_batch > 0 ? s->first_batch : s->options.poll_every;
+    bool first = s->first_batch > 0;
     for (;;) {
         for (int k = 0; k < batch; ++k) enqueue_step(s);
         steps += batch;
-        if (batch < kPollMax && steps >= 8ll * batch) batch = 2 * batch > kPollMax ? kPollMax : 2 * batch;
+        if (first) { batch = s->options.poll_every; first = false; }
+        else if (batch < kPollMax && steps >= 8ll * batch) batch = 2 * batch > kPollMax ? kPollMax : 2 * batch;
         HIP_TRY(read_scal(s));
+        s->last_read_was_retest = false;
         int st = s->h_scal->status;
         if (st == LBFGSB_CONVERGED && quad && s->steps_since_refresh > 0 && s->h_scal->iters > 0) {
             // the stopping quantity was computed from a gradient carried by recurrence: recompute
@@ -600,7 +614,9 @@ int solve_impl(lbfgsb_solver* s, lbfgsb_info* info) {
             enqueue_eval(s, 0);
             s->steps_since_refresh = 0;
             launch_gram(s->dm, s->op, s->ge, s->bf, 0, 1, s->stream);
+            if (s->after_retest) s->after_retest(s->after_retest_ctx);
             HIP_TRY(read_scal(s));
+            s->last_read_was_retest = s->after_retest != nullptr;
             st = s->h_scal->status;
         }
         if (st != LBFGSB_RUNNING) break;
@@ -1081,10 +1097,12 @@ __global__ void k_al_shift_g(int64_t n_eq, int64_t cols, int64_t ld, const T* __
 // One workgroup.  res holds a_r . x - beta_r of the constraint rows, freshly evaluated at x:
 // h_r = res_r - lambda_r/rho; with update != 0 the multipliers become lambda + rho h.  red[0] = ||h||_inf,
 // red[1] = rho/2 sum (h + lambda/rho)^2 (the penalty term at the OLD multipliers).
+// gate (or NULL): do nothing unless that scalar block says CONVERGED.
 __global__ __launch_bounds__(kBlock) void k_al_update(int64_t n_eq, double rho, int update,
                                                       const double* __restrict__ res, double* __restrict__ lambda,
-                                                      double* __restrict__ red) {
+                                                      double* __restrict__ red, const Scal* __restrict__ gate) {
     __shared__ double lds[kWaves * 2];
+    if (gate && gate->status != LBFGSB_CONVERGED) return;
     double viol = 0.0, pen = 0.0;
     for (int64_t r = threadIdx.x; r < n_eq; r += kBlock) {
         const double a = res[r];
@@ -1351,14 +1369,25 @@ int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info*
     // here or let a following read of the scalar block do it
     auto measure = [&](int update, bool wait) -> hipError_t {
         hipLaunchKernelGGL(k_al_update, dim3(1), dim3(kBlock), 0, al->stream, al->n_eq, al->rho, update, al->res_c,
-                           al->lambda, al->red);
+                           al->lambda, al->red, (const Scal*)nullptr);
         hipError_t e = hipMemcpyAsync(al->h_red, al->red, 16, hipMemcpyDeviceToHost, al->stream);
         if (e != hipSuccess || !wait) return e;
         return hipStreamSynchronize(al->stream);
     };
+    // The multiplier update of an inner solve whose convergence is being confirmed rides on that confirmation's wait:
+    // residuals are fresh behind the re-evaluation, and the kernel does nothing unless the status says CONVERGED.
+    s->after_retest = [](void* ctx) {
+        lbfgsb_auglag* a = (lbfgsb_auglag*)ctx;
+        hipLaunchKernelGGL(k_al_update, dim3(1), dim3(kBlock), 0, a->stream, a->n_eq, a->rho, 1, a->res_c, a->lambda,
+                           a->red, (const Scal*)a->inner->bf.scal);
+        (void)hipMemcpyAsync(a->h_red, a->red, 16, hipMemcpyDeviceToHost, a->stream);
+    };
+    s->after_retest_ctx = al;
+    struct HookReset { lbfgsb_solver* s; ~HookReset() { s->after_retest = nullptr; s->after_retest_ctx = nullptr; } } hook_reset{s};
     HIP_TRY(measure(0, true));
     double viol_prev = al->h_red[0];
     out.violation = viol_prev;
+    long long prev_inner = 0;
     for (int it = 0; it < al->ao.max_outer; ++it) {
         if (it > 0 && al->c_rows) {
             // new targets/weights of the stacked constraint rows: the pair memory is cleared, and f and g at the
@@ -1387,15 +1416,21 @@ int lbfgsb_auglag_solve(lbfgsb_auglag* al, const double* x0, lbfgsb_auglag_info*
             if (rc) return rc;
         }
         lbfgsb_info ii;
+        // (an inner solve that follows one which needed at most two iterations is likely to be over at once)
+        s->first_batch = (it > 0 && prev_inner <= 2) ? 1 : 0;
         rc = lbfgsb_solve(s, &ii);
+        s->first_batch = 0;
         if (rc) return rc;
+        prev_inner = ii.iters;
         out.outer = it + 1;
         out.inner_iters += ii.iters;
         out.pg2 = ii.pg2;
         if (ii.status == LBFGSB_LINESEARCH_FAILED) { out.status = ii.status; break; }
-        HIP_TRY(al_fresh_eval(s));
-        HIP_TRY(measure(1, false));               // lambda += rho h(x); violation; penalty term
-        HIP_TRY(read_scal(s));                    // (one wait for both)
+        if (!(ii.status == LBFGSB_CONVERGED && s->last_read_was_retest)) {
+            HIP_TRY(al_fresh_eval(s));
+            HIP_TRY(measure(1, false));           // lambda += rho h(x); violation; penalty term
+            HIP_TRY(read_scal(s));                // (one wait for both)
+        }                                         // (else: done behind the solve's last wait)
         out.L = s->h_scal->f;
         out.violation = al->h_red[0];
         out.f = out.L - al->h_red[1];
