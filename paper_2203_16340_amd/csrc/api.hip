@@ -1153,10 +1153,9 @@ size_t al_rows_extra_bytes(int64_t n_eq) {
 }
 
 // residual (all rows) and gradient recomputed from x unless they already are
+// (called right behind lbfgsb_solve, whose last act was to read the scalar block: the host copy is current)
 hipError_t al_fresh_eval(lbfgsb_solver* s) {
     if (s->steps_since_refresh > 0) {
-        hipError_t e = read_scal(s);
-        if (e != hipSuccess) return e;
         const int status = s->h_scal->status;
         launch_set_status(s->bf, LBFGSB_RUNNING, s->stream);   // the evaluation's last kernel only runs in this state
         enqueue_eval(s, 0);
