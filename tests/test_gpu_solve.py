@@ -363,6 +363,42 @@ def test_max_iter_and_start_at_optimum():
     s.close()
 
 
+@pytest.mark.parametrize("name,scale", [("C2", 0.05), ("C3", 0.05), ("C4", 0.02)])
+@pytest.mark.parametrize("a_pass", A_PASSES)
+def test_steps_behind_the_last_one_change_nothing(name, scale, a_pass):
+    """Steps enqueued without waiting go on after the solver has stopped (the iteration limit here, then the tolerance):
+    every kernel of such a step returns at once, whichever kernel of the sequence took the decision and through
+    whichever copy of the scalar block the others learn of it.  Iterate, gradient, counts and status stay as they were,
+    bit for bit, and the state equals that of a solver stopped by the same limit in lbfgsb_solve."""
+    prob = workloads.config(name, scale=scale)
+    a = _gpu_solver(prob, a_pass, tol=0.0, max_iter=5)
+    for _ in range(5):
+        a.step(want_info=False)
+    a.step(want_info=False)                     # the step whose stopping test finds the limit reached
+    at_limit = a.info()
+    x5, g5 = a.x().clone(), a.g().clone()
+    assert at_limit.status == L.MAX_ITER and at_limit.iters == 5
+    for _ in range(4):
+        a.step(want_info=False)
+    after = a.info()
+    assert torch.equal(a.x(), x5) and torch.equal(a.g(), g5)
+    assert after.as_dict() == at_limit.as_dict()
+    b = _gpu_solver(prob, a_pass, tol=0.0, max_iter=5)
+    ib = b.solve()
+    assert ib.status == L.MAX_ITER and ib.iters == 5
+    assert torch.equal(b.x(), x5) and ib.f == at_limit.f
+    a.close(); b.close()
+    # stopped by the tolerance: later steps are no-ops too
+    c = _gpu_solver(prob, a_pass, tol=1e-3, tol_relative=1)
+    ic = c.solve()
+    assert ic.status == L.CONVERGED
+    xc = c.x().clone()
+    for _ in range(3):
+        c.step(want_info=False)
+    assert torch.equal(c.x(), xc) and c.info().as_dict() == ic.as_dict()
+    c.close()
+
+
 def test_coinciding_and_infinite_bounds():
     rng = np.random.default_rng(77)
     A = rng.normal(size=(30, 6)); b = rng.normal(size=30)
