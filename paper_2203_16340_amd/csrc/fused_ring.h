@@ -355,7 +355,26 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
 
     double loss = 0.0;
     int par = 0;
+    int prio_now = -1;
+    constexpr int kSegStages = 6;                            // stages per priority segment
+    const int nseg = (nstage + kSegStages - 1) / kSegStages;
     for (int st0 = 0; st0 < nstage; st0 += STAGES) {
+        // Where two workgroups share a compute unit, the one dispatched first wins every arbitration between waves of
+        // equal priority: it runs at almost the speed it would have alone, the other at two thirds of that, and when
+        // the first has finished the second is left with a compute unit it cannot fill on its own.  So a workgroup
+        // steps its waves' priority down as it gets on with its rows -- 3, 2, 1, 0 over four segments of a few stages,
+        // then again, counted from the END so that the last four segments are one descent: whichever workgroup is
+        // ahead is in a lower segment of the descent and yields to the other.
+        const int prio = (nseg - 1 - st0 / kSegStages) & 3;
+        if (prio != prio_now) {
+            prio_now = prio;
+            switch (prio) {
+                case 3: __builtin_amdgcn_s_setprio(3); break;
+                case 2: __builtin_amdgcn_s_setprio(2); break;
+                case 1: __builtin_amdgcn_s_setprio(1); break;
+                default: __builtin_amdgcn_s_setprio(0); break;
+            }
+        }
 #pragma unroll
         for (int ss = 0; ss < STAGES; ++ss) {
             const int64_t lr0 = (int64_t)(st0 + ss) * R;     // first local row of the stage
