@@ -142,10 +142,16 @@ __device__ __forceinline__ void stage_row_op(const double* red, int lane, int wa
 
 // v[c] = (va[c] - vb[c]) * sc[c] (difference and scaling optional) for c < lcols into LDS: E entries per thread
 // and round, every load of a round issued before the first value is used (a round is one trip to memory).
-template <int NT, int E, bool HAS_VB, bool HAS_VS>
+// `after_last_issue` runs once, in every thread, when the loads of the last round have been issued and before they are
+// waited for: loads return in the order they were issued, so whatever it requests arrives behind v, not in front of it.
+template <int NT, int E, bool HAS_VB, bool HAS_VS, class Hook>
 __device__ __forceinline__ void stage_v(const double* __restrict__ va, const double* __restrict__ vb,
-                                        const double* __restrict__ sc, double* vs, int lcols, int tid) {
-    for (int c0 = tid; c0 < lcols; c0 += NT * E) {
+                                        const double* __restrict__ sc, double* vs, int lcols, int tid,
+                                        Hook&& after_last_issue) {
+    const int rounds = (lcols + NT * E - 1) / (NT * E);      // the same in every thread
+    if (rounds == 0) after_last_issue();
+    for (int r = 0; r < rounds; ++r) {
+        const int c0 = tid + r * NT * E;
         double v8[E], b8[E], s8[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) {
@@ -154,6 +160,11 @@ __device__ __forceinline__ void stage_v(const double* __restrict__ va, const dou
             v8[k] = va[cc];
             if (HAS_VB) b8[k] = vb[cc];
             if (HAS_VS) s8[k] = sc[cc];
+        }
+        if (r == rounds - 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            after_last_issue();
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int k = 0; k < E; ++k) {
@@ -237,11 +248,14 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             dst[k] = __builtin_nontemporal_load(reinterpret_cast<const RawT*>(rp + c * (unsigned)sizeof(T)));
         }
     };
-    // The ring is primed before anything else: the first rows of A depend on nothing, so their trip to memory
-    // overlaps with the reads of the status word and of v (which otherwise precede it, one after the other, while
-    // the memory system idles).  A launch that finds the solver stopped has fetched a few rows for nothing.
+    // The ring is primed as early as it can be without getting in the way: loads return in the order they were issued,
+    // so rows requested before the status word, the direction kernel's records and v would have to arrive in full
+    // (a whole ring: hundreds of kilobytes per workgroup) before any of those small reads did.  The rows are therefore
+    // requested right behind the last of v's loads and arrive while v is written to LDS.
+    auto prime = [&]() {
 #pragma unroll
-    for (int s = 0; s < NB; ++s) fetch(raw[s], (s / SPS) * R + (s % SPS) / U, (s % SPS) % U);
+        for (int s = 0; s < NB; ++s) fetch(raw[s], (s / SPS) * R + (s % SPS) / U, (s % SPS) % U);
+    };
     // Algorithm 2's choice between the candidate directions: from the scalar block, or made here from the direction
     // kernel's partial sums (every wave of every workgroup gets the same bits; workgroup 0 records them).  The status
     // word is requested first and looked at afterwards, so that its trip to memory and the records' are one.
@@ -305,13 +319,7 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
     // v into LDS, eight entries per thread and round with all their loads issued before the first is used (one
     // entry at a time this loop was a chain of dependent trips to memory: 3.5 us at 5000 columns).  The optional
     // difference and scaling are decided outside the loop, whose body then has no branch for a load to wait at.
-    constexpr int VE = 8;                                    // entries per thread and round (16 measured slower at 20000 columns)
-    if (vb) {
-        if (a.vs) stage_v<NT, VE, true, true>(va, vb, a.vs, vs, lcols, tid); else stage_v<NT, VE, true, false>(va, vb, a.vs, vs, lcols, tid);
-    } else {
-        if (a.vs) stage_v<NT, VE, false, true>(va, vb, a.vs, vs, lcols, tid); else stage_v<NT, VE, false, false>(va, vb, a.vs, vs, lcols, tid);
-    }
-    if (tid < kPad) vs[lcols + tid] = 0.0;
+    constexpr int VE = 8;                                    // entries per thread and round (12 and 16 measured no faster; 16 spills in the widest variants)
     double vreg[KR > 0 ? KR : 1][VEC];
 #pragma unroll
     for (int k = 0; k < KR; ++k) {
@@ -321,6 +329,12 @@ void k_fused_ring(const T* __restrict__ A, int64_t ld, int64_t rows, int64_t col
             vreg[k][j] = c < cols ? (vb ? va[c] - vb[c] : va[c]) * (a.vs ? a.vs[c] : 1.0) : 0.0;
         }
     }
+    if (vb) {
+        if (a.vs) stage_v<NT, VE, true, true>(va, vb, a.vs, vs, lcols, tid, prime); else stage_v<NT, VE, true, false>(va, vb, a.vs, vs, lcols, tid, prime);
+    } else {
+        if (a.vs) stage_v<NT, VE, false, true>(va, vb, a.vs, vs, lcols, tid, prime); else stage_v<NT, VE, false, false>(va, vb, a.vs, vs, lcols, tid, prime);
+    }
+    if (tid < kPad) vs[lcols + tid] = 0.0;
 
     // The row's entries of b (targets or labels) and of the row weights (quadratic kinds) or, for the
     // speculative logistic pass, of the stored margins are read one stage ahead through the scalar unit (the row index is uniform and neither
