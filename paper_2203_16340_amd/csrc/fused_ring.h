@@ -145,7 +145,7 @@ __device__ __forceinline__ void stage_row_op(const double* red, int lane, int wa
 // `after_last_issue` runs once, in every thread, when the loads of the last round have been issued and before they are
 // waited for: loads return in the order they were issued, so whatever it requests arrives behind v, not in front of it.
 template <int NT, int E, bool HAS_VB, bool HAS_VS, class Hook>
-__device__ __forceinline__ void stage_v(const double* __restrict__ va, const double* __restrict__ vb,
+__device__ __forceinline__ void stage_v_looped(const double* __restrict__ va, const double* __restrict__ vb,
                                         const double* __restrict__ sc, double* vs, int lcols, int tid,
                                         Hook&& after_last_issue) {
     const int rounds = (lcols + NT * E - 1) / (NT * E);      // the same in every thread
@@ -175,6 +175,69 @@ __device__ __forceinline__ void stage_v(const double* __restrict__ va, const dou
             if (c < lcols) vs[c] = v;
         }
     }
+}
+
+// The same with the last round outside the loop.
+template <int NT, int E, bool HAS_VB, bool HAS_VS, class Hook>
+__device__ __forceinline__ void stage_v_peeled(const double* __restrict__ va, const double* __restrict__ vb,
+                                        const double* __restrict__ sc, double* vs, int lcols, int tid,
+                                        Hook&& after_last_issue) {
+    const int rounds = (lcols + NT * E - 1) / (NT * E);      // the same in every thread, at least one (lcols >= 1)
+    // The last round stands outside the loop, in straight-line code: inside it, under a test of the round number, the
+    // wait the compiler puts in front of the use of v covers half of the hook's loads as well (it has to assume the
+    // path on which the hook did not run).
+    for (int r = 0; r + 1 < rounds; ++r) {
+        const int c0 = tid + r * NT * E;
+        double v8[E], b8[E], s8[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const int c = c0 + k * NT;                       // (not the last round: every entry exists)
+            v8[k] = va[c];
+            if (HAS_VB) b8[k] = vb[c];
+            if (HAS_VS) s8[k] = sc[c];
+        }
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            double v = v8[k];
+            if (HAS_VB) v -= b8[k];
+            if (HAS_VS) v *= s8[k];
+            vs[c0 + k * NT] = v;
+        }
+    }
+    {
+        const int c0 = tid + (rounds - 1) * NT * E;
+        double v8[E], b8[E], s8[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const int c = c0 + k * NT;
+            const int cc = c < lcols ? c : lcols - 1;
+            v8[k] = va[cc];
+            if (HAS_VB) b8[k] = vb[cc];
+            if (HAS_VS) s8[k] = sc[cc];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        after_last_issue();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const int c = c0 + k * NT;
+            double v = v8[k];
+            if (HAS_VB) v -= b8[k];
+            if (HAS_VS) v *= s8[k];
+            if (c < lcols) vs[c] = v;
+        }
+    }
+}
+
+// Which of the two: the peeled form where several workgroups share a compute unit (the narrow variants: C4's pass is
+// 4 us shorter with it), the loop where one workgroup of 512 threads has it to itself (there the peeled form measured
+// 0.7 us slower at C3 and no different at C2 and C5).
+template <int NT, int E, bool HAS_VB, bool HAS_VS, class Hook>
+__device__ __forceinline__ void stage_v(const double* __restrict__ va, const double* __restrict__ vb,
+                                        const double* __restrict__ sc, double* vs, int lcols, int tid,
+                                        Hook&& after_last_issue) {
+    if constexpr (NT < 512) stage_v_peeled<NT, E, HAS_VB, HAS_VS>(va, vb, sc, vs, lcols, tid, after_last_issue);
+    else stage_v_looped<NT, E, HAS_VB, HAS_VS>(va, vb, sc, vs, lcols, tid, after_last_issue);
 }
 
 // dynamic LDS a launch needs: v for the columns held there (all of them unless the variant keeps the v of
