@@ -65,14 +65,14 @@ WORKLOADS = {
 # under profiles/ for the (config, a_pass) pairs that have been profiled, else null in the output.
 # (bytes per launch, where the figure comes from: summary file and the commit whose kernels it profiled)
 MEASURED_TRAFFIC = {
-    ("C2", "fused"): (8.361e8, "profiles/c2_nnls_20000x5000_f64_fused_a_pass.md @ adb7394"),        # algorithmic 8.0e8
-    ("C3", "fused"): (1.682e9, "profiles/c3_l1ls_10000x20000_f64_fused_a_pass.md @ adb7394"),       # algorithmic 1.6e9
-    ("C4", "fused"): (1.627e9, "profiles/c4_logistic_200000x2000_f32_fused_a_pass.md @ adb7394"),   # algorithmic 1.6e9
-    ("C5", "fused"): (8.100e9, "profiles/c5_nnls_100000x20000_f32_fused_a_pass.md @ adb7394"),      # algorithmic 8.0e9
-    ("AL2", "fused"): (8.367e8, "profiles/al2_auglag_20001x5000_f64_fused_a_pass.md @ adb7394"),    # algorithmic 8.0004e8
-    ("SVM", "fused"): (8.640e8, "profiles/svm_dual_10000x10000_f64_row_products_pass.md @ adb7394"),   # algorithmic 8.0e8
-    ("JP1G", "gram"): (1.026e8, "profiles/jp1g_joint_probability_1000x1000_f64_gram_kernel.md @ adb7394"),   # algorithmic 0.83e8 at the final free set
-    ("JP2G", "gram"): (6.175e7, "profiles/jp2g_joint_probability_2000x1000_f64_gram_kernel.md @ adb7394"),   # algorithmic 0.51e8
+    ("C2", "fused"): (8.364e8, "profiles/c2_nnls_20000x5000_f64_fused_a_pass.md @ e4ff258"),        # algorithmic 8.0e8
+    ("C3", "fused"): (1.682e9, "profiles/c3_l1ls_10000x20000_f64_fused_a_pass.md @ e4ff258"),       # algorithmic 1.6e9
+    ("C4", "fused"): (1.626e9, "profiles/c4_logistic_200000x2000_f32_fused_a_pass.md @ e4ff258"),   # algorithmic 1.6e9
+    ("C5", "fused"): (8.099e9, "profiles/c5_nnls_100000x20000_f32_fused_a_pass.md @ e4ff258"),      # algorithmic 8.0e9
+    ("AL2", "fused"): (8.368e8, "profiles/al2_auglag_20001x5000_f64_fused_a_pass.md @ e4ff258"),    # algorithmic 8.0004e8
+    ("SVM", "fused"): (8.633e8, "profiles/svm_dual_10000x10000_f64_row_products_pass.md @ e4ff258"),   # algorithmic 8.0e8
+    ("JP1G", "gram"): (1.025e8, "profiles/jp1g_joint_probability_1000x1000_f64_gram_kernel.md @ e4ff258"),   # algorithmic 0.83e8 at the final free set
+    ("JP2G", "gram"): (6.175e7, "profiles/jp2g_joint_probability_2000x1000_f64_gram_kernel.md @ e4ff258"),   # algorithmic 0.51e8
 }
 
 
